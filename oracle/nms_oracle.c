@@ -1,0 +1,258 @@
+/*
+ * CPU oracle for the paper's parallel NMS ("Work-Efficient Parallel Non-Maximum
+ * Suppression Kernels").  TEST INFRASTRUCTURE ONLY: it exists to check the HIP
+ * library and to be timed as the CPU baseline.  Nothing in the product path may
+ * call, link or import it, and it shares no code with the HIP sources.
+ *
+ * Plain single-threaded loops, float32 arithmetic with every operation rounded
+ * on its own (build with -O2 -ffp-contract=off -fno-fast-math; SSE scalar math).
+ * No blocking, no early exit, no sorting shortcuts: each function is the
+ * definition it cites, written out.
+ *
+ * Readings of the paper taken here (each is exercised by a pin in tests/):
+ *   - A box is kept iff NO box that outranks it overlaps it beyond the
+ *     threshold, whether or not that other box is itself kept (Algorithm 1 and
+ *     Algorithm 2; postconditions of MapKernel and ReduceKernel in the section
+ *     "Algorithm Correctness": V_i is the AND over all j of B_ij).
+ *   - Overlap = area of the intersection divided by the area of the
+ *     higher-scoring box d_j, with the pixel-inclusive "+1" on widths, heights
+ *     and area (Algorithm 1; MapKernel postcondition A(d_i n d_j)/A(d_j)).
+ *   - B_ij is the test "overlap < theta", so a pair with overlap == theta
+ *     eliminates (Algorithm 1, last assignment).
+ *   - The paper's boxes are squares {x, y, z, s}; here each axis has its own
+ *     extent: x+z becomes x2, y+z becomes y2 and (z+1)^2 becomes
+ *     ((x2-x1)+1)*((y2-y1)+1).  nmso_alg12_square() below is the paper's
+ *     square form, printed-operation for printed-operation, and the tests check
+ *     that the two agree on square inputs.
+ *   - Equal scores: the paper's strict "<" lets two equal-score boxes ignore
+ *     each other.  This build's stated rule is a total order: of two boxes with
+ *     equal scores the one with the lower index outranks the other.
+ *   - The "D[j].z != 0" term of Algorithm 1 guards the zero-filled tail of the
+ *     fixed-capacity vector D.  Here n is explicit and there is no tail, so the
+ *     term does not appear (nmso_alg12_square() keeps it, as printed).
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ---- ranking -------------------------------------------------------------- */
+
+/* Does box j outrank box i?  Algorithm 1's guard "D[i].s < D[j].s", completed
+ * to a total order by the lower-index-wins tie rule.  -0.0f == +0.0f in C, so
+ * the two zeros tie, as floating-point comparison says they should. */
+static int outranks(const float *scores, int j, int i)
+{
+    if (scores[j] > scores[i]) return 1;
+    if (scores[j] == scores[i] && j < i) return 1;
+    return 0;
+}
+
+/* ---- overlap measure ------------------------------------------------------- */
+
+/* Area of a box with the inclusive-pixel convention (Algorithm 1, the line
+ * computing a; generalised from (z+1)*(z+1) to one extent per axis). */
+static float box_area(const float *b)
+{
+    float w = (b[2] - b[0]) + 1.0f;
+    float h = (b[3] - b[1]) + 1.0f;
+    return w * h;
+}
+
+/* Overlap of victim box bi with the outranking box bj: intersection width and
+ * height as in Algorithm 1 (min of the far edges minus max of the near edges,
+ * plus one, floored at zero), their product divided by the area of bj. */
+static float overlap(const float *bi, const float *bj)
+{
+    float far_x = bi[2] < bj[2] ? bi[2] : bj[2];
+    float near_x = bi[0] > bj[0] ? bi[0] : bj[0];
+    float w = (far_x - near_x) + 1.0f;
+    if (!(w > 0.0f)) w = 0.0f;
+
+    float far_y = bi[3] < bj[3] ? bi[3] : bj[3];
+    float near_y = bi[1] > bj[1] ? bi[1] : bj[1];
+    float h = (far_y - near_y) + 1.0f;
+    if (!(h > 0.0f)) h = 0.0f;
+
+    float a = box_area(bj);
+    return (w * h) / a;
+}
+
+/* Exported so that tests can recompute single pairs (witnesses, invariants). */
+float nmso_overlap(const float *bi, const float *bj) { return overlap(bi, bj); }
+float nmso_area(const float *b) { return box_area(b); }
+int nmso_outranks(const float *scores, int j, int i) { return outranks(scores, j, i); }
+
+/* ---- map: the boolean matrix B ------------------------------------------------ */
+
+/* MapKernel postcondition: B[i*n+j] = 1 unless j outranks i and their overlap
+ * is not below theta.  B starts as all ones (the paper's memset) and only the
+ * guarded entries are rewritten, exactly as Algorithm 1 does. */
+void nmso_map(const float *boxes, const float *scores, int n, float theta, uint8_t *B)
+{
+    memset(B, 1, (size_t)n * (size_t)n);
+    for (int i = 0; i < n; ++i) {
+        for (int j = 0; j < n; ++j) {
+            if (outranks(scores, j, i)) {
+                float q = overlap(boxes + 4 * (size_t)i, boxes + 4 * (size_t)j);
+                B[(size_t)i * n + j] = (q < theta) ? 1 : 0;
+            }
+        }
+    }
+}
+
+/* ReduceKernel postcondition: V_i = AND over j of B_ij. */
+void nmso_reduce(const uint8_t *B, int n, uint8_t *V)
+{
+    for (int i = 0; i < n; ++i) {
+        uint8_t v = 1;
+        for (int j = 0; j < n; ++j) v = (uint8_t)(v & B[(size_t)i * n + j]);
+        V[i] = v;
+    }
+}
+
+/* ---- the whole path without materialising B ------------------------------------ */
+
+/* keep[i] = V_i, in the order of the input (Equation 2 masks D by V index for
+ * index).  Same double loop as nmso_map + nmso_reduce, the matrix element used
+ * as soon as it is known; no early exit. */
+void nmso_keep(const float *boxes, const float *scores, int n, float theta, uint8_t *keep)
+{
+    for (int i = 0; i < n; ++i) {
+        uint8_t v = 1;
+        for (int j = 0; j < n; ++j) {
+            uint8_t b = 1;
+            if (outranks(scores, j, i)) {
+                float q = overlap(boxes + 4 * (size_t)i, boxes + 4 * (size_t)j);
+                b = (q < theta) ? 1 : 0;
+            }
+            v = (uint8_t)(v & b);
+        }
+        keep[i] = v;
+    }
+}
+
+/* ---- rank order and the ranked views that the library's steps expose ----------- */
+
+/* order[r] = index of the box with exactly r boxes outranking it.  The rank is
+ * counted from the definition; nothing is sorted. */
+void nmso_order(const float *scores, int n, int32_t *order)
+{
+    for (int i = 0; i < n; ++i) {
+        int r = 0;
+        for (int j = 0; j < n; ++j) r += outranks(scores, j, i);
+        order[r] = i;
+    }
+}
+
+/* Boxes gathered into rank order with their areas: out[r*5 + 0..3] = box of
+ * rank r, out[r*5 + 4] = its area.  (Row-per-box on purpose: the library's own
+ * buffer layout is the library's business; tests convert.) */
+void nmso_ranked_boxes(const float *boxes, const int32_t *order, int n, float *out)
+{
+    for (int r = 0; r < n; ++r) {
+        const float *b = boxes + 4 * (size_t)order[r];
+        out[5 * (size_t)r + 0] = b[0];
+        out[5 * (size_t)r + 1] = b[1];
+        out[5 * (size_t)r + 2] = b[2];
+        out[5 * (size_t)r + 3] = b[3];
+        out[5 * (size_t)r + 4] = box_area(b);
+    }
+}
+
+/* Elimination bits in rank order, one byte per ordered pair: E[r*n + c] = 1 iff
+ * the box of rank c outranks (c < r) and eliminates the box of rank r, i.e. the
+ * complement of B restricted to the ranked lower triangle; 0 elsewhere. */
+void nmso_ranked_eliminations(const float *boxes, const int32_t *order, int n, float theta, uint8_t *E)
+{
+    memset(E, 0, (size_t)n * (size_t)n);
+    for (int r = 0; r < n; ++r) {
+        for (int c = 0; c < r; ++c) {
+            float q = overlap(boxes + 4 * (size_t)order[r], boxes + 4 * (size_t)order[c]);
+            E[(size_t)r * n + c] = (q < theta) ? 0 : 1;
+        }
+    }
+}
+
+/* Same bits packed 64 to a word: word w of rank r holds ranks 64w..64w+63 in
+ * bits 0..63.  words[r*W + w], W = ceil(n/64).  For large n where the byte
+ * matrix would not fit. */
+void nmso_ranked_elimination_words(const float *boxes, const int32_t *order, int n, float theta, uint64_t *words)
+{
+    int W = (n + 63) / 64;
+    memset(words, 0, (size_t)n * (size_t)W * sizeof(uint64_t));
+    for (int r = 0; r < n; ++r) {
+        for (int c = 0; c < r; ++c) {
+            float q = overlap(boxes + 4 * (size_t)order[r], boxes + 4 * (size_t)order[c]);
+            if (!(q < theta)) words[(size_t)r * W + (c >> 6)] |= (uint64_t)1 << (c & 63);
+        }
+    }
+}
+
+/* ---- the paper's own square-box form, as printed -------------------------------- */
+
+/* Algorithm 1 then Algorithm 2 on D = {x, y, z, s} tuples of capacity dmax
+ * (unused slots all zero).  B is dmax*dmax bytes preset to 1, V is dmax bytes.
+ * Strict score comparison and the "z != 0" term exactly as the listing has
+ * them.  The reduce is Algorithm 2's k strided partial ANDs per row: partition p
+ * covers columns p*(dmax/k) .. (p+1)*(dmax/k)-1 and the block-wide AND is a
+ * plain loop.  dmax must be a multiple of k. */
+void nmso_alg12_square(const float *D, int dmax, float theta, int k, uint8_t *B, uint8_t *V)
+{
+    memset(B, 1, (size_t)dmax * (size_t)dmax);
+    for (int i = 0; i < dmax; ++i) {
+        for (int j = 0; j < dmax; ++j) {
+            const float *di = D + 4 * (size_t)i;
+            const float *dj = D + 4 * (size_t)j;
+            if (di[3] < dj[3]) {
+                float a = (dj[2] + 1.0f) * (dj[2] + 1.0f);
+                float fx = (di[0] + di[2]) < (dj[0] + dj[2]) ? (di[0] + di[2]) : (dj[0] + dj[2]);
+                float nx = di[0] > dj[0] ? di[0] : dj[0];
+                float w = (fx - nx) + 1.0f;
+                if (!(w > 0.0f)) w = 0.0f;
+                float fy = (di[1] + di[2]) < (dj[1] + dj[2]) ? (di[1] + di[2]) : (dj[1] + dj[2]);
+                float ny = di[1] > dj[1] ? di[1] : dj[1];
+                float h = (fy - ny) + 1.0f;
+                if (!(h > 0.0f)) h = 0.0f;
+                B[(size_t)i * dmax + j] = (uint8_t)(((w * h) / a < theta) && (dj[2] != 0.0f));
+            }
+        }
+    }
+    int part = dmax / k;
+    for (int i = 0; i < dmax; ++i) {
+        uint8_t v = 1;
+        for (int t = 0; t < part; ++t) v = (uint8_t)(v & B[(size_t)i * dmax + t]);
+        V[i] = v;
+        for (int p = 1; p < k; ++p) {
+            uint8_t blk = 1;
+            for (int t = 0; t < part; ++t) blk = (uint8_t)(blk & (V[i] && B[(size_t)i * dmax + p * part + t]));
+            V[i] = blk;
+        }
+    }
+}
+
+/* ---- classic sequential greedy NMS (a different function; not the default) -------- */
+
+/* Visit boxes in rank order; a box is kept iff no KEPT box that outranks it
+ * overlaps it with overlap >= theta (same overlap measure and tie rule as
+ * above).  This is what the paper's introduction calls the conventional greedy
+ * procedure; Algorithms 1 and 2 do not compute it (an eliminated box still
+ * eliminates others there).  Used by tests for the containment invariant and
+ * as the oracle of the selectable greedy rule. */
+void nmso_greedy_keep(const float *boxes, const float *scores, int n, float theta, uint8_t *keep)
+{
+    int32_t *order = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+    nmso_order(scores, n, order);
+    for (int r = 0; r < n; ++r) {
+        int i = order[r];
+        uint8_t v = 1;
+        for (int c = 0; c < r; ++c) {
+            int j = order[c];
+            if (keep[j]) {
+                float q = overlap(boxes + 4 * (size_t)i, boxes + 4 * (size_t)j);
+                if (!(q < theta)) v = 0;
+            }
+        }
+        keep[i] = v;
+    }
+    free(order);
+}

@@ -1,0 +1,60 @@
+"""Are the pins sharp?  Plant one plausible mistake at a time in a copy of the
+oracle's source (CPU only), rebuild it, and require that at least one pin fails.
+"""
+import os
+import subprocess
+
+import pytest
+
+from oracle import CFLAGS, SOURCE, Oracle
+from pins import ALL_PINS
+
+# (name, text in nms_oracle.c, replacement, how many occurrences must be replaced)
+MUTANTS = [
+    ("denominator_is_victim_area", "float a = box_area(bj);", "float a = box_area(bi);", 1),
+    ("intersection_over_union", "return (w * h) / a;", "return (w * h) / ((a + box_area(bi)) - (w * h));", 1),
+    ("equality_survives", "(q < theta) ? 1 : 0", "(q <= theta) ? 1 : 0", 2),
+    ("no_plus_one_on_width", "float w = (far_x - near_x) + 1.0f;", "float w = (far_x - near_x);", 1),
+    ("no_plus_one_on_height", "float h = (far_y - near_y) + 1.0f;", "float h = (far_y - near_y);", 1),
+    ("no_plus_one_in_area", "float w = (b[2] - b[0]) + 1.0f;", "float w = (b[2] - b[0]);", 1),
+    ("tie_to_higher_index", "scores[j] == scores[i] && j < i", "scores[j] == scores[i] && j > i", 1),
+    ("ties_ignored", "if (scores[j] == scores[i] && j < i) return 1;", "", 1),
+    ("rank_reversed", "if (scores[j] > scores[i]) return 1;", "if (scores[j] < scores[i]) return 1;", 1),
+    ("width_not_floored", "if (!(w > 0.0f)) w = 0.0f;\n\n    float far_y", "\n    float far_y", 1),
+    ("height_not_floored", "if (!(h > 0.0f)) h = 0.0f;\n\n    float a = box_area(bj);", "\n    float a = box_area(bj);", 1),
+    ("far_edge_is_max", "float far_x = bi[2] < bj[2] ? bi[2] : bj[2];", "float far_x = bi[2] > bj[2] ? bi[2] : bj[2];", 1),
+    ("near_edge_is_min", "float near_y = bi[1] > bj[1] ? bi[1] : bj[1];", "float near_y = bi[1] < bj[1] ? bi[1] : bj[1];", 1),
+    ("y_uses_x_edges", "float far_y = bi[3] < bj[3] ? bi[3] : bj[3];", "float far_y = bi[2] < bj[2] ? bi[2] : bj[2];", 1),
+    ("operands_transposed_keep", "float q = overlap(boxes + 4 * (size_t)i, boxes + 4 * (size_t)j);\n                b = ",
+     "float q = overlap(boxes + 4 * (size_t)j, boxes + 4 * (size_t)i);\n                b = ", 1),
+    ("operands_transposed_map", "float q = overlap(boxes + 4 * (size_t)i, boxes + 4 * (size_t)j);\n                B[",
+     "float q = overlap(boxes + 4 * (size_t)j, boxes + 4 * (size_t)i);\n                B[", 1),
+    ("reduce_is_or", "v = (uint8_t)(v & B[(size_t)i * n + j]);", "v = (uint8_t)(v | B[(size_t)i * n + j]);", 1),
+    ("keep_stops_at_diagonal", "for (int j = 0; j < n; ++j) {\n            uint8_t b = 1;", "for (int j = 0; j < i; ++j) {\n            uint8_t b = 1;", 1),
+    ("area_is_square_of_width", "return w * h;", "return w * w;", 1),
+    ("greedy_counts_dead_boxes", "if (keep[j]) {", "if (1) {", 1),
+    ("ranked_bits_upper_triangle", "for (int c = 0; c < r; ++c) {\n            float q = overlap(boxes + 4 * (size_t)order[r], boxes + 4 * (size_t)order[c]);\n            E[",
+     "for (int c = 0; c <= r; ++c) {\n            float q = overlap(boxes + 4 * (size_t)order[r], boxes + 4 * (size_t)order[c]);\n            E[", 1),
+    ("ranked_words_wrong_bit", "(uint64_t)1 << (c & 63)", "(uint64_t)1 << (c & 31)", 1),
+    ("ranked_area_missing", "out[5 * (size_t)r + 4] = box_area(b);", "out[5 * (size_t)r + 4] = b[2] - b[0];", 1),
+    ("printed_form_drops_partition", "for (int p = 1; p < k; ++p) {", "for (int p = 1; p < k - 1; ++p) {", 1),
+    ("printed_form_nonstrict", "if (di[3] < dj[3]) {", "if (di[3] <= dj[3]) {", 1),
+]
+
+
+@pytest.mark.parametrize("name,old,new,count", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_mutant_is_caught(tmp_path, name, old, new, count):
+    text = open(SOURCE).read()
+    assert text.count(old) == count, f"mutation site for {name} not found exactly {count} time(s)"
+    src = tmp_path / "mutant.c"
+    src.write_text(text.replace(old, new))
+    lib = tmp_path / f"libmutant_{name}.so"
+    subprocess.run(["gcc", *CFLAGS, str(src), "-o", str(lib)], check=True)
+    mutant = Oracle(str(lib))
+    failed = []
+    for pin_name, pin in ALL_PINS:
+        try:
+            pin(mutant)
+        except AssertionError:
+            failed.append(pin_name)
+    assert failed, f"no pin notices the planted mistake '{name}'"
