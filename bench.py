@@ -1,0 +1,279 @@
+#!/usr/bin/env python3
+"""Benchmark of the NMS hot path on one MI355X.
+
+A step = one pass of the whole path (rank -> pair tests with the row reduction
+folded in) over one batch of synthetic frames already resident in HBM.  The
+headline workload is configuration 4 (256 frames x 4096 SSD-style anchors, theta
+0.45); `value` is evaluated pair tests per second, F * n(n-1)/2 per step.
+
+Prints ONE JSON line.  Besides the contract fields it carries
+  roofline      the dominant kernel (the pair-test kernel) against the FP32 vector peak
+  cpu_baseline  the CPU oracle timed on a bounded sample of the same workload
+  extra         per-kernel split, the three-step (mask) pipeline, and the single-frame
+                latencies of the other configurations (us/frame at 1024 boxes etc.)
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+FLOPS_PER_PAIR = 13            # min,max,sub,add,max0 per axis (10) + mul + div + compare
+PEAK_FP32_VECTOR_TFLOPS = 157.3  # MI355X datasheet (packed FMA); see the design doc for the unpacked ceiling
+PEAK_UNPACKED_TOPS = 39.3        # 256 CU x 4 SIMD x 16 lanes x 2.4 GHz, one non-FMA op per lane per clock
+PEAK_HBM_GBS = 8000.0
+
+
+class HipEvents:
+    """Raw HIP events through ctypes (events that the library records itself)."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.made = []
+
+    def create(self) -> int:
+        ev = ctypes.c_void_p()
+        assert self.hip.hipEventCreate(ctypes.byref(ev)) == 0
+        self.made.append(ev.value)
+        return ev.value
+
+    def sync(self, ev):
+        assert self.hip.hipEventSynchronize(ctypes.c_void_p(ev)) == 0
+
+    def ms(self, a, b) -> float:
+        out = ctypes.c_float()
+        assert self.hip.hipEventElapsedTime(ctypes.byref(out), ctypes.c_void_p(a), ctypes.c_void_p(b)) == 0
+        return float(out.value)
+
+    def close(self):
+        for ev in self.made:
+            self.hip.hipEventDestroy(ctypes.c_void_p(ev))
+        self.made = []
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=4, help="workload configuration of the headline number (0..4)")
+    ap.add_argument("--no-extra", action="store_true", help="skip the secondary configurations")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-frames", type=int, default=128)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2502_00535_amd.binding as nms   # raises if the HIP library is missing: no fallback
+    from workloads import make_config
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(0)
+    K, W = args.steps, args.warmup
+    events = HipEvents()
+
+    def upload(w):
+        d = {
+            "w": w, "F": w.frames, "n": w.n,
+            "boxes": torch.from_numpy(w.boxes).to(dev), "scores": torch.from_numpy(w.scores).to(dev),
+            "keep": torch.empty((w.frames, w.n), dtype=torch.uint8, device=dev),
+            "ws": torch.empty(nms.nms_workspace_bytes(w.n, w.frames), dtype=torch.uint8, device=dev),
+        }
+        return d
+
+    def run_fused(d):
+        nms.nms_run_batched(d["boxes"], d["scores"], None, d["n"], d["F"], d["w"].theta, d["keep"], d["ws"])
+
+    def time_steps(fn, steps, warmup):
+        """wall clock of `steps` calls bracketed by device synchronisation, ms per step"""
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    # ------------------------------------------------------------------ headline workload
+    w = make_config(args.config)
+    d = upload(w)
+    ms_per_step = time_steps(lambda: run_fused(d), K, W)
+    pairs = w.pair_tests
+    value = pairs / (ms_per_step * 1e-3)
+
+    # per-kernel durations, live, with HIP events recorded by the library between its launches
+    ev = [[events.create() for _ in range(3)] for _ in range(K)]
+    for k in range(K):
+        nms.nms_run_batched_profiled(d["boxes"], d["scores"], None, d["n"], d["F"], w.theta, d["keep"], d["ws"], ev[k])
+    torch.cuda.synchronize()
+    rank_ms = sum(events.ms(e[0], e[1]) for e in ev) / K
+    map_ms = sum(events.ms(e[1], e[2]) for e in ev) / K
+    events.close()
+    keep_gpu = d["keep"].cpu().numpy()
+
+    achieved_tflops = FLOPS_PER_PAIR * pairs / (map_ms * 1e-3) / 1e12
+    roofline = {
+        "kernel": "map_tile_kernel<fast, fused> (pair tests + row reduction)",
+        "bound": "alu",
+        "achieved": round(achieved_tflops, 3),
+        "peak": PEAK_FP32_VECTOR_TFLOPS,
+        "unit": "TFLOP/s",
+        "frac": round(achieved_tflops / PEAK_FP32_VECTOR_TFLOPS, 4),
+        "traffic": None,
+        "kernel_ms": round(map_ms, 4),
+        "flops_per_pair": FLOPS_PER_PAIR,
+        "pairs_per_launch": pairs,
+        "frac_of_unpacked_issue_ceiling": round(achieved_tflops / PEAK_UNPACKED_TOPS, 4),
+        "peak_unpacked_issue_Tops": PEAK_UNPACKED_TOPS,
+    }
+    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(traffic_file):
+        try:
+            t = json.load(open(traffic_file))
+            roofline["traffic"] = t.get(w.name, {}).get("map_tile_kernel_fused_bytes")
+        except Exception:
+            pass
+
+    extra = {
+        "rank_kernel_ms": round(rank_ms, 4),
+        "map_kernel_ms": round(map_ms, 4),
+        "frames_per_s": round(w.frames / (ms_per_step * 1e-3), 1),
+        "us_per_frame": round(ms_per_step * 1e3 / w.frames, 3),
+        "survivors": int(keep_gpu.sum()),
+    }
+
+    # ------------------------------------------------------------------ three-step (mask) pipeline on the same workload
+    if not args.no_extra:
+        n_pad = nms.nms_padded_n(w.n)
+        order = torch.empty((w.frames, w.n), dtype=torch.int32, device=dev)
+        sorted5 = torch.empty((w.frames, 5 * n_pad), dtype=torch.float32, device=dev)
+        mask = torch.empty((w.frames, nms.nms_mask_words(w.n)), dtype=torch.int64, device=dev)
+        keep3 = torch.empty((w.frames, w.n), dtype=torch.uint8, device=dev)
+        sws = torch.empty(max(nms.nms_sort_workspace_bytes(w.n, w.frames), 256), dtype=torch.uint8, device=dev)
+
+        def run_steps():
+            nms.nms_sort_batched(d["boxes"], d["scores"], None, w.n, w.frames, order, sorted5, sws)
+            nms.nms_overlap_mask_batched(sorted5, None, w.n, w.frames, w.theta, mask)
+            nms.nms_reduce_batched(mask, order, None, w.n, w.frames, keep3)
+
+        steps3 = max(5, K // 5)
+        ms3 = time_steps(run_steps, steps3, 2)
+        te = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        split = [0.0, 0.0, 0.0]
+        for _ in range(steps3):
+            te[0].record()
+            nms.nms_sort_batched(d["boxes"], d["scores"], None, w.n, w.frames, order, sorted5, sws)
+            te[1].record()
+            nms.nms_overlap_mask_batched(sorted5, None, w.n, w.frames, w.theta, mask)
+            te[2].record()
+            nms.nms_reduce_batched(mask, order, None, w.n, w.frames, keep3)
+            te[3].record()
+            torch.cuda.synchronize()
+            for i in range(3):
+                split[i] += te[i].elapsed_time(te[i + 1]) / steps3
+        tri_bytes = w.frames * (n_pad // 64) * (n_pad // 64 + 1) // 2 * 512
+        extra["three_step"] = {
+            "ms_per_step": round(ms3, 4),
+            "pair_tests_per_s": round(pairs / (ms3 * 1e-3), 1),
+            "sort_ms": round(split[0], 4), "overlap_mask_ms": round(split[1], 4), "reduce_ms": round(split[2], 4),
+            "mask_write_GBs": round(tri_bytes / (split[1] * 1e-3) / 1e9, 1),
+            "mask_read_GBs": round(tri_bytes / (split[2] * 1e-3) / 1e9, 1),
+            "frac_hbm_peak_reduce": round(tri_bytes / (split[2] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+            "keep_equals_fused": bool(torch.equal(keep3, d["keep"])),
+        }
+        del order, sorted5, mask, keep3
+
+        # -------------------------------------------------------------- the other configurations (latency view)
+        others = {}
+        for idx in (0, 1, 2, 3):
+            if idx == args.config:
+                continue
+            wo = make_config(idx)
+            do = upload(wo)
+            steps_o = 200 if wo.n <= 4096 else 50
+            ms_o = time_steps(lambda: run_fused(do), steps_o, 10)
+            # what one caller sees for one call: enqueue -> synchronise
+            lat = []
+            for _ in range(30):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                run_fused(do)
+                torch.cuda.synchronize()
+                lat.append((time.perf_counter() - t0) * 1e6)
+            lat.sort()
+            others[wo.name] = {
+                "us_per_frame": round(ms_o * 1e3 / wo.frames, 3),
+                "frames_per_s": round(wo.frames / (ms_o * 1e-3), 1),
+                "pair_tests_per_s": round(wo.pair_tests / (ms_o * 1e-3), 1),
+                "frac_fp32_vector_peak": round(FLOPS_PER_PAIR * wo.pair_tests / (ms_o * 1e-3) / 1e12 / PEAK_FP32_VECTOR_TFLOPS, 5),
+                "sync_call_us_median": round(lat[len(lat) // 2], 2),
+            }
+        extra["other_configs"] = others
+        extra["us_per_frame_at_1024_boxes"] = others.get("cfg0_1x1024_1080p", {}).get("us_per_frame")
+
+    # ------------------------------------------------------------------ CPU oracle on a bounded sample
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import numpy as np
+        from oracle import Oracle
+
+        orc = Oracle()
+        sample = min(w.frames, max(1, args.cpu_sample_frames))
+        t0 = time.perf_counter()
+        differing = 0
+        for f in range(sample):
+            k = orc.keep(w.boxes[f], w.scores[f], np.float32(w.theta))
+            differing += int((k != keep_gpu[f]).sum())
+        cpu_s = time.perf_counter() - t0
+        sample_pairs = sample * (w.n * (w.n - 1) // 2)
+        cpu_baseline = {
+            "value": round(sample_pairs / cpu_s, 1),
+            "unit": "pair-tests/s",
+            "cores": 1,
+            "kind": "oracle",
+            "sample": f"first {sample} of {w.frames} frames of {w.name}, single thread, {cpu_s:.2f} s",
+            "differing_keep_bits_vs_gpu": differing,
+        }
+
+    line = {
+        "metric": "pair-tests/s (batched)",
+        "value": round(value, 1),
+        "unit": "pair-tests/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "frames": w.frames, "boxes_per_frame": w.n, "threshold": w.theta,
+                   "path": "nms_run_batched (rank + fused pair-test/reduce kernels)"},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "extra": extra,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

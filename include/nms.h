@@ -1,0 +1,168 @@
+/*
+ * nms.h - C ABI of the MI355X (gfx950) data-parallel non-maximum suppression library.
+ *
+ * The library computes what the paper's two kernels compute ("Proposed Parallel
+ * Algorithm": Algorithm 1, the all-pairs map kernel, and Algorithm 2, the row-AND
+ * reduce kernel; "Algorithm Correctness": their postconditions):
+ *
+ *   box i survives  <=>  there is no box j that outranks i with overlap(i, j) >= theta
+ *
+ *   outranks:  score_j > score_i, or score_j == score_i and j < i        (total order;
+ *              the paper's guard is the strict score test of Algorithm 1, the index
+ *              tie-break is this library's addition)
+ *   overlap:   iw = max(0, (min(x2_i, x2_j) - max(x1_i, x1_j)) + 1)
+ *              ih = max(0, (min(y2_i, y2_j) - max(y1_i, y1_j)) + 1)
+ *              overlap(i, j) = (iw * ih) / (((x2_j - x1_j) + 1) * ((y2_j - y1_j) + 1))
+ *              i.e. intersection over the area of the OUTRANKING box, pixel-inclusive
+ *              "+1" (Algorithm 1; MapKernel postcondition).  float32, every operation
+ *              rounded to nearest-even on its own, in the order written.
+ *
+ * An eliminated box still eliminates others (ReduceKernel postcondition: V_i is the
+ * AND of the whole row of B).  This is not the sequential greedy procedure.
+ *
+ * Conventions for every entry point
+ *   - Pointers are DEVICE pointers unless a parameter says "host".  `stream` is a
+ *     hipStream_t passed as void* (NULL = the default stream).
+ *   - Calls only enqueue work on `stream` and return; they never allocate device
+ *     memory, never synchronise, and keep no state (except nms_init's pool, below).
+ *   - The caller owns every buffer.  Buffers must stay valid until the stream has
+ *     passed the call.  Inputs are never written.
+ *   - Return value: NMS_OK or a negative nms_status.  Arguments are validated on the
+ *     host before anything is launched; on error nothing has been enqueued.
+ *     n == 0 (or frames == 0) is NMS_OK and enqueues nothing.
+ *   - Preconditions that are NOT checked (results unspecified, memory-safe anyway):
+ *     coordinates finite with |x| <= 2^40, x2 >= x1, y2 >= y1, scores not NaN.
+ *   - Same inputs give the same bits, on any stream.
+ *   - A box table ("sorted5") for n boxes is 5 * nms_padded_n(n) floats:
+ *     first nms_padded_n(n) rows of (x1, y1, x2, y2) in rank order, then
+ *     nms_padded_n(n) areas in rank order.  Rows at or beyond n hold the box (0,0,0,0), area 1.
+ *   - An elimination mask for n boxes is nms_mask_words(n) 64-bit words laid out
+ *     mask[w * nms_padded_n(n) + r]: bit b of that word is 1 iff the box of rank
+ *     64*w + b eliminates the box of rank r.  Only words with w <= r / 64 are written
+ *     (the ranked lower triangle; a box is only ever eliminated by a better-ranked
+ *     one); bits at or above the diagonal and rows at or beyond n are written as 0.
+ *   - Batched calls process `frames` independent frames.  Frame f uses
+ *     boxes + f*n_max*4, scores + f*n_max, order + f*n_max, keep_out + f*n_max,
+ *     sorted5 + f*5*nms_padded_n(n_max), mask + f*nms_mask_words(n_max).
+ *     counts[f] (device, may be NULL = every frame holds n_max boxes) is clamped to
+ *     [0, n_max]; keep_out entries at or beyond counts[f] are written 0.
+ */
+#ifndef NMS_MI355X_H
+#define NMS_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define NMS_VERSION 100          /* major*10000 + minor*100 + patch */
+#define NMS_TILE 64              /* boxes per tile = wavefront width */
+#define NMS_MAX_N 65536          /* largest n (and n_max) accepted */
+#define NMS_MAX_FRAMES 65535     /* largest batch accepted */
+#define NMS_SORT_CHUNK 4096      /* boxes ranked by one workgroup in LDS */
+
+typedef enum {
+    NMS_OK = 0,
+    NMS_ERR_INVALID_ARG = -1,   /* null pointer, negative size, NaN threshold */
+    NMS_ERR_TOO_LARGE = -2,     /* n > NMS_MAX_N or frames > NMS_MAX_FRAMES */
+    NMS_ERR_WORKSPACE = -3,     /* workspace missing, misaligned or too small; nms_run without nms_init */
+    NMS_ERR_LAUNCH = -4         /* the HIP runtime refused a launch */
+} nms_status;
+
+/* Static, never freed.  Unknown codes give "unknown status". */
+const char *nms_status_string(int status);
+int nms_version(void);
+
+/* Host-only size helpers (pure functions; 0 on invalid arguments). */
+int nms_padded_n(int n);                                  /* n rounded up to a multiple of NMS_TILE */
+size_t nms_mask_words(int n);                             /* ceil(n/64) * nms_padded_n(n) */
+size_t nms_sort_workspace_bytes(int n_max, int frames);   /* scratch of nms_sort*: 0 when n_max <= NMS_SORT_CHUNK */
+size_t nms_workspace_bytes(int n_max, int frames);        /* scratch of nms_run_ws / nms_run_batched */
+
+/*
+ * Step 1 - rank.  The total order that Algorithm 1 evaluates per pair as
+ * "D[i].s < D[j].s", hoisted out of the pair loop so that only the ranked lower
+ * triangle of B has to be evaluated.
+ *   boxes   [n][4] (x1, y1, x2, y2)      in
+ *   scores  [n]                           in
+ *   order   [n] int32                     out: order[r] = input index of the box of rank r
+ *   sorted5 5 * nms_padded_n(n) floats    out: box table (see above); area as in
+ *                                              Algorithm 1's first assignment, per axis
+ *   workspace  >= nms_sort_workspace_bytes(n, 1) bytes, 256-byte aligned; may be NULL when that is 0
+ */
+int nms_sort(const float *boxes, const float *scores, int n,
+             int32_t *order, float *sorted5, void *workspace, size_t ws_bytes, void *stream);
+int nms_sort_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                     int32_t *order, float *sorted5, void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * Step 2 - map.  Algorithm 1 on the ranked lower triangle, bit-packed and with the
+ * polarity inverted (bit = 1 where the paper's B_ij is false).  One 64-bit word per
+ * box per 64-box tile of outranking boxes.
+ *   sorted5   box table from step 1      in
+ *   threshold theta, any float but NaN (no clamping: theta <= 0 eliminates everything
+ *             below the top rank, theta > 1 nothing)
+ *   mask      nms_mask_words(n) words     out (layout above)
+ */
+int nms_overlap_mask(const float *sorted5, int n, float threshold, uint64_t *mask, void *stream);
+int nms_overlap_mask_batched(const float *sorted5, const int32_t *counts, int n_max, int frames,
+                             float threshold, uint64_t *mask, void *stream);
+
+/*
+ * Step 3 - reduce.  Algorithm 2's result (V_i = AND of row i of B), i.e. rank r
+ * survives iff all its mask words are zero, scattered back to input order
+ * (Equation 2 applies V to D index by index).
+ *   keep_out [n] bytes, 1 = survives, 0 = eliminated
+ */
+int nms_reduce(const uint64_t *mask, const int32_t *order, int n, uint8_t *keep_out, void *stream);
+int nms_reduce_batched(const uint64_t *mask, const int32_t *order, const int32_t *counts, int n_max, int frames,
+                       uint8_t *keep_out, void *stream);
+
+/*
+ * The whole path in one call: rank, then the pair tests with the row-AND folded
+ * into them (no mask is written to memory; the result is the same keep vector).
+ *   workspace >= nms_workspace_bytes(n or n_max, 1 or frames) bytes, 256-byte aligned.
+ * Two calls that share a workspace must be ordered on one stream.
+ */
+int nms_run_ws(const float *boxes, const float *scores, int n, float threshold,
+               uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream);
+int nms_run_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                    float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * Profiling variant of nms_run_batched: identical work, and in addition records the
+ * caller's HIP events on `stream`.  `events` is a HOST array of three hipEvent_t
+ * (each may be NULL = skip): [0] before the rank step, [1] between rank and map,
+ * [2] after the map step.  Event-record failures are reported as NMS_ERR_LAUNCH.
+ */
+int nms_run_batched_profiled(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                             float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream,
+                             void *const *events);
+
+/*
+ * nms_run: the same with the workspace taken from a pool registered once.
+ * nms_init stores the pointer (caller-owned device memory, at least
+ * nms_workspace_bytes(n_max, frames_max) bytes); nms_shutdown forgets it and never
+ * frees it.  This pool is the library's only global state: one nms_run in flight at
+ * a time, all on one stream.  nms_run before nms_init, or with n > the pool's n_max,
+ * returns NMS_ERR_WORKSPACE.
+ */
+int nms_init(int n_max, int frames_max, void *workspace, size_t ws_bytes);
+int nms_shutdown(void);
+int nms_run(const float *boxes, const float *scores, int n, float threshold,
+            uint8_t *keep_out, void *stream);
+
+/*
+ * Host-only test hook: evaluates, on the CPU, the exact arithmetic the device pair
+ * test uses for "does the outranking box eliminate the victim" (all pointers HOST:
+ * victim[4], outranking[4]).  Returns 1/0, or a negative status for a NaN threshold.
+ * Lets the decision procedure be checked against plain division without a GPU.
+ */
+int nms_host_pair_test(const float *victim, const float *outranking, float threshold);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NMS_MI355X_H */

@@ -1,0 +1,235 @@
+"""ctypes binding of ``include/nms.h``: argument marshalling only.
+
+Tensor arguments are torch tensors on the GPU (device memory is torch's job);
+their ``data_ptr()`` and the current torch HIP stream are handed to the C ABI.
+Every function returns nothing and raises :class:`NmsError` on a non-zero status.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libnms_mi355x.so")
+
+NMS_OK = 0
+NMS_ERR_INVALID_ARG = -1
+NMS_ERR_TOO_LARGE = -2
+NMS_ERR_WORKSPACE = -3
+NMS_ERR_LAUNCH = -4
+
+EXPORTS = (
+    "nms_status_string", "nms_version", "nms_padded_n", "nms_mask_words",
+    "nms_sort_workspace_bytes", "nms_workspace_bytes",
+    "nms_sort", "nms_sort_batched", "nms_overlap_mask", "nms_overlap_mask_batched",
+    "nms_reduce", "nms_reduce_batched", "nms_run_ws", "nms_run_batched", "nms_run_batched_profiled",
+    "nms_init", "nms_shutdown", "nms_run", "nms_host_pair_test",
+)
+
+
+class NmsError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {nms_status_string(status)} ({status})")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2502_00535_amd.build` "
+            "(there is no CPU fallback)")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i32, f32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    L.nms_status_string.restype = ctypes.c_char_p
+    L.nms_status_string.argtypes = [i32]
+    L.nms_version.restype = i32
+    L.nms_version.argtypes = []
+    L.nms_padded_n.restype = i32
+    L.nms_padded_n.argtypes = [i32]
+    L.nms_mask_words.restype = sz
+    L.nms_mask_words.argtypes = [i32]
+    L.nms_sort_workspace_bytes.restype = sz
+    L.nms_sort_workspace_bytes.argtypes = [i32, i32]
+    L.nms_workspace_bytes.restype = sz
+    L.nms_workspace_bytes.argtypes = [i32, i32]
+    L.nms_sort.restype = i32
+    L.nms_sort.argtypes = [vp, vp, i32, vp, vp, vp, sz, vp]
+    L.nms_sort_batched.restype = i32
+    L.nms_sort_batched.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, sz, vp]
+    L.nms_overlap_mask.restype = i32
+    L.nms_overlap_mask.argtypes = [vp, i32, f32, vp, vp]
+    L.nms_overlap_mask_batched.restype = i32
+    L.nms_overlap_mask_batched.argtypes = [vp, vp, i32, i32, f32, vp, vp]
+    L.nms_reduce.restype = i32
+    L.nms_reduce.argtypes = [vp, vp, i32, vp, vp]
+    L.nms_reduce_batched.restype = i32
+    L.nms_reduce_batched.argtypes = [vp, vp, vp, i32, i32, vp, vp]
+    L.nms_run_ws.restype = i32
+    L.nms_run_ws.argtypes = [vp, vp, i32, f32, vp, vp, sz, vp]
+    L.nms_run_batched.restype = i32
+    L.nms_run_batched.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp, sz, vp]
+    L.nms_run_batched_profiled.restype = i32
+    L.nms_run_batched_profiled.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp, sz, vp, ctypes.POINTER(vp)]
+    L.nms_init.restype = i32
+    L.nms_init.argtypes = [i32, i32, vp, sz]
+    L.nms_shutdown.restype = i32
+    L.nms_shutdown.argtypes = []
+    L.nms_run.restype = i32
+    L.nms_run.argtypes = [vp, vp, i32, f32, vp, vp]
+    L.nms_host_pair_test.restype = i32
+    L.nms_host_pair_test.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float), f32]
+    return L
+
+
+lib = _load()
+
+
+# ------------------------------------------------------------------ marshalling helpers
+
+def _ptr(t, dtype_name: str | None, what: str):
+    """Device pointer of a contiguous CUDA/HIP tensor (None -> NULL)."""
+    if t is None:
+        return None
+    import torch
+
+    if not isinstance(t, torch.Tensor):
+        raise TypeError(f"{what}: expected a torch tensor")
+    if not t.is_cuda:
+        raise ValueError(f"{what}: tensor must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError(f"{what}: tensor must be contiguous")
+    if dtype_name is not None and str(t.dtype) != f"torch.{dtype_name}":
+        raise TypeError(f"{what}: expected dtype {dtype_name}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _ws(t):
+    if t is None:
+        return None, 0
+    return _ptr(t, None, "workspace"), t.numel() * t.element_size()
+
+
+def _stream(stream):
+    import torch
+
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != NMS_OK:
+        raise NmsError(status, where)
+
+
+# ------------------------------------------------------------------ host-only helpers
+
+def nms_status_string(status: int) -> str:
+    return lib.nms_status_string(int(status)).decode()
+
+
+def nms_version() -> int:
+    return int(lib.nms_version())
+
+
+def nms_padded_n(n: int) -> int:
+    return int(lib.nms_padded_n(int(n)))
+
+
+def nms_mask_words(n: int) -> int:
+    return int(lib.nms_mask_words(int(n)))
+
+
+def nms_sort_workspace_bytes(n_max: int, frames: int) -> int:
+    return int(lib.nms_sort_workspace_bytes(int(n_max), int(frames)))
+
+
+def nms_workspace_bytes(n_max: int, frames: int) -> int:
+    return int(lib.nms_workspace_bytes(int(n_max), int(frames)))
+
+
+def nms_host_pair_test(victim, outranking, threshold: float) -> int:
+    v = (ctypes.c_float * 4)(*[float(x) for x in victim])
+    c = (ctypes.c_float * 4)(*[float(x) for x in outranking])
+    return int(lib.nms_host_pair_test(v, c, float(threshold)))
+
+
+# ------------------------------------------------------------------ device entry points
+
+def nms_sort(boxes, scores, n, order, sorted5, workspace=None, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib.nms_sort(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"), int(n),
+                        _ptr(order, "int32", "order"), _ptr(sorted5, "float32", "sorted5"),
+                        w, wb, _stream(stream)), "nms_sort")
+
+
+def nms_sort_batched(boxes, scores, counts, n_max, frames, order, sorted5, workspace=None, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib.nms_sort_batched(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
+                                _ptr(counts, "int32", "counts"), int(n_max), int(frames),
+                                _ptr(order, "int32", "order"), _ptr(sorted5, "float32", "sorted5"),
+                                w, wb, _stream(stream)), "nms_sort_batched")
+
+
+def nms_overlap_mask(sorted5, n, threshold, mask, stream=None):
+    _check(lib.nms_overlap_mask(_ptr(sorted5, "float32", "sorted5"), int(n), float(threshold),
+                                _ptr(mask, "int64", "mask"), _stream(stream)), "nms_overlap_mask")
+
+
+def nms_overlap_mask_batched(sorted5, counts, n_max, frames, threshold, mask, stream=None):
+    _check(lib.nms_overlap_mask_batched(_ptr(sorted5, "float32", "sorted5"), _ptr(counts, "int32", "counts"),
+                                        int(n_max), int(frames), float(threshold),
+                                        _ptr(mask, "int64", "mask"), _stream(stream)), "nms_overlap_mask_batched")
+
+
+def nms_reduce(mask, order, n, keep_out, stream=None):
+    _check(lib.nms_reduce(_ptr(mask, "int64", "mask"), _ptr(order, "int32", "order"), int(n),
+                          _ptr(keep_out, "uint8", "keep_out"), _stream(stream)), "nms_reduce")
+
+
+def nms_reduce_batched(mask, order, counts, n_max, frames, keep_out, stream=None):
+    _check(lib.nms_reduce_batched(_ptr(mask, "int64", "mask"), _ptr(order, "int32", "order"),
+                                  _ptr(counts, "int32", "counts"), int(n_max), int(frames),
+                                  _ptr(keep_out, "uint8", "keep_out"), _stream(stream)), "nms_reduce_batched")
+
+
+def nms_run_ws(boxes, scores, n, threshold, keep_out, workspace, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib.nms_run_ws(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"), int(n),
+                          float(threshold), _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream)),
+           "nms_run_ws")
+
+
+def nms_run_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib.nms_run_batched(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
+                               _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
+                               _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream)), "nms_run_batched")
+
+
+def nms_run_batched_profiled(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, events, stream=None):
+    """events: three raw hipEvent_t handles (ints) or None entries."""
+    w, wb = _ws(workspace)
+    ev = (ctypes.c_void_p * 3)(*[ctypes.c_void_p(e) if e else None for e in events])
+    _check(lib.nms_run_batched_profiled(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
+                                        _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
+                                        _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream), ev),
+           "nms_run_batched_profiled")
+
+
+def nms_init(n_max, frames_max, workspace):
+    w, wb = _ws(workspace)
+    _check(lib.nms_init(int(n_max), int(frames_max), w, wb), "nms_init")
+
+
+def nms_shutdown():
+    _check(lib.nms_shutdown(), "nms_shutdown")
+
+
+def nms_run(boxes, scores, n, threshold, keep_out, stream=None):
+    _check(lib.nms_run(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"), int(n),
+                       float(threshold), _ptr(keep_out, "uint8", "keep_out"), _stream(stream)), "nms_run")

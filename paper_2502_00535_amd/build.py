@@ -1,0 +1,51 @@
+"""Compile the HIP library in-tree for gfx950 (hipcc cross-compiles without a GPU)."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+SOURCES = [os.path.join(_HERE, "csrc", "nms_kernels.hip")]
+HEADERS = [os.path.join(_HERE, "csrc", "nms_pair.h"),
+           os.path.join(os.path.dirname(_HERE), "include", "nms.h")]
+LIBRARY = os.path.join(_HERE, "libnms_mi355x.so")
+
+# -ffp-contract=off: the pair test must round every operation on its own (the one
+#   fused multiply-add it uses is written explicitly).
+# -fno-honor-nans (device only): inputs are NaN-free by contract; without it every
+#   min/max operand fetched from memory is first re-quieted with an extra VALU
+#   instruction.  Host code keeps full NaN semantics for argument checking.
+# -packed-fp32-ops off: no packed float32 VALU instructions are generated.
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "-ffp-contract=off",
+    "-Xarch_device", "-fno-honor-nans",
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wno-unused-command-line-argument",
+]
+
+
+def is_stale() -> bool:
+    if not os.path.exists(LIBRARY):
+        return True
+    built = os.path.getmtime(LIBRARY)
+    return any(os.path.getmtime(p) > built for p in SOURCES + HEADERS)
+
+
+def build_library(verbose: bool = False) -> str:
+    """Always compiles; returns the path of the shared object."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = LIBRARY + f".tmp{os.getpid()}"
+    cmd = [hipcc, *HIPCC_FLAGS, *SOURCES, "-o", tmp]
+    proc = subprocess.run(cmd, capture_output=True, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + proc.stdout + proc.stderr)
+    if verbose:
+        # the host pass does not know the device-only target feature; that warning is expected
+        print("\n".join(l for l in proc.stderr.splitlines() if "not a recognized feature" not in l))
+    os.replace(tmp, LIBRARY)
+    return LIBRARY
+
+
+if __name__ == "__main__":
+    print(build_library(verbose=True))

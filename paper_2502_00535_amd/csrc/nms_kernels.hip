@@ -1,0 +1,563 @@
+// HIP kernels (gfx950, wave64) and the C ABI of the data-parallel NMS library.
+//
+// Steps (names follow the paper: D = detections, B = boolean matrix, V = survivors):
+//   rank     total order on scores (Algorithm 1's guard "D[i].s < D[j].s", hoisted)
+//   map      Algorithm 1 on the ranked lower triangle, one wavefront per 64x64 tile
+//   reduce   Algorithm 2's row AND (here: row OR of elimination bits == 0)
+//   fused    map with the row reduction folded in; no mask reaches memory
+//
+// Wave layout of the map step: lane = outranking box c of the tile's column block
+// (its box, area and -h*area live in VGPRs for the whole tile); the victim row r is
+// wave-uniform and is fetched with scalar loads, so each victim costs 4 SGPRs and the
+// 12 VALU instructions of the pair test.  The compare's lane mask IS the 64-bit
+// elimination word of (row r, column block): no cross-lane work is needed to form it.
+#include <hip/hip_runtime.h>
+
+#include <string.h>
+
+#include "../../include/nms.h"
+#include "nms_pair.h"
+
+namespace {
+
+constexpr int kTile = NMS_TILE;
+constexpr int kChunk = NMS_SORT_CHUNK;
+constexpr unsigned long long kSentinel = ~0ull;
+
+__device__ __forceinline__ int frame_count(const int32_t *counts, int f, int n_max)
+{
+    if (counts == nullptr) return n_max;
+    int c = counts[f];
+    return c < 0 ? 0 : (c > n_max ? n_max : c);
+}
+
+// ----------------------------------------------------------------------------- rank
+
+// Unique ascending 64-bit key: better score first, then lower index.
+__device__ __forceinline__ unsigned long long rank_key(float score, unsigned idx)
+{
+    unsigned u = __float_as_uint(score);
+    if (u == 0x80000000u) u = 0u;  // -0.0 ties with +0.0
+    unsigned asc = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    return ((unsigned long long)(~asc) << 32) | idx;
+}
+
+__device__ __forceinline__ void emit_ranked_box(const float *boxes_f, int idx, int r, int n_pad,
+                                               int32_t *order_f, float *sorted_f)
+{
+    const float4 b = reinterpret_cast<const float4 *>(boxes_f)[idx];
+    order_f[r] = idx;
+    reinterpret_cast<float4 *>(sorted_f)[r] = b;
+    sorted_f[4 * (size_t)n_pad + r] = nms_box_area(b.x, b.y, b.z, b.w);
+}
+
+__device__ __forceinline__ void emit_padding_row(int r, int n_pad, float *sorted_f)
+{
+    reinterpret_cast<float4 *>(sorted_f)[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+    sorted_f[4 * (size_t)n_pad + r] = 1.0f;  // the one-pixel box (0,0,0,0): never divides by zero
+}
+
+// One workgroup ranks one chunk of up to kChunk boxes of one frame with a bitonic
+// network in LDS.  With a single chunk it also writes order / sorted5 (and, for the
+// fused path, presets keep_out); with several chunks it leaves the chunk's sorted
+// keys in `keys_ws` for the merge kernel.
+__global__ void __launch_bounds__(1024)
+rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ scores,
+                  const int32_t *__restrict__ counts, int n_max, int n_pad, int n_chunks,
+                  int32_t *__restrict__ order, float *__restrict__ sorted5,
+                  unsigned long long *__restrict__ keys_ws, uint8_t *__restrict__ keep_preset)
+{
+    __shared__ unsigned long long keys[kChunk];
+    const int f = blockIdx.y;
+    const int chunk = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int nth = blockDim.x;
+    const int n_f = frame_count(counts, f, n_max);
+    const int base = chunk * kChunk;
+    int cnt = n_f - base;
+    cnt = cnt < 0 ? 0 : (cnt > kChunk ? kChunk : cnt);
+    int P = 64;
+    while (P < cnt) P <<= 1;
+
+    const float *scores_f = scores + (size_t)f * n_max;
+    for (int i = tid; i < P; i += nth)
+        keys[i] = (i < cnt) ? rank_key(scores_f[base + i], (unsigned)(base + i)) : kSentinel;
+    __syncthreads();
+
+    for (int k = 2; k <= P; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = tid; t < (P >> 1); t += nth) {
+                const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+                const int l = i | j;
+                const bool up = (i & k) == 0;
+                const unsigned long long a = keys[i];
+                const unsigned long long b = keys[l];
+                if ((a > b) == up) {
+                    keys[i] = b;
+                    keys[l] = a;
+                }
+            }
+            __syncthreads();
+        }
+    }
+
+    const float *boxes_f = boxes + (size_t)f * n_max * 4;
+    int32_t *order_f = order + (size_t)f * n_max;
+    float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
+    if (n_chunks == 1) {
+        for (int r = tid; r < n_pad; r += nth) {
+            if (r < n_f)
+                emit_ranked_box(boxes_f, (int)(unsigned)keys[r], r, n_pad, order_f, sorted_f);
+            else
+                emit_padding_row(r, n_pad, sorted_f);
+        }
+    } else {
+        unsigned long long *kw = keys_ws + (size_t)f * n_pad + base;
+        for (int i = tid; i < cnt; i += nth) kw[i] = keys[i];
+    }
+    if (keep_preset != nullptr) {
+        // fused path: every real box starts as a survivor, slots beyond the count are 0
+        uint8_t *kp = keep_preset + (size_t)f * n_max;
+        const int hi = (base + kChunk < n_max) ? base + kChunk : n_max;
+        for (int i = base + tid; i < hi; i += nth) kp[i] = (i < n_f) ? 1 : 0;
+    }
+}
+
+// Several chunks: the rank of a key is its position inside its own chunk plus the
+// number of smaller keys in every other chunk (keys are unique, so ranks are too).
+__global__ void __launch_bounds__(256)
+rank_merge_kernel(const float *__restrict__ boxes, const int32_t *__restrict__ counts, int n_max, int n_pad,
+                  int n_chunks, const unsigned long long *__restrict__ keys_ws,
+                  int32_t *__restrict__ order, float *__restrict__ sorted5)
+{
+    const int f = blockIdx.y;
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n_pad) return;
+    const int n_f = frame_count(counts, f, n_max);
+    float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
+    if (e >= n_f) {
+        emit_padding_row(e, n_pad, sorted_f);
+        return;
+    }
+    const unsigned long long *kw = keys_ws + (size_t)f * n_pad;
+    const unsigned long long key = kw[e];
+    const int own = e / kChunk;
+    int rank = e - own * kChunk;
+    for (int c = 0; c < n_chunks; ++c) {
+        if (c == own) continue;
+        const int base = c * kChunk;
+        int cnt = n_f - base;
+        cnt = cnt < 0 ? 0 : (cnt > kChunk ? kChunk : cnt);
+        int lo = 0, hi = cnt;  // first position whose key is not smaller
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (kw[base + mid] < key) lo = mid + 1; else hi = mid;
+        }
+        rank += lo;
+    }
+    emit_ranked_box(boxes + (size_t)f * n_max * 4, (int)(unsigned)key, rank, n_pad,
+                    order + (size_t)f * n_max, sorted_f);
+}
+
+// ----------------------------------------------------------------------------- map
+
+// Linear tile index -> (tile row tr, tile column tc <= tr) of the lower triangle.
+__device__ __forceinline__ void triangle_tile(int g, int &tr, int &tc)
+{
+    int r = (int)((__fsqrt_rn(8.0f * (float)g + 1.0f) - 1.0f) * 0.5f);
+    while (r * (r + 1) / 2 > g) --r;
+    while ((r + 1) * (r + 2) / 2 <= g) ++r;
+    tr = r;
+    tc = g - r * (r + 1) / 2;
+}
+
+constexpr int kMapWaves = 4;  // wavefronts (tiles) per workgroup
+
+// State a wavefront carries through the 64 rows of a tile.
+struct TileState {
+    unsigned lane_hit = 0;           // fused form: lane r = 1 when row r has an eliminator in this tile
+    unsigned w_lo = 0, w_hi = 0;     // mask form: lane r collects the 64-bit word of row r
+};
+
+// The 64 rows of a tile: victim r (wave-uniform, fetched with scalar loads) against
+// the 64 outranking boxes held one per lane.  The ballot of the compare is the
+// elimination word of row r.  Rows go in 4 groups of 16 in a real loop, so that at
+// most 64 victim SGPRs are live at a time.
+template <bool FAST, bool WRITE_MASK, bool DIAG>
+__device__ __forceinline__ void tile_sweep(const float4 *__restrict__ vb, const float4 cb, float c_area, float c_ng,
+                                           const NmsThetaConst &th, int lane, TileState &st)
+{
+#pragma unroll 1
+    for (int grp = 0; grp < kTile / 16; ++grp) {
+        const float4 *__restrict__ vg = vb + 16 * grp;
+        unsigned grp_bits = 0;  // wave-uniform: bit k = row 16*grp+k has an eliminator
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int r = 16 * grp + k;
+            const float4 v = vg[k];
+            bool hit;
+            if (FAST)
+                hit = nms_eliminates_fast(v.x, v.y, v.z, v.w, cb.x, cb.y, cb.z, cb.w, c_area, c_ng, th.neg_theta);
+            else
+                hit = nms_eliminates_exact(v.x, v.y, v.z, v.w, cb.x, cb.y, cb.z, cb.w, c_area, th.theta);
+            unsigned long long word = __ballot(hit);
+            if (DIAG) word &= (1ull << r) - 1ull;  // only better-ranked boxes eliminate
+            if (WRITE_MASK) {
+                if (word != 0) {  // wave-uniform branch; most rows of most tiles have no eliminator
+                    const bool mine = (lane == r);  // lane r collects the word of row r
+                    st.w_lo = mine ? (unsigned)word : st.w_lo;
+                    st.w_hi = mine ? (unsigned)(word >> 32) : st.w_hi;
+                }
+            } else {
+                grp_bits |= (word != 0 ? 1u : 0u) << k;
+            }
+        }
+        if (!WRITE_MASK)
+            st.lane_hit |= ((lane >> 4) == grp) ? ((grp_bits >> (lane & 15)) & 1u) : 0u;
+    }
+}
+
+// One wavefront = one 64x64 tile.  WRITE_MASK: store the tile's 64 words (mask
+// layout of nms.h).  Otherwise: fold the row reduction in and clear keep_out of every
+// victim that some lane eliminates (keep_out was preset to 1 by the rank step; all
+// writers store the same 0, so concurrent tiles need no atomics).
+template <bool FAST, bool WRITE_MASK>
+__global__ void __launch_bounds__(kMapWaves * 64)
+map_tile_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ counts, int n_max, int n_pad,
+                int tiles, NmsThetaConst th, unsigned long long *__restrict__ mask,
+                const int32_t *__restrict__ order, uint8_t *__restrict__ keep_out)
+{
+    const int lane = threadIdx.x & 63;
+    const int g = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * kMapWaves + (threadIdx.x >> 6)));
+    if (g >= tiles) return;
+    const int f = blockIdx.y;
+    const int n_f = frame_count(counts, f, n_max);
+    int tr, tc;
+    triangle_tile(g, tr, tc);
+    if (tr * kTile >= n_f) return;
+
+    const float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
+    const float4 *box4 = reinterpret_cast<const float4 *>(sorted_f);
+    const float *area = sorted_f + 4 * (size_t)n_pad;
+
+    // outranking box of this lane
+    const float4 cb = box4[tc * kTile + lane];
+    const float c_area = area[tc * kTile + lane];
+    const float c_ng = th.neg_h * c_area;
+    // victims of this tile: wave-uniform addresses -> scalar loads
+    const float4 *vb = box4 + tr * kTile;
+
+    TileState st;
+    if (tr == tc)
+        tile_sweep<FAST, WRITE_MASK, true>(vb, cb, c_area, c_ng, th, lane, st);
+    else
+        tile_sweep<FAST, WRITE_MASK, false>(vb, cb, c_area, c_ng, th, lane, st);
+
+    const int row = tr * kTile + lane;
+    if (WRITE_MASK) {
+        unsigned long long out = ((unsigned long long)st.w_hi << 32) | st.w_lo;
+        if (row >= n_f) out = 0;  // padding rows of the last tile
+        mask[(size_t)f * ((size_t)(n_pad / kTile) * n_pad) + (size_t)tc * n_pad + row] = out;
+    } else {
+        if (st.lane_hit && row < n_f)
+            keep_out[(size_t)f * n_max + order[(size_t)f * n_max + row]] = 0;
+    }
+}
+
+// ----------------------------------------------------------------------------- reduce
+
+// One workgroup per 64 rows: lane = row, the four wavefronts split the row's words,
+// reads are coalesced across rows for a fixed word index.
+__global__ void __launch_bounds__(256)
+reduce_rows_kernel(const unsigned long long *__restrict__ mask, const int32_t *__restrict__ order,
+                   const int32_t *__restrict__ counts, int n_max, int n_pad, uint8_t *__restrict__ keep_out)
+{
+    __shared__ unsigned long long part[4][kTile];
+    const int f = blockIdx.y;
+    const int tr = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wv = threadIdx.x >> 6;
+    const int n_f = frame_count(counts, f, n_max);
+    const int row = tr * kTile + lane;
+    unsigned long long acc = 0;
+    if (tr * kTile < n_f) {
+        const unsigned long long *m = mask + (size_t)f * ((size_t)(n_pad / kTile) * n_pad);
+        for (int w = wv; w <= tr; w += 4) acc |= m[(size_t)w * n_pad + row];
+    }
+    part[wv][lane] = acc;
+    __syncthreads();
+    if (wv == 0) {
+        const unsigned long long all = part[0][lane] | part[1][lane] | part[2][lane] | part[3][lane];
+        uint8_t *keep_f = keep_out + (size_t)f * n_max;
+        if (row < n_f)
+            keep_f[order[(size_t)f * n_max + row]] = (all == 0) ? 1 : 0;
+        else if (row < n_max)
+            keep_f[row] = 0;  // input slots beyond the frame's count
+    }
+}
+
+// ----------------------------------------------------------------------------- host side
+
+struct Pool {
+    void *ws = nullptr;
+    size_t bytes = 0;
+    int n_max = 0;
+    int frames_max = 0;
+};
+Pool g_pool;
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+inline bool sizes_ok(int n_max, int frames, int *status)
+{
+    if (n_max < 0 || frames < 0) { *status = NMS_ERR_INVALID_ARG; return false; }
+    if (n_max > NMS_MAX_N || frames > NMS_MAX_FRAMES) { *status = NMS_ERR_TOO_LARGE; return false; }
+    return true;
+}
+
+inline bool is_nan(float v)
+{
+    uint32_t b;
+    memcpy(&b, &v, sizeof b);
+    return (b & 0x7fffffffu) > 0x7f800000u;
+}
+
+inline int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? NMS_OK : NMS_ERR_LAUNCH;
+}
+
+int rank_launch(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                int32_t *order, float *sorted5, void *workspace, uint8_t *keep_preset, hipStream_t stream)
+{
+    const int n_pad = nms_padded_n(n_max);
+    const int n_chunks = (n_max + kChunk - 1) / kChunk;
+    int threads = 64;
+    const int widest = n_max < kChunk ? n_max : kChunk;
+    while (threads < 1024 && threads * 2 < widest) threads <<= 1;  // half the padded chunk size
+    auto *keys_ws = static_cast<unsigned long long *>(workspace);
+    rank_chunk_kernel<<<dim3(n_chunks, frames), dim3(threads), 0, stream>>>(
+        boxes, scores, counts, n_max, n_pad, n_chunks, order, sorted5, keys_ws, keep_preset);
+    int st = launch_status();
+    if (st != NMS_OK || n_chunks == 1) return st;
+    rank_merge_kernel<<<dim3((n_pad + 255) / 256, frames), dim3(256), 0, stream>>>(
+        boxes, counts, n_max, n_pad, n_chunks, keys_ws, order, sorted5);
+    return launch_status();
+}
+
+template <bool WRITE_MASK>
+int map_launch(const float *sorted5, const int32_t *counts, int n_max, int frames, float threshold,
+               unsigned long long *mask, const int32_t *order, uint8_t *keep_out, hipStream_t stream)
+{
+    const int n_pad = nms_padded_n(n_max);
+    const int T = n_pad / kTile;
+    const int tiles = T * (T + 1) / 2;
+    const NmsThetaConst th = nms_make_theta_const(threshold);
+    const dim3 grid((tiles + kMapWaves - 1) / kMapWaves, frames);
+    const dim3 block(kMapWaves * 64);
+    if (th.fast)
+        map_tile_kernel<true, WRITE_MASK><<<grid, block, 0, stream>>>(sorted5, counts, n_max, n_pad, tiles, th, mask, order, keep_out);
+    else
+        map_tile_kernel<false, WRITE_MASK><<<grid, block, 0, stream>>>(sorted5, counts, n_max, n_pad, tiles, th, mask, order, keep_out);
+    return launch_status();
+}
+
+}  // namespace
+
+// ----------------------------------------------------------------------------- C ABI
+
+extern "C" {
+
+const char *nms_status_string(int status)
+{
+    switch (status) {
+    case NMS_OK: return "ok";
+    case NMS_ERR_INVALID_ARG: return "invalid argument";
+    case NMS_ERR_TOO_LARGE: return "size beyond NMS_MAX_N or NMS_MAX_FRAMES";
+    case NMS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case NMS_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown status";
+    }
+}
+
+int nms_version(void) { return NMS_VERSION; }
+
+int nms_padded_n(int n)
+{
+    if (n < 0 || n > NMS_MAX_N) return 0;
+    return (n + kTile - 1) / kTile * kTile;
+}
+
+size_t nms_mask_words(int n)
+{
+    if (n < 0 || n > NMS_MAX_N) return 0;
+    const size_t n_pad = (size_t)nms_padded_n(n);
+    return (n_pad / kTile) * n_pad;
+}
+
+size_t nms_sort_workspace_bytes(int n_max, int frames)
+{
+    int st;
+    if (!sizes_ok(n_max, frames, &st)) return 0;
+    if (n_max <= kChunk) return 0;
+    return align256((size_t)frames * nms_padded_n(n_max) * sizeof(unsigned long long));
+}
+
+size_t nms_workspace_bytes(int n_max, int frames)
+{
+    int st;
+    if (!sizes_ok(n_max, frames, &st)) return 0;
+    const size_t n_pad = (size_t)nms_padded_n(n_max);
+    return align256((size_t)frames * n_max * sizeof(int32_t))      // order
+         + align256((size_t)frames * 5 * n_pad * sizeof(float))    // sorted5
+         + nms_sort_workspace_bytes(n_max, frames);                // chunk keys
+}
+
+int nms_sort_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                     int32_t *order, float *sorted5, void *workspace, size_t ws_bytes, void *stream)
+{
+    int st;
+    if (!sizes_ok(n_max, frames, &st)) return st;
+    if (n_max == 0 || frames == 0) return NMS_OK;
+    if (!boxes || !scores || !order || !sorted5) return NMS_ERR_INVALID_ARG;
+    const size_t need = nms_sort_workspace_bytes(n_max, frames);
+    if (need != 0 && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))) return NMS_ERR_WORKSPACE;
+    return rank_launch(boxes, scores, counts, n_max, frames, order, sorted5, workspace, nullptr,
+                       static_cast<hipStream_t>(stream));
+}
+
+int nms_sort(const float *boxes, const float *scores, int n, int32_t *order, float *sorted5,
+             void *workspace, size_t ws_bytes, void *stream)
+{
+    return nms_sort_batched(boxes, scores, nullptr, n, 1, order, sorted5, workspace, ws_bytes, stream);
+}
+
+int nms_overlap_mask_batched(const float *sorted5, const int32_t *counts, int n_max, int frames,
+                             float threshold, uint64_t *mask, void *stream)
+{
+    int st;
+    if (!sizes_ok(n_max, frames, &st)) return st;
+    if (is_nan(threshold)) return NMS_ERR_INVALID_ARG;
+    if (n_max == 0 || frames == 0) return NMS_OK;
+    if (!sorted5 || !mask) return NMS_ERR_INVALID_ARG;
+    return map_launch<true>(sorted5, counts, n_max, frames, threshold,
+                            reinterpret_cast<unsigned long long *>(mask), nullptr, nullptr,
+                            static_cast<hipStream_t>(stream));
+}
+
+int nms_overlap_mask(const float *sorted5, int n, float threshold, uint64_t *mask, void *stream)
+{
+    return nms_overlap_mask_batched(sorted5, nullptr, n, 1, threshold, mask, stream);
+}
+
+int nms_reduce_batched(const uint64_t *mask, const int32_t *order, const int32_t *counts, int n_max, int frames,
+                       uint8_t *keep_out, void *stream)
+{
+    int st;
+    if (!sizes_ok(n_max, frames, &st)) return st;
+    if (n_max == 0 || frames == 0) return NMS_OK;
+    if (!mask || !order || !keep_out) return NMS_ERR_INVALID_ARG;
+    const int n_pad = nms_padded_n(n_max);
+    reduce_rows_kernel<<<dim3(n_pad / kTile, frames), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
+        reinterpret_cast<const unsigned long long *>(mask), order, counts, n_max, n_pad, keep_out);
+    return launch_status();
+}
+
+int nms_reduce(const uint64_t *mask, const int32_t *order, int n, uint8_t *keep_out, void *stream)
+{
+    return nms_reduce_batched(mask, order, nullptr, n, 1, keep_out, stream);
+}
+
+int nms_run_batched_profiled(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                             float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream,
+                             void *const *events)
+{
+    int st;
+    if (!sizes_ok(n_max, frames, &st)) return st;
+    if (is_nan(threshold)) return NMS_ERR_INVALID_ARG;
+    if (n_max == 0 || frames == 0) return NMS_OK;
+    if (!boxes || !scores || !keep_out) return NMS_ERR_INVALID_ARG;
+    const size_t need = nms_workspace_bytes(n_max, frames);
+    if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)) return NMS_ERR_WORKSPACE;
+
+    const size_t n_pad = (size_t)nms_padded_n(n_max);
+    char *p = static_cast<char *>(workspace);
+    int32_t *order = reinterpret_cast<int32_t *>(p);
+    p += align256((size_t)frames * n_max * sizeof(int32_t));
+    float *sorted5 = reinterpret_cast<float *>(p);
+    p += align256((size_t)frames * 5 * n_pad * sizeof(float));
+    void *keys_ws = p;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    auto mark = [&](int i) {
+        if (events && events[i] && hipEventRecord(static_cast<hipEvent_t>(events[i]), s) != hipSuccess) return false;
+        return true;
+    };
+    if (!mark(0)) return NMS_ERR_LAUNCH;
+    st = rank_launch(boxes, scores, counts, n_max, frames, order, sorted5, keys_ws, keep_out, s);
+    if (st != NMS_OK) return st;
+    if (!mark(1)) return NMS_ERR_LAUNCH;
+    st = map_launch<false>(sorted5, counts, n_max, frames, threshold, nullptr, order, keep_out, s);
+    if (st != NMS_OK) return st;
+    return mark(2) ? NMS_OK : NMS_ERR_LAUNCH;
+}
+
+int nms_run_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                    float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream)
+{
+    return nms_run_batched_profiled(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, ws_bytes,
+                                    stream, nullptr);
+}
+
+int nms_run_ws(const float *boxes, const float *scores, int n, float threshold,
+               uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream)
+{
+    return nms_run_batched(boxes, scores, nullptr, n, 1, threshold, keep_out, workspace, ws_bytes, stream);
+}
+
+int nms_init(int n_max, int frames_max, void *workspace, size_t ws_bytes)
+{
+    int st;
+    if (!sizes_ok(n_max, frames_max, &st)) return st;
+    if (n_max == 0 || frames_max == 0) return NMS_ERR_INVALID_ARG;
+    if (!workspace || ((uintptr_t)workspace & 255) || ws_bytes < nms_workspace_bytes(n_max, frames_max))
+        return NMS_ERR_WORKSPACE;
+    g_pool.ws = workspace;
+    g_pool.bytes = ws_bytes;
+    g_pool.n_max = n_max;
+    g_pool.frames_max = frames_max;
+    return NMS_OK;
+}
+
+int nms_shutdown(void)
+{
+    g_pool = Pool();
+    return NMS_OK;
+}
+
+int nms_run(const float *boxes, const float *scores, int n, float threshold, uint8_t *keep_out, void *stream)
+{
+    int st;
+    if (!sizes_ok(n, 1, &st)) return st;
+    if (is_nan(threshold)) return NMS_ERR_INVALID_ARG;
+    if (n == 0) return NMS_OK;
+    if (!g_pool.ws || n > g_pool.n_max) return NMS_ERR_WORKSPACE;
+    return nms_run_batched(boxes, scores, nullptr, n, 1, threshold, keep_out, g_pool.ws, g_pool.bytes, stream);
+}
+
+int nms_host_pair_test(const float *victim, const float *outranking, float threshold)
+{
+    if (!victim || !outranking || is_nan(threshold)) return NMS_ERR_INVALID_ARG;
+    const NmsThetaConst th = nms_make_theta_const(threshold);
+    const float a = nms_box_area(outranking[0], outranking[1], outranking[2], outranking[3]);
+    bool hit;
+    if (th.fast)
+        hit = nms_eliminates_fast(victim[0], victim[1], victim[2], victim[3],
+                                  outranking[0], outranking[1], outranking[2], outranking[3], a, th.neg_h * a, th.neg_theta);
+    else
+        hit = nms_eliminates_exact(victim[0], victim[1], victim[2], victim[3],
+                                   outranking[0], outranking[1], outranking[2], outranking[3], a, th.theta);
+    return hit ? 1 : 0;
+}
+
+}  // extern "C"

@@ -1,0 +1,129 @@
+"""The C-ABI library without a GPU: it loads, exports every symbol that
+include/nms.h declares, its host-only helpers are right, and every argument
+error is reported before anything is launched.  No compute call is made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def nms():
+    from paper_2502_00535_amd import build as nms_build
+
+    if nms_build.is_stale():
+        nms_build.build_library()
+    import paper_2502_00535_amd.binding as binding
+
+    return binding
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "nms.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(nms_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_and_exports_agree(nms):
+    declared = declared_functions()
+    assert len(declared) >= 18
+    assert sorted(nms.EXPORTS) == declared
+    raw = ctypes.CDLL(nms.library_path())
+    for name in declared:
+        assert hasattr(raw, name), f"{name} declared in nms.h but not exported"
+
+
+def test_version_and_strings(nms):
+    assert nms.nms_version() == 100
+    assert nms.nms_status_string(0) == "ok"
+    for code in (-1, -2, -3, -4):
+        assert nms.nms_status_string(code) not in ("ok", "unknown status")
+    assert nms.nms_status_string(-99) == "unknown status"
+
+
+def test_size_helpers(nms):
+    assert [nms.nms_padded_n(n) for n in (0, 1, 63, 64, 65, 1000, 4096, 65536)] == [0, 64, 64, 64, 128, 1024, 4096, 65536]
+    assert nms.nms_padded_n(-1) == 0 and nms.nms_padded_n(65537) == 0
+    assert nms.nms_mask_words(1024) == 16 * 1024
+    assert nms.nms_mask_words(4096) == 64 * 4096
+    assert nms.nms_mask_words(65) == 2 * 128
+    assert nms.nms_mask_words(0) == 0
+    assert nms.nms_sort_workspace_bytes(4096, 256) == 0
+    assert nms.nms_sort_workspace_bytes(4097, 1) == 4160 * 8
+    assert nms.nms_sort_workspace_bytes(16384, 2) == 2 * 16384 * 8
+    # order (int32) + box table (5 floats) per padded box, 256-byte aligned parts
+    assert nms.nms_workspace_bytes(1024, 1) == 1024 * 4 + 1024 * 20
+    assert nms.nms_workspace_bytes(16384, 1) == 16384 * 4 + 16384 * 20 + 16384 * 8
+    assert nms.nms_workspace_bytes(100, 3) == 1280 + 7680  # 3*100*4=1200 -> 1280; 3*5*128*4 = 7680
+    assert nms.nms_workspace_bytes(-1, 1) == 0 and nms.nms_workspace_bytes(1, 70000) == 0
+
+
+def test_argument_errors_before_launch(nms):
+    L = nms.lib
+    p = ctypes.c_void_p(0x1000)  # never dereferenced: every call below must fail validation first
+    null = None
+    # negative / too large sizes
+    assert L.nms_sort(p, p, -1, p, p, null, 0, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_sort(p, p, 65537, p, p, null, 0, null) == nms.NMS_ERR_TOO_LARGE
+    assert L.nms_sort_batched(p, p, null, 16, 70000, p, p, null, 0, null) == nms.NMS_ERR_TOO_LARGE
+    assert L.nms_overlap_mask(p, -5, 0.5, p, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_reduce(p, p, 1 << 20, p, null) == nms.NMS_ERR_TOO_LARGE
+    assert L.nms_run_ws(p, p, -1, 0.5, p, p, 1 << 20, null) == nms.NMS_ERR_INVALID_ARG
+    # null pointers
+    assert L.nms_sort(null, p, 8, p, p, null, 0, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_sort(p, null, 8, p, p, null, 0, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_sort(p, p, 8, null, p, null, 0, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_sort(p, p, 8, p, null, null, 0, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_overlap_mask(null, 8, 0.5, p, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_overlap_mask(p, 8, 0.5, null, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_reduce(null, p, 8, p, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_reduce(p, null, 8, p, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_reduce(p, p, 8, null, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_run_ws(null, p, 8, 0.5, p, p, 1 << 20, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_run_ws(p, p, 8, 0.5, null, p, 1 << 20, null) == nms.NMS_ERR_INVALID_ARG
+    # NaN threshold
+    nan = float("nan")
+    assert L.nms_overlap_mask(p, 8, nan, p, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_run_ws(p, p, 8, nan, p, p, 1 << 20, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_run_batched(p, p, null, 8, 2, nan, p, p, 1 << 20, null) == nms.NMS_ERR_INVALID_ARG
+    # workspace: missing, too small, misaligned
+    assert L.nms_run_ws(p, p, 8, 0.5, p, null, 0, null) == nms.NMS_ERR_WORKSPACE
+    assert L.nms_run_ws(p, p, 8, 0.5, p, p, 16, null) == nms.NMS_ERR_WORKSPACE
+    assert L.nms_run_ws(p, p, 8, 0.5, p, ctypes.c_void_p(0x1010), 1 << 20, null) == nms.NMS_ERR_WORKSPACE
+    assert L.nms_sort(p, p, 5000, p, p, null, 0, null) == nms.NMS_ERR_WORKSPACE
+    assert L.nms_sort(p, p, 5000, p, p, p, 100, null) == nms.NMS_ERR_WORKSPACE
+    # empty work is fine and launches nothing
+    assert L.nms_sort(null, null, 0, null, null, null, 0, null) == nms.NMS_OK
+    assert L.nms_overlap_mask(null, 0, 0.5, null, null) == nms.NMS_OK
+    assert L.nms_reduce(null, null, 0, null, null) == nms.NMS_OK
+    assert L.nms_run_ws(null, null, 0, 0.5, null, null, 0, null) == nms.NMS_OK
+    assert L.nms_run_batched(null, null, null, 64, 0, 0.5, null, null, 0, null) == nms.NMS_OK
+
+
+def test_pool_protocol(nms):
+    L = nms.lib
+    p = ctypes.c_void_p(0x1000)
+    assert L.nms_shutdown() == nms.NMS_OK
+    assert L.nms_run(p, p, 8, 0.5, p, None) == nms.NMS_ERR_WORKSPACE       # no pool yet
+    assert L.nms_init(0, 1, p, 1 << 20) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_init(1024, 1, None, 1 << 20) == nms.NMS_ERR_WORKSPACE
+    assert L.nms_init(1024, 1, p, 100) == nms.NMS_ERR_WORKSPACE
+    assert L.nms_init(1024, 1, ctypes.c_void_p(0x1001), 1 << 20) == nms.NMS_ERR_WORKSPACE
+    assert L.nms_init(70000, 1, p, 1 << 30) == nms.NMS_ERR_TOO_LARGE
+    assert L.nms_init(1024, 1, p, 1 << 20) == nms.NMS_OK
+    assert L.nms_run(p, p, 2000, 0.5, p, None) == nms.NMS_ERR_WORKSPACE    # beyond the pool's n_max
+    assert L.nms_run(p, p, 8, float("nan"), p, None) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_run(p, p, 0, 0.5, p, None) == nms.NMS_OK
+    assert L.nms_shutdown() == nms.NMS_OK
+    assert L.nms_run(p, p, 8, 0.5, p, None) == nms.NMS_ERR_WORKSPACE
+
+
+def test_binding_refuses_cpu_tensors(nms):
+    import torch
+
+    t = torch.zeros(8, 4)
+    with pytest.raises(ValueError):
+        nms.nms_sort(t, torch.zeros(8), 8, torch.zeros(8, dtype=torch.int32), torch.zeros(5 * 64))

@@ -1,0 +1,114 @@
+"""The device's division-free pair test, run on the host through the library's
+test hook, against plain float32 division (numpy) on adversarial inputs: pairs
+whose overlap lies within a few float32 steps of the threshold, on both sides.
+No GPU, and nothing from oracle/ (this checks the product's own arithmetic)."""
+import numpy as np
+import pytest
+
+
+@pytest.fixture(scope="module")
+def nms():
+    from paper_2502_00535_amd import build as nms_build
+
+    if nms_build.is_stale():
+        nms_build.build_library()
+    import paper_2502_00535_amd.binding as binding
+
+    return binding
+
+
+def plain_decision(v, c, theta):
+    """not(overlap < theta) with every operation a separate float32 numpy operation."""
+    one, zero = np.float32(1), np.float32(0)
+    iw = max(zero, (min(v[2], c[2]) - max(v[0], c[0])) + one)
+    ih = max(zero, (min(v[3], c[3]) - max(v[1], c[1])) + one)
+    area = ((c[2] - c[0]) + one) * ((c[3] - c[1]) + one)
+    q = (iw * ih) / area
+    assert isinstance(q, np.float32)
+    return int(not (q < theta)), q
+
+
+def random_pair(rng):
+    cx1, cy1 = rng.uniform(0, 3000, 2)
+    cw, ch = rng.uniform(1, 400, 2)
+    c = np.array([cx1, cy1, cx1 + cw, cy1 + ch], np.float32)
+    vx1 = cx1 + rng.uniform(-0.9, 0.9) * cw
+    vy1 = cy1 + rng.uniform(-0.9, 0.9) * ch
+    vw, vh = rng.uniform(1, 400, 2)
+    v = np.array([vx1, vy1, vx1 + vw, vy1 + vh], np.float32)
+    return v, c
+
+
+def steps(x, k):
+    x = np.float32(x)
+    for _ in range(abs(k)):
+        x = np.nextafter(x, np.float32(np.inf if k > 0 else -np.inf), dtype=np.float32)
+    return x
+
+
+def test_threshold_within_a_few_steps_of_the_overlap(nms):
+    rng = np.random.default_rng(2024)
+    checked = flips = 0
+    for _ in range(6000):
+        v, c = random_pair(rng)
+        _, q = plain_decision(v, c, np.float32(0.5))
+        if not (q > 1e-6):
+            continue
+        for k in (-3, -2, -1, 0, 1, 2, 3):
+            theta = steps(q, k)
+            want, _ = plain_decision(v, c, theta)
+            got = nms.nms_host_pair_test(v, c, float(theta))
+            assert got == want, f"v={v.tolist()} c={c.tolist()} theta={theta!r} q={q!r}"
+            checked += 1
+        flips += 1
+    assert checked > 30000 and flips > 4000
+
+
+def test_fixed_thresholds_random_pairs(nms):
+    rng = np.random.default_rng(7)
+    thetas = [np.float32(t) for t in (0.5, 0.3, 0.45, 0.7, 0.1, 1.0, 0.999999, 1e-3, 0.33333334)]
+    hits = 0
+    for i in range(20000):
+        v, c = random_pair(rng)
+        theta = thetas[i % len(thetas)]
+        want, _ = plain_decision(v, c, theta)
+        assert nms.nms_host_pair_test(v, c, float(theta)) == want
+        hits += want
+    assert 500 < hits < 19500
+
+
+def test_overlap_steered_onto_the_threshold(nms):
+    """Victims shifted so that the overlap with a W x H box lands within a few
+    float32 steps of theta (the same construction the GPU parity test uses)."""
+    rng = np.random.default_rng(99)
+    near = 0
+    for i in range(20000):
+        theta = np.float32([0.5, 0.3, 0.45, 0.7][i % 4])
+        W, H = rng.integers(8, 300, 2)
+        x0, y0 = rng.integers(0, 2000, 2)
+        c = np.array([x0, y0, x0 + W - 1, y0 + H - 1], np.float32)
+        ih = float(theta) * H * (1.0 + rng.integers(-4, 5) * 2.0 ** -24)
+        v = np.array([x0, y0 + H - ih, x0 + W - 1, y0 + 2 * H], np.float32)
+        want, q = plain_decision(v, c, theta)
+        assert nms.nms_host_pair_test(v, c, float(theta)) == want, f"v={v.tolist()} c={c.tolist()} theta={theta!r}"
+        near += abs(float(q) - float(theta)) <= 8 * float(np.spacing(theta))
+    assert near > 5000
+
+
+def test_out_of_range_thresholds_take_the_literal_form(nms):
+    rng = np.random.default_rng(5)
+    for theta in (0.0, -0.0, -1.0, 1e-20, 2.0 ** -41, 2.0 ** 21, 1e30, float("inf"), -float("inf")):
+        for _ in range(300):
+            v, c = random_pair(rng)
+            want, _ = plain_decision(v, c, np.float32(theta))
+            assert nms.nms_host_pair_test(v, c, theta) == want
+    assert nms.nms_host_pair_test([0, 0, 1, 1], [0, 0, 1, 1], float("nan")) == nms.NMS_ERR_INVALID_ARG
+
+
+def test_disjoint_on_both_axes_never_eliminates(nms):
+    # both extents negative: their product must not be taken for an overlap
+    assert nms.nms_host_pair_test([20, 20, 29, 29], [0, 0, 9, 9], 0.5) == 0
+    assert nms.nms_host_pair_test([20, 20, 29, 29], [0, 0, 9, 9], 1e-6) == 0
+    assert nms.nms_host_pair_test([0, 20, 9, 29], [0, 0, 9, 9], 1e-6) == 0
+    assert nms.nms_host_pair_test([20, 0, 29, 9], [0, 0, 9, 9], 1e-6) == 0
+    assert nms.nms_host_pair_test([20, 20, 29, 29], [0, 0, 9, 9], 0.0) == 1  # overlap 0 is not below 0
