@@ -74,6 +74,8 @@ typedef enum {
 /* Static, never freed.  Unknown codes give "unknown status". */
 const char *nms_status_string(int status);
 int nms_version(void);
+/* HIP runtime's description of the calling thread's most recent NMS_ERR_LAUNCH (static string). */
+const char *nms_last_launch_error(void);
 
 /* Host-only size helpers (pure functions; 0 on invalid arguments). */
 int nms_padded_n(int n);                                  /* n rounded up to a multiple of NMS_TILE */

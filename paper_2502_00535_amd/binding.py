@@ -19,7 +19,7 @@ NMS_ERR_WORKSPACE = -3
 NMS_ERR_LAUNCH = -4
 
 EXPORTS = (
-    "nms_status_string", "nms_version", "nms_padded_n", "nms_mask_words",
+    "nms_status_string", "nms_version", "nms_last_launch_error", "nms_padded_n", "nms_mask_words",
     "nms_sort_workspace_bytes", "nms_workspace_bytes",
     "nms_sort", "nms_sort_batched", "nms_overlap_mask", "nms_overlap_mask_batched",
     "nms_reduce", "nms_reduce_batched", "nms_run_ws", "nms_run_batched", "nms_run_batched_profiled",
@@ -30,7 +30,8 @@ EXPORTS = (
 class NmsError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__(f"{where}: {nms_status_string(status)} ({status})")
+        detail = f" [{lib.nms_last_launch_error().decode()}]" if status == NMS_ERR_LAUNCH else ""
+        super().__init__(f"{where}: {nms_status_string(status)} ({status}){detail}")
 
 
 def library_path() -> str:
@@ -38,6 +39,11 @@ def library_path() -> str:
 
 
 def _load() -> ctypes.CDLL:
+    # torch first: its wheel carries its own HIP runtime (soname libamdhip64.so.7).  Once
+    # that copy is in the process the loader binds this library to it; loaded the other
+    # way round, the system runtime would come in as a second, unusable instance.
+    import torch  # noqa: F401
+
     if not os.path.exists(_LIB_PATH):
         raise ImportError(
             f"{_LIB_PATH} is missing: build it with `python -m paper_2502_00535_amd.build` "
@@ -48,6 +54,8 @@ def _load() -> ctypes.CDLL:
     L.nms_status_string.argtypes = [i32]
     L.nms_version.restype = i32
     L.nms_version.argtypes = []
+    L.nms_last_launch_error.restype = ctypes.c_char_p
+    L.nms_last_launch_error.argtypes = []
     L.nms_padded_n.restype = i32
     L.nms_padded_n.argtypes = [i32]
     L.nms_mask_words.restype = sz

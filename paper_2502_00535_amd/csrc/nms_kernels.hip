@@ -322,9 +322,19 @@ inline bool is_nan(float v)
     return (b & 0x7fffffffu) > 0x7f800000u;
 }
 
+thread_local hipError_t g_last_hip_error = hipSuccess;
+
+// The runtime's "last error" is per thread and sticky across libraries: an unrelated
+// earlier failure (for example a probe made by the host framework) would otherwise be
+// reported as ours.  begin_launch() discards it, launch_status() reads ours.
+inline void begin_launch() { (void)hipGetLastError(); }
+
 inline int launch_status()
 {
-    return hipGetLastError() == hipSuccess ? NMS_OK : NMS_ERR_LAUNCH;
+    const hipError_t e = hipGetLastError();
+    if (e == hipSuccess) return NMS_OK;
+    g_last_hip_error = e;
+    return NMS_ERR_LAUNCH;
 }
 
 int rank_launch(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
@@ -336,10 +346,12 @@ int rank_launch(const float *boxes, const float *scores, const int32_t *counts, 
     const int widest = n_max < kChunk ? n_max : kChunk;
     while (threads < 1024 && threads * 2 < widest) threads <<= 1;  // half the padded chunk size
     auto *keys_ws = static_cast<unsigned long long *>(workspace);
+    begin_launch();
     rank_chunk_kernel<<<dim3(n_chunks, frames), dim3(threads), 0, stream>>>(
         boxes, scores, counts, n_max, n_pad, n_chunks, order, sorted5, keys_ws, keep_preset);
     int st = launch_status();
     if (st != NMS_OK || n_chunks == 1) return st;
+    begin_launch();
     rank_merge_kernel<<<dim3((n_pad + 255) / 256, frames), dim3(256), 0, stream>>>(
         boxes, counts, n_max, n_pad, n_chunks, keys_ws, order, sorted5);
     return launch_status();
@@ -355,6 +367,7 @@ int map_launch(const float *sorted5, const int32_t *counts, int n_max, int frame
     const NmsThetaConst th = nms_make_theta_const(threshold);
     const dim3 grid((tiles + kMapWaves - 1) / kMapWaves, frames);
     const dim3 block(kMapWaves * 64);
+    begin_launch();
     if (th.fast)
         map_tile_kernel<true, WRITE_MASK><<<grid, block, 0, stream>>>(sorted5, counts, n_max, n_pad, tiles, th, mask, order, keep_out);
     else
@@ -381,6 +394,8 @@ const char *nms_status_string(int status)
 }
 
 int nms_version(void) { return NMS_VERSION; }
+
+const char *nms_last_launch_error(void) { return hipGetErrorString(g_last_hip_error); }
 
 int nms_padded_n(int n)
 {
@@ -458,6 +473,7 @@ int nms_reduce_batched(const uint64_t *mask, const int32_t *order, const int32_t
     if (n_max == 0 || frames == 0) return NMS_OK;
     if (!mask || !order || !keep_out) return NMS_ERR_INVALID_ARG;
     const int n_pad = nms_padded_n(n_max);
+    begin_launch();
     reduce_rows_kernel<<<dim3(n_pad / kTile, frames), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
         reinterpret_cast<const unsigned long long *>(mask), order, counts, n_max, n_pad, keep_out);
     return launch_status();
@@ -490,8 +506,10 @@ int nms_run_batched_profiled(const float *boxes, const float *scores, const int3
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     auto mark = [&](int i) {
-        if (events && events[i] && hipEventRecord(static_cast<hipEvent_t>(events[i]), s) != hipSuccess) return false;
-        return true;
+        if (!events || !events[i]) return true;
+        const hipError_t e = hipEventRecord(static_cast<hipEvent_t>(events[i]), s);
+        if (e != hipSuccess) g_last_hip_error = e;
+        return e == hipSuccess;
     };
     if (!mark(0)) return NMS_ERR_LAUNCH;
     st = rank_launch(boxes, scores, counts, n_max, frames, order, sorted5, keys_ws, keep_out, s);

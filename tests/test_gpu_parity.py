@@ -113,17 +113,18 @@ def test_batched_ragged_counts(nms, oracle):
 
 
 def steered_pairs(F, theta, seed):
-    """F two-box frames whose overlap lands within a few float32 steps of theta."""
+    """F two-box frames whose overlap lands within a few float32 steps of theta: a
+    W x H box at the origin and a victim of the same width whose top edge is placed
+    so that the shared height is theta * H, up to a perturbation of a few 2^-24."""
     rng = np.random.default_rng(seed)
     boxes = np.zeros((F, 2, 4), np.float32)
     scores = np.tile(np.array([0.9, 0.8], np.float32), (F, 1))
-    W = rng.integers(8, 300, F)
-    H = rng.integers(8, 300, F)
-    x0 = rng.integers(0, 2000, F)
-    y0 = rng.integers(0, 2000, F)
-    ih = float(theta) * H * (1.0 + rng.integers(-4, 5, F) * 2.0 ** -24)
-    boxes[:, 0] = np.stack([x0, y0, x0 + W - 1, y0 + H - 1], axis=1)
-    boxes[:, 1] = np.stack([x0, y0 + H - ih, x0 + W - 1, y0 + 2 * H], axis=1)
+    W = rng.uniform(8, 300, F)
+    H = rng.uniform(8, 300, F)
+    ih = float(theta) * H * (1.0 + rng.integers(-6, 7, F) * 2.0 ** -24)
+    z = np.zeros(F)
+    boxes[:, 0] = np.stack([z, z, W - 1, H - 1], axis=1)
+    boxes[:, 1] = np.stack([z, H - ih, W - 1, 2 * H], axis=1)
     swap = rng.integers(0, 2, F).astype(bool)  # the outranking box is not always index 0
     boxes[swap] = boxes[swap][:, ::-1]
     scores[swap] = scores[swap][:, ::-1]
@@ -138,7 +139,12 @@ def test_overlap_within_steps_of_threshold(nms, oracle, theta):
     F = 60000
     boxes, scores = steered_pairs(F, theta, seed=int(theta * 1000))
     want = oracle_keep_frames(oracle, boxes, scores, np.float32(theta))
-    assert 0.2 * F < (want.sum() - F) < 0.8 * F  # both outcomes are common
+    assert 0.3 * F < (want.sum() - F) < 0.7 * F  # both outcomes are common
+    t32 = float(np.float32(theta))
+    sample = range(0, F, 30)
+    near = sum(abs(float(oracle.overlap(boxes[f, 1 - int(np.argmax(scores[f]))], boxes[f, int(np.argmax(scores[f]))])) - t32)
+               <= 4 * float(np.spacing(np.float32(theta))) for f in sample)
+    assert near > 0.6 * len(sample)  # and the overlaps really sit within a few steps of theta
     dev = DeviceFrames(nms, boxes, scores)
     assert np.array_equal(dev.fused(theta), want)
     assert np.array_equal(dev.steps(theta), want)
