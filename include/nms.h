@@ -123,9 +123,11 @@ int nms_reduce_batched(const uint64_t *mask, const int32_t *order, const int32_t
                        uint8_t *keep_out, void *stream);
 
 /*
- * The whole path in one call: rank, then the pair tests with the row-AND folded
- * into them (no mask is written to memory; the result is the same keep vector).
- *   workspace >= nms_workspace_bytes(n or n_max, 1 or frames) bytes, 256-byte aligned.
+ * The whole path in one call.  No mask is written to memory: the row AND is folded
+ * into the pair tests, and the result is the same keep vector as steps 1-3 give.
+ * The call picks the ranked or the direct route (below) by size.
+ *   workspace >= nms_workspace_bytes(n or n_max, 1 or frames) bytes, 256-byte aligned
+ *             (always required, whichever route is taken).
  * Two calls that share a workspace must be ordered on one stream.
  */
 int nms_run_ws(const float *boxes, const float *scores, int n, float threshold,
@@ -134,10 +136,26 @@ int nms_run_batched(const float *boxes, const float *scores, const int32_t *coun
                     float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * The two routes that nms_run_batched chooses between, callable on their own.
+ *   ranked  rank step, then pair tests on the ranked lower triangle (each pair once).
+ *           Needs the workspace.  Chosen for batches and large frames.
+ *   direct  one launch, no workspace: Algorithm 1 on the full n x n grid of the unsorted
+ *           input with the score guard evaluated per pair, row AND finished in the
+ *           workgroup.  About 2.5x the arithmetic, so it is chosen only where launch
+ *           latency dominates (n_max <= 4096 and frames * n_max^2 <= 2^25).
+ * Both give the same keep_out as nms_run_batched, bit for bit, for any sizes.
+ */
+int nms_run_ranked_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                           float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream);
+int nms_run_direct_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                           float threshold, uint8_t *keep_out, void *stream);
+
+/*
  * Profiling variant of nms_run_batched: identical work, and in addition records the
  * caller's HIP events on `stream`.  `events` is a HOST array of three hipEvent_t
  * (each may be NULL = skip): [0] before the rank step, [1] between rank and map,
- * [2] after the map step.  Event-record failures are reported as NMS_ERR_LAUNCH.
+ * [2] after the map step ([1] directly follows [0] on the direct route, which has no
+ * rank step).  Event-record failures are reported as NMS_ERR_LAUNCH.
  */
 int nms_run_batched_profiled(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
                              float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream,

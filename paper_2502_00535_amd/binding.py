@@ -22,7 +22,8 @@ EXPORTS = (
     "nms_status_string", "nms_version", "nms_last_launch_error", "nms_padded_n", "nms_mask_words",
     "nms_sort_workspace_bytes", "nms_workspace_bytes",
     "nms_sort", "nms_sort_batched", "nms_overlap_mask", "nms_overlap_mask_batched",
-    "nms_reduce", "nms_reduce_batched", "nms_run_ws", "nms_run_batched", "nms_run_batched_profiled",
+    "nms_reduce", "nms_reduce_batched", "nms_run_ws", "nms_run_batched", "nms_run_ranked_batched", "nms_run_direct_batched",
+    "nms_run_batched_profiled",
     "nms_init", "nms_shutdown", "nms_run", "nms_host_pair_test",
 )
 
@@ -80,6 +81,10 @@ def _load() -> ctypes.CDLL:
     L.nms_run_ws.argtypes = [vp, vp, i32, f32, vp, vp, sz, vp]
     L.nms_run_batched.restype = i32
     L.nms_run_batched.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp, sz, vp]
+    L.nms_run_ranked_batched.restype = i32
+    L.nms_run_ranked_batched.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp, sz, vp]
+    L.nms_run_direct_batched.restype = i32
+    L.nms_run_direct_batched.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp]
     L.nms_run_batched_profiled.restype = i32
     L.nms_run_batched_profiled.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp, sz, vp, ctypes.POINTER(vp)]
     L.nms_init.restype = i32
@@ -217,6 +222,21 @@ def nms_run_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, w
     _check(lib.nms_run_batched(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
                                _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
                                _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream)), "nms_run_batched")
+
+
+def nms_run_ranked_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib.nms_run_ranked_batched(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
+                                      _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
+                                      _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream)),
+           "nms_run_ranked_batched")
+
+
+def nms_run_direct_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, stream=None):
+    _check(lib.nms_run_direct_batched(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
+                                      _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
+                                      _ptr(keep_out, "uint8", "keep_out"), _stream(stream)),
+           "nms_run_direct_batched")
 
 
 def nms_run_batched_profiled(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, events, stream=None):

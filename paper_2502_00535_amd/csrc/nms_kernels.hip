@@ -7,12 +7,13 @@
 //   fused    map with the row reduction folded in; no mask reaches memory
 //
 // Wave layout of the map step: lane = outranking box c of the tile's column block
-// (its box, area and -h*area live in VGPRs for the whole tile); the victim row r is
-// wave-uniform and is fetched with scalar loads, so each victim costs 4 SGPRs and the
-// 12 VALU instructions of the pair test.  The compare's lane mask IS the 64-bit
+// (its box and its per-box decision threshold live in VGPRs for the whole tile); the
+// victim row r is wave-uniform and is fetched with scalar loads, so each victim costs
+// 4 SGPRs and the 11 VALU instructions of the pair test.  The compare's lane mask IS the 64-bit
 // elimination word of (row r, column block): no cross-lane work is needed to form it.
 #include <hip/hip_runtime.h>
 
+#include <math.h>
 #include <string.h>
 
 #include "../../include/nms.h"
@@ -184,7 +185,7 @@ struct TileState {
 // elimination word of row r.  Rows go in 4 groups of 16 in a real loop, so that at
 // most 64 victim SGPRs are live at a time.
 template <bool FAST, bool WRITE_MASK, bool DIAG>
-__device__ __forceinline__ void tile_sweep(const float4 *__restrict__ vb, const float4 cb, float c_area, float c_ng,
+__device__ __forceinline__ void tile_sweep(const float4 *__restrict__ vb, const float4 cb, float c_area, float c_T,
                                            const NmsThetaConst &th, int lane, TileState &st)
 {
 #pragma unroll 1
@@ -197,7 +198,7 @@ __device__ __forceinline__ void tile_sweep(const float4 *__restrict__ vb, const 
             const float4 v = vg[k];
             bool hit;
             if (FAST)
-                hit = nms_eliminates_fast(v.x, v.y, v.z, v.w, cb.x, cb.y, cb.z, cb.w, c_area, c_ng, th.neg_theta);
+                hit = nms_eliminates_fast(v.x, v.y, v.z, v.w, cb.x, cb.y, cb.z, cb.w, c_T);
             else
                 hit = nms_eliminates_exact(v.x, v.y, v.z, v.w, cb.x, cb.y, cb.z, cb.w, c_area, th.theta);
             unsigned long long word = __ballot(hit);
@@ -243,15 +244,15 @@ map_tile_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ c
     // outranking box of this lane
     const float4 cb = box4[tc * kTile + lane];
     const float c_area = area[tc * kTile + lane];
-    const float c_ng = th.neg_h * c_area;
+    const float c_T = FAST ? nms_pair_threshold(c_area, th.m) : 0.0f;
     // victims of this tile: wave-uniform addresses -> scalar loads
     const float4 *vb = box4 + tr * kTile;
 
     TileState st;
     if (tr == tc)
-        tile_sweep<FAST, WRITE_MASK, true>(vb, cb, c_area, c_ng, th, lane, st);
+        tile_sweep<FAST, WRITE_MASK, true>(vb, cb, c_area, c_T, th, lane, st);
     else
-        tile_sweep<FAST, WRITE_MASK, false>(vb, cb, c_area, c_ng, th, lane, st);
+        tile_sweep<FAST, WRITE_MASK, false>(vb, cb, c_area, c_T, th, lane, st);
 
     const int row = tr * kTile + lane;
     if (WRITE_MASK) {
@@ -261,6 +262,147 @@ map_tile_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ c
     } else {
         if (st.lane_hit && row < n_f)
             keep_out[(size_t)f * n_max + order[(size_t)f * n_max + row]] = 0;
+    }
+}
+
+// ----------------------------------------------------------------------------- direct (unranked) form
+
+// The paper's own formulation for small frames: Algorithm 1 on the full n x n grid of
+// the UNSORTED input with the score guard evaluated per pair, and Algorithm 2's row
+// AND finished inside the workgroup, in one launch (no rank step, no mask, no scratch).
+// It evaluates every unordered pair twice and pays two extra compares per pair for the
+// guard, so it only wins where launch latency dominates: single frames up to a few
+// thousand boxes.
+//
+// A workgroup owns kDirectRows consecutive victims; its wavefronts split the n outranking
+// candidates in 64-box tiles (lane = candidate c, victim r wave-uniform through scalar
+// loads, exactly as in map_tile_kernel).  Each wavefront ends with one bit per victim,
+// the workgroup ORs them through LDS and writes keep_out in input order.
+constexpr int kDirectRows = 16;
+
+// Which score compare decides "candidate c outranks victim r" for a whole tile:
+// every candidate index below every victim index -> equal scores outrank (>=);
+// every candidate index above -> strictly better only (>); the one tile that
+// contains the victims themselves -> per lane.
+enum { kGuardLowerIndex = 0, kGuardHigherIndex = 1, kGuardMixed = 2 };
+
+// One victim row of the direct form: lane mask of the candidates that eliminate it.
+template <bool FAST, int GUARD>
+__device__ __forceinline__ unsigned long long direct_row(const float4 v, float v_score, int r, const float4 cb,
+                                                         float c_score, float c_area, float c_T, int c,
+                                                         const NmsThetaConst &th)
+{
+    bool hit;
+    if (FAST)
+        hit = nms_eliminates_fast(v.x, v.y, v.z, v.w, cb.x, cb.y, cb.z, cb.w, c_T);
+    else
+        hit = nms_eliminates_exact(v.x, v.y, v.z, v.w, cb.x, cb.y, cb.z, cb.w, c_area, th.theta);
+    unsigned long long outranks;
+    if (GUARD == kGuardLowerIndex) {
+        outranks = __ballot(c_score >= v_score);
+    } else if (GUARD == kGuardHigherIndex) {
+        outranks = __ballot(c_score > v_score);
+    } else {
+        const unsigned long long lower = __ballot(c < r);
+        outranks = (__ballot(c_score >= v_score) & lower) | (__ballot(c_score > v_score) & ~lower);
+    }
+    return __ballot(hit) & outranks;
+}
+
+template <bool FAST, int GUARD, bool CLAMP>
+__device__ __forceinline__ unsigned direct_rows(const float4 *__restrict__ box4, const float *__restrict__ score,
+                                                int v0, int n_f, const float4 cb, float c_score, float c_area, float c_T,
+                                                int c, const NmsThetaConst &th)
+{
+    unsigned bits = 0;  // wave-uniform: bit k = victim v0+k is eliminated by a lane of this tile
+    if (CLAMP) {
+        // ragged last group of a frame: plain loop over the victims that exist
+#pragma unroll 1
+        for (int k = 0; k < kDirectRows && v0 + k < n_f; ++k) {
+            const unsigned long long word = direct_row<FAST, GUARD>(box4[v0 + k], score[v0 + k], v0 + k, cb, c_score,
+                                                                    c_area, c_T, c, th);
+            bits |= (word != 0 ? 1u : 0u) << k;
+        }
+        return bits;
+    }
+#pragma unroll 1
+    for (int half = 0; half < kDirectRows / 8; ++half) {
+        // eight victims at a time: their scalar loads issue together, 40 SGPRs live
+        float4 v[8];
+        float v_score[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            v[k] = box4[v0 + 8 * half + k];
+            v_score[k] = score[v0 + 8 * half + k];
+        }
+        unsigned half_bits = 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const unsigned long long word = direct_row<FAST, GUARD>(v[k], v_score[k], v0 + 8 * half + k, cb, c_score,
+                                                                    c_area, c_T, c, th);
+            half_bits |= (word != 0 ? 1u : 0u) << k;
+        }
+        bits |= half_bits << (8 * half);
+    }
+    return bits;
+}
+
+template <bool FAST, bool CLAMP>
+__device__ __forceinline__ unsigned direct_tile(const float4 *__restrict__ box4, const float *__restrict__ score,
+                                                int v0, int n_f, int t, const float4 cb, float c_score, float c_area,
+                                                float c_T, int c, const NmsThetaConst &th)
+{
+    if (t * kTile + kTile - 1 < v0)
+        return direct_rows<FAST, kGuardLowerIndex, CLAMP>(box4, score, v0, n_f, cb, c_score, c_area, c_T, c, th);
+    if (t * kTile > v0 + kDirectRows - 1)
+        return direct_rows<FAST, kGuardHigherIndex, CLAMP>(box4, score, v0, n_f, cb, c_score, c_area, c_T, c, th);
+    return direct_rows<FAST, kGuardMixed, CLAMP>(box4, score, v0, n_f, cb, c_score, c_area, c_T, c, th);
+}
+
+template <bool FAST>
+__global__ void __launch_bounds__(1024)
+direct_kernel(const float *__restrict__ boxes, const float *__restrict__ scores, const int32_t *__restrict__ counts,
+              int n_max, NmsThetaConst th, uint8_t *__restrict__ keep_out)
+{
+    __shared__ unsigned hits[16];
+    const int f = blockIdx.y;
+    const int v0 = blockIdx.x * kDirectRows;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int n_waves = blockDim.x >> 6;
+    const int n_f = frame_count(counts, f, n_max);
+    uint8_t *keep_f = keep_out + (size_t)f * n_max;
+    if (v0 >= n_f) {  // whole group beyond the frame's count (uniform for the workgroup)
+        if (threadIdx.x < kDirectRows && v0 + (int)threadIdx.x < n_max) keep_f[v0 + threadIdx.x] = 0;
+        return;
+    }
+    const float4 *box4 = reinterpret_cast<const float4 *>(boxes) + (size_t)f * n_max;
+    const float *score = scores + (size_t)f * n_max;
+    const int tiles = (n_f + kTile - 1) / kTile;
+    const bool full = v0 + kDirectRows <= n_f;
+
+    unsigned acc = 0;
+    for (int t = wave; t < tiles; t += n_waves) {
+        const int c = t * kTile + lane;
+        const bool valid = c < n_f;
+        const int cc = valid ? c : n_f - 1;
+        const float4 cb = box4[cc];
+        // a lane beyond the count never outranks anything: score -inf, index >= n_f
+        const float c_score = valid ? score[cc] : -INFINITY;
+        const float c_area = nms_box_area(cb.x, cb.y, cb.z, cb.w);
+        const float c_T = FAST ? nms_pair_threshold(c_area, th.m) : 0.0f;
+        if (full)
+            acc |= direct_tile<FAST, false>(box4, score, v0, n_f, t, cb, c_score, c_area, c_T, c, th);
+        else
+            acc |= direct_tile<FAST, true>(box4, score, v0, n_f, t, cb, c_score, c_area, c_T, c, th);
+    }
+    if (lane == 0) hits[wave] = acc;
+    __syncthreads();
+    if (threadIdx.x < kDirectRows) {
+        const int r = v0 + threadIdx.x;
+        unsigned any = 0;
+        for (int w = 0; w < n_waves; ++w) any |= hits[w];
+        if (r < n_max) keep_f[r] = (r < n_f) ? (uint8_t)(((any >> threadIdx.x) & 1u) ^ 1u) : (uint8_t)0;
     }
 }
 
@@ -354,6 +496,29 @@ int rank_launch(const float *boxes, const float *scores, const int32_t *counts, 
     begin_launch();
     rank_merge_kernel<<<dim3((n_pad + 255) / 256, frames), dim3(256), 0, stream>>>(
         boxes, counts, n_max, n_pad, n_chunks, keys_ws, order, sorted5);
+    return launch_status();
+}
+
+// Frames small enough that launch latency, not arithmetic, decides: one launch of the
+// direct form instead of rank + map.  (Twice the pairs and two more compares per pair:
+// about 2.5x the VALU work of the ranked triangle.)
+inline bool use_direct_form(int n_max, int frames)
+{
+    return n_max <= 4096 && (long long)frames * n_max * n_max <= (1ll << 25);
+}
+
+int direct_launch(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                  float threshold, uint8_t *keep_out, hipStream_t stream)
+{
+    const NmsThetaConst th = nms_make_theta_const(threshold);
+    const int tiles = (n_max + kTile - 1) / kTile;
+    const int waves = tiles < 16 ? tiles : 16;
+    const dim3 grid((n_max + kDirectRows - 1) / kDirectRows, frames);
+    begin_launch();
+    if (th.fast)
+        direct_kernel<true><<<grid, dim3(waves * 64), 0, stream>>>(boxes, scores, counts, n_max, th, keep_out);
+    else
+        direct_kernel<false><<<grid, dim3(waves * 64), 0, stream>>>(boxes, scores, counts, n_max, th, keep_out);
     return launch_status();
 }
 
@@ -484,25 +649,22 @@ int nms_reduce(const uint64_t *mask, const int32_t *order, int n, uint8_t *keep_
     return nms_reduce_batched(mask, order, nullptr, n, 1, keep_out, stream);
 }
 
-int nms_run_batched_profiled(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
-                             float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream,
-                             void *const *events)
+enum Route { kRouteAuto = 0, kRouteRanked = 1, kRouteDirect = 2 };
+
+static int run_routed(Route route, const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                      float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream,
+                      void *const *events)
 {
     int st;
     if (!sizes_ok(n_max, frames, &st)) return st;
     if (is_nan(threshold)) return NMS_ERR_INVALID_ARG;
     if (n_max == 0 || frames == 0) return NMS_OK;
     if (!boxes || !scores || !keep_out) return NMS_ERR_INVALID_ARG;
-    const size_t need = nms_workspace_bytes(n_max, frames);
-    if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)) return NMS_ERR_WORKSPACE;
-
-    const size_t n_pad = (size_t)nms_padded_n(n_max);
-    char *p = static_cast<char *>(workspace);
-    int32_t *order = reinterpret_cast<int32_t *>(p);
-    p += align256((size_t)frames * n_max * sizeof(int32_t));
-    float *sorted5 = reinterpret_cast<float *>(p);
-    p += align256((size_t)frames * 5 * n_pad * sizeof(float));
-    void *keys_ws = p;
+    const bool direct = route == kRouteDirect || (route == kRouteAuto && use_direct_form(n_max, frames));
+    if (route != kRouteDirect) {  // the automatic route validates the workspace whichever way it goes
+        const size_t need = nms_workspace_bytes(n_max, frames);
+        if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)) return NMS_ERR_WORKSPACE;
+    }
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     auto mark = [&](int i) {
@@ -512,6 +674,21 @@ int nms_run_batched_profiled(const float *boxes, const float *scores, const int3
         return e == hipSuccess;
     };
     if (!mark(0)) return NMS_ERR_LAUNCH;
+    if (direct) {
+        if (!mark(1)) return NMS_ERR_LAUNCH;  // no rank step on this route
+        st = direct_launch(boxes, scores, counts, n_max, frames, threshold, keep_out, s);
+        if (st != NMS_OK) return st;
+        return mark(2) ? NMS_OK : NMS_ERR_LAUNCH;
+    }
+
+    const size_t n_pad = (size_t)nms_padded_n(n_max);
+    char *p = static_cast<char *>(workspace);
+    int32_t *order = reinterpret_cast<int32_t *>(p);
+    p += align256((size_t)frames * n_max * sizeof(int32_t));
+    float *sorted5 = reinterpret_cast<float *>(p);
+    p += align256((size_t)frames * 5 * n_pad * sizeof(float));
+    void *keys_ws = p;
+
     st = rank_launch(boxes, scores, counts, n_max, frames, order, sorted5, keys_ws, keep_out, s);
     if (st != NMS_OK) return st;
     if (!mark(1)) return NMS_ERR_LAUNCH;
@@ -520,11 +697,33 @@ int nms_run_batched_profiled(const float *boxes, const float *scores, const int3
     return mark(2) ? NMS_OK : NMS_ERR_LAUNCH;
 }
 
+int nms_run_batched_profiled(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                             float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream,
+                             void *const *events)
+{
+    return run_routed(kRouteAuto, boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, ws_bytes,
+                      stream, events);
+}
+
 int nms_run_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
                     float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream)
 {
-    return nms_run_batched_profiled(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, ws_bytes,
-                                    stream, nullptr);
+    return run_routed(kRouteAuto, boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, ws_bytes,
+                      stream, nullptr);
+}
+
+int nms_run_ranked_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                           float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream)
+{
+    return run_routed(kRouteRanked, boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, ws_bytes,
+                      stream, nullptr);
+}
+
+int nms_run_direct_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                           float threshold, uint8_t *keep_out, void *stream)
+{
+    return run_routed(kRouteDirect, boxes, scores, counts, n_max, frames, threshold, keep_out, nullptr, 0, stream,
+                      nullptr);
 }
 
 int nms_run_ws(const float *boxes, const float *scores, int n, float threshold,
@@ -571,7 +770,7 @@ int nms_host_pair_test(const float *victim, const float *outranking, float thres
     bool hit;
     if (th.fast)
         hit = nms_eliminates_fast(victim[0], victim[1], victim[2], victim[3],
-                                  outranking[0], outranking[1], outranking[2], outranking[3], a, th.neg_h * a, th.neg_theta);
+                                  outranking[0], outranking[1], outranking[2], outranking[3], nms_pair_threshold(a, th.m));
     else
         hit = nms_eliminates_exact(victim[0], victim[1], victim[2], victim[3],
                                    outranking[0], outranking[1], outranking[2], outranking[3], a, th.theta);

@@ -5,36 +5,33 @@
 // per operation):
 //     iw = max(0, (min(x2_v, x2_c) - max(x1_v, x1_c)) + 1)
 //     ih = max(0, (min(y2_v, y2_c) - max(y1_v, y1_c)) + 1)
-//     eliminated  <=>  not( (iw * ih) / area_c  <  theta )
+//     inter = iw * ih
+//     eliminated  <=>  not( inter / area_c  <  theta )
 // v = victim (lower rank), c = the outranking box, area_c = ((x2_c-x1_c)+1)*((y2_c-y1_c)+1).
 //
 // A correctly rounded float32 division costs about ten VALU instructions on CDNA.
-// The fast form below reaches the same decision with one FMA and one compare:
+// The fast form replaces the division AND the threshold compare by one compare against
+// a per-box constant that is worked out once per 64 victims:
 //
-//     q = RN(inter / area) >= theta
-//       <=>  inter / area  >=  m          (m = theta - h, the rounding boundary just below
-//                                          theta; h = half the gap to theta's predecessor)
-//       <=>  inter - theta*area  >=  -h*area
+//     RN(inter / area) >= theta
+//       <=>  inter / area >= m        m = theta - h is the rounding boundary just below theta
+//                                     (h = half the gap to theta's float32 predecessor);
+//                                     everything at or above m rounds to theta or higher
+//       <=>  inter >= m * area        (real numbers; area > 0)
+//       <=>  inter >= T(area)         T = the smallest float32 that is >= m * area,
+//                                     because inter itself is a float32
 //
-// (inter / area == m exactly cannot happen, so the tie rule of the rounding never
-// matters: in units of h, m is an odd integer of 25 bits, so m*area has an odd part
-// of more than 24 bits and is not a float32, whereas inter is one.)
+// m has 25 significant bits and area 24, so m * area is exact in float64, and T is that
+// product converted to float32 rounding upwards.  (inter / area == m exactly cannot
+// happen -- in units of h, m is an odd 25-bit integer, so m * area is never a float32 --
+// hence the ties-to-even rule of the division never comes into play.)
 //
-// E = inter - theta*area is what fma(-theta, area, inter) computes with a single
-// rounding.  theta*area is a multiple of 2^(e_theta+e_area-46).  Whenever
-// |E| < 2^(e_theta+e_area-22), inter is at least 2^(e_theta+e_area-1), so its own ulp
-// is a multiple of that same unit, hence E is an integer below 2^24 times that unit
-// and the FMA returns E exactly.  Otherwise the rounded value keeps E's sign and
-// stays at or beyond 2^(e_theta+e_area-22) in magnitude, which exceeds h*area
-// (< 2^(e_theta+e_area-23)).  Either way comparing the FMA result with -h*area
-// (exact: h is a power of two) decides exactly as the division does.
+// One further saving, valid because the fast form is only used for theta > 0: the floor
+// at zero is applied to one extent only.  If the other extent is negative the product is
+// <= 0 < T and the test fails, exactly as it does for a product floored to 0.
 //
-// Two further savings, valid because the fast form is only used for theta > 0:
-// the floor at zero is applied to one extent only (if the other is negative the
-// product is <= 0 and the test fails, exactly as it does for a product floored to 0).
-//
-// The fast form is used for 2^-40 <= theta <= 2^20 (no overflow or underflow can
-// occur for areas in [1, 2^82]); any other theta takes the literal division form.
+// The fast form is used for 2^-40 <= theta <= 2^20 (no overflow or underflow for areas
+// in [1, 2^100]); any other theta takes the literal division form.
 #pragma once
 
 #include <math.h>
@@ -48,18 +45,16 @@
 #endif
 
 struct NmsThetaConst {
-    float theta;      // threshold as given
-    float neg_theta;  // -theta
-    float neg_h;      // -(half the distance from theta down to the next float32)
-    int fast;         // 1: the FMA form is valid for this theta
+    float theta;   // threshold as given
+    double m;      // rounding boundary just below theta (exact in float64)
+    int fast;      // 1: the compare-against-T form is valid for this theta
 };
 
 static inline NmsThetaConst nms_make_theta_const(float theta)
 {
     NmsThetaConst k;
     k.theta = theta;
-    k.neg_theta = -theta;
-    k.neg_h = 0.0f;
+    k.m = 0.0;
     k.fast = 0;
     if (theta >= 0x1p-40f && theta <= 0x1p20f) {
         uint32_t bits;
@@ -67,11 +62,25 @@ static inline NmsThetaConst nms_make_theta_const(float theta)
         uint32_t below = bits - 1u;  // predecessor of a positive normal float
         float pred;
         memcpy(&pred, &below, sizeof pred);
-        float gap = theta - pred;  // exact (neighbouring floats)
-        k.neg_h = -0.5f * gap;     // exact (power of two)
+        k.m = 0.5 * ((double)theta + (double)pred);  // exact: 25 significant bits
         k.fast = 1;
     }
     return k;
+}
+
+// T(area): smallest float32 >= m * area.  The product is exact in float64; the
+// conversion rounds to nearest and is bumped to the next float32 when it fell short.
+NMS_HD float nms_pair_threshold(float area, double m)
+{
+    const double prod = m * (double)area;
+    float t = (float)prod;
+    if ((double)t < prod) {
+        uint32_t b;
+        memcpy(&b, &t, sizeof b);
+        b += 1u;  // next float32 up (t is positive and finite)
+        memcpy(&t, &b, sizeof t);
+    }
+    return t;
 }
 
 // Literal form: the definition, operation by operation.
@@ -85,16 +94,13 @@ NMS_HD bool nms_eliminates_exact(float vx1, float vy1, float vx2, float vy2,
     return !(q < theta);
 }
 
-// Fast form.  c_ng = neg_h * c_area (per outranking box, exact).
+// Fast form.  c_T = nms_pair_threshold(area of the outranking box, m).
 NMS_HD bool nms_eliminates_fast(float vx1, float vy1, float vx2, float vy2,
-                                float cx1, float cy1, float cx2, float cy2,
-                                float c_area, float c_ng, float neg_theta)
+                                float cx1, float cy1, float cx2, float cy2, float c_T)
 {
     float iw = (fminf(vx2, cx2) - fmaxf(vx1, cx1)) + 1.0f;  // may be negative, see above
     float ih = fmaxf(0.0f, (fminf(vy2, cy2) - fmaxf(vy1, cy1)) + 1.0f);
-    float inter = iw * ih;
-    float e = fmaf(neg_theta, c_area, inter);
-    return e >= c_ng;
+    return iw * ih >= c_T;
 }
 
 // Area of a box, pixel-inclusive (Algorithm 1's first assignment, one extent per axis).

@@ -55,11 +55,27 @@ class DeviceFrames:
         self.torch.cuda.synchronize()
         return self.keep.cpu().numpy()
 
-    def fused(self, theta):
+    def fused(self, theta, want=None):
+        """nms_run_batched (automatic route).  With `want`, the ranked and the direct route
+        are run as well and all three must equal it bit for bit."""
         self.keep.fill_(77)
         self.nms.nms_run_batched(self.boxes, self.scores, self.counts, self.n_max, self.F, theta, self.keep, self.run_ws)
         self.torch.cuda.synchronize()
-        return self.keep.cpu().numpy()
+        got = self.keep.cpu().numpy()
+        if want is not None:
+            assert np.array_equal(got, want), f"automatic route: {(got != want).sum()} differing keep bits"
+            self.keep.fill_(77)
+            self.nms.nms_run_ranked_batched(self.boxes, self.scores, self.counts, self.n_max, self.F, theta, self.keep, self.run_ws)
+            self.torch.cuda.synchronize()
+            ranked = self.keep.cpu().numpy()
+            assert np.array_equal(ranked, want), f"ranked route: {(ranked != want).sum()} differing keep bits"
+            if self.F * self.n_max * self.n_max <= (1 << 31):  # the direct route is quadratic in full: keep it bounded
+                self.keep.fill_(77)
+                self.nms.nms_run_direct_batched(self.boxes, self.scores, self.counts, self.n_max, self.F, theta, self.keep)
+                self.torch.cuda.synchronize()
+                direct = self.keep.cpu().numpy()
+                assert np.array_equal(direct, want), f"direct route: {(direct != want).sum()} differing keep bits"
+        return got
 
     def host_order(self):
         return self.order.cpu().numpy()

@@ -93,6 +93,12 @@ def test_argument_errors_before_launch(nms):
     assert L.nms_run_ws(p, p, 8, 0.5, p, null, 0, null) == nms.NMS_ERR_WORKSPACE
     assert L.nms_run_ws(p, p, 8, 0.5, p, p, 16, null) == nms.NMS_ERR_WORKSPACE
     assert L.nms_run_ws(p, p, 8, 0.5, p, ctypes.c_void_p(0x1010), 1 << 20, null) == nms.NMS_ERR_WORKSPACE
+    assert L.nms_run_ranked_batched(p, p, null, 8, 2, 0.5, p, null, 0, null) == nms.NMS_ERR_WORKSPACE
+    assert L.nms_run_direct_batched(null, p, null, 8, 2, 0.5, p, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_run_direct_batched(p, p, null, 8, 2, 0.5, null, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_run_direct_batched(p, p, null, 70000, 2, 0.5, p, null) == nms.NMS_ERR_TOO_LARGE
+    assert L.nms_run_direct_batched(p, p, null, 8, 2, float("nan"), p, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_run_direct_batched(null, null, null, 0, 2, 0.5, null, null) == nms.NMS_OK
     assert L.nms_sort(p, p, 5000, p, p, null, 0, null) == nms.NMS_ERR_WORKSPACE
     assert L.nms_sort(p, p, 5000, p, p, p, 100, null) == nms.NMS_ERR_WORKSPACE
     # empty work is fine and launches nothing

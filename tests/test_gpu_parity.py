@@ -63,7 +63,7 @@ def test_fused_single_frame(nms, oracle, n):
     boxes, scores = frame_for(n, seed=1000 + n)
     theta = np.float32(0.4)
     dev = DeviceFrames(nms, boxes[None], scores[None])
-    assert np.array_equal(dev.fused(float(theta))[0], oracle.keep(boxes, scores, theta))
+    dev.fused(float(theta), want=oracle.keep(boxes, scores, theta)[None])
     if n > 4096:  # several rank chunks: check the merged order as well
         dev.steps(float(theta))
         assert np.array_equal(dev.host_order()[0], oracle.order(scores))
@@ -78,7 +78,7 @@ def test_threshold_range(nms, oracle, theta):
     boxes, scores = frame_for(700, seed=31)
     dev = DeviceFrames(nms, boxes[None], scores[None])
     want = oracle.keep(boxes, scores, np.float32(theta))
-    assert np.array_equal(dev.fused(theta)[0], want)
+    dev.fused(theta, want=want[None])
     assert np.array_equal(dev.steps(theta)[0], want)
     if theta <= 0:
         assert want.sum() == 1
@@ -101,14 +101,14 @@ def test_batched_ragged_counts(nms, oracle):
     theta = np.float32(0.45)
     want = oracle_keep_frames(oracle, boxes, scores, theta, counts)
     dev = DeviceFrames(nms, boxes, scores, counts)
-    assert np.array_equal(dev.fused(float(theta)), want)
+    dev.fused(float(theta), want=want)
     assert np.array_equal(dev.steps(float(theta)), want)
     # negative and oversized counts are clamped
     counts2 = counts.copy()
     counts2[0], counts2[1] = -5, n_max + 100
     want2 = oracle_keep_frames(oracle, boxes, scores, theta, np.clip(counts2, 0, n_max))
     dev2 = DeviceFrames(nms, boxes, scores, counts2)
-    assert np.array_equal(dev2.fused(float(theta)), want2)
+    dev2.fused(float(theta), want=want2)
     assert np.array_equal(dev2.steps(float(theta)), want2)
 
 
@@ -146,7 +146,7 @@ def test_overlap_within_steps_of_threshold(nms, oracle, theta):
                <= 4 * float(np.spacing(np.float32(theta))) for f in sample)
     assert near > 0.6 * len(sample)  # and the overlaps really sit within a few steps of theta
     dev = DeviceFrames(nms, boxes, scores)
-    assert np.array_equal(dev.fused(theta), want)
+    dev.fused(theta, want=want)
     assert np.array_equal(dev.steps(theta), want)
 
 
@@ -167,7 +167,7 @@ def test_threshold_equal_to_observed_overlaps(nms, oracle):
             continue
         tried += 1
         for theta in (q, np.nextafter(q, np.float32(2)), np.nextafter(q, np.float32(0))):
-            assert np.array_equal(dev.fused(float(theta))[0], oracle.keep(boxes, scores, theta)), f"theta={theta!r}"
+            dev.fused(float(theta), want=oracle.keep(boxes, scores, theta)[None])
 
 
 @pytest.mark.parametrize("index", [0, 1, 2, 3, 4])
@@ -178,8 +178,7 @@ def test_configs_full_size(nms, oracle, index):
     w = make_config(index)
     want = oracle_keep_frames(oracle, w.boxes, w.scores, np.float32(w.theta))
     dev = DeviceFrames(nms, w.boxes, w.scores)
-    got = dev.fused(w.theta)
-    assert np.array_equal(got, want), f"{w.name}: {(got != want).sum()} differing keep bits (fused)"
+    dev.fused(w.theta, want=want)  # automatic, ranked and (where bounded) direct route
     got = dev.steps(w.theta)
     assert np.array_equal(got, want), f"{w.name}: {(got != want).sum()} differing keep bits (steps)"
     assert 0 < want.sum() < want.size
