@@ -72,6 +72,8 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-frames", type=int, default=128)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 256 MiB device copies (a known-size kernel to scale HBM counters by)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -228,6 +230,15 @@ def main():
             }
         extra["other_configs"] = others
         extra["us_per_frame_at_1024_boxes"] = others.get("cfg0_1x1024_1080p", {}).get("us_per_frame")
+
+    if args.calibrate_copy:
+        src = torch.empty(64 << 20, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        extra["calibration_copy_bytes_read_and_written_each"] = src.numel() * 4
+        del src, dst
 
     # ------------------------------------------------------------------ CPU oracle on a bounded sample
     cpu_baseline = None

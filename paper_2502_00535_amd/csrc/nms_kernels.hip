@@ -225,13 +225,26 @@ __device__ __forceinline__ void tile_sweep(const float4 *__restrict__ vb, const 
 template <bool FAST, bool WRITE_MASK>
 __global__ void __launch_bounds__(kMapWaves * 64)
 map_tile_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ counts, int n_max, int n_pad,
-                int tiles, NmsThetaConst th, unsigned long long *__restrict__ mask,
-                const int32_t *__restrict__ order, uint8_t *__restrict__ keep_out)
+                int tiles, int tile_blocks, int frames, int xcd_frames, NmsThetaConst th,
+                unsigned long long *__restrict__ mask, const int32_t *__restrict__ order,
+                uint8_t *__restrict__ keep_out)
 {
     const int lane = threadIdx.x & 63;
-    const int g = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * kMapWaves + (threadIdx.x >> 6)));
+    int f, bx;
+    if (xcd_frames) {
+        // Workgroups are dealt to the 8 XCDs round-robin by linear id, and each XCD has its
+        // own L2.  Give all tiles of a frame to one XCD (frame f -> XCD f mod 8) so that the
+        // frame's box table is fetched from HBM once instead of once per XCD.
+        const int slot = blockIdx.x >> 3;
+        f = (slot / tile_blocks) * 8 + (int)(blockIdx.x & 7);
+        bx = slot % tile_blocks;
+        if (f >= frames) return;
+    } else {
+        f = blockIdx.y;
+        bx = blockIdx.x;
+    }
+    const int g = __builtin_amdgcn_readfirstlane(bx * kMapWaves + (int)(threadIdx.x >> 6));
     if (g >= tiles) return;
-    const int f = blockIdx.y;
     const int n_f = frame_count(counts, f, n_max);
     int tr, tc;
     triangle_tile(g, tr, tc);
@@ -530,13 +543,18 @@ int map_launch(const float *sorted5, const int32_t *counts, int n_max, int frame
     const int T = n_pad / kTile;
     const int tiles = T * (T + 1) / 2;
     const NmsThetaConst th = nms_make_theta_const(threshold);
-    const dim3 grid((tiles + kMapWaves - 1) / kMapWaves, frames);
+    const int tile_blocks = (tiles + kMapWaves - 1) / kMapWaves;
+    // batches: one frame per XCD at a time (see the kernel); a few large frames: spread each over all XCDs
+    const int xcd_frames = frames >= 8 ? 1 : 0;
+    const dim3 grid = xcd_frames ? dim3((unsigned)(((frames + 7) / 8) * 8 * tile_blocks)) : dim3(tile_blocks, frames);
     const dim3 block(kMapWaves * 64);
     begin_launch();
     if (th.fast)
-        map_tile_kernel<true, WRITE_MASK><<<grid, block, 0, stream>>>(sorted5, counts, n_max, n_pad, tiles, th, mask, order, keep_out);
+        map_tile_kernel<true, WRITE_MASK><<<grid, block, 0, stream>>>(sorted5, counts, n_max, n_pad, tiles, tile_blocks,
+                                                                      frames, xcd_frames, th, mask, order, keep_out);
     else
-        map_tile_kernel<false, WRITE_MASK><<<grid, block, 0, stream>>>(sorted5, counts, n_max, n_pad, tiles, th, mask, order, keep_out);
+        map_tile_kernel<false, WRITE_MASK><<<grid, block, 0, stream>>>(sorted5, counts, n_max, n_pad, tiles, tile_blocks,
+                                                                       frames, xcd_frames, th, mask, order, keep_out);
     return launch_status();
 }
 
