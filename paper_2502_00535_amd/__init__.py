@@ -10,7 +10,7 @@ built library raises ImportError.  ``python -m paper_2502_00535_amd.build`` comp
 import importlib
 
 _BINDING_NAMES = (
-    "NmsError", "library_path", "lib", "EXPORTS",
+    "NmsError", "RunPlan", "library_path", "lib", "EXPORTS",
     "nms_status_string", "nms_version", "nms_last_launch_error", "nms_padded_n", "nms_mask_words",
     "nms_sort_workspace_bytes", "nms_workspace_bytes", "nms_host_pair_test",
     "nms_sort", "nms_sort_batched", "nms_overlap_mask", "nms_overlap_mask_batched",

@@ -224,6 +224,29 @@ def nms_run_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, w
                                _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream)), "nms_run_batched")
 
 
+class RunPlan:
+    """nms_run_batched with its arguments marshalled once.
+
+    For serving loops that call the library many times on the same buffers: the tensors
+    are validated and their pointers taken at construction; each call is then a single
+    foreign call.  The plan holds references to its tensors, and uses the stream that was
+    current when it was built unless one is given.
+    """
+
+    def __init__(self, boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, stream=None):
+        self._keepalive = (boxes, scores, counts, keep_out, workspace)
+        w, wb = _ws(workspace)
+        self._args = (_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
+                      _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
+                      _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream))
+        self._fn = lib.nms_run_batched
+
+    def __call__(self):
+        status = self._fn(*self._args)
+        if status != NMS_OK:
+            raise NmsError(status, "nms_run_batched")
+
+
 def nms_run_ranked_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, stream=None):
     w, wb = _ws(workspace)
     _check(lib.nms_run_ranked_batched(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),

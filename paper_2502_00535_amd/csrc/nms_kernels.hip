@@ -58,10 +58,26 @@ __device__ __forceinline__ void emit_padding_row(int r, int n_pad, float *sorted
     sorted_f[4 * (size_t)n_pad + r] = 1.0f;  // the one-pixel box (0,0,0,0): never divides by zero
 }
 
+// Compare-exchange: afterwards lo <= hi when `up`, lo >= hi otherwise.
+__device__ __forceinline__ void compare_exchange(unsigned long long &lo, unsigned long long &hi, bool up)
+{
+    const bool swap = (lo > hi) == up;
+    const unsigned long long a = swap ? hi : lo;
+    const unsigned long long b = swap ? lo : hi;
+    lo = a;
+    hi = b;
+}
+
 // One workgroup ranks one chunk of up to kChunk boxes of one frame with a bitonic
-// network in LDS.  With a single chunk it also writes order / sorted5 (and, for the
-// fused path, presets keep_out); with several chunks it leaves the chunk's sorted
-// keys in `keys_ws` for the merge kernel.
+// network over P = 4 * blockDim.x keys (P a power of two, 256..4096).  Each thread keeps
+// four keys in registers: wavefront w owns elements 256w..256w+255, lane l holds elements
+// 256w + 64q + l (q = 0..3).  Strides 64 and 128 are exchanges between a thread's own
+// registers, strides 1..32 are lane shuffles, and only strides >= 256 (between
+// wavefronts) go through LDS with workgroup barriers: 18 barriers for 4096 keys instead of
+// one per stage (78).
+// With a single chunk the kernel also writes order / sorted5 (and, for the fused path,
+// presets keep_out); with several chunks it leaves the chunk's sorted keys in `keys_ws`
+// for the merge kernel.
 __global__ void __launch_bounds__(1024)
 rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ scores,
                   const int32_t *__restrict__ counts, int n_max, int n_pad, int n_chunks,
@@ -73,34 +89,71 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
     const int chunk = blockIdx.x;
     const int tid = threadIdx.x;
     const int nth = blockDim.x;
+    const int lane = tid & 63;
     const int n_f = frame_count(counts, f, n_max);
     const int base = chunk * kChunk;
     int cnt = n_f - base;
     cnt = cnt < 0 ? 0 : (cnt > kChunk ? kChunk : cnt);
-    int P = 64;
-    while (P < cnt) P <<= 1;
+    const int P = nth * 4;
 
     const float *scores_f = scores + (size_t)f * n_max;
-    for (int i = tid; i < P; i += nth)
-        keys[i] = (i < cnt) ? rank_key(scores_f[base + i], (unsigned)(base + i)) : kSentinel;
-    __syncthreads();
+    int e[4];
+    unsigned long long K[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        e[q] = (tid >> 6) * 256 + q * 64 + lane;
+        K[q] = (e[q] < cnt) ? rank_key(scores_f[base + e[q]], (unsigned)(base + e[q])) : kSentinel;
+    }
 
     for (int k = 2; k <= P; k <<= 1) {
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int t = tid; t < (P >> 1); t += nth) {
-                const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-                const int l = i | j;
-                const bool up = (i & k) == 0;
-                const unsigned long long a = keys[i];
-                const unsigned long long b = keys[l];
-                if ((a > b) == up) {
-                    keys[i] = b;
-                    keys[l] = a;
-                }
-            }
+        if (k >= 512) {
+            // strides k/2 .. 256 cross wavefronts: through LDS
+#pragma unroll
+            for (int q = 0; q < 4; ++q) keys[e[q]] = K[q];
             __syncthreads();
+            for (int j = k >> 1; j >= 256; j >>= 1) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int c = tid + h * nth;  // P/2 exchanges per stage, two per thread
+                    const int i = ((c & ~(j - 1)) << 1) | (c & (j - 1));
+                    const int l = i | j;
+                    const bool up = (i & k) == 0;
+                    const unsigned long long a = keys[i];
+                    const unsigned long long b = keys[l];
+                    if ((a > b) == up) {
+                        keys[i] = b;
+                        keys[l] = a;
+                    }
+                }
+                __syncthreads();
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) K[q] = keys[e[q]];
+        }
+        if (k >= 256) {  // stride 128: registers q and q+2
+            compare_exchange(K[0], K[2], (e[0] & k) == 0);
+            compare_exchange(K[1], K[3], (e[1] & k) == 0);
+        }
+        if (k >= 128) {  // stride 64: registers q and q+1
+            compare_exchange(K[0], K[1], (e[0] & k) == 0);
+            compare_exchange(K[2], K[3], (e[2] & k) == 0);
+        }
+        for (int j = (k >> 1) < 32 ? (k >> 1) : 32; j >= 1; j >>= 1) {  // strides <= 32: lane shuffles
+            const bool lower = (lane & j) == 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const unsigned long long other = __shfl_xor(K[q], j);
+                const bool take_min = lower == ((e[q] & k) == 0);
+                const bool other_smaller = other < K[q];
+                K[q] = (take_min == other_smaller) ? other : K[q];
+            }
         }
     }
+    // sorted keys back to LDS for the gather below (each thread wrote and read only its own
+    // slots since the last barrier, so no barrier is needed before these stores)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) keys[e[q]] = K[q];
+    __syncthreads();
 
     const float *boxes_f = boxes + (size_t)f * n_max * 4;
     int32_t *order_f = order + (size_t)f * n_max;
@@ -162,14 +215,29 @@ rank_merge_kernel(const float *__restrict__ boxes, const int32_t *__restrict__ c
 
 // ----------------------------------------------------------------------------- map
 
-// Linear tile index -> (tile row tr, tile column tc <= tr) of the lower triangle.
-__device__ __forceinline__ void triangle_tile(int g, int &tr, int &tc)
+// Work unit of the map step: one column tile tc (64 outranking boxes, held in registers)
+// against a "super-row" of kSuper consecutive victim tile rows, i.e. up to kSuper tiles of
+// the ranked lower triangle.  Super-row sr has min(kSuper*(sr+1), T) units (tc = 0 .. last
+// tile row of the super-row), so the units before super-row sr number
+// kSuper * sr*(sr+1)/2.  Linear unit index -> (sr, tc) by integer square root.
+// kSuper = 4 amortises the per-lane set-up over 256 rows and is used when the launch has
+// plenty of units; kSuper = 1 (one tile per wavefront) keeps small launches balanced.
+template <int kSuper>
+__device__ __forceinline__ void triangle_unit(int g, int &sr, int &tc)
 {
-    int r = (int)((__fsqrt_rn(8.0f * (float)g + 1.0f) - 1.0f) * 0.5f);
-    while (r * (r + 1) / 2 > g) --r;
-    while ((r + 1) * (r + 2) / 2 <= g) ++r;
-    tr = r;
-    tc = g - r * (r + 1) / 2;
+    // largest sr with kSuper*sr*(sr+1)/2 <= g
+    int r = (int)((__fsqrt_rn(1.0f + (8.0f / kSuper) * (float)g) - 1.0f) * 0.5f);
+    while (kSuper * r * (r + 1) / 2 > g) --r;
+    while (kSuper * (r + 1) * (r + 2) / 2 <= g) ++r;
+    sr = r;
+    tc = g - kSuper * r * (r + 1) / 2;
+}
+
+// Number of units for T tile rows.
+inline int triangle_units(int T, int super)
+{
+    const int SR = (T + super - 1) / super;
+    return SR == 0 ? 0 : super * (SR - 1) * SR / 2 + T;
 }
 
 constexpr int kMapWaves = 4;  // wavefronts (tiles) per workgroup
@@ -218,11 +286,12 @@ __device__ __forceinline__ void tile_sweep(const float4 *__restrict__ vb, const 
     }
 }
 
-// One wavefront = one 64x64 tile.  WRITE_MASK: store the tile's 64 words (mask
+// One wavefront = one unit: a column tile against up to kSuper victim tiles, so the
+// per-lane set-up (loads, threshold) is paid once per 4 x 64 rows.  WRITE_MASK: store each tile's 64 words (mask
 // layout of nms.h).  Otherwise: fold the row reduction in and clear keep_out of every
 // victim that some lane eliminates (keep_out was preset to 1 by the rank step; all
 // writers store the same 0, so concurrent tiles need no atomics).
-template <bool FAST, bool WRITE_MASK>
+template <bool FAST, bool WRITE_MASK, int kSuper>
 __global__ void __launch_bounds__(kMapWaves * 64)
 map_tile_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ counts, int n_max, int n_pad,
                 int tiles, int tile_blocks, int frames, int xcd_frames, NmsThetaConst th,
@@ -246,35 +315,40 @@ map_tile_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ c
     const int g = __builtin_amdgcn_readfirstlane(bx * kMapWaves + (int)(threadIdx.x >> 6));
     if (g >= tiles) return;
     const int n_f = frame_count(counts, f, n_max);
-    int tr, tc;
-    triangle_tile(g, tr, tc);
-    if (tr * kTile >= n_f) return;
+    int sr, tc;
+    triangle_unit<kSuper>(g, sr, tc);
+    const int tiles_f = (n_f + kTile - 1) / kTile;  // tile rows that hold boxes of this frame
+    int tr = kSuper * sr > tc ? kSuper * sr : tc;
+    int tr_end = kSuper * sr + kSuper < tiles_f ? kSuper * sr + kSuper : tiles_f;
+    if (tr >= tr_end) return;
 
     const float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
     const float4 *box4 = reinterpret_cast<const float4 *>(sorted_f);
     const float *area = sorted_f + 4 * (size_t)n_pad;
 
-    // outranking box of this lane
+    // outranking box of this lane, and the float32 its intersections are compared with
     const float4 cb = box4[tc * kTile + lane];
     const float c_area = area[tc * kTile + lane];
     const float c_T = FAST ? nms_pair_threshold(c_area, th.m) : 0.0f;
-    // victims of this tile: wave-uniform addresses -> scalar loads
-    const float4 *vb = box4 + tr * kTile;
 
-    TileState st;
-    if (tr == tc)
-        tile_sweep<FAST, WRITE_MASK, true>(vb, cb, c_area, c_T, th, lane, st);
-    else
-        tile_sweep<FAST, WRITE_MASK, false>(vb, cb, c_area, c_T, th, lane, st);
+    for (; tr < tr_end; ++tr) {
+        // victims of this tile: wave-uniform addresses -> scalar loads
+        const float4 *vb = box4 + tr * kTile;
+        TileState st;
+        if (tr == tc)
+            tile_sweep<FAST, WRITE_MASK, true>(vb, cb, c_area, c_T, th, lane, st);
+        else
+            tile_sweep<FAST, WRITE_MASK, false>(vb, cb, c_area, c_T, th, lane, st);
 
-    const int row = tr * kTile + lane;
-    if (WRITE_MASK) {
-        unsigned long long out = ((unsigned long long)st.w_hi << 32) | st.w_lo;
-        if (row >= n_f) out = 0;  // padding rows of the last tile
-        mask[(size_t)f * ((size_t)(n_pad / kTile) * n_pad) + (size_t)tc * n_pad + row] = out;
-    } else {
-        if (st.lane_hit && row < n_f)
-            keep_out[(size_t)f * n_max + order[(size_t)f * n_max + row]] = 0;
+        const int row = tr * kTile + lane;
+        if (WRITE_MASK) {
+            unsigned long long out = ((unsigned long long)st.w_hi << 32) | st.w_lo;
+            if (row >= n_f) out = 0;  // padding rows of the last tile
+            mask[(size_t)f * ((size_t)(n_pad / kTile) * n_pad) + (size_t)tc * n_pad + row] = out;
+        } else {
+            if (st.lane_hit && row < n_f)
+                keep_out[(size_t)f * n_max + order[(size_t)f * n_max + row]] = 0;
+        }
     }
 }
 
@@ -497,9 +571,9 @@ int rank_launch(const float *boxes, const float *scores, const int32_t *counts, 
 {
     const int n_pad = nms_padded_n(n_max);
     const int n_chunks = (n_max + kChunk - 1) / kChunk;
-    int threads = 64;
+    int threads = 64;  // four keys per thread, at least one wavefront
     const int widest = n_max < kChunk ? n_max : kChunk;
-    while (threads < 1024 && threads * 2 < widest) threads <<= 1;  // half the padded chunk size
+    while (threads < 1024 && threads * 4 < widest) threads <<= 1;
     auto *keys_ws = static_cast<unsigned long long *>(workspace);
     begin_launch();
     rank_chunk_kernel<<<dim3(n_chunks, frames), dim3(threads), 0, stream>>>(
@@ -541,7 +615,9 @@ int map_launch(const float *sorted5, const int32_t *counts, int n_max, int frame
 {
     const int n_pad = nms_padded_n(n_max);
     const int T = n_pad / kTile;
-    const int tiles = T * (T + 1) / 2;
+    // four tiles per wavefront when that still leaves every SIMD several wavefronts
+    const bool super4 = (long long)frames * triangle_units(T, 4) >= 16384;
+    const int tiles = triangle_units(T, super4 ? 4 : 1);  // work units, one per wavefront
     const NmsThetaConst th = nms_make_theta_const(threshold);
     const int tile_blocks = (tiles + kMapWaves - 1) / kMapWaves;
     // batches: one frame per XCD at a time (see the kernel); a few large frames: spread each over all XCDs
@@ -549,12 +625,16 @@ int map_launch(const float *sorted5, const int32_t *counts, int n_max, int frame
     const dim3 grid = xcd_frames ? dim3((unsigned)(((frames + 7) / 8) * 8 * tile_blocks)) : dim3(tile_blocks, frames);
     const dim3 block(kMapWaves * 64);
     begin_launch();
-    if (th.fast)
-        map_tile_kernel<true, WRITE_MASK><<<grid, block, 0, stream>>>(sorted5, counts, n_max, n_pad, tiles, tile_blocks,
-                                                                      frames, xcd_frames, th, mask, order, keep_out);
-    else
-        map_tile_kernel<false, WRITE_MASK><<<grid, block, 0, stream>>>(sorted5, counts, n_max, n_pad, tiles, tile_blocks,
-                                                                       frames, xcd_frames, th, mask, order, keep_out);
+#define NMS_LAUNCH_MAP(FAST_, SUPER_)                                                                             \
+    map_tile_kernel<FAST_, WRITE_MASK, SUPER_><<<grid, block, 0, stream>>>(sorted5, counts, n_max, n_pad, tiles,  \
+                                                                           tile_blocks, frames, xcd_frames, th,   \
+                                                                           mask, order, keep_out)
+    if (th.fast) {
+        if (super4) NMS_LAUNCH_MAP(true, 4); else NMS_LAUNCH_MAP(true, 1);
+    } else {
+        if (super4) NMS_LAUNCH_MAP(false, 4); else NMS_LAUNCH_MAP(false, 1);
+    }
+#undef NMS_LAUNCH_MAP
     return launch_status();
 }
 

@@ -112,6 +112,36 @@ def test_batched_ragged_counts(nms, oracle):
     assert np.array_equal(dev2.steps(float(theta)), want2)
 
 
+def test_batched_ragged_counts_many_frames(nms, oracle):
+    """Enough frames that the map step packs four tiles into a wavefront: ragged
+    counts, a tile-row count (11) that is not a multiple of four, both map kernels."""
+    rng = np.random.default_rng(21)
+    n_max, F = 700, 720
+    counts = rng.integers(0, n_max + 1, F).astype(np.int32)
+    counts[:8] = [0, 1, 63, 64, 65, 256, 257, n_max]
+    boxes = np.zeros((F, n_max, 4), np.float32)
+    scores = np.zeros((F, n_max), np.float32)
+    for f in range(F):
+        boxes[f], scores[f] = frame_for(n_max, seed=3000 + f)
+    theta = np.float32(0.35)
+    want = oracle_keep_frames(oracle, boxes, scores, theta, counts)
+    dev = DeviceFrames(nms, boxes, scores, counts)
+    dev.fused(float(theta), want=want)
+    assert np.array_equal(dev.steps(float(theta)), want)
+    # every mask word of three frames against the oracle's ranked view
+    n_pad, W = dev.n_pad, dev.n_pad // 64
+    masks = dev.host_mask()
+    orders = dev.host_order()
+    for f in (5, 7, 100):
+        n = int(counts[f])
+        order = oracle.order(scores[f, :n])
+        assert np.array_equal(orders[f, :n], order)
+        words = oracle.ranked_elimination_words(boxes[f, :n], order, theta)
+        got = masks[f].reshape(W, n_pad)
+        for w in range((n + 63) // 64):
+            assert np.array_equal(got[w, 64 * w:n], words[64 * w:, w]), f"frame {f}, mask word column {w}"
+
+
 def steered_pairs(F, theta, seed):
     """F two-box frames whose overlap lands within a few float32 steps of theta: a
     W x H box at the origin and a victim of the same width whose top edge is placed
@@ -230,3 +260,11 @@ def test_pool_entry_point_and_side_stream(nms, oracle):
     nms.nms_run_ws(dev.boxes, dev.scores, 1024, w.theta, keep2, ws)
     torch.cuda.synchronize()
     assert np.array_equal(keep.cpu().numpy(), want) and np.array_equal(keep2.cpu().numpy(), want)
+    # arguments marshalled once, called repeatedly
+    keep3 = torch.zeros(1024, dtype=torch.uint8, device="cuda:0")
+    plan = nms.RunPlan(dev.boxes, dev.scores, None, 1024, 1, w.theta, keep3, ws)
+    for _ in range(3):
+        keep3.fill_(5)
+        plan()
+        torch.cuda.synchronize()
+        assert np.array_equal(keep3.cpu().numpy(), want)
