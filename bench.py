@@ -204,7 +204,23 @@ def main():
             "frac_hbm_peak_reduce": round(tri_bytes / (split[2] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
             "keep_equals_fused": bool(torch.equal(keep3, d["keep"])),
         }
-        del order, sorted5, mask, keep3
+        # the selectable classic greedy rule on the same mask (sequential sweep, one workgroup per frame)
+        keep_g = torch.empty((w.frames, w.n), dtype=torch.uint8, device=dev)
+        tg = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        sweep_ms = 0.0
+        for _ in range(steps3):
+            tg[0].record()
+            nms.nms_reduce_greedy_batched(mask, order, None, w.n, w.frames, keep_g)
+            tg[1].record()
+            torch.cuda.synchronize()
+            sweep_ms += tg[0].elapsed_time(tg[1]) / steps3
+        extra["greedy_rule"] = {
+            "sweep_ms": round(sweep_ms, 4),
+            "ms_per_step_rank_mask_sweep": round(split[0] + split[1] + sweep_ms, 4),
+            "survivors": int(keep_g.sum().item()),
+            "survivors_paper_rule": int(d["keep"].sum().item()),
+        }
+        del order, sorted5, mask, keep3, keep_g
 
         # -------------------------------------------------------------- the other configurations (latency view)
         others = {}

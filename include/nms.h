@@ -151,6 +151,23 @@ int nms_run_direct_batched(const float *boxes, const float *scores, const int32_
                            float threshold, uint8_t *keep_out, void *stream);
 
 /*
+ * The classic sequential greedy rule as a selectable reduce: rank r survives iff no
+ * SURVIVING better-ranked box eliminates it (the procedure the paper's introduction and
+ * related-work section describe; Algorithms 1 and 2 themselves let eliminated boxes
+ * eliminate too).  Same mask, same overlap measure, same tie rule; every box kept by
+ * nms_reduce is also kept here.
+ *   nms_reduce_greedy*        step 3 alternative on the mask of step 2
+ *   nms_run_greedy_batched    rank + map + greedy sweep; needs the mask in its workspace:
+ *                             >= nms_greedy_workspace_bytes(n_max, frames) bytes, 256-byte aligned
+ */
+int nms_reduce_greedy(const uint64_t *mask, const int32_t *order, int n, uint8_t *keep_out, void *stream);
+int nms_reduce_greedy_batched(const uint64_t *mask, const int32_t *order, const int32_t *counts, int n_max,
+                              int frames, uint8_t *keep_out, void *stream);
+size_t nms_greedy_workspace_bytes(int n_max, int frames);   /* host-only, pure; 0 on invalid arguments */
+int nms_run_greedy_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                           float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * Profiling variant of nms_run_batched: identical work, and in addition records the
  * caller's HIP events on `stream`.  `events` is a HOST array of three hipEvent_t
  * (each may be NULL = skip): [0] before the rank step, [1] between rank and map,

@@ -23,7 +23,8 @@ EXPORTS = (
     "nms_sort_workspace_bytes", "nms_workspace_bytes",
     "nms_sort", "nms_sort_batched", "nms_overlap_mask", "nms_overlap_mask_batched",
     "nms_reduce", "nms_reduce_batched", "nms_run_ws", "nms_run_batched", "nms_run_ranked_batched", "nms_run_direct_batched",
-    "nms_run_batched_profiled",
+    "nms_run_batched_profiled", "nms_reduce_greedy", "nms_reduce_greedy_batched",
+    "nms_greedy_workspace_bytes", "nms_run_greedy_batched",
     "nms_init", "nms_shutdown", "nms_run", "nms_host_pair_test",
 )
 
@@ -85,6 +86,14 @@ def _load() -> ctypes.CDLL:
     L.nms_run_ranked_batched.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp, sz, vp]
     L.nms_run_direct_batched.restype = i32
     L.nms_run_direct_batched.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp]
+    L.nms_reduce_greedy.restype = i32
+    L.nms_reduce_greedy.argtypes = [vp, vp, i32, vp, vp]
+    L.nms_reduce_greedy_batched.restype = i32
+    L.nms_reduce_greedy_batched.argtypes = [vp, vp, vp, i32, i32, vp, vp]
+    L.nms_greedy_workspace_bytes.restype = sz
+    L.nms_greedy_workspace_bytes.argtypes = [i32, i32]
+    L.nms_run_greedy_batched.restype = i32
+    L.nms_run_greedy_batched.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp, sz, vp]
     L.nms_run_batched_profiled.restype = i32
     L.nms_run_batched_profiled.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp, sz, vp, ctypes.POINTER(vp)]
     L.nms_init.restype = i32
@@ -270,6 +279,30 @@ def nms_run_batched_profiled(boxes, scores, counts, n_max, frames, threshold, ke
                                         _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
                                         _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream), ev),
            "nms_run_batched_profiled")
+
+
+def nms_reduce_greedy(mask, order, n, keep_out, stream=None):
+    _check(lib.nms_reduce_greedy(_ptr(mask, "int64", "mask"), _ptr(order, "int32", "order"), int(n),
+                                 _ptr(keep_out, "uint8", "keep_out"), _stream(stream)), "nms_reduce_greedy")
+
+
+def nms_reduce_greedy_batched(mask, order, counts, n_max, frames, keep_out, stream=None):
+    _check(lib.nms_reduce_greedy_batched(_ptr(mask, "int64", "mask"), _ptr(order, "int32", "order"),
+                                         _ptr(counts, "int32", "counts"), int(n_max), int(frames),
+                                         _ptr(keep_out, "uint8", "keep_out"), _stream(stream)),
+           "nms_reduce_greedy_batched")
+
+
+def nms_greedy_workspace_bytes(n_max: int, frames: int) -> int:
+    return int(lib.nms_greedy_workspace_bytes(int(n_max), int(frames)))
+
+
+def nms_run_greedy_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib.nms_run_greedy_batched(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
+                                      _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
+                                      _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream)),
+           "nms_run_greedy_batched")
 
 
 def nms_init(n_max, frames_max, workspace):

@@ -68,12 +68,51 @@ __device__ __forceinline__ void compare_exchange(unsigned long long &lo, unsigne
     hi = b;
 }
 
+// Value of lane (l ^ J) for every lane l of the wavefront.  J = 1, 2: one DPP quad
+// permutation; J = 4, 8: two DPP row shifts, each enabled for the banks (groups of four
+// lanes) that look in its direction; J = 16, 32: ds_bpermute (crosses DPP rows).
+template <int J>
+__device__ __forceinline__ unsigned lane_xor(unsigned v, int lane)
+{
+    if (J == 1) return (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xf, 0xf, false);  // quad_perm [1,0,3,2]
+    if (J == 2) return (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xf, 0xf, false);  // quad_perm [2,3,0,1]
+    if (J == 4) {
+        int r = __builtin_amdgcn_update_dpp((int)v, (int)v, 0x104, 0xf, 0x5, false);  // row_shl:4 -> banks 0,2 read lane+4
+        return (unsigned)__builtin_amdgcn_update_dpp(r, (int)v, 0x114, 0xf, 0xA, false);  // row_shr:4 -> banks 1,3 read lane-4
+    }
+    if (J == 8) {
+        int r = __builtin_amdgcn_update_dpp((int)v, (int)v, 0x108, 0xf, 0x3, false);  // row_shl:8 -> banks 0,1 read lane+8
+        return (unsigned)__builtin_amdgcn_update_dpp(r, (int)v, 0x118, 0xf, 0xC, false);  // row_shr:8 -> banks 2,3 read lane-8
+    }
+    return (unsigned)__builtin_amdgcn_ds_bpermute((lane ^ J) << 2, (int)v);
+}
+
+// One stage of the bitonic network with stride J < 64 on the four keys of every lane.
+template <int J>
+__device__ __forceinline__ void lane_stage(unsigned long long (&K)[4], const int (&e)[4], int k, int lane)
+{
+    // lanes that hold the lower element of their pair: a constant lane mask per stride
+    constexpr unsigned long long kLowerLanes = J == 1 ? 0x5555555555555555ull : J == 2 ? 0x3333333333333333ull
+                                             : J == 4 ? 0x0f0f0f0f0f0f0f0full : J == 8 ? 0x00ff00ff00ff00ffull
+                                             : J == 16 ? 0x0000ffff0000ffffull : 0x00000000ffffffffull;
+    const bool lower = __builtin_amdgcn_inverse_ballot_w64(kLowerLanes);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const unsigned lo = lane_xor<J>((unsigned)K[q], lane);
+        const unsigned hi = lane_xor<J>((unsigned)(K[q] >> 32), lane);
+        const unsigned long long other = ((unsigned long long)hi << 32) | lo;
+        const bool take_min = lower == ((e[q] & k) == 0);
+        const bool other_smaller = other < K[q];
+        K[q] = (take_min == other_smaller) ? other : K[q];
+    }
+}
+
 // One workgroup ranks one chunk of up to kChunk boxes of one frame with a bitonic
 // network over P = 4 * blockDim.x keys (P a power of two, 256..4096).  Each thread keeps
 // four keys in registers: wavefront w owns elements 256w..256w+255, lane l holds elements
 // 256w + 64q + l (q = 0..3).  Strides 64 and 128 are exchanges between a thread's own
-// registers, strides 1..32 are lane shuffles, and only strides >= 256 (between
-// wavefronts) go through LDS with workgroup barriers: 18 barriers for 4096 keys instead of
+// registers, strides 1..32 are lane exchanges (DPP up to 8, ds_bpermute for 16 and 32),
+// and only strides >= 256 (between wavefronts) go through LDS with workgroup barriers: 18 barriers for 4096 keys instead of
 // one per stage (78).
 // With a single chunk the kernel also writes order / sorted5 (and, for the fused path,
 // presets keep_out); with several chunks it leaves the chunk's sorted keys in `keys_ws`
@@ -138,16 +177,13 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
             compare_exchange(K[0], K[1], (e[0] & k) == 0);
             compare_exchange(K[2], K[3], (e[2] & k) == 0);
         }
-        for (int j = (k >> 1) < 32 ? (k >> 1) : 32; j >= 1; j >>= 1) {  // strides <= 32: lane shuffles
-            const bool lower = (lane & j) == 0;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const unsigned long long other = __shfl_xor(K[q], j);
-                const bool take_min = lower == ((e[q] & k) == 0);
-                const bool other_smaller = other < K[q];
-                K[q] = (take_min == other_smaller) ? other : K[q];
-            }
-        }
+        // strides <= 32: exchanges between lanes of the wavefront
+        if (k >= 64) lane_stage<32>(K, e, k, lane);
+        if (k >= 32) lane_stage<16>(K, e, k, lane);
+        if (k >= 16) lane_stage<8>(K, e, k, lane);
+        if (k >= 8) lane_stage<4>(K, e, k, lane);
+        if (k >= 4) lane_stage<2>(K, e, k, lane);
+        lane_stage<1>(K, e, k, lane);
     }
     // sorted keys back to LDS for the gather below (each thread wrote and read only its own
     // slots since the last barrier, so no barrier is needed before these stores)
@@ -525,6 +561,66 @@ reduce_rows_kernel(const unsigned long long *__restrict__ mask, const int32_t *_
     }
 }
 
+// ----------------------------------------------------------------------------- greedy sweep
+
+// The classic sequential procedure on the same mask: rank r survives iff no SURVIVING
+// better-ranked box eliminates it.  (Not what the paper's Algorithm 2 computes -- there
+// every better-ranked box counts -- but the rule its introduction describes; offered as a
+// selectable reduce.)  One workgroup per frame walks the tile rows in rank order:
+//   - the wavefront that owns tile t (t mod 4) settles its 64 rows: rows already marked
+//     dead by earlier survivors are out; among the rest, survivors inside the tile are the
+//     unique solution of  kept[r] = alive[r] and no kept c < r of this tile hits r,  found by
+//     iterating that equation from kept = alive until it stops changing (row r is final
+//     after r+1 rounds at most; typically a few rounds);
+//   - after a barrier every wavefront applies tile t's survivors to the later tiles it
+//     owns: dead |= (mask word of column tile t) & kept_t, one coalesced 512-byte read per
+//     tile, and records the result as a ballot in LDS (each tile has one owner: no atomics).
+__global__ void __launch_bounds__(256)
+greedy_sweep_kernel(const unsigned long long *__restrict__ mask, const int32_t *__restrict__ order,
+                    const int32_t *__restrict__ counts, int n_max, int n_pad, uint8_t *__restrict__ keep_out)
+{
+    __shared__ unsigned long long dead_s[NMS_MAX_N / kTile];
+    __shared__ unsigned long long kept_s[NMS_MAX_N / kTile];
+    const int f = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int n_f = frame_count(counts, f, n_max);
+    const int tiles_f = (n_f + kTile - 1) / kTile;
+    const unsigned long long *m = mask + (size_t)f * ((size_t)(n_pad / kTile) * n_pad);
+    uint8_t *keep_f = keep_out + (size_t)f * n_max;
+
+    for (int j = threadIdx.x; j < tiles_f; j += blockDim.x) dead_s[j] = 0;
+    __syncthreads();
+
+    for (int t = 0; t < tiles_f; ++t) {
+        if (wave == (t & 3)) {
+            const int r = t * kTile + lane;
+            const bool alive = r < n_f && ((dead_s[t] >> lane) & 1ull) == 0;
+            const unsigned long long diag = m[(size_t)t * n_pad + r];  // better-ranked boxes of this tile that hit r
+            unsigned long long kept = __ballot(alive);
+            for (int round = 0; round < kTile; ++round) {
+                const unsigned long long next = __ballot(alive && (diag & kept) == 0);
+                if (next == kept) break;
+                kept = next;
+            }
+            if (lane == 0) kept_s[t] = kept;
+            if (r < n_f) keep_f[order[(size_t)f * n_max + r]] = (uint8_t)((kept >> lane) & 1ull);
+        }
+        __syncthreads();
+        const unsigned long long kept_t = kept_s[t];
+        if (kept_t != 0) {
+            int j = t + 1;
+            j += (wave - j) & 3;  // first later tile owned by this wavefront
+            for (; j < tiles_f; j += 4) {
+                const unsigned long long word = m[(size_t)t * n_pad + j * kTile + lane];
+                const unsigned long long hit = __ballot((word & kept_t) != 0);
+                if (lane == 0 && hit != 0) dead_s[j] |= hit;
+            }
+        }
+    }
+    for (int i = n_f + (int)threadIdx.x; i < n_max; i += blockDim.x) keep_f[i] = 0;  // slots beyond the count
+}
+
 // ----------------------------------------------------------------------------- host side
 
 struct Pool {
@@ -822,6 +918,60 @@ int nms_run_direct_batched(const float *boxes, const float *scores, const int32_
 {
     return run_routed(kRouteDirect, boxes, scores, counts, n_max, frames, threshold, keep_out, nullptr, 0, stream,
                       nullptr);
+}
+
+int nms_reduce_greedy_batched(const uint64_t *mask, const int32_t *order, const int32_t *counts, int n_max,
+                              int frames, uint8_t *keep_out, void *stream)
+{
+    int st;
+    if (!sizes_ok(n_max, frames, &st)) return st;
+    if (n_max == 0 || frames == 0) return NMS_OK;
+    if (!mask || !order || !keep_out) return NMS_ERR_INVALID_ARG;
+    begin_launch();
+    greedy_sweep_kernel<<<dim3(frames), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
+        reinterpret_cast<const unsigned long long *>(mask), order, counts, n_max, nms_padded_n(n_max), keep_out);
+    return launch_status();
+}
+
+int nms_reduce_greedy(const uint64_t *mask, const int32_t *order, int n, uint8_t *keep_out, void *stream)
+{
+    return nms_reduce_greedy_batched(mask, order, nullptr, n, 1, keep_out, stream);
+}
+
+size_t nms_greedy_workspace_bytes(int n_max, int frames)
+{
+    int st;
+    if (!sizes_ok(n_max, frames, &st)) return 0;
+    return nms_workspace_bytes(n_max, frames) + align256((size_t)frames * nms_mask_words(n_max) * sizeof(uint64_t));
+}
+
+int nms_run_greedy_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                           float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream)
+{
+    int st;
+    if (!sizes_ok(n_max, frames, &st)) return st;
+    if (is_nan(threshold)) return NMS_ERR_INVALID_ARG;
+    if (n_max == 0 || frames == 0) return NMS_OK;
+    if (!boxes || !scores || !keep_out) return NMS_ERR_INVALID_ARG;
+    if (!workspace || ws_bytes < nms_greedy_workspace_bytes(n_max, frames) || ((uintptr_t)workspace & 255))
+        return NMS_ERR_WORKSPACE;
+    const size_t n_pad = (size_t)nms_padded_n(n_max);
+    char *p = static_cast<char *>(workspace);
+    int32_t *order = reinterpret_cast<int32_t *>(p);
+    p += align256((size_t)frames * n_max * sizeof(int32_t));
+    float *sorted5 = reinterpret_cast<float *>(p);
+    p += align256((size_t)frames * 5 * n_pad * sizeof(float));
+    void *keys_ws = p;
+    p += nms_sort_workspace_bytes(n_max, frames);
+    unsigned long long *mask = reinterpret_cast<unsigned long long *>(p);
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    st = rank_launch(boxes, scores, counts, n_max, frames, order, sorted5, keys_ws, nullptr, s);
+    if (st != NMS_OK) return st;
+    st = map_launch<true>(sorted5, counts, n_max, frames, threshold, mask, nullptr, nullptr, s);
+    if (st != NMS_OK) return st;
+    return nms_reduce_greedy_batched(reinterpret_cast<const uint64_t *>(mask), order, counts, n_max, frames, keep_out,
+                                     stream);
 }
 
 int nms_run_ws(const float *boxes, const float *scores, int n, float threshold,

@@ -7,16 +7,17 @@ from concurrent.futures import ThreadPoolExecutor
 import numpy as np
 
 
-def oracle_keep_frames(oracle, boxes, scores, theta, counts=None, workers=16):
-    """oracle.keep per frame (the C call releases the GIL) -> [F, n_max] uint8,
-    zero beyond each frame's count."""
+def oracle_keep_frames(oracle, boxes, scores, theta, counts=None, workers=16, rule="paper"):
+    """oracle.keep (or oracle.greedy_keep) per frame (the C call releases the GIL)
+    -> [F, n_max] uint8, zero beyond each frame's count."""
     F, n_max = scores.shape
     out = np.zeros((F, n_max), np.uint8)
+    fn = oracle.keep if rule == "paper" else oracle.greedy_keep
 
     def one(f):
         n = n_max if counts is None else int(counts[f])
         if n > 0:
-            out[f, :n] = oracle.keep(boxes[f, :n], scores[f, :n], theta)
+            out[f, :n] = fn(boxes[f, :n], scores[f, :n], theta)
 
     with ThreadPoolExecutor(max_workers=workers) as pool:
         list(pool.map(one, range(F)))
@@ -76,6 +77,23 @@ class DeviceFrames:
                 direct = self.keep.cpu().numpy()
                 assert np.array_equal(direct, want), f"direct route: {(direct != want).sum()} differing keep bits"
         return got
+
+    def greedy(self, theta):
+        """Greedy rule two ways: nms_reduce_greedy_batched on the mask of the step calls, and
+        the one-call nms_run_greedy_batched.  Returns both keep arrays."""
+        nms = self.nms
+        nms.nms_sort_batched(self.boxes, self.scores, self.counts, self.n_max, self.F, self.order, self.sorted5, self.sort_ws)
+        nms.nms_overlap_mask_batched(self.sorted5, self.counts, self.n_max, self.F, theta, self.mask)
+        self.keep.fill_(77)
+        nms.nms_reduce_greedy_batched(self.mask, self.order, self.counts, self.n_max, self.F, self.keep)
+        self.torch.cuda.synchronize()
+        via_steps = self.keep.cpu().numpy()
+        ws = self.torch.zeros(max(nms.nms_greedy_workspace_bytes(self.n_max, self.F), 256), dtype=self.torch.uint8,
+                              device=self.boxes.device)
+        self.keep.fill_(77)
+        nms.nms_run_greedy_batched(self.boxes, self.scores, self.counts, self.n_max, self.F, theta, self.keep, ws)
+        self.torch.cuda.synchronize()
+        return via_steps, self.keep.cpu().numpy()
 
     def host_order(self):
         return self.order.cpu().numpy()

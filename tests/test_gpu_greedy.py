@@ -1,0 +1,73 @@
+"""The selectable classic greedy rule (a box is eliminated only by SURVIVING better-ranked
+boxes) against the oracle's sequential implementation, 0 differing bits."""
+import numpy as np
+import pytest
+
+from gpu_util import DeviceFrames, oracle_keep_frames
+from pins import staircase
+from workloads import make_config, random_frame
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def nms():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2502_00535_amd.binding as binding
+
+    return binding
+
+
+def check(nms, oracle, boxes, scores, theta, counts=None):
+    want = oracle_keep_frames(oracle, boxes, scores, np.float32(theta), counts, rule="greedy")
+    dev = DeviceFrames(nms, boxes, scores, counts)
+    via_steps, one_call = dev.greedy(float(theta))
+    assert np.array_equal(via_steps, want), f"{(via_steps != want).sum()} differing keep bits (reduce_greedy)"
+    assert np.array_equal(one_call, want), f"{(one_call != want).sum()} differing keep bits (run_greedy)"
+    return want
+
+
+@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 128, 129, 1000, 1024, 4096, 4097, 9000])
+def test_single_frame(nms, oracle, n):
+    print(f"case n={n}", flush=True)
+    boxes, scores = random_frame(7000 + n, n, extent=1500 if n > 600 else 300, max_side=90,
+                                 integer=(n % 2 == 0), score_levels=max(3, n // 4))
+    check(nms, oracle, boxes[None], scores[None], [0.5, 0.3, 0.45][n % 3])
+
+
+def test_long_chains(nms, oracle):
+    """Staircase of boxes: each eliminates only its successor, so survivors alternate and
+    the tile-internal fixed point needs its full depth; chains cross tile borders."""
+    for N in (64, 65, 200, 1000):
+        boxes, scores = staircase(N)
+        want = check(nms, oracle, boxes[None], scores[None], 0.5)
+        assert want[0].tolist() == [1 - (k & 1) for k in range(N)]
+        want = check(nms, oracle, boxes[None], scores[None], np.float32(0.4))
+        assert want[0].tolist() == [1 if k % 3 == 0 else 0 for k in range(N)]
+        # reversed input: ranks run against the index order
+        check(nms, oracle, boxes[::-1].copy()[None], scores[::-1].copy()[None], 0.5)
+
+
+def test_batched_ragged(nms, oracle):
+    rng = np.random.default_rng(77)
+    n_max, F = 500, 48
+    counts = rng.integers(0, n_max + 1, F).astype(np.int32)
+    counts[:6] = [0, 1, 64, 65, n_max, 257]
+    boxes = np.zeros((F, n_max, 4), np.float32)
+    scores = np.zeros((F, n_max), np.float32)
+    for f in range(F):
+        boxes[f], scores[f] = random_frame(8000 + f, n_max, extent=300, max_side=90, integer=(f % 2 == 0),
+                                           score_levels=60)
+    check(nms, oracle, boxes, scores, 0.4, counts)
+
+
+@pytest.mark.parametrize("index", [0, 1, 2, 3, 4])
+def test_configs_full_size(nms, oracle, index):
+    print(f"case config {index}", flush=True)
+    w = make_config(index)
+    want = check(nms, oracle, w.boxes, w.scores, w.theta)
+    paper = oracle_keep_frames(oracle, w.boxes, w.scores, np.float32(w.theta))
+    assert not (paper & ~want & 1).any()       # the paper's rule keeps a subset
+    assert want.sum() > paper.sum()            # and a strict one on these workloads
