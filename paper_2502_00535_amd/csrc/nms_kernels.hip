@@ -574,7 +574,8 @@ reduce_rows_kernel(const unsigned long long *__restrict__ mask, const int32_t *_
 //     after r+1 rounds at most; typically a few rounds);
 //   - after a barrier every wavefront applies tile t's survivors to the later tiles it
 //     owns: dead |= (mask word of column tile t) & kept_t, one coalesced 512-byte read per
-//     tile, and records the result as a ballot in LDS (each tile has one owner: no atomics).
+//     tile (issued one step ahead), and records the result as a ballot in LDS (each tile
+//     has one owner: no atomics).
 __global__ void __launch_bounds__(256)
 greedy_sweep_kernel(const unsigned long long *__restrict__ mask, const int32_t *__restrict__ order,
                     const int32_t *__restrict__ counts, int n_max, int n_pad, uint8_t *__restrict__ keep_out)
@@ -592,11 +593,33 @@ greedy_sweep_kernel(const unsigned long long *__restrict__ mask, const int32_t *
     for (int j = threadIdx.x; j < tiles_f; j += blockDim.x) dead_s[j] = 0;
     __syncthreads();
 
+    // The mask words a step needs do not depend on the step before it, only what is done
+    // with them does.  They are therefore fetched one step ahead (up to kAhead tiles per
+    // wavefront, which covers frames of up to 64 * 4 * kAhead boxes completely) so that the
+    // memory latency overlaps the previous tile's settling and barrier.
+    constexpr int kAhead = 16;
+    unsigned long long ahead[kAhead];
+    unsigned long long diag_ahead = 0;
+    auto fetch = [&](int t) {
+        if (t >= tiles_f) return;
+        int j = t + 1;
+        j += (wave - j) & 3;  // first later tile owned by this wavefront
+#pragma unroll
+        for (int i = 0; i < kAhead; ++i, j += 4)
+            ahead[i] = j < tiles_f ? m[(size_t)t * n_pad + j * kTile + lane] : 0ull;
+        if (wave == (t & 3)) diag_ahead = m[(size_t)t * n_pad + t * kTile + lane];
+    };
+    fetch(0);
+
     for (int t = 0; t < tiles_f; ++t) {
+        unsigned long long cur[kAhead];
+#pragma unroll
+        for (int i = 0; i < kAhead; ++i) cur[i] = ahead[i];
+        const unsigned long long diag = diag_ahead;  // better-ranked boxes of tile t that hit row 64t+lane
+        fetch(t + 1);
         if (wave == (t & 3)) {
             const int r = t * kTile + lane;
             const bool alive = r < n_f && ((dead_s[t] >> lane) & 1ull) == 0;
-            const unsigned long long diag = m[(size_t)t * n_pad + r];  // better-ranked boxes of this tile that hit r
             unsigned long long kept = __ballot(alive);
             for (int round = 0; round < kTile; ++round) {
                 const unsigned long long next = __ballot(alive && (diag & kept) == 0);
@@ -610,8 +633,15 @@ greedy_sweep_kernel(const unsigned long long *__restrict__ mask, const int32_t *
         const unsigned long long kept_t = kept_s[t];
         if (kept_t != 0) {
             int j = t + 1;
-            j += (wave - j) & 3;  // first later tile owned by this wavefront
-            for (; j < tiles_f; j += 4) {
+            j += (wave - j) & 3;
+#pragma unroll
+            for (int i = 0; i < kAhead; ++i, j += 4) {
+                if (j < tiles_f) {  // uniform
+                    const unsigned long long hit = __ballot((cur[i] & kept_t) != 0);
+                    if (lane == 0 && hit != 0) dead_s[j] |= hit;
+                }
+            }
+            for (; j < tiles_f; j += 4) {  // frames beyond the look-ahead window
                 const unsigned long long word = m[(size_t)t * n_pad + j * kTile + lane];
                 const unsigned long long hit = __ballot((word & kept_t) != 0);
                 if (lane == 0 && hit != 0) dead_s[j] |= hit;
