@@ -43,19 +43,24 @@ __device__ __forceinline__ unsigned long long rank_key(float score, unsigned idx
     return ((unsigned long long)(~asc) << 32) | idx;
 }
 
-__device__ __forceinline__ void emit_ranked_box(const float *boxes_f, int idx, int r, int n_pad,
-                                               int32_t *order_f, float *sorted_f)
+// Rank-ordered row r: the box and its area, and (fused path only, ysc != nullptr) the same
+// box with y multiplied by NMS_YSCALE.  Returns whether the box may use the y-scaled form.
+__device__ __forceinline__ bool emit_ranked_box(const float *boxes_f, int idx, int r, int n_pad,
+                                               int32_t *order_f, float *sorted_f, float4 *ysc_f)
 {
     const float4 b = reinterpret_cast<const float4 *>(boxes_f)[idx];
     order_f[r] = idx;
     reinterpret_cast<float4 *>(sorted_f)[r] = b;
     sorted_f[4 * (size_t)n_pad + r] = nms_box_area(b.x, b.y, b.z, b.w);
+    if (ysc_f != nullptr) ysc_f[r] = make_float4(b.x, b.y * NMS_YSCALE, b.z, b.w * NMS_YSCALE);
+    return nms_y_regular(b.y) && nms_y_regular(b.w);
 }
 
-__device__ __forceinline__ void emit_padding_row(int r, int n_pad, float *sorted_f)
+__device__ __forceinline__ void emit_padding_row(int r, int n_pad, float *sorted_f, float4 *ysc_f)
 {
     reinterpret_cast<float4 *>(sorted_f)[r] = make_float4(0.f, 0.f, 0.f, 0.f);
     sorted_f[4 * (size_t)n_pad + r] = 1.0f;  // the one-pixel box (0,0,0,0): never divides by zero
+    if (ysc_f != nullptr) ysc_f[r] = make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
 // Compare-exchange: afterwards lo <= hi when `up`, lo >= hi otherwise.
@@ -121,7 +126,8 @@ __global__ void __launch_bounds__(1024)
 rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ scores,
                   const int32_t *__restrict__ counts, int n_max, int n_pad, int n_chunks,
                   int32_t *__restrict__ order, float *__restrict__ sorted5,
-                  unsigned long long *__restrict__ keys_ws, uint8_t *__restrict__ keep_preset)
+                  unsigned long long *__restrict__ keys_ws, uint8_t *__restrict__ keep_preset,
+                  float4 *__restrict__ ysc, unsigned *__restrict__ ytile)
 {
     __shared__ unsigned long long keys[kChunk];
     const int f = blockIdx.y;
@@ -194,16 +200,27 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
     const float *boxes_f = boxes + (size_t)f * n_max * 4;
     int32_t *order_f = order + (size_t)f * n_max;
     float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
+    float4 *ysc_f = ysc ? ysc + (size_t)f * n_pad : nullptr;
+    unsigned *ytile_f = ytile ? ytile + (size_t)f * (n_pad / kTile) : nullptr;
     if (n_chunks == 1) {
+        // a wavefront covers 64 consecutive ranks = one tile per trip (nth is a multiple of 64)
         for (int r = tid; r < n_pad; r += nth) {
+            bool regular = true;
             if (r < n_f)
-                emit_ranked_box(boxes_f, (int)(unsigned)keys[r], r, n_pad, order_f, sorted_f);
+                regular = emit_ranked_box(boxes_f, (int)(unsigned)keys[r], r, n_pad, order_f, sorted_f, ysc_f);
             else
-                emit_padding_row(r, n_pad, sorted_f);
+                emit_padding_row(r, n_pad, sorted_f, ysc_f);
+            if (ytile_f != nullptr) {
+                const unsigned long long irregular = __ballot(!regular);
+                if (lane == 0) ytile_f[r / kTile] = irregular == 0 ? 1u : 0u;
+            }
         }
     } else {
         unsigned long long *kw = keys_ws + (size_t)f * n_pad + base;
         for (int i = tid; i < cnt; i += nth) kw[i] = keys[i];
+        // the merge kernel scatters rows, so it can only clear tile flags: preset them here
+        if (ytile_f != nullptr && chunk == 0)
+            for (int t = tid; t < n_pad / kTile; t += nth) ytile_f[t] = 1u;
     }
     if (keep_preset != nullptr) {
         // fused path: every real box starts as a survivor, slots beyond the count are 0
@@ -218,15 +235,17 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
 __global__ void __launch_bounds__(256)
 rank_merge_kernel(const float *__restrict__ boxes, const int32_t *__restrict__ counts, int n_max, int n_pad,
                   int n_chunks, const unsigned long long *__restrict__ keys_ws,
-                  int32_t *__restrict__ order, float *__restrict__ sorted5)
+                  int32_t *__restrict__ order, float *__restrict__ sorted5,
+                  float4 *__restrict__ ysc, unsigned *__restrict__ ytile)
 {
     const int f = blockIdx.y;
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= n_pad) return;
     const int n_f = frame_count(counts, f, n_max);
     float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
+    float4 *ysc_f = ysc ? ysc + (size_t)f * n_pad : nullptr;
     if (e >= n_f) {
-        emit_padding_row(e, n_pad, sorted_f);
+        emit_padding_row(e, n_pad, sorted_f, ysc_f);
         return;
     }
     const unsigned long long *kw = keys_ws + (size_t)f * n_pad;
@@ -245,8 +264,10 @@ rank_merge_kernel(const float *__restrict__ boxes, const int32_t *__restrict__ c
         }
         rank += lo;
     }
-    emit_ranked_box(boxes + (size_t)f * n_max * 4, (int)(unsigned)key, rank, n_pad,
-                    order + (size_t)f * n_max, sorted_f);
+    const bool regular = emit_ranked_box(boxes + (size_t)f * n_max * 4, (int)(unsigned)key, rank, n_pad,
+                                         order + (size_t)f * n_max, sorted_f, ysc_f);
+    // tile flags were preset to 1 by the chunk kernel; concurrent writers all store 0
+    if (ytile != nullptr && !regular) ytile[(size_t)f * (n_pad / kTile) + rank / kTile] = 0u;
 }
 
 // ----------------------------------------------------------------------------- map
@@ -288,9 +309,14 @@ struct TileState {
 // the 64 outranking boxes held one per lane.  The ballot of the compare is the
 // elimination word of row r.  Rows go in 4 groups of 16 in a real loop, so that at
 // most 64 victim SGPRs are live at a time.
-template <bool FAST, bool WRITE_MASK, bool DIAG>
+// Which evaluation of the pair test a tile uses.
+enum { kPairExact = 0, kPairFast = 1, kPairFastYScaled = 2 };
+
+// For kPairFastYScaled, vb/cb hold y * NMS_YSCALE, c_T is NMS_YSCALE * T and y_one is
+// NMS_YSCALE in a vector register.
+template <int PAIR, bool WRITE_MASK, bool DIAG>
 __device__ __forceinline__ void tile_sweep(const float4 *__restrict__ vb, const float4 cb, float c_area, float c_T,
-                                           const NmsThetaConst &th, int lane, TileState &st)
+                                           float y_one, const NmsThetaConst &th, int lane, TileState &st)
 {
 #pragma unroll 1
     for (int grp = 0; grp < kTile / 16; ++grp) {
@@ -301,7 +327,9 @@ __device__ __forceinline__ void tile_sweep(const float4 *__restrict__ vb, const 
             const int r = 16 * grp + k;
             const float4 v = vg[k];
             bool hit;
-            if (FAST)
+            if (PAIR == kPairFastYScaled)
+                hit = nms_eliminates_fast_yscaled(v.x, v.y, v.z, v.w, cb.x, cb.y, cb.z, cb.w, c_T, y_one);
+            else if (PAIR == kPairFast)
                 hit = nms_eliminates_fast(v.x, v.y, v.z, v.w, cb.x, cb.y, cb.z, cb.w, c_T);
             else
                 hit = nms_eliminates_exact(v.x, v.y, v.z, v.w, cb.x, cb.y, cb.z, cb.w, c_area, th.theta);
@@ -332,7 +360,7 @@ __global__ void __launch_bounds__(kMapWaves * 64)
 map_tile_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ counts, int n_max, int n_pad,
                 int tiles, int tile_blocks, int frames, int xcd_frames, NmsThetaConst th,
                 unsigned long long *__restrict__ mask, const int32_t *__restrict__ order,
-                uint8_t *__restrict__ keep_out)
+                uint8_t *__restrict__ keep_out, const float4 *__restrict__ ysc, const unsigned *__restrict__ ytile)
 {
     const int lane = threadIdx.x & 63;
     int f, bx;
@@ -367,14 +395,34 @@ map_tile_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ c
     const float c_area = area[tc * kTile + lane];
     const float c_T = FAST ? nms_pair_threshold(c_area, th.m) : 0.0f;
 
+    // y-scaled form (fused kernel with a fast threshold only; its launcher always passes the
+    // scaled table): usable for a tile pair when the rank step flagged both tiles regular.
+    // The pointers are formed unconditionally so that the victims' loads stay scalar loads.
+    constexpr bool kScaled = FAST && !WRITE_MASK;
+    const float4 *__restrict__ ysc4 = ysc + (size_t)f * n_pad;
+    const unsigned *__restrict__ ytile_f = ytile + (size_t)f * (n_pad / kTile);
+    bool c_regular = false;
+    if (kScaled) c_regular = ytile_f[tc] != 0;
+    const float4 cbs = make_float4(cb.x, cb.y * NMS_YSCALE, cb.z, cb.w * NMS_YSCALE);
+    const float c_Ts = c_T * NMS_YSCALE;
+    float y_one;  // NMS_YSCALE in a vector register (opaque to the compiler so it stays there)
+    asm volatile("v_mov_b32 %0, 0x38800000" : "=v"(y_one));
+
     for (; tr < tr_end; ++tr) {
-        // victims of this tile: wave-uniform addresses -> scalar loads
-        const float4 *vb = box4 + tr * kTile;
         TileState st;
-        if (tr == tc)
-            tile_sweep<FAST, WRITE_MASK, true>(vb, cb, c_area, c_T, th, lane, st);
-        else
-            tile_sweep<FAST, WRITE_MASK, false>(vb, cb, c_area, c_T, th, lane, st);
+        if (kScaled && c_regular && ytile_f[tr] != 0) {
+            const float4 *vb = ysc4 + tr * kTile;  // victims: wave-uniform addresses -> scalar loads
+            if (tr == tc)
+                tile_sweep<kPairFastYScaled, WRITE_MASK, true>(vb, cbs, c_area, c_Ts, y_one, th, lane, st);
+            else
+                tile_sweep<kPairFastYScaled, WRITE_MASK, false>(vb, cbs, c_area, c_Ts, y_one, th, lane, st);
+        } else {
+            const float4 *vb = box4 + tr * kTile;
+            if (tr == tc)
+                tile_sweep<FAST ? kPairFast : kPairExact, WRITE_MASK, true>(vb, cb, c_area, c_T, y_one, th, lane, st);
+            else
+                tile_sweep<FAST ? kPairFast : kPairExact, WRITE_MASK, false>(vb, cb, c_area, c_T, y_one, th, lane, st);
+        }
 
         const int row = tr * kTile + lane;
         if (WRITE_MASK) {
@@ -693,7 +741,8 @@ inline int launch_status()
 }
 
 int rank_launch(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
-                int32_t *order, float *sorted5, void *workspace, uint8_t *keep_preset, hipStream_t stream)
+                int32_t *order, float *sorted5, void *workspace, uint8_t *keep_preset, float4 *ysc, unsigned *ytile,
+                hipStream_t stream)
 {
     const int n_pad = nms_padded_n(n_max);
     const int n_chunks = (n_max + kChunk - 1) / kChunk;
@@ -703,12 +752,12 @@ int rank_launch(const float *boxes, const float *scores, const int32_t *counts, 
     auto *keys_ws = static_cast<unsigned long long *>(workspace);
     begin_launch();
     rank_chunk_kernel<<<dim3(n_chunks, frames), dim3(threads), 0, stream>>>(
-        boxes, scores, counts, n_max, n_pad, n_chunks, order, sorted5, keys_ws, keep_preset);
+        boxes, scores, counts, n_max, n_pad, n_chunks, order, sorted5, keys_ws, keep_preset, ysc, ytile);
     int st = launch_status();
     if (st != NMS_OK || n_chunks == 1) return st;
     begin_launch();
     rank_merge_kernel<<<dim3((n_pad + 255) / 256, frames), dim3(256), 0, stream>>>(
-        boxes, counts, n_max, n_pad, n_chunks, keys_ws, order, sorted5);
+        boxes, counts, n_max, n_pad, n_chunks, keys_ws, order, sorted5, ysc, ytile);
     return launch_status();
 }
 
@@ -737,7 +786,8 @@ int direct_launch(const float *boxes, const float *scores, const int32_t *counts
 
 template <bool WRITE_MASK>
 int map_launch(const float *sorted5, const int32_t *counts, int n_max, int frames, float threshold,
-               unsigned long long *mask, const int32_t *order, uint8_t *keep_out, hipStream_t stream)
+               unsigned long long *mask, const int32_t *order, uint8_t *keep_out, const float4 *ysc,
+               const unsigned *ytile, hipStream_t stream)
 {
     const int n_pad = nms_padded_n(n_max);
     const int T = n_pad / kTile;
@@ -754,7 +804,7 @@ int map_launch(const float *sorted5, const int32_t *counts, int n_max, int frame
 #define NMS_LAUNCH_MAP(FAST_, SUPER_)                                                                             \
     map_tile_kernel<FAST_, WRITE_MASK, SUPER_><<<grid, block, 0, stream>>>(sorted5, counts, n_max, n_pad, tiles,  \
                                                                            tile_blocks, frames, xcd_frames, th,   \
-                                                                           mask, order, keep_out)
+                                                                           mask, order, keep_out, ysc, ytile)
     if (th.fast) {
         if (super4) NMS_LAUNCH_MAP(true, 4); else NMS_LAUNCH_MAP(true, 1);
     } else {
@@ -812,9 +862,11 @@ size_t nms_workspace_bytes(int n_max, int frames)
     int st;
     if (!sizes_ok(n_max, frames, &st)) return 0;
     const size_t n_pad = (size_t)nms_padded_n(n_max);
-    return align256((size_t)frames * n_max * sizeof(int32_t))      // order
-         + align256((size_t)frames * 5 * n_pad * sizeof(float))    // sorted5
-         + nms_sort_workspace_bytes(n_max, frames);                // chunk keys
+    return align256((size_t)frames * n_max * sizeof(int32_t))               // order
+         + align256((size_t)frames * 5 * n_pad * sizeof(float))             // sorted5
+         + align256((size_t)frames * n_pad * 4 * sizeof(float))             // y-scaled boxes
+         + align256((size_t)frames * (n_pad / kTile) * sizeof(unsigned))    // tile flags
+         + nms_sort_workspace_bytes(n_max, frames);                         // chunk keys
 }
 
 int nms_sort_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
@@ -826,7 +878,7 @@ int nms_sort_batched(const float *boxes, const float *scores, const int32_t *cou
     if (!boxes || !scores || !order || !sorted5) return NMS_ERR_INVALID_ARG;
     const size_t need = nms_sort_workspace_bytes(n_max, frames);
     if (need != 0 && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))) return NMS_ERR_WORKSPACE;
-    return rank_launch(boxes, scores, counts, n_max, frames, order, sorted5, workspace, nullptr,
+    return rank_launch(boxes, scores, counts, n_max, frames, order, sorted5, workspace, nullptr, nullptr, nullptr,
                        static_cast<hipStream_t>(stream));
 }
 
@@ -845,7 +897,7 @@ int nms_overlap_mask_batched(const float *sorted5, const int32_t *counts, int n_
     if (n_max == 0 || frames == 0) return NMS_OK;
     if (!sorted5 || !mask) return NMS_ERR_INVALID_ARG;
     return map_launch<true>(sorted5, counts, n_max, frames, threshold,
-                            reinterpret_cast<unsigned long long *>(mask), nullptr, nullptr,
+                            reinterpret_cast<unsigned long long *>(mask), nullptr, nullptr, nullptr, nullptr,
                             static_cast<hipStream_t>(stream));
 }
 
@@ -871,6 +923,35 @@ int nms_reduce_batched(const uint64_t *mask, const int32_t *order, const int32_t
 int nms_reduce(const uint64_t *mask, const int32_t *order, int n, uint8_t *keep_out, void *stream)
 {
     return nms_reduce_batched(mask, order, nullptr, n, 1, keep_out, stream);
+}
+
+// Carve-up of the fused path's workspace (every part 256-byte aligned).
+struct RunWorkspace {
+    int32_t *order;     // [frames][n_max]
+    float *sorted5;     // [frames][5 * n_pad]
+    float4 *ysc;        // [frames][n_pad]       boxes with y * NMS_YSCALE, rank order
+    unsigned *ytile;    // [frames][n_pad / 64]  1 = every box of the tile may use the y-scaled form
+    void *keys;         // rank scratch (n_max > NMS_SORT_CHUNK only)
+    char *end;
+};
+
+inline RunWorkspace carve_workspace(void *workspace, int n_max, int frames)
+{
+    const size_t n_pad = (size_t)nms_padded_n(n_max);
+    RunWorkspace w;
+    char *p = static_cast<char *>(workspace);
+    w.order = reinterpret_cast<int32_t *>(p);
+    p += align256((size_t)frames * n_max * sizeof(int32_t));
+    w.sorted5 = reinterpret_cast<float *>(p);
+    p += align256((size_t)frames * 5 * n_pad * sizeof(float));
+    w.ysc = reinterpret_cast<float4 *>(p);
+    p += align256((size_t)frames * n_pad * sizeof(float4));
+    w.ytile = reinterpret_cast<unsigned *>(p);
+    p += align256((size_t)frames * (n_pad / kTile) * sizeof(unsigned));
+    w.keys = p;
+    p += nms_sort_workspace_bytes(n_max, frames);
+    w.end = p;
+    return w;
 }
 
 enum Route { kRouteAuto = 0, kRouteRanked = 1, kRouteDirect = 2 };
@@ -905,18 +986,11 @@ static int run_routed(Route route, const float *boxes, const float *scores, cons
         return mark(2) ? NMS_OK : NMS_ERR_LAUNCH;
     }
 
-    const size_t n_pad = (size_t)nms_padded_n(n_max);
-    char *p = static_cast<char *>(workspace);
-    int32_t *order = reinterpret_cast<int32_t *>(p);
-    p += align256((size_t)frames * n_max * sizeof(int32_t));
-    float *sorted5 = reinterpret_cast<float *>(p);
-    p += align256((size_t)frames * 5 * n_pad * sizeof(float));
-    void *keys_ws = p;
-
-    st = rank_launch(boxes, scores, counts, n_max, frames, order, sorted5, keys_ws, keep_out, s);
+    const RunWorkspace w = carve_workspace(workspace, n_max, frames);
+    st = rank_launch(boxes, scores, counts, n_max, frames, w.order, w.sorted5, w.keys, keep_out, w.ysc, w.ytile, s);
     if (st != NMS_OK) return st;
     if (!mark(1)) return NMS_ERR_LAUNCH;
-    st = map_launch<false>(sorted5, counts, n_max, frames, threshold, nullptr, order, keep_out, s);
+    st = map_launch<false>(w.sorted5, counts, n_max, frames, threshold, nullptr, w.order, keep_out, w.ysc, w.ytile, s);
     if (st != NMS_OK) return st;
     return mark(2) ? NMS_OK : NMS_ERR_LAUNCH;
 }
@@ -985,20 +1059,14 @@ int nms_run_greedy_batched(const float *boxes, const float *scores, const int32_
     if (!boxes || !scores || !keep_out) return NMS_ERR_INVALID_ARG;
     if (!workspace || ws_bytes < nms_greedy_workspace_bytes(n_max, frames) || ((uintptr_t)workspace & 255))
         return NMS_ERR_WORKSPACE;
-    const size_t n_pad = (size_t)nms_padded_n(n_max);
-    char *p = static_cast<char *>(workspace);
-    int32_t *order = reinterpret_cast<int32_t *>(p);
-    p += align256((size_t)frames * n_max * sizeof(int32_t));
-    float *sorted5 = reinterpret_cast<float *>(p);
-    p += align256((size_t)frames * 5 * n_pad * sizeof(float));
-    void *keys_ws = p;
-    p += nms_sort_workspace_bytes(n_max, frames);
-    unsigned long long *mask = reinterpret_cast<unsigned long long *>(p);
+    const RunWorkspace w = carve_workspace(workspace, n_max, frames);
+    unsigned long long *mask = reinterpret_cast<unsigned long long *>(w.end);
+    int32_t *order = w.order;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    st = rank_launch(boxes, scores, counts, n_max, frames, order, sorted5, keys_ws, nullptr, s);
+    st = rank_launch(boxes, scores, counts, n_max, frames, w.order, w.sorted5, w.keys, nullptr, nullptr, nullptr, s);
     if (st != NMS_OK) return st;
-    st = map_launch<true>(sorted5, counts, n_max, frames, threshold, mask, nullptr, nullptr, s);
+    st = map_launch<true>(w.sorted5, counts, n_max, frames, threshold, mask, nullptr, nullptr, nullptr, nullptr, s);
     if (st != NMS_OK) return st;
     return nms_reduce_greedy_batched(reinterpret_cast<const uint64_t *>(mask), order, counts, n_max, frames, keep_out,
                                      stream);
@@ -1046,7 +1114,13 @@ int nms_host_pair_test(const float *victim, const float *outranking, float thres
     const NmsThetaConst th = nms_make_theta_const(threshold);
     const float a = nms_box_area(outranking[0], outranking[1], outranking[2], outranking[3]);
     bool hit;
-    if (th.fast)
+    const bool regular = nms_y_regular(victim[1]) && nms_y_regular(victim[3]) && nms_y_regular(outranking[1]) &&
+                         nms_y_regular(outranking[3]);
+    if (th.fast && regular)  // what the fused kernel does for a pair of regular tiles
+        hit = nms_eliminates_fast_yscaled(victim[0], victim[1] * NMS_YSCALE, victim[2], victim[3] * NMS_YSCALE,
+                                          outranking[0], outranking[1] * NMS_YSCALE, outranking[2],
+                                          outranking[3] * NMS_YSCALE, nms_pair_threshold(a, th.m) * NMS_YSCALE, NMS_YSCALE);
+    else if (th.fast)
         hit = nms_eliminates_fast(victim[0], victim[1], victim[2], victim[3],
                                   outranking[0], outranking[1], outranking[2], outranking[3], nms_pair_threshold(a, th.m));
     else

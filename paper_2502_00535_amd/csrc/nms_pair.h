@@ -32,6 +32,17 @@
 //
 // The fast form is used for 2^-40 <= theta <= 2^20 (no overflow or underflow for areas
 // in [1, 2^100]); any other theta takes the literal division form.
+//
+// y-scaled variant of the fast form.  max(0, .) is a half-rate VALU instruction on gfx950,
+// whereas an add with the clamp output modifier (result limited to [0, 1]) runs at full
+// rate and is the same thing as long as the sum stays below 1.  So the y coordinates are
+// carried multiplied by S = 2^-14 and the "+1" becomes "+S":
+//     ih_S = clamp01((min(y2_v S, y2_c S) - max(y1_v S, y1_c S)) + S)  =  S * ih
+// Multiplying by a power of two commutes with every rounding involved as long as nothing
+// leaves the normal range, which holds when every y is 0 or 2^-60 <= |y| <= 8190 (then
+// differences are 0 or >= 2^-83, extents are 0 or >= 2^-24, ih <= 16381 < 2^14).  The
+// product iw * ih_S = S * inter is compared with S * T.  Boxes are grouped in tiles of 64;
+// a tile whose boxes do not all meet the condition is simply processed in the unscaled form.
 #pragma once
 
 #include <math.h>
@@ -101,6 +112,28 @@ NMS_HD bool nms_eliminates_fast(float vx1, float vy1, float vx2, float vy2,
     float iw = (fminf(vx2, cx2) - fmaxf(vx1, cx1)) + 1.0f;  // may be negative, see above
     float ih = fmaxf(0.0f, (fminf(vy2, cy2) - fmaxf(vy1, cy1)) + 1.0f);
     return iw * ih >= c_T;
+}
+
+// ---- y-scaled fast form ---------------------------------------------------------------
+#define NMS_YSCALE 0x1p-14f
+
+// May this y coordinate take part in the scaled form?
+NMS_HD bool nms_y_regular(float y)
+{
+    const float a = fabsf(y);
+    return a == 0.0f || (a >= 0x1p-60f && a <= 8190.0f);
+}
+
+// vy1s.. are y coordinates times NMS_YSCALE, c_Ts = NMS_YSCALE * T, y_one = NMS_YSCALE.
+// (y_one is a parameter so that device code can keep it in a vector register: with a
+// scalar-register or literal operand the add would drop to half rate.)
+NMS_HD bool nms_eliminates_fast_yscaled(float vx1, float vy1s, float vx2, float vy2s,
+                                        float cx1, float cy1s, float cx2, float cy2s, float c_Ts, float y_one)
+{
+    float iw = (fminf(vx2, cx2) - fmaxf(vx1, cx1)) + 1.0f;
+    float ihs = (fminf(vy2s, cy2s) - fmaxf(vy1s, cy1s)) + y_one;
+    ihs = fminf(fmaxf(ihs, 0.0f), 1.0f);  // folds into the add as its clamp modifier
+    return iw * ihs >= c_Ts;
 }
 
 // Area of a box, pixel-inclusive (Algorithm 1's first assignment, one extent per axis).

@@ -46,6 +46,8 @@ __global__ void k_andor(float *out, float a, float sb, int iters) { BODY("v_and_
 __global__ void k_fma3(float *out, float a, float sb, int iters) { BODY("v_fma_f32 %0, %1, %1, %0") }
 __global__ void k_mulabs(float *out, float a, float sb, int iters) { BODY("v_mul_f32_e64 %0, %1, |%0|") }
 __global__ void k_cnd(float *out, float a, float sb, int iters) { BODY("v_cndmask_b32 %0, %1, %0, vcc") }
+__global__ void k_addclamp(float *out, float a, float sb, int iters) { BODY("v_add_f32_e64 %0, 1.0, %0 clamp") }
+__global__ void k_subclamp(float *out, float a, float sb, int iters) { BODY("v_sub_f32_e64 %0, %1, %0 clamp") }
 __global__ void k_rcp(float *out, float a, float sb, int iters) { BODY("v_rcp_f32 %0, %0") }
 
 typedef void (*kern_t)(float *, float, float, int);
@@ -63,7 +65,7 @@ int main()
         {"v_add_f32 vv", k_add, 1}, {"v_add_f32 sv", k_add_s, 1}, {"v_min_f32 vv", k_min, 1}, {"v_min_f32 sv", k_min_s, 1},
         {"v_max_f32", k_max, 1}, {"v_mul_f32", k_mul, 1}, {"v_sub_f32", k_sub, 1}, {"v_fma_f32", k_fma, 1}, {"v_fmac_f32", k_fmac, 1},
         {"v_cmp vcc", k_cmp, 1}, {"v_cmp sgpr", k_cmp64, 1}, {"v_mov_b32", k_mov, 1}, {"v_and_b32", k_and, 1}, {"v_max3_f32", k_max3, 1},
-        {"v_add_u32", k_pkadd, 1}, {"v_rcp_f32", k_rcp, 1}, {"v_min_i32", k_mini, 1}, {"v_max_u32", k_maxu, 1}, {"v_add_f32 1.0", k_addc, 1}, {"v_and_or_b32", k_andor, 1}, {"v_fma_f32 3src", k_fma3, 1}, {"v_mul_f32 |abs|", k_mulabs, 1}, {"v_cndmask", k_cnd, 1},
+        {"v_add_u32", k_pkadd, 1}, {"v_rcp_f32", k_rcp, 1}, {"v_min_i32", k_mini, 1}, {"v_max_u32", k_maxu, 1}, {"v_add_f32 1.0", k_addc, 1}, {"v_and_or_b32", k_andor, 1}, {"v_fma_f32 3src", k_fma3, 1}, {"v_mul_f32 |abs|", k_mulabs, 1}, {"v_cndmask", k_cnd, 1}, {"v_add_f32 clamp", k_addclamp, 1}, {"v_sub_f32 clamp", k_subclamp, 1},
     };
     const int iters = 2000;
     hipEvent_t e0, e1;

@@ -142,6 +142,56 @@ def test_batched_ragged_counts_many_frames(nms, oracle):
             assert np.array_equal(got[w, 64 * w:n], words[64 * w:, w]), f"frame {f}, mask word column {w}"
 
 
+def test_y_ranges_for_the_scaled_form(nms, oracle):
+    """The ranked route evaluates tiles whose y coordinates are all 0 or within
+    [2^-60, 8190] in magnitude with y scaled by 2^-14, other tiles unscaled.  Frames that
+    mix both kinds of tile (decided per 64 ranks), negative coordinates, boxes as tall as
+    the range allows, tiny and zero coordinates."""
+    rng = np.random.default_rng(8)
+    n = 1500
+    frames = []
+    for kind in range(6):
+        x1 = rng.uniform(-300, 300, n)
+        w = rng.uniform(1, 250, n)
+        if kind == 0:    # all regular, negative and positive y
+            y1 = rng.uniform(-8190, 8000, n); h = rng.uniform(1, 180, n)
+        elif kind == 1:  # a tenth of the boxes out of range, scattered over the ranks
+            y1 = rng.uniform(-3000, 3000, n); h = rng.uniform(1, 400, n)
+            far = rng.random(n) < 0.1
+            y1[far] += 9000.0
+        elif kind == 2:  # tall boxes up to the full range
+            y1 = rng.uniform(-8190, -4000, n); h = rng.uniform(4000, 16000, n)
+        elif kind == 3:  # tiny and zero y1 (some below 2^-60: irregular)
+            y1 = rng.choice([0.0, -0.0, 2.0 ** -60, 2.0 ** -61, 1e-30, 1e-40, 3.0], n); h = rng.uniform(1, 50, n)
+        elif kind == 4:  # far out of range everywhere
+            y1 = rng.uniform(1e5, 2e5, n); h = rng.uniform(1, 3000, n)
+        else:            # exactly at the limits
+            y1 = rng.choice([-8190.0, -8191.0, 0.0, 8000.0], n); h = rng.choice([190.0, 191.0, 16380.0], n)
+        y2 = np.minimum(y1 + h, np.where(kind in (1, 4), 1e9, 8190.0 if kind != 5 else 8191.0))
+        b = np.stack([x1, y1, x1 + w, np.maximum(y2, y1)], axis=1).astype(np.float32)
+        b[:, 3] = np.maximum(b[:, 3], b[:, 1])
+        s = rng.uniform(0.01, 1.0, n).astype(np.float32)
+        frames.append((b, s))
+    boxes = np.stack([f[0] for f in frames])
+    scores = np.stack([f[1] for f in frames])
+    for theta in (0.5, 0.05):
+        want = oracle_keep_frames(oracle, boxes, scores, np.float32(theta))
+        assert all(0 < want[f].sum() < n for f in range(len(frames)))
+        dev = DeviceFrames(nms, boxes, scores)
+        dev.fused(theta, want=want)
+        assert np.array_equal(dev.steps(theta), want)
+    # many frames: the four-tiles-per-wavefront kernel with mixed tiles
+    many_b = np.concatenate([boxes[:, :640]] * 134)
+    many_s = np.concatenate([scores[:, :640]] * 134)
+    want = oracle_keep_frames(oracle, many_b, many_s, np.float32(0.3))
+    DeviceFrames(nms, many_b, many_s).fused(0.3, want=want)
+    # a large frame (several rank chunks: the merge kernel sets the tile flags)
+    big_b = np.concatenate([boxes[0], boxes[1], boxes[3], boxes[5]] * 2)[None]
+    big_s = rng.uniform(0.01, 1.0, big_b.shape[1]).astype(np.float32)[None]
+    want = oracle_keep_frames(oracle, big_b, big_s, np.float32(0.4))
+    DeviceFrames(nms, big_b, big_s).fused(0.4, want=want)
+
+
 def steered_pairs(F, theta, seed):
     """F two-box frames whose overlap lands within a few float32 steps of theta: a
     W x H box at the origin and a victim of the same width whose top edge is placed

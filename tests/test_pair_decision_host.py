@@ -113,3 +113,49 @@ def test_disjoint_on_both_axes_never_eliminates(nms):
     assert nms.nms_host_pair_test([0, 20, 9, 29], [0, 0, 9, 9], 1e-6) == 0
     assert nms.nms_host_pair_test([20, 0, 29, 9], [0, 0, 9, 9], 1e-6) == 0
     assert nms.nms_host_pair_test([20, 20, 29, 29], [0, 0, 9, 9], 0.0) == 1  # overlap 0 is not below 0
+
+
+def test_y_scaled_form_and_its_fallback(nms):
+    """The fused kernel evaluates y multiplied by 2^-14 with a clamped add when every y of a
+    tile is 0 or within [2^-60, 8190] in magnitude, and the unscaled form otherwise; the
+    hook makes the same choice per pair.  Both must agree with plain division at the edges
+    of that range: largest extents, negative and zero coordinates, tiny coordinates,
+    coordinates just inside and just outside the range."""
+    rng = np.random.default_rng(41)
+
+    def check(v, c, theta):
+        v = np.asarray(v, np.float32)
+        c = np.asarray(c, np.float32)
+        want, q = plain_decision(v, c, np.float32(theta))
+        assert nms.nms_host_pair_test(v, c, float(theta)) == want, f"v={v.tolist()} c={c.tolist()} theta={theta!r} q={q!r}"
+        return want
+
+    hits = 0
+    for i in range(6000):
+        span = [8190.0, 8191.0, 8250.0, 30000.0][i % 4]      # in range, just outside, outside, far outside
+        cy1 = rng.uniform(-span, span * 0.2)
+        c = [rng.uniform(-500, 500), cy1, rng.uniform(500, 900), rng.uniform(cy1 + 1, span)]
+        vy1 = rng.uniform(-span, span * 0.2)
+        v = [rng.uniform(-500, 500), vy1, rng.uniform(500, 900), rng.uniform(vy1 + 1, span)]
+        _, q = plain_decision(np.asarray(v, np.float32), np.asarray(c, np.float32), np.float32(0.5))
+        for theta in (0.5, q if q > 1e-6 else 0.25, np.nextafter(np.float32(max(q, 1e-6)), np.float32(2))):
+            hits += check(v, c, theta)
+    assert hits > 2000
+    # full-height boxes: the largest extent the scaled form may see, 8190 - (-8190) + 1 = 16381
+    check([0, -8190, 99, 8190], [0, -8190, 99, 8190], 0.999)
+    check([0, -8190, 99, 8190], [0, -8190, 99, 8190], 1.0)
+    check([0, -8190, 99, 8190], [10, -8190, 60, 8190], 0.5)
+    check([0, -8191, 99, 8191], [0, -8191, 99, 8191], 1.0)       # just outside: unscaled form
+    # zeros, signed zeros and tiny coordinates
+    tiny = [2.0 ** -60, 2.0 ** -61, 2.0 ** -100, 1e-40, 0.0, -0.0]
+    for a in tiny:
+        for b in tiny:
+            for theta in (0.5, 1.0, 0.25):
+                check([0, a, 9, 9], [0, b, 9, 9], theta)
+                check([0, -a, 9, 9 + b], [0, 0, 9, 9], theta)
+                check([0, 0, 9, a], [0, 0, 9, b], theta)
+    # extents that barely exist: (min - max) + 1 just above zero, in y and in x
+    e = np.float32(1) - np.float32(2.0 ** -24)
+    for theta in (1e-6, 2.0 ** -30, 0.5):
+        check([0, 0, 9, 100], [0, float(100 + e), 9, 200], theta)
+        check([0, 0, 100, 9], [float(100 + e), 0, 200, 9], theta)
