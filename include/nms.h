@@ -62,6 +62,7 @@ extern "C" {
 #define NMS_MAX_N 65536          /* largest n (and n_max) accepted */
 #define NMS_MAX_FRAMES 65535     /* largest batch accepted */
 #define NMS_SORT_CHUNK 4096      /* boxes ranked by one workgroup in LDS */
+#define NMS_MAX_MATRIX 16384     /* largest capacity of the byte-matrix form (256 MiB of B) */
 
 typedef enum {
     NMS_OK = 0,
@@ -166,6 +167,26 @@ int nms_reduce_greedy_batched(const uint64_t *mask, const int32_t *order, const 
 size_t nms_greedy_workspace_bytes(int n_max, int frames);   /* host-only, pure; 0 on invalid arguments */
 int nms_run_greedy_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
                            float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * The paper's own data layout, for measuring its form on this hardware: the boolean
+ * matrix B as capacity x capacity BYTES over the UNSORTED input (Algorithm 1, one
+ * matrix element per ordered pair, the score guard evaluated per pair), and
+ * Algorithm 2's reduce with its k row partitions (one workgroup per row, capacity / k
+ * threads, k block-wide ANDs).
+ *   nms_map_matrix     B[i * capacity + j] = 0 iff j outranks i and overlap(i, j) >= theta,
+ *                      else 1.  Every byte of B is written (the paper presets B to 1 with
+ *                      a memset and rewrites the guarded entries; slots at or beyond n
+ *                      never pass the guard there and come out as 1 here).
+ *                      Outranking is this library's total order (index breaks score ties).
+ *   nms_reduce_matrix  V[i] = AND over j of B[i * capacity + j], for all capacity rows
+ *                      (rows of unused slots give 1, as in the paper).
+ *   n <= capacity <= NMS_MAX_MATRIX, capacity a multiple of 64; k >= 1 divides capacity and
+ *   capacity / k <= 1024 (the workgroup size); otherwise NMS_ERR_INVALID_ARG.
+ */
+int nms_map_matrix(const float *boxes, const float *scores, int n, int capacity, float threshold,
+                   uint8_t *B, void *stream);
+int nms_reduce_matrix(const uint8_t *B, int capacity, int k, uint8_t *V, void *stream);
 
 /*
  * Profiling variant of nms_run_batched: identical work, and in addition records the

@@ -111,6 +111,29 @@ def test_argument_errors_before_launch(nms):
     assert L.nms_run_batched(null, null, null, 64, 0, 0.5, null, null, 0, null) == nms.NMS_OK
 
 
+def test_matrix_form_argument_errors(nms):
+    L = nms.lib
+    p = ctypes.c_void_p(0x1000)
+    null = None
+    assert L.nms_map_matrix(p, p, -1, 64, 0.5, p, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_map_matrix(p, p, 65, 64, 0.5, p, null) == nms.NMS_ERR_INVALID_ARG      # n beyond the capacity
+    assert L.nms_map_matrix(p, p, 10, 100, 0.5, p, null) == nms.NMS_ERR_INVALID_ARG     # capacity not a multiple of 64
+    assert L.nms_map_matrix(p, p, 10, 16448, 0.5, p, null) == nms.NMS_ERR_TOO_LARGE
+    assert L.nms_map_matrix(p, p, 10, 64, float("nan"), p, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_map_matrix(null, p, 10, 64, 0.5, p, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_map_matrix(p, null, 10, 64, 0.5, p, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_map_matrix(p, p, 10, 64, 0.5, null, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_map_matrix(null, null, 0, 0, 0.5, null, null) == nms.NMS_OK
+    assert L.nms_reduce_matrix(p, 64, 0, p, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_reduce_matrix(p, 64, 3, p, null) == nms.NMS_ERR_INVALID_ARG            # k does not divide the capacity
+    assert L.nms_reduce_matrix(p, 4096, 2, p, null) == nms.NMS_ERR_INVALID_ARG          # 2048 threads per row
+    assert L.nms_reduce_matrix(p, 100, 4, p, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_reduce_matrix(p, 16448, 64, p, null) == nms.NMS_ERR_TOO_LARGE
+    assert L.nms_reduce_matrix(null, 64, 4, p, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_reduce_matrix(p, 64, 4, null, null) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_reduce_matrix(null, 0, 4, null, null) == nms.NMS_OK
+
+
 def test_pool_protocol(nms):
     L = nms.lib
     p = ctypes.c_void_p(0x1000)
