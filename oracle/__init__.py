@@ -65,6 +65,12 @@ def load(library: str | None = None) -> ctypes.CDLL:
     lib.nmso_alg12_square.argtypes = [_f32p, ctypes.c_int, ctypes.c_float, ctypes.c_int, _u8p, _u8p]
     lib.nmso_greedy_keep.restype = None
     lib.nmso_greedy_keep.argtypes = [_f32p, _f32p, ctypes.c_int, ctypes.c_float, _u8p]
+    lib.nmso_keep_ex.restype = None
+    lib.nmso_keep_ex.argtypes = [_f32p, _f32p, ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_int,
+                                 ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_float, _u8p]
+    lib.nmso_eliminates_ex.restype = ctypes.c_int
+    lib.nmso_eliminates_ex.argtypes = [_f32p, _f32p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_float,
+                                       ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_float]
     return lib
 
 
@@ -118,6 +124,38 @@ class Oracle:
         keep = np.zeros(n, dtype=np.uint8)
         self.lib.nmso_greedy_keep(boxes, scores, n, float(np.float32(theta)), keep)
         return keep
+
+    @staticmethod
+    def _classes(classes, n):
+        if classes is None:
+            return None, None
+        c = np.ascontiguousarray(classes, dtype=np.int32).reshape(-1)
+        if c.shape[0] != n:
+            raise ValueError("classes and scores disagree on n")
+        return c, c.ctypes.data_as(ctypes.c_void_p)
+
+    def keep_ex(self, boxes, scores, theta, rule="paper", measure="outranking_area", compare="ge",
+                ties="index", pixel_offset=1.0, classes=None) -> np.ndarray:
+        """The rule with its selectable variants (see nmso_keep_ex)."""
+        boxes, scores, n = self._frame(boxes, scores)
+        held, cptr = self._classes(classes, n)
+        keep = np.zeros(n, dtype=np.uint8)
+        self.lib.nmso_keep_ex(boxes, scores, cptr, n, float(np.float32(theta)),
+                              {"paper": 0, "greedy": 1}[rule], {"outranking_area": 0, "iou": 1}[measure],
+                              {"ge": 0, "gt": 1}[compare], {"index": 0, "ignore": 1}[ties],
+                              float(np.float32(pixel_offset)), keep)
+        del held
+        return keep
+
+    def eliminates_ex(self, boxes, scores, j, i, theta, measure="outranking_area", compare="ge",
+                      ties="index", pixel_offset=1.0, classes=None) -> bool:
+        boxes, scores, n = self._frame(boxes, scores)
+        held, cptr = self._classes(classes, n)
+        r = self.lib.nmso_eliminates_ex(boxes, scores, cptr, int(j), int(i), float(np.float32(theta)),
+                                        {"outranking_area": 0, "iou": 1}[measure], {"ge": 0, "gt": 1}[compare],
+                                        {"index": 0, "ignore": 1}[ties], float(np.float32(pixel_offset)))
+        del held
+        return bool(r)
 
     def order(self, scores) -> np.ndarray:
         scores = np.ascontiguousarray(scores, dtype=np.float32).reshape(-1)

@@ -256,3 +256,85 @@ void nmso_greedy_keep(const float *boxes, const float *scores, int n, float thet
     }
     free(order);
 }
+
+/* ---- selectable variants of the rule ------------------------------------------------ */
+
+/* The same map/reduce pattern with the choices that the paper's closing section says it
+ * extends to, each one a switch; all switches off (and classes NULL) is nmso_keep /
+ * nmso_greedy_keep above.
+ *   measure 0: intersection over the area of the outranking box (Algorithm 1)
+ *           1: intersection over union, union = (area_i + area_j) - intersection
+ *   strict  0: overlap >= theta eliminates (Algorithm 1's "B = overlap < theta")
+ *           1: only overlap > theta eliminates
+ *   ties    0: equal scores are ordered by index (this build's total order)
+ *           1: equal scores never eliminate each other (Algorithm 1's strict "<" as printed)
+ *   offset    added to every extent before areas and intersections are formed: 1 is the
+ *             paper's pixel-inclusive convention, 0 treats coordinates as continuous
+ *   classes   NULL, or one label per box: only boxes with equal labels interact
+ *   greedy  0: every outranking box counts (Algorithms 1 + 2)
+ *           1: only outranking boxes that are themselves kept count */
+static float extent(float lo, float hi, float offset) { return (hi - lo) + offset; }
+
+static int eliminates_ex(const float *boxes, const float *scores, const int32_t *classes, int j, int i,
+                         float theta, int measure, int strict, int ties, float offset)
+{
+    if (ties ? !(scores[j] > scores[i]) : !outranks(scores, j, i)) return 0;
+    if (classes && classes[j] != classes[i]) return 0;
+    const float *bi = boxes + 4 * (size_t)i;
+    const float *bj = boxes + 4 * (size_t)j;
+
+    float right = bi[2] < bj[2] ? bi[2] : bj[2];   /* intersection: the nearer of the far edges ... */
+    float left = bi[0] > bj[0] ? bi[0] : bj[0];    /* ... and the farther of the near edges */
+    float w = extent(left, right, offset);
+    if (!(w > 0.0f)) w = 0.0f;
+    float bottom = bi[3] < bj[3] ? bi[3] : bj[3];
+    float top = bi[1] > bj[1] ? bi[1] : bj[1];
+    float h = extent(top, bottom, offset);
+    if (!(h > 0.0f)) h = 0.0f;
+    float inter = w * h;
+
+    float area_j = extent(bj[0], bj[2], offset) * extent(bj[1], bj[3], offset);
+    float q;
+    if (measure == 0) {
+        q = inter / area_j;
+    } else {
+        float area_i = extent(bi[0], bi[2], offset) * extent(bi[1], bi[3], offset);
+        q = inter / ((area_i + area_j) - inter);
+    }
+    return strict ? (q > theta) : !(q < theta);
+}
+
+void nmso_keep_ex(const float *boxes, const float *scores, const int32_t *classes, int n, float theta,
+                  int greedy, int measure, int strict, int ties, float offset, uint8_t *keep)
+{
+    if (!greedy) {
+        for (int i = 0; i < n; ++i) {
+            uint8_t v = 1;
+            for (int j = 0; j < n; ++j)
+                if (eliminates_ex(boxes, scores, classes, j, i, theta, measure, strict, ties, offset)) v = 0;
+            keep[i] = v;
+        }
+        return;
+    }
+    /* boxes are visited from the best rank down, so keep[j] is final for every j that can
+     * eliminate i (such a j has a strictly better rank in the total order) */
+    int32_t *order = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+    nmso_order(scores, n, order);
+    for (int r = 0; r < n; ++r) {
+        int i = order[r];
+        uint8_t v = 1;
+        for (int c = 0; c < r; ++c) {
+            int j = order[c];
+            if (keep[j] && eliminates_ex(boxes, scores, classes, j, i, theta, measure, strict, ties, offset)) v = 0;
+        }
+        keep[i] = v;
+    }
+    free(order);
+}
+
+/* One pair under the options, for tests that recompute witnesses: does j eliminate i? */
+int nmso_eliminates_ex(const float *boxes, const float *scores, const int32_t *classes, int j, int i,
+                       float theta, int measure, int strict, int ties, float offset)
+{
+    return eliminates_ex(boxes, scores, classes, j, i, theta, measure, strict, ties, offset);
+}

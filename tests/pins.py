@@ -351,3 +351,12 @@ ALL_PINS = [
     ("clusters", pin_clusters),
     ("square_form", pin_square_form),
 ]
+
+
+def _with_variants():
+    from pins_variants import VARIANT_PINS  # imports f32_round from this module: resolved lazily
+
+    return VARIANT_PINS
+
+
+ALL_PINS = ALL_PINS + _with_variants()

@@ -39,6 +39,29 @@ MUTANTS = [
     ("ranked_area_missing", "out[5 * (size_t)r + 4] = box_area(b);", "out[5 * (size_t)r + 4] = b[2] - b[0];", 1),
     ("printed_form_drops_partition", "for (int p = 1; p < k; ++p) {", "for (int p = 1; p < k - 1; ++p) {", 1),
     ("printed_form_nonstrict", "if (di[3] < dj[3]) {", "if (di[3] <= dj[3]) {", 1),
+    # the selectable variants
+    ("ex_union_forgets_intersection", "q = inter / ((area_i + area_j) - inter);", "q = inter / (area_i + area_j);", 1),
+    ("ex_iou_divides_by_victim", "q = inter / ((area_i + area_j) - inter);", "q = inter / area_i;", 1),
+    ("ex_measure_switch_inverted", "if (measure == 0) {", "if (measure != 0) {", 1),
+    ("ex_strict_switch_inverted", "return strict ? (q > theta) : !(q < theta);", "return strict ? !(q < theta) : (q > theta);", 1),
+    ("ex_strict_ignored", "return strict ? (q > theta) : !(q < theta);", "return !(q < theta);", 1),
+    ("ex_ties_ignored_switch_dead", "if (ties ? !(scores[j] > scores[i]) : !outranks(scores, j, i)) return 0;",
+     "if (!outranks(scores, j, i)) return 0;", 1),
+    ("ex_ties_lets_equal_scores_through", "if (ties ? !(scores[j] > scores[i])", "if (ties ? !(scores[j] >= scores[i])", 1),
+    ("ex_classes_ignored", "if (classes && classes[j] != classes[i]) return 0;", "", 1),
+    ("ex_classes_inverted", "classes[j] != classes[i]", "classes[j] == classes[i]", 1),
+    ("ex_offset_always_one", "static float extent(float lo, float hi, float offset) { return (hi - lo) + offset; }",
+     "static float extent(float lo, float hi, float offset) { return (hi - lo) + 1.0f; }", 1),
+    ("ex_offset_missing_in_area", "float area_j = extent(bj[0], bj[2], offset) * extent(bj[1], bj[3], offset);",
+     "float area_j = (bj[2] - bj[0]) * (bj[3] - bj[1]);", 1),
+    ("ex_width_not_floored", "float w = extent(left, right, offset);\n    if (!(w > 0.0f)) w = 0.0f;", "float w = extent(left, right, offset);", 1),
+    ("ex_height_not_floored", "float h = extent(top, bottom, offset);\n    if (!(h > 0.0f)) h = 0.0f;", "float h = extent(top, bottom, offset);", 1),
+    ("ex_greedy_counts_dead_boxes", "if (keep[j] && eliminates_ex(", "if (eliminates_ex(", 1),
+    ("ex_greedy_switch_dead", "if (!greedy) {", "if (1) {", 1),
+    ("ex_right_edge_is_max", "float right = bi[2] < bj[2] ? bi[2] : bj[2];", "float right = bi[2] > bj[2] ? bi[2] : bj[2];", 1),
+    ("ex_top_edge_is_min", "float top = bi[1] > bj[1] ? bi[1] : bj[1];", "float top = bi[1] < bj[1] ? bi[1] : bj[1];", 1),
+    ("ex_operands_transposed", "const float *bi = boxes + 4 * (size_t)i;\n    const float *bj = boxes + 4 * (size_t)j;",
+     "const float *bi = boxes + 4 * (size_t)j;\n    const float *bj = boxes + 4 * (size_t)i;", 1),
 ]
 
 
