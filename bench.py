@@ -222,6 +222,23 @@ def main():
         }
         del order, sorted5, mask, keep3, keep_g
 
+        # -------------------------------------------------------------- selectable variants on the same workload
+        # (literal division form, one tile per wavefront, mask in memory: a coverage path, not the tuned one)
+        ws_ex = torch.empty(nms.nms_ex_workspace_bytes(w.n, w.frames), dtype=torch.uint8, device=dev)
+        keep_ex = torch.empty((w.frames, w.n), dtype=torch.uint8, device=dev)
+        variants = {}
+        for label, kw in (("defaults", {}), ("iou_greedy_offset0", dict(rule="greedy", measure="iou", pixel_offset=0.0)),
+                          ("iou_paper_rule", dict(measure="iou"))):
+            fn = lambda: nms.nms_run_ex_batched(d["boxes"], d["scores"], None, w.n, w.frames, w.theta, keep_ex, ws_ex, **kw)
+            ms_v = time_steps(fn, steps3, 2)
+            variants[label] = {"ms_per_step": round(ms_v, 4), "pair_tests_per_s": round(pairs / (ms_v * 1e-3), 1),
+                               "survivors": int(keep_ex.sum().item())}
+        variants["defaults_equal_fused"] = None
+        nms.nms_run_ex_batched(d["boxes"], d["scores"], None, w.n, w.frames, w.theta, keep_ex, ws_ex)
+        variants["defaults_equal_fused"] = bool(torch.equal(keep_ex, d["keep"]))
+        extra["variants_nms_run_ex_batched"] = variants
+        del ws_ex, keep_ex
+
         # -------------------------------------------------------------- the other configurations (latency view)
         others = {}
         for idx in (0, 1, 2, 3):

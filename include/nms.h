@@ -169,6 +169,45 @@ int nms_run_greedy_batched(const float *boxes, const float *scores, const int32_
                            float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * Selectable variants of the rule (the paper's closing section: the map/reduce pattern
+ * carries over to the members of the greedy NMS family with changes in the merging step).
+ * Every switch at its first value is the default path above.
+ *   rule     NMS_RULE_PAPER   every outranking box counts (Algorithms 1 + 2)
+ *            NMS_RULE_GREEDY  only outranking boxes that survive themselves count
+ *   measure  NMS_MEASURE_OUTRANKING_AREA  intersection / area of the outranking box (Algorithm 1)
+ *            NMS_MEASURE_IOU              intersection / ((area_i + area_j) - intersection)
+ *   compare  NMS_COMPARE_GE   overlap >= theta eliminates (Algorithm 1: B = overlap < theta)
+ *            NMS_COMPARE_GT   only overlap > theta eliminates
+ *   ties     NMS_TIES_BY_INDEX  equal scores: the lower index outranks
+ *            NMS_TIES_IGNORE    equal scores never eliminate each other (Algorithm 1's strict "<" as printed)
+ *   pixel_offset  added to every extent before areas and intersections are formed:
+ *            1.0f (the paper's pixel-inclusive convention) or 0.0f (continuous coordinates;
+ *            then x2 > x1 and y2 > y1 is an unchecked precondition).  Other values: NMS_ERR_INVALID_ARG.
+ *   classes  NULL, or device int32 [frames][n_max]: only boxes with equal labels interact.
+ * float32, one rounding per operation, in the order written above; the division is IEEE.
+ * nms_run_ex_batched: rank, map into a mask (workspace), then the reduce of the chosen rule.
+ *   options    HOST pointer, read before the call returns; NULL = all defaults
+ *   workspace  >= nms_ex_workspace_bytes(n_max, frames) bytes, 256-byte aligned
+ */
+enum { NMS_RULE_PAPER = 0, NMS_RULE_GREEDY = 1 };
+enum { NMS_MEASURE_OUTRANKING_AREA = 0, NMS_MEASURE_IOU = 1 };
+enum { NMS_COMPARE_GE = 0, NMS_COMPARE_GT = 1 };
+enum { NMS_TIES_BY_INDEX = 0, NMS_TIES_IGNORE = 1 };
+typedef struct nms_options {
+    int32_t rule;
+    int32_t measure;
+    int32_t compare;
+    int32_t ties;
+    float pixel_offset;
+    int32_t reserved;          /* must be 0 */
+    const int32_t *classes;    /* device, or NULL */
+} nms_options;
+size_t nms_ex_workspace_bytes(int n_max, int frames);   /* host-only, pure; 0 on invalid arguments */
+int nms_run_ex_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                       float threshold, const nms_options *options, uint8_t *keep_out,
+                       void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * The paper's own data layout, for measuring its form on this hardware: the boolean
  * matrix B as capacity x capacity BYTES over the UNSORTED input (Algorithm 1, one
  * matrix element per ordered pair, the score guard evaluated per pair), and

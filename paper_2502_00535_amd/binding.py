@@ -25,8 +25,22 @@ EXPORTS = (
     "nms_reduce", "nms_reduce_batched", "nms_run_ws", "nms_run_batched", "nms_run_ranked_batched", "nms_run_direct_batched",
     "nms_run_batched_profiled", "nms_reduce_greedy", "nms_reduce_greedy_batched",
     "nms_greedy_workspace_bytes", "nms_run_greedy_batched", "nms_map_matrix", "nms_reduce_matrix",
+    "nms_ex_workspace_bytes", "nms_run_ex_batched",
     "nms_init", "nms_shutdown", "nms_run", "nms_host_pair_test",
 )
+
+
+class NmsOptions(ctypes.Structure):
+    """struct nms_options of include/nms.h."""
+    _fields_ = [("rule", ctypes.c_int32), ("measure", ctypes.c_int32), ("compare", ctypes.c_int32),
+                ("ties", ctypes.c_int32), ("pixel_offset", ctypes.c_float), ("reserved", ctypes.c_int32),
+                ("classes", ctypes.c_void_p)]
+
+
+RULES = {"paper": 0, "greedy": 1}
+MEASURES = {"outranking_area": 0, "iou": 1}
+COMPARES = {"ge": 0, "gt": 1}
+TIES = {"index": 0, "ignore": 1}
 
 
 class NmsError(RuntimeError):
@@ -100,6 +114,10 @@ def _load() -> ctypes.CDLL:
     L.nms_map_matrix.argtypes = [vp, vp, i32, i32, f32, vp, vp]
     L.nms_reduce_matrix.restype = i32
     L.nms_reduce_matrix.argtypes = [vp, i32, i32, vp, vp]
+    L.nms_ex_workspace_bytes.restype = sz
+    L.nms_ex_workspace_bytes.argtypes = [i32, i32]
+    L.nms_run_ex_batched.restype = i32
+    L.nms_run_ex_batched.argtypes = [vp, vp, vp, i32, i32, f32, ctypes.POINTER(NmsOptions), vp, vp, sz, vp]
     L.nms_init.restype = i32
     L.nms_init.argtypes = [i32, i32, vp, sz]
     L.nms_shutdown.restype = i32
@@ -318,6 +336,23 @@ def nms_map_matrix(boxes, scores, n, capacity, threshold, B, stream=None):
 def nms_reduce_matrix(B, capacity, k, V, stream=None):
     _check(lib.nms_reduce_matrix(_ptr(B, "uint8", "B"), int(capacity), int(k), _ptr(V, "uint8", "V"),
                                  _stream(stream)), "nms_reduce_matrix")
+
+
+def nms_ex_workspace_bytes(n_max: int, frames: int) -> int:
+    return int(lib.nms_ex_workspace_bytes(int(n_max), int(frames)))
+
+
+def nms_run_ex_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, rule="paper",
+                       measure="outranking_area", compare="ge", ties="index", pixel_offset=1.0, classes=None,
+                       stream=None):
+    w, wb = _ws(workspace)
+    cls = _ptr(classes, "int32", "classes")
+    opt = NmsOptions(RULES[rule], MEASURES[measure], COMPARES[compare], TIES[ties], float(pixel_offset), 0,
+                     cls.value if cls is not None else None)
+    _check(lib.nms_run_ex_batched(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
+                                  _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
+                                  ctypes.byref(opt), _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream)),
+           "nms_run_ex_batched")
 
 
 def nms_init(n_max, frames_max, workspace):

@@ -699,6 +699,94 @@ greedy_sweep_kernel(const unsigned long long *__restrict__ mask, const int32_t *
     for (int i = n_f + (int)threadIdx.x; i < n_max; i += blockDim.x) keep_f[i] = 0;  // slots beyond the count
 }
 
+// ----------------------------------------------------------------------------- map with options
+
+// Rank-ordered scores and class labels (victims of a row are fetched with scalar loads, so
+// the map kernel wants them contiguous in rank order like the box table).
+__global__ void __launch_bounds__(256)
+gather_ranked_kernel(const int32_t *__restrict__ order, const float *__restrict__ scores,
+                     const int32_t *__restrict__ classes, const int32_t *__restrict__ counts, int n_max, int n_pad,
+                     float *__restrict__ ranked_score, int32_t *__restrict__ ranked_class)
+{
+    const int f = blockIdx.y;
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= n_pad) return;
+    const int n_f = frame_count(counts, f, n_max);
+    const bool real = r < n_f;
+    const int idx = real ? order[(size_t)f * n_max + r] : 0;
+    ranked_score[(size_t)f * n_pad + r] = real ? scores[(size_t)f * n_max + idx] : -INFINITY;
+    if (classes != nullptr) ranked_class[(size_t)f * n_pad + r] = real ? classes[(size_t)f * n_max + idx] : 0;
+}
+
+enum { kExStrict = 1, kExTiesIgnore = 2, kExClasses = 4 };
+
+// The map step with the selectable measure / compare / tie / label / offset variants, in the
+// literal form (IEEE division), one wavefront per 64x64 tile of the ranked lower triangle, mask
+// layout as in map_tile_kernel.  Rank order puts equal scores next to each other, so "ties
+// ignored" is the extra test score_c > score_r on the pairs the triangle already holds.
+template <bool IOU>
+__global__ void __launch_bounds__(kMapWaves * 64)
+map_tile_ex_kernel(const float *__restrict__ sorted5, const float *__restrict__ ranked_score,
+                   const int32_t *__restrict__ ranked_class, const int32_t *__restrict__ counts, int n_max, int n_pad,
+                   int tiles, float theta, float offset, int flags, unsigned long long *__restrict__ mask)
+{
+    const int lane = threadIdx.x & 63;
+    const int f = blockIdx.y;
+    const int g = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * kMapWaves + (threadIdx.x >> 6)));
+    if (g >= tiles) return;
+    const int n_f = frame_count(counts, f, n_max);
+    int tr, tc;
+    triangle_unit<1>(g, tr, tc);
+    if (tr * kTile >= n_f) return;
+
+    const float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
+    const float4 *box4 = reinterpret_cast<const float4 *>(sorted_f);
+    const float *score_f = ranked_score + (size_t)f * n_pad;
+    const int32_t *class_f = ranked_class + (size_t)f * n_pad;  // only dereferenced with kExClasses
+    const bool strict = (flags & kExStrict) != 0;
+    const bool ties_ignore = (flags & kExTiesIgnore) != 0;
+    const bool labelled = (flags & kExClasses) != 0;
+
+    const int c = tc * kTile + lane;
+    const float4 cb = box4[c];
+    const float c_area = ((cb.z - cb.x) + offset) * ((cb.w - cb.y) + offset);
+    const float c_score = score_f[c];
+    const int c_class = labelled ? class_f[c] : 0;
+
+    const float4 *__restrict__ vb = box4 + tr * kTile;  // wave-uniform addresses: scalar loads
+    const float *__restrict__ vs = score_f + tr * kTile;
+    const int32_t *__restrict__ vc = class_f + tr * kTile;
+    unsigned w_lo = 0, w_hi = 0;
+#pragma unroll 4
+    for (int r = 0; r < kTile; ++r) {
+        const float4 v = vb[r];
+        const float iw = fmaxf(0.0f, (fminf(v.z, cb.z) - fmaxf(v.x, cb.x)) + offset);
+        const float ih = fmaxf(0.0f, (fminf(v.w, cb.w) - fmaxf(v.y, cb.y)) + offset);
+        const float inter = iw * ih;
+        float q;
+        if (IOU) {
+            const float v_area = ((v.z - v.x) + offset) * ((v.w - v.y) + offset);
+            q = inter / ((v_area + c_area) - inter);
+        } else {
+            q = inter / c_area;
+        }
+        bool hit = strict ? (q > theta) : !(q < theta);
+        if (ties_ignore) hit = hit && (c_score > vs[r]);
+        if (labelled) hit = hit && (c_class == vc[r]);
+        unsigned long long word = __ballot(hit);
+        if (tr == tc) word &= (1ull << r) - 1ull;  // only better-ranked boxes eliminate
+        if (word != 0) {
+            const bool mine = (lane == r);
+            w_lo = mine ? (unsigned)word : w_lo;
+            w_hi = mine ? (unsigned)(word >> 32) : w_hi;
+        }
+    }
+    const int row = tr * kTile + lane;
+    unsigned long long out = ((unsigned long long)w_hi << 32) | w_lo;
+    if (row >= n_f) out = 0;
+    mask[(size_t)f * ((size_t)(n_pad / kTile) * n_pad) + (size_t)tc * n_pad + row] = out;
+}
+
 // ----------------------------------------------------------------------------- the paper's matrix form
 
 // Algorithm 1 with the paper's own data layout: the boolean matrix B as capacity x capacity
@@ -1144,6 +1232,70 @@ int nms_run_greedy_batched(const float *boxes, const float *scores, const int32_
     if (st != NMS_OK) return st;
     return nms_reduce_greedy_batched(reinterpret_cast<const uint64_t *>(mask), order, counts, n_max, frames, keep_out,
                                      stream);
+}
+
+size_t nms_ex_workspace_bytes(int n_max, int frames)
+{
+    int st;
+    if (!sizes_ok(n_max, frames, &st)) return 0;
+    return nms_greedy_workspace_bytes(n_max, frames)
+         + 2 * align256((size_t)frames * nms_padded_n(n_max) * sizeof(float));  // ranked scores, ranked labels
+}
+
+int nms_run_ex_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                       float threshold, const nms_options *options, uint8_t *keep_out,
+                       void *workspace, size_t ws_bytes, void *stream)
+{
+    int st;
+    if (!sizes_ok(n_max, frames, &st)) return st;
+    if (is_nan(threshold)) return NMS_ERR_INVALID_ARG;
+    nms_options opt = {NMS_RULE_PAPER, NMS_MEASURE_OUTRANKING_AREA, NMS_COMPARE_GE, NMS_TIES_BY_INDEX, 1.0f, 0, nullptr};
+    if (options) opt = *options;
+    if ((opt.rule | opt.measure | opt.compare | opt.ties) & ~1) return NMS_ERR_INVALID_ARG;
+    if (opt.reserved != 0 || !(opt.pixel_offset == 0.0f || opt.pixel_offset == 1.0f)) return NMS_ERR_INVALID_ARG;
+    if (n_max == 0 || frames == 0) return NMS_OK;
+    if (!boxes || !scores || !keep_out) return NMS_ERR_INVALID_ARG;
+    if (!workspace || ws_bytes < nms_ex_workspace_bytes(n_max, frames) || ((uintptr_t)workspace & 255))
+        return NMS_ERR_WORKSPACE;
+
+    const int n_pad = nms_padded_n(n_max);
+    const RunWorkspace w = carve_workspace(workspace, n_max, frames);
+    char *p = w.end;
+    unsigned long long *mask = reinterpret_cast<unsigned long long *>(p);
+    p += align256((size_t)frames * nms_mask_words(n_max) * sizeof(uint64_t));
+    float *ranked_score = reinterpret_cast<float *>(p);
+    p += align256((size_t)frames * n_pad * sizeof(float));
+    int32_t *ranked_class = reinterpret_cast<int32_t *>(p);
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    st = rank_launch(boxes, scores, counts, n_max, frames, w.order, w.sorted5, w.keys, nullptr, nullptr, nullptr, s);
+    if (st != NMS_OK) return st;
+    begin_launch();
+    gather_ranked_kernel<<<dim3((n_pad + 255) / 256, frames), dim3(256), 0, s>>>(
+        w.order, scores, opt.classes, counts, n_max, n_pad, ranked_score, ranked_class);
+    st = launch_status();
+    if (st != NMS_OK) return st;
+
+    const int tiles = triangle_units(n_pad / kTile, 1);
+    const dim3 grid((tiles + kMapWaves - 1) / kMapWaves, frames);
+    const int flags = (opt.compare == NMS_COMPARE_GT ? kExStrict : 0) | (opt.ties == NMS_TIES_IGNORE ? kExTiesIgnore : 0) |
+                      (opt.classes ? kExClasses : 0);
+    begin_launch();
+    if (opt.measure == NMS_MEASURE_IOU)
+        map_tile_ex_kernel<true><<<grid, dim3(kMapWaves * 64), 0, s>>>(w.sorted5, ranked_score, ranked_class, counts,
+                                                                        n_max, n_pad, tiles, threshold,
+                                                                        opt.pixel_offset, flags, mask);
+    else
+        map_tile_ex_kernel<false><<<grid, dim3(kMapWaves * 64), 0, s>>>(w.sorted5, ranked_score, ranked_class, counts,
+                                                                         n_max, n_pad, tiles, threshold,
+                                                                         opt.pixel_offset, flags, mask);
+    st = launch_status();
+    if (st != NMS_OK) return st;
+    if (opt.rule == NMS_RULE_GREEDY)
+        return nms_reduce_greedy_batched(reinterpret_cast<const uint64_t *>(mask), w.order, counts, n_max, frames,
+                                         keep_out, stream);
+    return nms_reduce_batched(reinterpret_cast<const uint64_t *>(mask), w.order, counts, n_max, frames, keep_out,
+                              stream);
 }
 
 int nms_map_matrix(const float *boxes, const float *scores, int n, int capacity, float threshold,

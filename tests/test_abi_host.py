@@ -134,6 +134,38 @@ def test_matrix_form_argument_errors(nms):
     assert L.nms_reduce_matrix(null, 0, 4, null, null) == nms.NMS_OK
 
 
+def test_options_argument_errors(nms):
+    L = nms.lib
+    p = ctypes.c_void_p(0x1000)
+    big = 1 << 30
+
+    def call(opt, n=8, frames=1, theta=0.5, ws=p, ws_bytes=big, boxes=p, keep=p):
+        ref = ctypes.byref(opt) if opt is not None else None
+        return L.nms_run_ex_batched(boxes, p, None, n, frames, theta, ref, keep, ws, ws_bytes, None)
+
+    ok = lambda **kw: nms.NmsOptions(kw.get("rule", 0), kw.get("measure", 0), kw.get("compare", 0), kw.get("ties", 0),
+                                     kw.get("pixel_offset", 1.0), kw.get("reserved", 0), None)
+    for field in ("rule", "measure", "compare", "ties"):
+        assert call(ok(**{field: 2})) == nms.NMS_ERR_INVALID_ARG
+        assert call(ok(**{field: -1})) == nms.NMS_ERR_INVALID_ARG
+    assert call(ok(pixel_offset=0.5)) == nms.NMS_ERR_INVALID_ARG
+    assert call(ok(pixel_offset=float("nan"))) == nms.NMS_ERR_INVALID_ARG
+    assert call(ok(reserved=1)) == nms.NMS_ERR_INVALID_ARG
+    assert call(ok(), theta=float("nan")) == nms.NMS_ERR_INVALID_ARG
+    assert call(ok(), n=-1) == nms.NMS_ERR_INVALID_ARG
+    assert call(ok(), n=70000) == nms.NMS_ERR_TOO_LARGE
+    assert call(ok(), boxes=None) == nms.NMS_ERR_INVALID_ARG
+    assert call(ok(), keep=None) == nms.NMS_ERR_INVALID_ARG
+    assert call(ok(), ws=None) == nms.NMS_ERR_WORKSPACE
+    assert call(ok(), ws_bytes=1000) == nms.NMS_ERR_WORKSPACE
+    assert call(ok(), ws=ctypes.c_void_p(0x1008)) == nms.NMS_ERR_WORKSPACE
+    assert call(ok(), n=0) == nms.NMS_OK
+    assert call(None, n=0) == nms.NMS_OK
+    # mask + ranked scores + ranked labels on top of the fused path's workspace
+    assert nms.nms_ex_workspace_bytes(1024, 2) == nms.nms_greedy_workspace_bytes(1024, 2) + 2 * (2 * 1024 * 4)
+    assert nms.nms_ex_workspace_bytes(-1, 2) == 0
+
+
 def test_pool_protocol(nms):
     L = nms.lib
     p = ctypes.c_void_p(0x1000)

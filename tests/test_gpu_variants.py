@@ -1,0 +1,145 @@
+"""nms_run_ex_batched (selectable rule / measure / compare / ties / pixel offset / labels)
+against the oracle's keep_ex on the same seeded inputs.  Bar: 0 differing keep bits."""
+import itertools
+
+import numpy as np
+import pytest
+
+from workloads import make_config, random_frame
+
+pytestmark = pytest.mark.gpu
+
+GRID = [dict(rule=r, measure=m, compare=c, ties=t, pixel_offset=o, labelled=k)
+        for r, m, c, t, o, k in itertools.product(("paper", "greedy"), ("outranking_area", "iou"), ("ge", "gt"),
+                                                  ("index", "ignore"), (1.0, 0.0), (False, True))]
+
+
+@pytest.fixture(scope="module")
+def nms():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2502_00535_amd.binding as binding
+
+    return binding
+
+
+class ExFrames:
+    def __init__(self, nms, boxes, scores, classes, counts=None):
+        import torch
+
+        self.nms, self.torch = nms, torch
+        dev = torch.device("cuda:0")
+        self.F, self.n_max = scores.shape
+        self.boxes = torch.from_numpy(np.ascontiguousarray(boxes, np.float32)).to(dev)
+        self.scores = torch.from_numpy(np.ascontiguousarray(scores, np.float32)).to(dev)
+        self.classes = torch.from_numpy(np.ascontiguousarray(classes, np.int32)).to(dev)
+        self.counts = None if counts is None else torch.from_numpy(np.ascontiguousarray(counts, np.int32)).to(dev)
+        self.keep = torch.empty((self.F, self.n_max), dtype=torch.uint8, device=dev)
+        self.ws = torch.zeros(max(nms.nms_ex_workspace_bytes(self.n_max, self.F), 256), dtype=torch.uint8, device=dev)
+
+    def run(self, theta, opts):
+        self.keep.fill_(77)
+        self.nms.nms_run_ex_batched(self.boxes, self.scores, self.counts, self.n_max, self.F, float(theta), self.keep,
+                                    self.ws, rule=opts["rule"], measure=opts["measure"], compare=opts["compare"],
+                                    ties=opts["ties"], pixel_offset=opts["pixel_offset"],
+                                    classes=self.classes if opts["labelled"] else None)
+        self.torch.cuda.synchronize()
+        return self.keep.cpu().numpy()
+
+
+def oracle_ex(oracle, boxes, scores, classes, theta, opts, counts=None):
+    F, n_max = scores.shape
+    out = np.zeros((F, n_max), np.uint8)
+    for f in range(F):
+        n = n_max if counts is None else int(np.clip(counts[f], 0, n_max))
+        if n:
+            out[f, :n] = oracle.keep_ex(boxes[f, :n], scores[f, :n], np.float32(theta), rule=opts["rule"],
+                                        measure=opts["measure"], compare=opts["compare"], ties=opts["ties"],
+                                        pixel_offset=opts["pixel_offset"],
+                                        classes=classes[f, :n] if opts["labelled"] else None)
+    return out
+
+
+@pytest.mark.parametrize("n", [1, 64, 65, 700, 1500])
+def test_all_option_combinations(nms, oracle, n):
+    print(f"case n={n}", flush=True)
+    rng = np.random.default_rng(n)
+    boxes, scores = random_frame(9000 + n, n, extent=400, max_side=110, integer=(n % 2 == 0),
+                                 score_levels=max(3, n // 5))
+    classes = rng.integers(0, 4, n).astype(np.int32)
+    dev = ExFrames(nms, boxes[None], scores[None], classes[None])
+    for theta in (0.4, 0.5):
+        for opts in GRID:
+            want = oracle_ex(oracle, boxes[None], scores[None], classes[None], theta, opts)
+            got = dev.run(theta, opts)
+            assert np.array_equal(got, want), f"{opts} theta={theta}: {(got != want).sum()} differing keep bits"
+
+
+def test_equal_overlaps_decide_compare(nms, oracle):
+    """Thresholds equal to overlaps that occur (IoU and area measure): '>=' and '>' must split
+    exactly there."""
+    boxes, scores = random_frame(321, 600, extent=200, max_side=60, integer=True, score_levels=0)
+    classes = np.zeros(600, np.int32)
+    dev = ExFrames(nms, boxes[None], scores[None], classes[None])
+    for theta in (np.float32(0.5), np.float32(1.0 / 3.0), np.float32(0.25), np.float32(0.2), np.float32(1.0)):
+        for measure in ("outranking_area", "iou"):
+            for compare in ("ge", "gt"):
+                for off in (0.0, 1.0):
+                    opts = dict(rule="paper", measure=measure, compare=compare, ties="index", pixel_offset=off, labelled=False)
+                    want = oracle_ex(oracle, boxes[None], scores[None], classes[None], theta, opts)
+                    assert np.array_equal(dev.run(theta, opts), want), f"{opts} theta={theta}"
+    # integer boxes give many overlaps of exactly 1/2, 1/3, 1/4: the two compares must differ somewhere
+    a = oracle_ex(oracle, boxes[None], scores[None], classes[None], 0.5,
+                  dict(rule="paper", measure="outranking_area", compare="ge", ties="index", pixel_offset=0.0, labelled=False))
+    b = oracle_ex(oracle, boxes[None], scores[None], classes[None], 0.5,
+                  dict(rule="paper", measure="outranking_area", compare="gt", ties="index", pixel_offset=0.0, labelled=False))
+    assert (a != b).any()
+
+
+def test_batched_ragged_with_labels(nms, oracle):
+    rng = np.random.default_rng(5)
+    n_max, F = 300, 24
+    counts = rng.integers(0, n_max + 1, F).astype(np.int32)
+    counts[:4] = [0, 1, 65, n_max]
+    boxes = np.zeros((F, n_max, 4), np.float32)
+    scores = np.zeros((F, n_max), np.float32)
+    for f in range(F):
+        boxes[f], scores[f] = random_frame(4000 + f, n_max, extent=250, max_side=80, integer=(f % 2 == 0), score_levels=40)
+    classes = rng.integers(-2, 3, (F, n_max)).astype(np.int32)
+    dev = ExFrames(nms, boxes, scores, classes, counts)
+    for opts in GRID[::5]:
+        want = oracle_ex(oracle, boxes, scores, classes, 0.45, opts, counts)
+        got = dev.run(0.45, opts)
+        assert np.array_equal(got, want), f"{opts}: {(got != want).sum()} differing keep bits"
+
+
+def test_defaults_equal_the_default_path(nms, oracle):
+    w = make_config(2)
+    classes = np.zeros((w.frames, w.n), np.int32)
+    dev = ExFrames(nms, w.boxes, w.scores, classes)
+    opts = dict(rule="paper", measure="outranking_area", compare="ge", ties="index", pixel_offset=1.0, labelled=False)
+    got = dev.run(w.theta, opts)
+    import torch
+
+    keep = torch.empty((w.frames, w.n), dtype=torch.uint8, device="cuda:0")
+    ws = torch.zeros(nms.nms_workspace_bytes(w.n, w.frames), dtype=torch.uint8, device="cuda:0")
+    nms.nms_run_batched(dev.boxes, dev.scores, None, w.n, w.frames, w.theta, keep, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(got, keep.cpu().numpy())
+
+
+@pytest.mark.parametrize("opts", [
+    dict(rule="greedy", measure="iou", compare="gt", ties="index", pixel_offset=0.0, labelled=False),
+    dict(rule="paper", measure="iou", compare="ge", ties="ignore", pixel_offset=1.0, labelled=True),
+], ids=["greedy_iou_gt_offset0", "paper_iou_ties_ignored_labels"])
+def test_config3_dense_crowd_with_ties(nms, oracle, opts):
+    """16384 boxes, 1 % exact score ties, several rank chunks."""
+    w = make_config(3)
+    rng = np.random.default_rng(33)
+    classes = rng.integers(0, 3, (1, w.n)).astype(np.int32)
+    dev = ExFrames(nms, w.boxes, w.scores, classes)
+    want = oracle_ex(oracle, w.boxes, w.scores, classes, w.theta, opts)
+    got = dev.run(w.theta, opts)
+    assert np.array_equal(got, want), f"{(got != want).sum()} differing keep bits"
+    assert 0 < want.sum() < want.size
