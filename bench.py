@@ -27,7 +27,12 @@ if ROOT not in sys.path:
 
 FLOPS_PER_PAIR = 13            # min,max,sub,add,max0 per axis (10) + mul + div + compare
 PEAK_FP32_VECTOR_TFLOPS = 157.3  # MI355X datasheet (packed FMA); see the design doc for the unpacked ceiling
-PEAK_UNPACKED_TOPS = 39.3        # 256 CU x 4 SIMD x 16 lanes x 2.4 GHz, one non-FMA op per lane per clock
+# Issue model of the pair-test kernel: per row of 64 pairs a SIMD issues 5 instructions of the
+# 4-cycle class (4 x v_min/v_max, v_cmp) and 5 of the 2-cycle class (2 x v_sub, 2 x v_add, v_mul);
+# cycle counts measured with the stand-alone probe (profiles/valu_issue_rates__gfx950.txt).
+ISSUE_CYCLES_PER_ROW = 5 * 4 + 5 * 2
+SIMDS = 256 * 4
+CLOCK_HZ = 2.4e9
 PEAK_HBM_GBS = 8000.0
 
 
@@ -71,7 +76,7 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="workload configuration of the headline number (0..4)")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-frames", type=int, default=128)
+    ap.add_argument("--cpu-sample-frames", type=int, default=256)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device copies (a known-size kernel to scale HBM counters by)")
     args = ap.parse_args()
@@ -146,9 +151,10 @@ def main():
         "kernel_ms": round(map_ms, 4),
         "flops_per_pair": FLOPS_PER_PAIR,
         "pairs_per_launch": pairs,
-        "frac_of_unpacked_issue_ceiling": round(achieved_tflops / PEAK_UNPACKED_TOPS, 4),
-        "peak_unpacked_issue_Tops": PEAK_UNPACKED_TOPS,
     }
+    issue_bound_ms = pairs / 64 * ISSUE_CYCLES_PER_ROW / (SIMDS * CLOCK_HZ) * 1e3
+    roofline["valu_issue_bound_ms"] = round(issue_bound_ms, 4)          # this instruction mix issued back to back
+    roofline["frac_of_valu_issue_bound"] = round(issue_bound_ms / map_ms, 4)
     traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(traffic_file):
         try:
@@ -214,7 +220,16 @@ def main():
             tg[1].record()
             torch.cuda.synchronize()
             sweep_ms += tg[0].elapsed_time(tg[1]) / steps3
+        ws_g = torch.empty(nms.nms_greedy_workspace_bytes(w.n, w.frames), dtype=torch.uint8, device=dev)
+        keep_g1 = torch.empty((w.frames, w.n), dtype=torch.uint8, device=dev)
+        ms_g = time_steps(lambda: nms.nms_run_greedy_batched(d["boxes"], d["scores"], None, w.n, w.frames, w.theta,
+                                                             keep_g1, ws_g), steps3, 2)
+        greedy_same = bool(torch.equal(keep_g1, keep_g))
+        del ws_g, keep_g1
         extra["greedy_rule"] = {
+            "nms_run_greedy_batched_ms_per_step": round(ms_g, 4),
+            "pair_tests_per_s": round(pairs / (ms_g * 1e-3), 1),
+            "one_call_equals_steps": greedy_same,
             "sweep_ms": round(sweep_ms, 4),
             "ms_per_step_rank_mask_sweep": round(split[0] + split[1] + sweep_ms, 4),
             "survivors": int(keep_g.sum().item()),
@@ -329,6 +344,16 @@ def main():
             "sample": f"first {sample} of {w.frames} frames of {w.name}, single thread, {cpu_s:.2f} s",
             "differing_keep_bits_vs_gpu": differing,
         }
+        # the same oracle function, one frame per task, on all host cores the box gives this process
+        from concurrent.futures import ThreadPoolExecutor
+
+        threads = max(1, min(16, len(os.sched_getaffinity(0))))
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(max_workers=threads) as pool:  # the C call releases the GIL
+            list(pool.map(lambda f: orc.keep(w.boxes[f], w.scores[f], np.float32(w.theta)), range(sample)))
+        par_s = time.perf_counter() - t0
+        cpu_baseline["frames_parallel"] = {"value": round(sample_pairs / par_s, 1), "unit": "pair-tests/s",
+                                           "cores": threads, "seconds": round(par_s, 2)}
 
     line = {
         "metric": "pair-tests/s (batched)",

@@ -318,13 +318,17 @@ template <int PAIR, bool WRITE_MASK, bool DIAG>
 __device__ __forceinline__ void tile_sweep(const float4 *__restrict__ vb, const float4 cb, float c_area, float c_T,
                                            float y_one, const NmsThetaConst &th, int lane, TileState &st)
 {
+    // Rows go in groups of kGroup: the group's victims are fetched together (their scalar
+    // loads issue back to back) and its words are formed without any branch in between.
+    constexpr int kGroup = WRITE_MASK ? 8 : 16;
 #pragma unroll 1
-    for (int grp = 0; grp < kTile / 16; ++grp) {
-        const float4 *__restrict__ vg = vb + 16 * grp;
-        unsigned grp_bits = 0;  // wave-uniform: bit k = row 16*grp+k has an eliminator
+    for (int grp = 0; grp < kTile / kGroup; ++grp) {
+        const float4 *__restrict__ vg = vb + kGroup * grp;
+        unsigned grp_bits = 0;  // wave-uniform: bit k = row kGroup*grp+k has an eliminator
+        unsigned long long words[kGroup];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            const int r = 16 * grp + k;
+        for (int k = 0; k < kGroup; ++k) {
+            const int r = kGroup * grp + k;
             const float4 v = vg[k];
             bool hit;
             if (PAIR == kPairFastYScaled)
@@ -335,18 +339,24 @@ __device__ __forceinline__ void tile_sweep(const float4 *__restrict__ vb, const 
                 hit = nms_eliminates_exact(v.x, v.y, v.z, v.w, cb.x, cb.y, cb.z, cb.w, c_area, th.theta);
             unsigned long long word = __ballot(hit);
             if (DIAG) word &= (1ull << r) - 1ull;  // only better-ranked boxes eliminate
-            if (WRITE_MASK) {
-                if (word != 0) {  // wave-uniform branch; most rows of most tiles have no eliminator
-                    const bool mine = (lane == r);  // lane r collects the word of row r
-                    st.w_lo = mine ? (unsigned)word : st.w_lo;
-                    st.w_hi = mine ? (unsigned)(word >> 32) : st.w_hi;
-                }
-            } else {
-                grp_bits |= (word != 0 ? 1u : 0u) << k;
-            }
+            words[k] = word;
+            grp_bits |= (word != 0 ? 1u : 0u) << k;
         }
-        if (!WRITE_MASK)
+        if (WRITE_MASK) {
+            // lane r collects the word of row r.  Most rows of most tiles have no eliminator:
+            // the move sits behind a wave-uniform branch.
+#pragma unroll
+            for (int k = 0; k < kGroup; ++k) {
+                if (words[k] != 0) {
+                    const int r = kGroup * grp + k;
+                    const bool mine = (lane == r);
+                    st.w_lo = mine ? (unsigned)words[k] : st.w_lo;
+                    st.w_hi = mine ? (unsigned)(words[k] >> 32) : st.w_hi;
+                }
+            }
+        } else {
             st.lane_hit |= ((lane >> 4) == grp) ? ((grp_bits >> (lane & 15)) & 1u) : 0u;
+        }
     }
 }
 
@@ -395,14 +405,15 @@ map_tile_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ c
     const float c_area = area[tc * kTile + lane];
     const float c_T = FAST ? nms_pair_threshold(c_area, th.m) : 0.0f;
 
-    // y-scaled form (fused kernel with a fast threshold only; its launcher always passes the
-    // scaled table): usable for a tile pair when the rank step flagged both tiles regular.
-    // The pointers are formed unconditionally so that the victims' loads stay scalar loads.
-    constexpr bool kScaled = FAST && !WRITE_MASK;
+    // y-scaled form (fast threshold, and the caller has the scaled table and the tile flags
+    // of the rank step: the whole-path calls do, the stand-alone map step does not): usable
+    // for a tile pair when the rank step flagged both tiles regular.  The pointers are formed
+    // unconditionally so that the victims' loads stay scalar loads.
+    constexpr bool kScaled = FAST;
     const float4 *__restrict__ ysc4 = ysc + (size_t)f * n_pad;
     const unsigned *__restrict__ ytile_f = ytile + (size_t)f * (n_pad / kTile);
     bool c_regular = false;
-    if (kScaled) c_regular = ytile_f[tc] != 0;
+    if (kScaled && ysc != nullptr) c_regular = ytile_f[tc] != 0;
     const float4 cbs = make_float4(cb.x, cb.y * NMS_YSCALE, cb.z, cb.w * NMS_YSCALE);
     const float c_Ts = c_T * NMS_YSCALE;
     float y_one;  // NMS_YSCALE in a vector register (opaque to the compiler so it stays there)
@@ -1226,9 +1237,9 @@ int nms_run_greedy_batched(const float *boxes, const float *scores, const int32_
     int32_t *order = w.order;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    st = rank_launch(boxes, scores, counts, n_max, frames, w.order, w.sorted5, w.keys, nullptr, nullptr, nullptr, s);
+    st = rank_launch(boxes, scores, counts, n_max, frames, w.order, w.sorted5, w.keys, nullptr, w.ysc, w.ytile, s);
     if (st != NMS_OK) return st;
-    st = map_launch<true>(w.sorted5, counts, n_max, frames, threshold, mask, nullptr, nullptr, nullptr, nullptr, s);
+    st = map_launch<true>(w.sorted5, counts, n_max, frames, threshold, mask, nullptr, nullptr, w.ysc, w.ytile, s);
     if (st != NMS_OK) return st;
     return nms_reduce_greedy_batched(reinterpret_cast<const uint64_t *>(mask), order, counts, n_max, frames, keep_out,
                                      stream);
