@@ -456,11 +456,11 @@ map_tile_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ c
 // guard, so it only wins where launch latency dominates: single frames up to a few
 // thousand boxes.
 //
-// A workgroup owns kDirectRows consecutive victims; its wavefronts split the n outranking
+// A workgroup owns ROWS consecutive victims (16, or fewer when that is needed to put a
+// workgroup on every compute unit); its wavefronts split the n outranking
 // candidates in 64-box tiles (lane = candidate c, victim r wave-uniform through scalar
 // loads, exactly as in map_tile_kernel).  Each wavefront ends with one bit per victim,
 // the workgroup ORs them through LDS and writes keep_out in input order.
-constexpr int kDirectRows = 16;
 
 // Which score compare decides "candidate c outranks victim r" for a whole tile:
 // every candidate index below every victim index -> equal scores outrank (>=);
@@ -491,7 +491,7 @@ __device__ __forceinline__ unsigned long long direct_row(const float4 v, float v
     return __ballot(hit) & outranks;
 }
 
-template <bool FAST, int GUARD, bool CLAMP>
+template <bool FAST, int GUARD, bool CLAMP, int ROWS>
 __device__ __forceinline__ unsigned direct_rows(const float4 *__restrict__ box4, const float *__restrict__ score,
                                                 int v0, int n_f, const float4 cb, float c_score, float c_area, float c_T,
                                                 int c, const NmsThetaConst &th)
@@ -500,68 +500,69 @@ __device__ __forceinline__ unsigned direct_rows(const float4 *__restrict__ box4,
     if (CLAMP) {
         // ragged last group of a frame: plain loop over the victims that exist
 #pragma unroll 1
-        for (int k = 0; k < kDirectRows && v0 + k < n_f; ++k) {
+        for (int k = 0; k < ROWS && v0 + k < n_f; ++k) {
             const unsigned long long word = direct_row<FAST, GUARD>(box4[v0 + k], score[v0 + k], v0 + k, cb, c_score,
                                                                     c_area, c_T, c, th);
             bits |= (word != 0 ? 1u : 0u) << k;
         }
         return bits;
     }
+    constexpr int kBatch = ROWS < 8 ? ROWS : 8;
 #pragma unroll 1
-    for (int half = 0; half < kDirectRows / 8; ++half) {
-        // eight victims at a time: their scalar loads issue together, 40 SGPRs live
-        float4 v[8];
-        float v_score[8];
+    for (int half = 0; half < ROWS / kBatch; ++half) {
+        // up to eight victims at a time: their scalar loads issue together, 40 SGPRs live
+        float4 v[kBatch];
+        float v_score[kBatch];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            v[k] = box4[v0 + 8 * half + k];
-            v_score[k] = score[v0 + 8 * half + k];
+        for (int k = 0; k < kBatch; ++k) {
+            v[k] = box4[v0 + kBatch * half + k];
+            v_score[k] = score[v0 + kBatch * half + k];
         }
         unsigned half_bits = 0;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const unsigned long long word = direct_row<FAST, GUARD>(v[k], v_score[k], v0 + 8 * half + k, cb, c_score,
-                                                                    c_area, c_T, c, th);
+        for (int k = 0; k < kBatch; ++k) {
+            const unsigned long long word = direct_row<FAST, GUARD>(v[k], v_score[k], v0 + kBatch * half + k, cb,
+                                                                    c_score, c_area, c_T, c, th);
             half_bits |= (word != 0 ? 1u : 0u) << k;
         }
-        bits |= half_bits << (8 * half);
+        bits |= half_bits << (kBatch * half);
     }
     return bits;
 }
 
-template <bool FAST, bool CLAMP>
+template <bool FAST, bool CLAMP, int ROWS>
 __device__ __forceinline__ unsigned direct_tile(const float4 *__restrict__ box4, const float *__restrict__ score,
                                                 int v0, int n_f, int t, const float4 cb, float c_score, float c_area,
                                                 float c_T, int c, const NmsThetaConst &th)
 {
     if (t * kTile + kTile - 1 < v0)
-        return direct_rows<FAST, kGuardLowerIndex, CLAMP>(box4, score, v0, n_f, cb, c_score, c_area, c_T, c, th);
-    if (t * kTile > v0 + kDirectRows - 1)
-        return direct_rows<FAST, kGuardHigherIndex, CLAMP>(box4, score, v0, n_f, cb, c_score, c_area, c_T, c, th);
-    return direct_rows<FAST, kGuardMixed, CLAMP>(box4, score, v0, n_f, cb, c_score, c_area, c_T, c, th);
+        return direct_rows<FAST, kGuardLowerIndex, CLAMP, ROWS>(box4, score, v0, n_f, cb, c_score, c_area, c_T, c, th);
+    if (t * kTile > v0 + ROWS - 1)
+        return direct_rows<FAST, kGuardHigherIndex, CLAMP, ROWS>(box4, score, v0, n_f, cb, c_score, c_area, c_T, c, th);
+    return direct_rows<FAST, kGuardMixed, CLAMP, ROWS>(box4, score, v0, n_f, cb, c_score, c_area, c_T, c, th);
 }
 
-template <bool FAST>
+template <bool FAST, int ROWS>
 __global__ void __launch_bounds__(1024)
 direct_kernel(const float *__restrict__ boxes, const float *__restrict__ scores, const int32_t *__restrict__ counts,
               int n_max, NmsThetaConst th, uint8_t *__restrict__ keep_out)
 {
     __shared__ unsigned hits[16];
     const int f = blockIdx.y;
-    const int v0 = blockIdx.x * kDirectRows;
+    const int v0 = blockIdx.x * ROWS;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int n_waves = blockDim.x >> 6;
     const int n_f = frame_count(counts, f, n_max);
     uint8_t *keep_f = keep_out + (size_t)f * n_max;
     if (v0 >= n_f) {  // whole group beyond the frame's count (uniform for the workgroup)
-        if (threadIdx.x < kDirectRows && v0 + (int)threadIdx.x < n_max) keep_f[v0 + threadIdx.x] = 0;
+        if (threadIdx.x < ROWS && v0 + (int)threadIdx.x < n_max) keep_f[v0 + threadIdx.x] = 0;
         return;
     }
     const float4 *box4 = reinterpret_cast<const float4 *>(boxes) + (size_t)f * n_max;
     const float *score = scores + (size_t)f * n_max;
     const int tiles = (n_f + kTile - 1) / kTile;
-    const bool full = v0 + kDirectRows <= n_f;
+    const bool full = v0 + ROWS <= n_f;
 
     unsigned acc = 0;
     for (int t = wave; t < tiles; t += n_waves) {
@@ -574,13 +575,13 @@ direct_kernel(const float *__restrict__ boxes, const float *__restrict__ scores,
         const float c_area = nms_box_area(cb.x, cb.y, cb.z, cb.w);
         const float c_T = FAST ? nms_pair_threshold(c_area, th.m) : 0.0f;
         if (full)
-            acc |= direct_tile<FAST, false>(box4, score, v0, n_f, t, cb, c_score, c_area, c_T, c, th);
+            acc |= direct_tile<FAST, false, ROWS>(box4, score, v0, n_f, t, cb, c_score, c_area, c_T, c, th);
         else
-            acc |= direct_tile<FAST, true>(box4, score, v0, n_f, t, cb, c_score, c_area, c_T, c, th);
+            acc |= direct_tile<FAST, true, ROWS>(box4, score, v0, n_f, t, cb, c_score, c_area, c_T, c, th);
     }
     if (lane == 0) hits[wave] = acc;
     __syncthreads();
-    if (threadIdx.x < kDirectRows) {
+    if (threadIdx.x < ROWS) {
         const int r = v0 + threadIdx.x;
         unsigned any = 0;
         for (int w = 0; w < n_waves; ++w) any |= hits[w];
@@ -948,12 +949,20 @@ int direct_launch(const float *boxes, const float *scores, const int32_t *counts
     const NmsThetaConst th = nms_make_theta_const(threshold);
     const int tiles = (n_max + kTile - 1) / kTile;
     const int waves = tiles < 16 ? tiles : 16;
-    const dim3 grid((n_max + kDirectRows - 1) / kDirectRows, frames);
+    // victims per workgroup: 16, or 8 / 4 when that is what it takes to have a workgroup for
+    // every compute unit (a single 1024-box frame is 64 workgroups of 16 rows on a 256-CU chip)
+    int rows = 16;
+    while (rows > 4 && (long long)frames * ((n_max + rows - 1) / rows) < 256) rows >>= 1;
+    const dim3 grid((n_max + rows - 1) / rows, frames);
     begin_launch();
-    if (th.fast)
-        direct_kernel<true><<<grid, dim3(waves * 64), 0, stream>>>(boxes, scores, counts, n_max, th, keep_out);
-    else
-        direct_kernel<false><<<grid, dim3(waves * 64), 0, stream>>>(boxes, scores, counts, n_max, th, keep_out);
+#define NMS_LAUNCH_DIRECT(FAST_, ROWS_) \
+    direct_kernel<FAST_, ROWS_><<<grid, dim3(waves * 64), 0, stream>>>(boxes, scores, counts, n_max, th, keep_out)
+    if (th.fast) {
+        if (rows == 16) NMS_LAUNCH_DIRECT(true, 16); else if (rows == 8) NMS_LAUNCH_DIRECT(true, 8); else NMS_LAUNCH_DIRECT(true, 4);
+    } else {
+        if (rows == 16) NMS_LAUNCH_DIRECT(false, 16); else if (rows == 8) NMS_LAUNCH_DIRECT(false, 8); else NMS_LAUNCH_DIRECT(false, 4);
+    }
+#undef NMS_LAUNCH_DIRECT
     return launch_status();
 }
 
