@@ -591,31 +591,37 @@ direct_kernel(const float *__restrict__ boxes, const float *__restrict__ scores,
 
 // ----------------------------------------------------------------------------- reduce
 
-// One workgroup per 64 rows: lane = row, the four wavefronts split the row's words,
-// reads are coalesced across rows for a fixed word index.
+// Lane = row.  Row tile tr owns tr + 1 words per row (the triangle), so a wavefront takes the
+// tile rows p and T - 1 - p: T + 1 words of 512 contiguous bytes each, the same for every
+// wavefront, all loads independent of each other (eight in flight per wavefront), no LDS and no
+// barrier.  Each mask byte is read exactly once.  (Two rows per lane with 16-byte loads, and
+// non-temporal loads, both measured slower.)
 __global__ void __launch_bounds__(256)
 reduce_rows_kernel(const unsigned long long *__restrict__ mask, const int32_t *__restrict__ order,
                    const int32_t *__restrict__ counts, int n_max, int n_pad, uint8_t *__restrict__ keep_out)
 {
-    __shared__ unsigned long long part[4][kTile];
     const int f = blockIdx.y;
-    const int tr = blockIdx.x;
     const int lane = threadIdx.x & 63;
-    const int wv = threadIdx.x >> 6;
+    const int T = n_pad / kTile;
+    const int p = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+    if (p >= (T + 1) / 2) return;
     const int n_f = frame_count(counts, f, n_max);
-    const int row = tr * kTile + lane;
-    unsigned long long acc = 0;
-    if (tr * kTile < n_f) {
-        const unsigned long long *m = mask + (size_t)f * ((size_t)(n_pad / kTile) * n_pad);
-        for (int w = wv; w <= tr; w += 4) acc |= m[(size_t)w * n_pad + row];
-    }
-    part[wv][lane] = acc;
-    __syncthreads();
-    if (wv == 0) {
-        const unsigned long long all = part[0][lane] | part[1][lane] | part[2][lane] | part[3][lane];
-        uint8_t *keep_f = keep_out + (size_t)f * n_max;
+    const unsigned long long *m = mask + (size_t)f * ((size_t)T * n_pad);
+    uint8_t *keep_f = keep_out + (size_t)f * n_max;
+    const int32_t *order_f = order + (size_t)f * n_max;
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+        const int tr = half == 0 ? p : T - 1 - p;
+        if (half == 1 && tr == p) break;  // odd T: the middle tile row has no partner
+        const int row = tr * kTile + lane;
+        unsigned long long acc = 0;
+        if (tr * kTile < n_f) {  // tile rows beyond the count are not written by the map step
+            const unsigned long long *col = m + row;
+#pragma unroll 8
+            for (int w = 0; w <= tr; ++w) acc |= col[(size_t)w * n_pad];
+        }
         if (row < n_f)
-            keep_f[order[(size_t)f * n_max + row]] = (all == 0) ? 1 : 0;
+            keep_f[order_f[row]] = (acc == 0) ? 1 : 0;
         else if (row < n_max)
             keep_f[row] = 0;  // input slots beyond the frame's count
     }
@@ -1097,7 +1103,8 @@ int nms_reduce_batched(const uint64_t *mask, const int32_t *order, const int32_t
     if (!mask || !order || !keep_out) return NMS_ERR_INVALID_ARG;
     const int n_pad = nms_padded_n(n_max);
     begin_launch();
-    reduce_rows_kernel<<<dim3(n_pad / kTile, frames), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
+    const int row_pairs = (n_pad / kTile + 1) / 2;  // one wavefront per pair of tile rows, four per workgroup
+    reduce_rows_kernel<<<dim3((row_pairs + 3) / 4, frames), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
         reinterpret_cast<const unsigned long long *>(mask), order, counts, n_max, n_pad, keep_out);
     return launch_status();
 }
