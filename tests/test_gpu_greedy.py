@@ -40,7 +40,7 @@ def test_single_frame(nms, oracle, n):
 def test_long_chains(nms, oracle):
     """Staircase of boxes: each eliminates only its successor, so survivors alternate and
     the tile-internal fixed point needs its full depth; chains cross tile borders."""
-    for N in (64, 65, 200, 1000):
+    for N in (64, 65, 200, 1000, 4096, 4097, 10000):  # the last two span several 4096-rank blocks
         boxes, scores = staircase(N)
         want = check(nms, oracle, boxes[None], scores[None], 0.5)
         assert want[0].tolist() == [1 - (k & 1) for k in range(N)]
@@ -61,6 +61,20 @@ def test_batched_ragged(nms, oracle):
         boxes[f], scores[f] = random_frame(8000 + f, n_max, extent=300, max_side=90, integer=(f % 2 == 0),
                                            score_levels=60)
     check(nms, oracle, boxes, scores, 0.4, counts)
+
+
+def test_batched_ragged_several_blocks(nms, oracle):
+    """Frames longer than one 4096-rank block of the sweep, with counts on both sides of the
+    block borders (and empty frames) in one call."""
+    rng = np.random.default_rng(78)
+    n_max, F = 9000, 10
+    counts = np.array([0, 1, 4095, 4096, 4097, 8192, 8193, 9000, 5000, 64], np.int32)
+    boxes = np.zeros((F, n_max, 4), np.float32)
+    scores = np.zeros((F, n_max), np.float32)
+    for f in range(F):
+        boxes[f], scores[f] = random_frame(8100 + f, n_max, extent=1200, max_side=120, integer=(f % 2 == 0),
+                                           score_levels=500)
+    check(nms, oracle, boxes, scores, 0.3, counts)
 
 
 @pytest.mark.parametrize("index", [0, 1, 2, 3, 4])
