@@ -264,6 +264,29 @@ def test_configs_full_size(nms, oracle, index):
     assert 0 < want.sum() < want.size
 
 
+def test_largest_frame(nms, oracle):
+    """n = NMS_MAX_N = 65536: sixteen rank chunks, a 512 MiB mask, sixteen blocks of the greedy
+    sweep; both rules, every keep bit.  (The two oracle runs take about half a minute; they run
+    side by side on two host threads.)"""
+    from concurrent.futures import ThreadPoolExecutor
+
+    n = 65536
+    boxes, scores = random_frame(65536, n, extent=6000, max_side=100, integer=False, score_levels=20000)
+    theta = np.float32(0.4)
+    print("case n=65536: oracle running", flush=True)
+    with ThreadPoolExecutor(max_workers=2) as pool:
+        fut = pool.submit(oracle.keep, boxes, scores, theta)
+        fut_g = pool.submit(oracle.greedy_keep, boxes, scores, theta)
+        want, want_g = fut.result(), fut_g.result()
+    print("case n=65536: GPU running", flush=True)
+    dev = DeviceFrames(nms, boxes[None], scores[None])
+    dev.fused(float(theta), want=want[None])   # automatic and ranked route (the direct one is skipped: 4.3 G pair slots)
+    assert np.array_equal(dev.steps(float(theta))[0], want)
+    via_steps, one_call = dev.greedy(float(theta))
+    assert np.array_equal(via_steps[0], want_g) and np.array_equal(one_call[0], want_g)
+    assert 0 < want.sum() < want_g.sum() < n
+
+
 def test_deterministic_and_inputs_untouched(nms):
     w = make_config(2)
     dev = DeviceFrames(nms, w.boxes, w.scores)
