@@ -828,17 +828,29 @@ gather_ranked_kernel(const int32_t *__restrict__ order, const float *__restrict_
     if (classes != nullptr) ranked_class[(size_t)f * n_pad + r] = real ? classes[(size_t)f * n_max + idx] : 0;
 }
 
-enum { kExStrict = 1, kExTiesIgnore = 2, kExClasses = 4 };
+enum { kExTiesIgnore = 2, kExClasses = 4 };
 
-// The map step with the selectable measure / compare / tie / label / offset variants, in the
-// literal form (IEEE division), one wavefront per 64x64 tile of the ranked lower triangle, mask
-// layout as in map_tile_kernel.  Rank order puts equal scores next to each other, so "ties
-// ignored" is the extra test score_c > score_r on the pairs the triangle already holds.
-template <bool IOU>
+// The map step with the selectable measure / compare / tie / label / offset variants, one
+// wavefront per 64x64 tile of the ranked lower triangle, mask layout as in map_tile_kernel.
+// The denominator changes per pair under intersection-over-union, so there is no per-box
+// threshold to precompute; the division and the compare are still decided without dividing:
+//     RN(inter / d) >= theta  <=>  inter >= m * d     m = rounding boundary just below theta
+//     RN(inter / d) >  theta  <=>  inter >= m' * d    m' = rounding boundary just above theta
+// (d > 0; equality with m*d or m'*d cannot occur, by the same argument as in nms_pair.h).  m and m'
+// have 25 significant bits and d 24, so the product is exact in float64 and the compare is
+// done there.  Thresholds outside [2^-40, 2^20] take the literal float32 division (kExDivide).
+// Rank order puts equal scores next to each other, so "ties ignored" is the extra test
+// score_c > score_r on the pairs the triangle already holds.
+enum { kExBoundary = 0, kExDivideGe = 1, kExDivideGt = 2 };
+
+// IOU: the measure.  MODE: how the threshold is decided (above).  AUX: the launch uses the
+// rank-ordered scores and / or labels (ties ignored, labels given).
+template <bool IOU, int MODE, bool AUX>
 __global__ void __launch_bounds__(kMapWaves * 64)
 map_tile_ex_kernel(const float *__restrict__ sorted5, const float *__restrict__ ranked_score,
                    const int32_t *__restrict__ ranked_class, const int32_t *__restrict__ counts, int n_max, int n_pad,
-                   int tiles, float theta, float offset, int flags, unsigned long long *__restrict__ mask)
+                   int tiles, float theta, double boundary, float offset, int flags,
+                   unsigned long long *__restrict__ mask)
 {
     const int lane = threadIdx.x & 63;
     const int f = blockIdx.y;
@@ -852,43 +864,67 @@ map_tile_ex_kernel(const float *__restrict__ sorted5, const float *__restrict__ 
     const float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
     const float4 *box4 = reinterpret_cast<const float4 *>(sorted_f);
     const float *score_f = ranked_score + (size_t)f * n_pad;
-    const int32_t *class_f = ranked_class + (size_t)f * n_pad;  // only dereferenced with kExClasses
-    const bool strict = (flags & kExStrict) != 0;
+    const int32_t *class_f = ranked_class + (size_t)f * n_pad;  // unwritten (but allocated) when no labels were given
     const bool ties_ignore = (flags & kExTiesIgnore) != 0;
     const bool labelled = (flags & kExClasses) != 0;
 
     const int c = tc * kTile + lane;
     const float4 cb = box4[c];
     const float c_area = ((cb.z - cb.x) + offset) * ((cb.w - cb.y) + offset);
-    const float c_score = score_f[c];
-    const int c_class = labelled ? class_f[c] : 0;
+    const float c_score = AUX ? score_f[c] : 0.0f;
+    const int c_class = AUX ? class_f[c] : 0;
 
     const float4 *__restrict__ vb = box4 + tr * kTile;  // wave-uniform addresses: scalar loads
     const float *__restrict__ vs = score_f + tr * kTile;
     const int32_t *__restrict__ vc = class_f + tr * kTile;
     unsigned w_lo = 0, w_hi = 0;
-#pragma unroll 4
-    for (int r = 0; r < kTile; ++r) {
-        const float4 v = vb[r];
-        const float iw = fmaxf(0.0f, (fminf(v.z, cb.z) - fmaxf(v.x, cb.x)) + offset);
-        const float ih = fmaxf(0.0f, (fminf(v.w, cb.w) - fmaxf(v.y, cb.y)) + offset);
-        const float inter = iw * ih;
-        float q;
-        if (IOU) {
-            const float v_area = ((v.z - v.x) + offset) * ((v.w - v.y) + offset);
-            q = inter / ((v_area + c_area) - inter);
-        } else {
-            q = inter / c_area;
+    constexpr int kGroup = 8;
+#pragma unroll 1
+    for (int grp = 0; grp < kTile / kGroup; ++grp) {
+        // a group's victims are fetched together, its words formed without a branch in between
+        float4 v[kGroup];
+        float v_score[kGroup];
+        int v_class[kGroup];
+#pragma unroll
+        for (int k = 0; k < kGroup; ++k) {
+            v[k] = vb[kGroup * grp + k];
+            v_score[k] = AUX ? vs[kGroup * grp + k] : 0.0f;
+            v_class[k] = AUX ? vc[kGroup * grp + k] : 0;
         }
-        bool hit = strict ? (q > theta) : !(q < theta);
-        if (ties_ignore) hit = hit && (c_score > vs[r]);
-        if (labelled) hit = hit && (c_class == vc[r]);
-        unsigned long long word = __ballot(hit);
-        if (tr == tc) word &= (1ull << r) - 1ull;  // only better-ranked boxes eliminate
-        if (word != 0) {
-            const bool mine = (lane == r);
-            w_lo = mine ? (unsigned)word : w_lo;
-            w_hi = mine ? (unsigned)(word >> 32) : w_hi;
+        unsigned long long words[kGroup];
+#pragma unroll
+        for (int k = 0; k < kGroup; ++k) {
+            const int r = kGroup * grp + k;
+            const float iw = fmaxf(0.0f, (fminf(v[k].z, cb.z) - fmaxf(v[k].x, cb.x)) + offset);
+            const float ih = fmaxf(0.0f, (fminf(v[k].w, cb.w) - fmaxf(v[k].y, cb.y)) + offset);
+            const float inter = iw * ih;
+            float denom = c_area;
+            if (IOU) {
+                const float v_area = ((v[k].z - v[k].x) + offset) * ((v[k].w - v[k].y) + offset);
+                denom = (v_area + c_area) - inter;
+            }
+            bool hit;
+            if (MODE == kExBoundary)
+                hit = (double)inter >= boundary * (double)denom;
+            else if (MODE == kExDivideGe)
+                hit = !(inter / denom < theta);
+            else
+                hit = inter / denom > theta;
+            if (AUX) {
+                hit = hit && (!ties_ignore || c_score > v_score[k]);
+                hit = hit && (!labelled || c_class == v_class[k]);
+            }
+            unsigned long long word = __ballot(hit);
+            if (tr == tc) word &= (1ull << r) - 1ull;  // only better-ranked boxes eliminate
+            words[k] = word;
+        }
+#pragma unroll
+        for (int k = 0; k < kGroup; ++k) {
+            if (words[k] != 0) {  // wave-uniform
+                const bool mine = (lane == kGroup * grp + k);
+                w_lo = mine ? (unsigned)words[k] : w_lo;
+                w_hi = mine ? (unsigned)(words[k] >> 32) : w_hi;
+            }
         }
     }
     const int row = tr * kTile + lane;
@@ -1417,17 +1453,40 @@ int nms_run_ex_batched(const float *boxes, const float *scores, const int32_t *c
 
     const int tiles = triangle_units(n_pad / kTile, 1);
     const dim3 grid((tiles + kMapWaves - 1) / kMapWaves, frames);
-    const int flags = (opt.compare == NMS_COMPARE_GT ? kExStrict : 0) | (opt.ties == NMS_TIES_IGNORE ? kExTiesIgnore : 0) |
-                      (opt.classes ? kExClasses : 0);
+    // rounding boundary of the division next to theta, exact in float64: below theta for ">=", above it for ">"
+    double boundary = 0.0;
+    bool divide = true;
+    if (threshold >= 0x1p-40f && threshold <= 0x1p20f) {
+        uint32_t bits;
+        memcpy(&bits, &threshold, sizeof bits);
+        const uint32_t other_bits = opt.compare == NMS_COMPARE_GT ? bits + 1u : bits - 1u;
+        float other;
+        memcpy(&other, &other_bits, sizeof other);
+        boundary = 0.5 * ((double)threshold + (double)other);
+        divide = false;
+    }
+    const int flags = (opt.ties == NMS_TIES_IGNORE ? kExTiesIgnore : 0) | (opt.classes ? kExClasses : 0);
+    const int mode = !divide ? kExBoundary : (opt.compare == NMS_COMPARE_GT ? kExDivideGt : kExDivideGe);
+    const bool iou = opt.measure == NMS_MEASURE_IOU;
+    const bool aux = flags != 0;
     begin_launch();
-    if (opt.measure == NMS_MEASURE_IOU)
-        map_tile_ex_kernel<true><<<grid, dim3(kMapWaves * 64), 0, s>>>(w.sorted5, ranked_score, ranked_class, counts,
-                                                                        n_max, n_pad, tiles, threshold,
-                                                                        opt.pixel_offset, flags, mask);
-    else
-        map_tile_ex_kernel<false><<<grid, dim3(kMapWaves * 64), 0, s>>>(w.sorted5, ranked_score, ranked_class, counts,
-                                                                         n_max, n_pad, tiles, threshold,
-                                                                         opt.pixel_offset, flags, mask);
+#define NMS_LAUNCH_EX(IOU_, MODE_, AUX_)                                                                          \
+    map_tile_ex_kernel<IOU_, MODE_, AUX_><<<grid, dim3(kMapWaves * 64), 0, s>>>(                                 \
+        w.sorted5, ranked_score, ranked_class, counts, n_max, n_pad, tiles, threshold, boundary, opt.pixel_offset, \
+        flags, mask)
+#define NMS_LAUNCH_EX_MODE(IOU_, AUX_)                                                    \
+    do {                                                                                  \
+        if (mode == kExBoundary) NMS_LAUNCH_EX(IOU_, kExBoundary, AUX_);                  \
+        else if (mode == kExDivideGe) NMS_LAUNCH_EX(IOU_, kExDivideGe, AUX_);             \
+        else NMS_LAUNCH_EX(IOU_, kExDivideGt, AUX_);                                      \
+    } while (0)
+    if (iou) {
+        if (aux) NMS_LAUNCH_EX_MODE(true, true); else NMS_LAUNCH_EX_MODE(true, false);
+    } else {
+        if (aux) NMS_LAUNCH_EX_MODE(false, true); else NMS_LAUNCH_EX_MODE(false, false);
+    }
+#undef NMS_LAUNCH_EX_MODE
+#undef NMS_LAUNCH_EX
     st = launch_status();
     if (st != NMS_OK) return st;
     if (opt.rule == NMS_RULE_GREEDY)

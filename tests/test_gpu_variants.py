@@ -97,6 +97,19 @@ def test_equal_overlaps_decide_compare(nms, oracle):
     assert (a != b).any()
 
 
+@pytest.mark.parametrize("theta", [0.0, -1.0, 1.5, 2.0 ** -41, float("inf")])
+def test_thresholds_that_take_the_literal_division(nms, oracle, theta):
+    """Outside [2^-40, 2^20] the variants kernel divides; closed forms: theta <= 0 with '>=' leaves
+    one box per class at most... checked against the oracle for every measure / compare pair."""
+    boxes, scores = random_frame(99, 500, extent=250, max_side=70, integer=True, score_levels=50)
+    classes = np.random.default_rng(2).integers(0, 3, 500).astype(np.int32)
+    dev = ExFrames(nms, boxes[None], scores[None], classes[None])
+    for opts in GRID[::3]:
+        want = oracle_ex(oracle, boxes[None], scores[None], classes[None], theta, opts)
+        got = dev.run(theta, opts)
+        assert np.array_equal(got, want), f"{opts} theta={theta}: {(got != want).sum()} differing keep bits"
+
+
 def test_batched_ragged_with_labels(nms, oracle):
     rng = np.random.default_rng(5)
     n_max, F = 300, 24
