@@ -135,7 +135,12 @@ def main():
         nms.nms_run_batched_profiled(d["boxes"], d["scores"], None, d["n"], d["F"], w.theta, d["keep"], d["ws"], ev[k])
     torch.cuda.synchronize()
     rank_ms = sum(events.ms(e[0], e[1]) for e in ev) / K
-    map_ms = sum(events.ms(e[1], e[2]) for e in ev) / K
+    map_all = sorted(events.ms(e[1], e[2]) for e in ev)
+    map_ms = sum(map_all) / K
+    step_all = sorted(events.ms(e[0], e[2]) for e in ev)
+
+    def pct(v, q):
+        return round(v[min(len(v) - 1, int(q * len(v)))], 4)
     events.close()
     keep_gpu = d["keep"].cpu().numpy()
 
@@ -166,6 +171,8 @@ def main():
     extra = {
         "rank_kernel_ms": round(rank_ms, 4),
         "map_kernel_ms": round(map_ms, 4),
+        "map_kernel_ms_p10_p50_p90": [pct(map_all, 0.1), pct(map_all, 0.5), pct(map_all, 0.9)],
+        "step_ms_by_events_p10_p50_p90": [pct(step_all, 0.1), pct(step_all, 0.5), pct(step_all, 0.9)],
         "frames_per_s": round(w.frames / (ms_per_step * 1e-3), 1),
         "us_per_frame": round(ms_per_step * 1e3 / w.frames, 3),
         "survivors": int(keep_gpu.sum()),
