@@ -45,10 +45,9 @@ __device__ __forceinline__ unsigned long long rank_key(float score, unsigned idx
 
 // Rank-ordered row r: the box and its area, and (fused path only, ysc != nullptr) the same
 // box with y multiplied by NMS_YSCALE.  Returns whether the box may use the y-scaled form.
-__device__ __forceinline__ bool emit_ranked_box(const float *boxes_f, int idx, int r, int n_pad,
+__device__ __forceinline__ bool emit_ranked_box(const float4 b, int idx, int r, int n_pad,
                                                int32_t *order_f, float *sorted_f, float4 *ysc_f)
 {
-    const float4 b = reinterpret_cast<const float4 *>(boxes_f)[idx];
     order_f[r] = idx;
     reinterpret_cast<float4 *>(sorted_f)[r] = b;
     sorted_f[4 * (size_t)n_pad + r] = nms_box_area(b.x, b.y, b.z, b.w);
@@ -63,62 +62,110 @@ __device__ __forceinline__ void emit_padding_row(int r, int n_pad, float *sorted
     if (ysc_f != nullptr) ysc_f[r] = make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
-// Compare-exchange: afterwards lo <= hi when `up`, lo >= hi otherwise.
-__device__ __forceinline__ void compare_exchange(unsigned long long &lo, unsigned long long &hi, bool up)
+// Inclusive prefix sum over the 64 lanes of a wavefront with DPP: shifts by 1, 2, 4, 8 inside
+// each row of 16 lanes (lanes shifted in from outside a row read 0), then lane 15 of each row
+// broadcast into the next row (rows 1 and 3), then lane 31 into rows 2 and 3.
+__device__ __forceinline__ unsigned wave_inclusive_sum(unsigned x)
 {
-    const bool swap = (lo > hi) == up;
-    const unsigned long long a = swap ? hi : lo;
-    const unsigned long long b = swap ? lo : hi;
-    lo = a;
-    hi = b;
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, true);  // row_shr:1
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, true);  // row_shr:2
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, true);  // row_shr:4
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, true);  // row_shr:8
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false); // row_bcast:15 into rows 1, 3
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false); // row_bcast:31 into rows 2, 3
+    return x;
 }
 
-// Value of lane (l ^ J) for every lane l of the wavefront.  J = 1, 2: one DPP quad
-// permutation; J = 4, 8: two DPP row shifts, each enabled for the banks (groups of four
-// lanes) that look in its direction; J = 16, 32: ds_bpermute (crosses DPP rows).
-template <int J>
-__device__ __forceinline__ unsigned lane_xor(unsigned v, int lane)
+// Stable LSD radix sort of the P = 4 * blockDim.x (key, index) pairs of a workgroup, eight
+// bits per pass, four passes.  Element e = 256 * wave + 64 * q + lane is register q of its
+// thread.  Stability is what makes 32-bit keys enough: elements start in index order, so
+// equal scores keep the lower index first (the tie rule) without the index taking part in
+// any compare.  Per pass:
+//   - every wavefront ranks its 256 elements among themselves: for q = 0..3 in turn, the
+//     lanes that hold the same digit find each other with eight ballots, take their place
+//     after the elements of earlier q with that digit (running per-wavefront histogram in
+//     LDS, touched by its own wavefront only) and the group's first lane bumps the histogram;
+//   - the histograms are turned into start offsets per (digit, wavefront): column sums,
+//     then one wavefront scans the 256 digit totals;
+//   - every element goes to start + place in `buf`, and the threads read their elements back.
+// After the last pass `buf` holds ((key << 32) | index) in sorted order.
+__device__ __forceinline__ void radix_rank_chunk(unsigned (&key)[4], unsigned (&idx)[4], const int (&e)[4],
+                                                 unsigned long long *buf, unsigned *hist, unsigned *tot,
+                                                 unsigned *dbase)
 {
-    if (J == 1) return (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xf, 0xf, false);  // quad_perm [1,0,3,2]
-    if (J == 2) return (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xf, 0xf, false);  // quad_perm [2,3,0,1]
-    if (J == 4) {
-        int r = __builtin_amdgcn_update_dpp((int)v, (int)v, 0x104, 0xf, 0x5, false);  // row_shl:4 -> banks 0,2 read lane+4
-        return (unsigned)__builtin_amdgcn_update_dpp(r, (int)v, 0x114, 0xf, 0xA, false);  // row_shr:4 -> banks 1,3 read lane-4
-    }
-    if (J == 8) {
-        int r = __builtin_amdgcn_update_dpp((int)v, (int)v, 0x108, 0xf, 0x3, false);  // row_shl:8 -> banks 0,1 read lane+8
-        return (unsigned)__builtin_amdgcn_update_dpp(r, (int)v, 0x118, 0xf, 0xC, false);  // row_shr:8 -> banks 2,3 read lane-8
-    }
-    return (unsigned)__builtin_amdgcn_ds_bpermute((lane ^ J) << 2, (int)v);
-}
-
-// One stage of the bitonic network with stride J < 64 on the four keys of every lane.
-template <int J>
-__device__ __forceinline__ void lane_stage(unsigned long long (&K)[4], const int (&e)[4], int k, int lane)
-{
-    // lanes that hold the lower element of their pair: a constant lane mask per stride
-    constexpr unsigned long long kLowerLanes = J == 1 ? 0x5555555555555555ull : J == 2 ? 0x3333333333333333ull
-                                             : J == 4 ? 0x0f0f0f0f0f0f0f0full : J == 8 ? 0x00ff00ff00ff00ffull
-                                             : J == 16 ? 0x0000ffff0000ffffull : 0x00000000ffffffffull;
-    const bool lower = __builtin_amdgcn_inverse_ballot_w64(kLowerLanes);
+    const int tid = threadIdx.x;
+    const int nth = blockDim.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int W = nth >> 6;
+    unsigned *myhist = hist + wave * 256;
+#pragma unroll 1
+    for (int shift = 0; shift < 32; shift += 8) {
+        for (int i = lane; i < 256; i += 64) myhist[i] = 0;
+        unsigned place[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const unsigned lo = lane_xor<J>((unsigned)K[q], lane);
-        const unsigned hi = lane_xor<J>((unsigned)(K[q] >> 32), lane);
-        const unsigned long long other = ((unsigned long long)hi << 32) | lo;
-        const bool take_min = lower == ((e[q] & k) == 0);
-        const bool other_smaller = other < K[q];
-        K[q] = (take_min == other_smaller) ? other : K[q];
+        for (int q = 0; q < 4; ++q) {
+            const unsigned d = (key[q] >> shift) & 255u;
+            unsigned m_lo = ~0u, m_hi = ~0u;  // lanes whose digit equals mine
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                const unsigned all = 0u - ((d >> b) & 1u);  // all ones if my bit b is set
+                const unsigned long long set = __ballot(all != 0);
+                m_lo &= ~((unsigned)set ^ all);
+                m_hi &= ~((unsigned)(set >> 32) ^ all);
+            }
+            const unsigned below = __builtin_amdgcn_mbcnt_hi(m_hi, __builtin_amdgcn_mbcnt_lo(m_lo, 0u));
+            const unsigned total = __popc(m_lo) + __popc(m_hi);
+            const unsigned base = myhist[d];
+            if (below == 0) myhist[d] = base + total;
+            place[q] = base + below;
+        }
+        __syncthreads();
+        for (int d = tid; d < 256; d += nth) {
+            // the counts of digit d in every wavefront (all reads issued together), then their running sums
+            unsigned t[kChunk / 256];
+#pragma unroll
+            for (int w = 0; w < kChunk / 256; ++w) t[w] = w < W ? hist[w * 256 + d] : 0u;
+            unsigned run = 0;
+#pragma unroll
+            for (int w = 0; w < kChunk / 256; ++w) {
+                if (w < W) hist[w * 256 + d] = run;
+                run += t[w];
+            }
+            tot[d] = run;
+        }
+        __syncthreads();
+        if (wave == 0) {
+            const unsigned a0 = tot[4 * lane], a1 = tot[4 * lane + 1], a2 = tot[4 * lane + 2], a3 = tot[4 * lane + 3];
+            const unsigned sum = a0 + a1 + a2 + a3;
+            const unsigned incl = wave_inclusive_sum(sum);
+            const unsigned excl = incl - sum;
+            dbase[4 * lane] = excl;
+            dbase[4 * lane + 1] = excl + a0;
+            dbase[4 * lane + 2] = excl + a0 + a1;
+            dbase[4 * lane + 3] = excl + a0 + a1 + a2;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const unsigned d = (key[q] >> shift) & 255u;
+            const unsigned dest = dbase[d] + myhist[d] + place[q];
+            buf[dest] = ((unsigned long long)key[q] << 32) | idx[q];
+        }
+        __syncthreads();
+        if (shift < 24) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const unsigned long long v = buf[e[q]];
+                key[q] = (unsigned)(v >> 32);
+                idx[q] = (unsigned)v;
+            }
+        }
     }
 }
 
-// One workgroup ranks one chunk of up to kChunk boxes of one frame with a bitonic
-// network over P = 4 * blockDim.x keys (P a power of two, 256..4096).  Each thread keeps
-// four keys in registers: wavefront w owns elements 256w..256w+255, lane l holds elements
-// 256w + 64q + l (q = 0..3).  Strides 64 and 128 are exchanges between a thread's own
-// registers, strides 1..32 are lane exchanges (DPP up to 8, ds_bpermute for 16 and 32),
-// and only strides >= 256 (between wavefronts) go through LDS with workgroup barriers: 18 barriers for 4096 keys instead of
-// one per stage (78).
+// One workgroup ranks one chunk of up to kChunk boxes of one frame: P = 4 * blockDim.x
+// elements (P a multiple of 256, 256..4096), four per thread, sorted by radix_rank_chunk.
 // With a single chunk the kernel also writes order / sorted5 (and, for the fused path,
 // presets keep_out); with several chunks it leaves the chunk's sorted keys in `keys_ws`
 // for the merge kernel.
@@ -130,6 +177,9 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
                   float4 *__restrict__ ysc, unsigned *__restrict__ ytile)
 {
     __shared__ unsigned long long keys[kChunk];
+    __shared__ unsigned hist[(kChunk / 256) * 256];  // one row of 256 digit counts per wavefront
+    __shared__ unsigned tot[256];
+    __shared__ unsigned dbase[256];
     const int f = blockIdx.y;
     const int chunk = blockIdx.x;
     const int tid = threadIdx.x;
@@ -139,8 +189,6 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
     const int base = chunk * kChunk;
     int cnt = n_f - base;
     cnt = cnt < 0 ? 0 : (cnt > kChunk ? kChunk : cnt);
-    const int P = nth * 4;
-
     const float *scores_f = scores + (size_t)f * n_max;
     int e[4];
     unsigned long long K[4];
@@ -150,52 +198,13 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
         K[q] = (e[q] < cnt) ? rank_key(scores_f[base + e[q]], (unsigned)(base + e[q])) : kSentinel;
     }
 
-    for (int k = 2; k <= P; k <<= 1) {
-        if (k >= 512) {
-            // strides k/2 .. 256 cross wavefronts: through LDS
+    unsigned key32[4], index[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) keys[e[q]] = K[q];
-            __syncthreads();
-            for (int j = k >> 1; j >= 256; j >>= 1) {
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int c = tid + h * nth;  // P/2 exchanges per stage, two per thread
-                    const int i = ((c & ~(j - 1)) << 1) | (c & (j - 1));
-                    const int l = i | j;
-                    const bool up = (i & k) == 0;
-                    const unsigned long long a = keys[i];
-                    const unsigned long long b = keys[l];
-                    if ((a > b) == up) {
-                        keys[i] = b;
-                        keys[l] = a;
-                    }
-                }
-                __syncthreads();
-            }
-#pragma unroll
-            for (int q = 0; q < 4; ++q) K[q] = keys[e[q]];
-        }
-        if (k >= 256) {  // stride 128: registers q and q+2
-            compare_exchange(K[0], K[2], (e[0] & k) == 0);
-            compare_exchange(K[1], K[3], (e[1] & k) == 0);
-        }
-        if (k >= 128) {  // stride 64: registers q and q+1
-            compare_exchange(K[0], K[1], (e[0] & k) == 0);
-            compare_exchange(K[2], K[3], (e[2] & k) == 0);
-        }
-        // strides <= 32: exchanges between lanes of the wavefront
-        if (k >= 64) lane_stage<32>(K, e, k, lane);
-        if (k >= 32) lane_stage<16>(K, e, k, lane);
-        if (k >= 16) lane_stage<8>(K, e, k, lane);
-        if (k >= 8) lane_stage<4>(K, e, k, lane);
-        if (k >= 4) lane_stage<2>(K, e, k, lane);
-        lane_stage<1>(K, e, k, lane);
+    for (int q = 0; q < 4; ++q) {
+        key32[q] = (unsigned)(K[q] >> 32);
+        index[q] = (unsigned)K[q];
     }
-    // sorted keys back to LDS for the gather below (each thread wrote and read only its own
-    // slots since the last barrier, so no barrier is needed before these stores)
-#pragma unroll
-    for (int q = 0; q < 4; ++q) keys[e[q]] = K[q];
-    __syncthreads();
+    radix_rank_chunk(key32, index, e, keys, hist, tot, dbase);  // ends with a barrier; keys[] is sorted
 
     const float *boxes_f = boxes + (size_t)f * n_max * 4;
     int32_t *order_f = order + (size_t)f * n_max;
@@ -203,16 +212,30 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
     float4 *ysc_f = ysc ? ysc + (size_t)f * n_pad : nullptr;
     unsigned *ytile_f = ytile ? ytile + (size_t)f * (n_pad / kTile) : nullptr;
     if (n_chunks == 1) {
-        // a wavefront covers 64 consecutive ranks = one tile per trip (nth is a multiple of 64)
-        for (int r = tid; r < n_pad; r += nth) {
-            bool regular = true;
-            if (r < n_f)
-                regular = emit_ranked_box(boxes_f, (int)(unsigned)keys[r], r, n_pad, order_f, sorted_f, ysc_f);
-            else
-                emit_padding_row(r, n_pad, sorted_f, ysc_f);
-            if (ytile_f != nullptr) {
-                const unsigned long long irregular = __ballot(!regular);
-                if (lane == 0) ytile_f[r / kTile] = irregular == 0 ? 1u : 0u;
+        // n_pad <= 4 * nth: at most four ranks per thread, r = tid + q * nth (a wavefront covers 64
+        // consecutive ranks = one tile per q).  The four gathers are issued before anything is
+        // stored, so the thread waits for memory once, not once per rank.
+        float4 b[4];
+        int idx[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int r = tid + q * nth;
+            idx[q] = r < n_f ? (int)(unsigned)keys[r] : -1;
+            b[q] = idx[q] >= 0 ? reinterpret_cast<const float4 *>(boxes_f)[idx[q]] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int r = tid + q * nth;
+            if (r < n_pad) {  // uniform per wavefront (n_pad and nth are multiples of 64)
+                bool regular = true;
+                if (idx[q] >= 0)
+                    regular = emit_ranked_box(b[q], idx[q], r, n_pad, order_f, sorted_f, ysc_f);
+                else
+                    emit_padding_row(r, n_pad, sorted_f, ysc_f);
+                if (ytile_f != nullptr) {
+                    const unsigned long long irregular = __ballot(!regular);
+                    if (lane == 0) ytile_f[r / kTile] = irregular == 0 ? 1u : 0u;
+                }
             }
         }
     } else {
@@ -264,8 +287,9 @@ rank_merge_kernel(const float *__restrict__ boxes, const int32_t *__restrict__ c
         }
         rank += lo;
     }
-    const bool regular = emit_ranked_box(boxes + (size_t)f * n_max * 4, (int)(unsigned)key, rank, n_pad,
-                                         order + (size_t)f * n_max, sorted_f, ysc_f);
+    const int idx = (int)(unsigned)key;
+    const bool regular = emit_ranked_box(reinterpret_cast<const float4 *>(boxes + (size_t)f * n_max * 4)[idx], idx, rank,
+                                         n_pad, order + (size_t)f * n_max, sorted_f, ysc_f);
     // tile flags were preset to 1 by the chunk kernel; concurrent writers all store 0
     if (ytile != nullptr && !regular) ytile[(size_t)f * (n_pad / kTile) + rank / kTile] = 0u;
 }
