@@ -897,6 +897,7 @@ map_tile_ex_kernel(const float *__restrict__ sorted5, const float *__restrict__ 
     const float c_area = ((cb.z - cb.x) + offset) * ((cb.w - cb.y) + offset);
     const float c_score = AUX ? score_f[c] : 0.0f;
     const int c_class = AUX ? class_f[c] : 0;
+    const float c_T = (MODE == kExBoundary && !IOU) ? nms_pair_threshold(c_area, boundary) : 0.0f;
 
     const float4 *__restrict__ vb = box4 + tr * kTile;  // wave-uniform addresses: scalar loads
     const float *__restrict__ vs = score_f + tr * kTile;
@@ -928,7 +929,9 @@ map_tile_ex_kernel(const float *__restrict__ sorted5, const float *__restrict__ 
                 denom = (v_area + c_area) - inter;
             }
             bool hit;
-            if (MODE == kExBoundary)
+            if (MODE == kExBoundary && !IOU)
+                hit = inter >= c_T;  // the denominator is the lane's own area: one float32 threshold per box, as in nms_pair.h
+            else if (MODE == kExBoundary)
                 hit = (double)inter >= boundary * (double)denom;
             else if (MODE == kExDivideGe)
                 hit = !(inter / denom < theta);
