@@ -279,7 +279,26 @@ def main():
                 torch.cuda.synchronize()
                 lat.append((time.perf_counter() - t0) * 1e6)
             lat.sort()
+            keep_o = do["keep"].cpu().numpy()
+            # the classic greedy rule on the same frames, for the structure of the workload
+            ws_go = torch.empty(nms.nms_greedy_workspace_bytes(wo.n, wo.frames), dtype=torch.uint8, device=dev)
+            keep_go = torch.empty((wo.frames, wo.n), dtype=torch.uint8, device=dev)
+            nms.nms_run_greedy_batched(do["boxes"], do["scores"], None, wo.n, wo.frames, wo.theta, keep_go, ws_go)
+            torch.cuda.synchronize()
+            structure = {"survivors_per_frame": round(float(keep_o.sum()) / wo.frames, 1),
+                         "survivors_per_frame_greedy_rule": round(float(keep_go.sum().item()) / wo.frames, 1)}
+            if not args.no_cpu_baseline:
+                from oracle import Oracle
+
+                orc_o = Oracle()
+                t0 = time.perf_counter()
+                differing = sum(int((orc_o.keep(wo.boxes[f], wo.scores[f], np.float32(wo.theta)) != keep_o[f]).sum())
+                                for f in range(wo.frames))
+                structure["differing_keep_bits_vs_oracle"] = differing
+                structure["oracle_1_core_us_per_frame"] = round((time.perf_counter() - t0) * 1e6 / wo.frames, 1)
+            del ws_go, keep_go
             others[wo.name] = {
+                **structure,
                 "us_per_frame": round(ms_o * 1e3 / wo.frames, 3),
                 "frames_per_s": round(wo.frames / (ms_o * 1e-3), 1),
                 "pair_tests_per_s": round(wo.pair_tests / (ms_o * 1e-3), 1),
