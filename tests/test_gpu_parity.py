@@ -192,6 +192,29 @@ def test_y_ranges_for_the_scaled_form(nms, oracle):
     DeviceFrames(nms, big_b, big_s).fused(0.4, want=want)
 
 
+def test_wide_range_of_magnitudes(nms, oracle):
+    """Frames whose coordinates are scaled by powers of two between 2^-20 and 2^36 (x and y
+    independently; areas up to about 2^80, y both inside and far outside the range of the scaled
+    form), negative offsets included: every route against the oracle."""
+    rng = np.random.default_rng(19)
+    n, F = 900, 12
+    boxes = np.zeros((F, n, 4), np.float32)
+    scores = np.zeros((F, n), np.float32)
+    for f in range(F):
+        b, s = random_frame(600 + f, n, extent=400, max_side=120, integer=(f % 3 == 0), score_levels=100)
+        sx = np.float32(2.0 ** int(rng.integers(-20, 37)))
+        sy = np.float32(2.0 ** int(rng.integers(-20, 37)))
+        shift = np.float32(-200.0 if f % 2 else 0.0)
+        boxes[f] = ((b + shift) * np.array([sx, sy, sx, sy], np.float32)).astype(np.float32)
+        scores[f] = s
+    for theta in (0.5, 0.05, 0.9):
+        want = oracle_keep_frames(oracle, boxes, scores, np.float32(theta))
+        dev = DeviceFrames(nms, boxes, scores)
+        dev.fused(theta, want=want)
+        assert np.array_equal(dev.steps(theta), want)
+    assert 0 < want.sum() < want.size
+
+
 def steered_pairs(F, theta, seed):
     """F two-box frames whose overlap lands within a few float32 steps of theta: a
     W x H box at the origin and a victim of the same width whose top edge is placed

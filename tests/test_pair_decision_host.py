@@ -159,3 +159,28 @@ def test_y_scaled_form_and_its_fallback(nms):
     for theta in (1e-6, 2.0 ** -30, 0.5):
         check([0, 0, 9, 100], [0, float(100 + e), 9, 200], theta)
         check([0, 0, 100, 9], [float(100 + e), 0, 200, 9], theta)
+
+
+def test_magnitudes_from_tiny_to_two_to_the_forty(nms):
+    """Coordinates scaled by powers of two from 2^-30 to 2^38 in x (areas up to about 2^80):
+    the per-box threshold must stay exact wherever its product with the area lands."""
+    rng = np.random.default_rng(77)
+    hits = checked = 0
+    for i in range(12000):
+        v, c = random_pair(rng)
+        k = int(rng.integers(-30, 39))
+        sx = np.float32(2.0 ** k)
+        sy = np.float32(2.0 ** int(rng.integers(-20, 2)))       # keep |y| <= 8190 half of the time, beyond it otherwise
+        if i % 2:
+            sy = np.float32(2.0 ** int(rng.integers(2, 30)))
+        v = (v * np.array([sx, sy, sx, sy], np.float32)).astype(np.float32)
+        c = (c * np.array([sx, sy, sx, sy], np.float32)).astype(np.float32)
+        _, q = plain_decision(v, c, np.float32(0.5))
+        for theta in (np.float32(0.5), q, steps(q, 1), steps(q, -1)):
+            if not (theta > 0):
+                continue
+            want, _ = plain_decision(v, c, theta)
+            assert nms.nms_host_pair_test(v, c, float(theta)) == want, f"v={v.tolist()} c={c.tolist()} theta={theta!r}"
+            checked += 1
+            hits += want
+    assert checked > 30000 and 5000 < hits < checked - 5000
