@@ -159,7 +159,17 @@ int nms_run_direct_batched(const float *boxes, const float *scores, const int32_
  * nms_reduce is also kept here.
  *   nms_reduce_greedy*        step 3 alternative on the mask of step 2
  *   nms_run_greedy_batched    rank + map + greedy sweep; needs the mask in its workspace:
- *                             >= nms_greedy_workspace_bytes(n_max, frames) bytes, 256-byte aligned
+ *                             >= nms_greedy_workspace_bytes(n_max, frames) bytes, 256-byte aligned.
+ *                             Batches of frames of at most NMS_SORT_CHUNK boxes with
+ *                             frames * n_max >= 128 * 4096 take the route below instead (same
+ *                             result, bit for bit).
+ *   nms_run_greedy_fused_batched   rank, then one workgroup per frame walks the tile columns
+ *                             in rank order and tests only victims that are still alive against
+ *                             boxes that survived: no mask, and most of the pair grid is never
+ *                             evaluated.  n_max <= NMS_SORT_CHUNK (else NMS_ERR_TOO_LARGE);
+ *                             workspace >= nms_workspace_bytes(n_max, frames).  Frames are
+ *                             walked sequentially, so it pays when the batch has about as many
+ *                             frames as the chip has compute units.
  */
 int nms_reduce_greedy(const uint64_t *mask, const int32_t *order, int n, uint8_t *keep_out, void *stream);
 int nms_reduce_greedy_batched(const uint64_t *mask, const int32_t *order, const int32_t *counts, int n_max,
@@ -167,6 +177,9 @@ int nms_reduce_greedy_batched(const uint64_t *mask, const int32_t *order, const 
 size_t nms_greedy_workspace_bytes(int n_max, int frames);   /* host-only, pure; 0 on invalid arguments */
 int nms_run_greedy_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
                            float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream);
+int nms_run_greedy_fused_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max,
+                                 int frames, float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes,
+                                 void *stream);
 
 /*
  * Selectable variants of the rule (the paper's closing section: the map/reduce pattern

@@ -93,7 +93,16 @@ class DeviceFrames:
         self.keep.fill_(77)
         nms.nms_run_greedy_batched(self.boxes, self.scores, self.counts, self.n_max, self.F, theta, self.keep, ws)
         self.torch.cuda.synchronize()
-        return via_steps, self.keep.cpu().numpy()
+        one_call = self.keep.cpu().numpy()
+        if 0 < self.n_max <= 4096:
+            # the mask-free route (one workgroup per frame), whatever the batch size
+            self.keep.fill_(77)
+            nms.nms_run_greedy_fused_batched(self.boxes, self.scores, self.counts, self.n_max, self.F, theta, self.keep,
+                                             self.run_ws)
+            self.torch.cuda.synchronize()
+            fused = self.keep.cpu().numpy()
+            assert np.array_equal(fused, via_steps), f"mask-free greedy route: {(fused != via_steps).sum()} bits differ from the sweep"
+        return via_steps, one_call
 
     def host_order(self):
         return self.order.cpu().numpy()
