@@ -854,15 +854,52 @@ constexpr int kFusedWaves = 16;
 constexpr int kFusedOwned = NMS_SORT_CHUNK / kTile / kFusedWaves;  // 4
 constexpr long long kGreedyFusedBoxes = 128ll * 4096;  // nms_run_greedy_batched takes this route from frames * n_max boxes on
 
-struct FusedCandidate {  // a survivor as an outranking box
-    float x1, y1, x2, y2, area, T;
+struct FusedCandidate {  // a survivor as an outranking box (fields a variant does not use are never read)
+    float x1, y1, x2, y2, area, T, score;
+    int label;
 };
 
-template <bool FAST>
-__device__ __forceinline__ bool fused_pair(const float4 v, const FusedCandidate &c, float theta)
+enum { kExTiesIgnore = 2, kExClasses = 4 };                       // flags of the variants (AUX)
+enum { kExBoundary = 0, kExDivideGe = 1, kExDivideGt = 2 };      // how a variant decides the threshold (MODE)
+
+// What the walk needs beyond the box table when it runs a variant of the rule (EX): see
+// map_tile_ex_kernel below for the arithmetic.
+struct FusedVariant {
+    const float *ranked_score;    // [frames][n_pad], rank order (AUX)
+    const int32_t *ranked_label;  // [frames][n_pad], rank order (AUX with labels)
+    double boundary;              // rounding boundary of the division next to theta (MODE == kExBoundary)
+    float offset;                 // 1 or 0
+    int flags;
+};
+
+// Does candidate c eliminate the victim?  !EX: the default measure (MODE kExBoundary = the
+// division-free form of nms_pair.h, else the literal division).  EX: the variants.
+template <bool EX, bool IOU, int MODE, bool AUX>
+__device__ __forceinline__ bool fused_hit(const float4 v, float v_area, float v_score, int v_label,
+                                          const FusedCandidate &c, float theta, const FusedVariant &o)
 {
-    if (FAST) return nms_eliminates_fast(v.x, v.y, v.z, v.w, c.x1, c.y1, c.x2, c.y2, c.T);
-    return nms_eliminates_exact(v.x, v.y, v.z, v.w, c.x1, c.y1, c.x2, c.y2, c.area, theta);
+    if (!EX) {
+        if (MODE == kExBoundary) return nms_eliminates_fast(v.x, v.y, v.z, v.w, c.x1, c.y1, c.x2, c.y2, c.T);
+        return nms_eliminates_exact(v.x, v.y, v.z, v.w, c.x1, c.y1, c.x2, c.y2, c.area, theta);
+    }
+    const float iw = fmaxf(0.0f, (fminf(v.z, c.x2) - fmaxf(v.x, c.x1)) + o.offset);
+    const float ih = fmaxf(0.0f, (fminf(v.w, c.y2) - fmaxf(v.y, c.y1)) + o.offset);
+    const float inter = iw * ih;
+    const float denom = IOU ? (v_area + c.area) - inter : c.area;
+    bool hit;
+    if (MODE == kExBoundary && !IOU)
+        hit = inter >= c.T;
+    else if (MODE == kExBoundary)
+        hit = (double)inter >= o.boundary * (double)denom;
+    else if (MODE == kExDivideGe)
+        hit = !(inter / denom < theta);
+    else
+        hit = inter / denom > theta;
+    if (AUX) {
+        hit = hit && ((o.flags & kExTiesIgnore) == 0 || c.score > v_score);
+        hit = hit && ((o.flags & kExClasses) == 0 || c.label == v_label);
+    }
+    return hit;
 }
 
 // Lane `src` (wave-uniform) of a per-lane candidate, as a wave-uniform value.
@@ -875,13 +912,15 @@ __device__ __forceinline__ FusedCandidate broadcast_candidate(const FusedCandida
     c.y2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mine.y2), src));
     c.area = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mine.area), src));
     c.T = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mine.T), src));
+    c.score = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mine.score), src));
+    c.label = __builtin_amdgcn_readlane(mine.label, src);
     return c;
 }
 
-template <bool FAST>
+template <bool EX, bool IOU, int MODE, bool AUX>
 __global__ void __launch_bounds__(kFusedWaves * 64)
 greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ order,
-                    const int32_t *__restrict__ counts, int n_max, int n_pad, NmsThetaConst th,
+                    const int32_t *__restrict__ counts, int n_max, int n_pad, NmsThetaConst th, FusedVariant opt,
                     uint8_t *__restrict__ keep_out)
 {
     __shared__ FusedCandidate list_s[2][kTile];  // survivors of tile t in buffer t & 1
@@ -907,8 +946,13 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
         const bool has = tr < tiles_f;
         const int r = has ? tr * kTile + lane : 0;  // rows of a partial last tile beyond n_f are padding rows of the table
         vb[i] = box4[r];
-        const float a = area[r];
-        self[i] = FusedCandidate{vb[i].x, vb[i].y, vb[i].z, vb[i].w, a, FAST ? nms_pair_threshold(a, th.m) : 0.0f};
+        FusedCandidate me;
+        me.x1 = vb[i].x, me.y1 = vb[i].y, me.x2 = vb[i].z, me.y2 = vb[i].w;
+        me.area = EX ? ((vb[i].z - vb[i].x) + opt.offset) * ((vb[i].w - vb[i].y) + opt.offset) : area[r];
+        me.T = MODE == kExBoundary ? nms_pair_threshold(me.area, EX ? opt.boundary : th.m) : 0.0f;
+        me.score = AUX ? opt.ranked_score[(size_t)f * n_pad + r] : 0.0f;
+        me.label = (AUX && (opt.flags & kExClasses)) ? opt.ranked_label[(size_t)f * n_pad + r] : 0;
+        self[i] = me;
         const int first = tr * kTile;
         out[i] = !has ? ~0ull : (first + kTile <= n_f ? 0ull : ~0ull << (n_f - first));
     }
@@ -935,7 +979,8 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
                 todo &= todo - 1ull;
                 kept |= 1ull << c;
                 const FusedCandidate cand = broadcast_candidate(mine, c);
-                const bool hit = fused_pair<FAST>(v, cand, th.theta) && lane > c;
+                const bool hit = fused_hit<EX, IOU, MODE, AUX>(v, mine.area, mine.score, mine.label, cand, th.theta, opt) &&
+                                 lane > c;
                 todo &= ~__ballot(hit);
                 if (lane == 0) list_s[buf][count] = cand;
                 ++count;
@@ -960,7 +1005,8 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
 #pragma unroll
                 for (int i = 0; i < kFusedOwned; ++i) {
                     if (wave + kFusedWaves * i > t && out[i] != ~0ull)  // wave-uniform
-                        out[i] |= __ballot(fused_pair<FAST>(vb[i], cand, th.theta));
+                        out[i] |= __ballot(fused_hit<EX, IOU, MODE, AUX>(vb[i], self[i].area, self[i].score, self[i].label,
+                                                                          cand, th.theta, opt));
                 }
             }
         }
@@ -987,8 +1033,6 @@ gather_ranked_kernel(const int32_t *__restrict__ order, const float *__restrict_
     if (classes != nullptr) ranked_class[(size_t)f * n_pad + r] = real ? classes[(size_t)f * n_max + idx] : 0;
 }
 
-enum { kExTiesIgnore = 2, kExClasses = 4 };
-
 // The map step with the selectable measure / compare / tie / label / offset variants, one
 // wavefront per 64x64 tile of the ranked lower triangle, mask layout as in map_tile_kernel.
 // The denominator changes per pair under intersection-over-union, so there is no per-box
@@ -1000,8 +1044,6 @@ enum { kExTiesIgnore = 2, kExClasses = 4 };
 // done there.  Thresholds outside [2^-40, 2^20] take the literal float32 division (kExDivide).
 // Rank order puts equal scores next to each other, so "ties ignored" is the extra test
 // score_c > score_r on the pairs the triangle already holds.
-enum { kExBoundary = 0, kExDivideGe = 1, kExDivideGt = 2 };
-
 // IOU: the measure.  MODE: how the threshold is decided (above).  AUX: the launch uses the
 // rank-ordered scores and / or labels (ties ignored, labels given).
 template <bool IOU, int MODE, bool AUX>
@@ -1558,12 +1600,13 @@ static int run_greedy_fused(const float *boxes, const float *scores, const int32
     const NmsThetaConst th = nms_make_theta_const(threshold);
     const int n_pad = nms_padded_n(n_max);
     begin_launch();
+    const FusedVariant none = {nullptr, nullptr, 0.0, 1.0f, 0};
     if (th.fast)
-        greedy_fused_kernel<true><<<dim3(frames), dim3(kFusedWaves * 64), 0, s>>>(w.sorted5, w.order, counts, n_max,
-                                                                                   n_pad, th, keep_out);
+        greedy_fused_kernel<false, false, kExBoundary, false><<<dim3(frames), dim3(kFusedWaves * 64), 0, s>>>(
+            w.sorted5, w.order, counts, n_max, n_pad, th, none, keep_out);
     else
-        greedy_fused_kernel<false><<<dim3(frames), dim3(kFusedWaves * 64), 0, s>>>(w.sorted5, w.order, counts, n_max,
-                                                                                    n_pad, th, keep_out);
+        greedy_fused_kernel<false, false, kExDivideGe, false><<<dim3(frames), dim3(kFusedWaves * 64), 0, s>>>(
+            w.sorted5, w.order, counts, n_max, n_pad, th, none, keep_out);
     return launch_status();
 }
 
@@ -1670,6 +1713,29 @@ int nms_run_ex_batched(const float *boxes, const float *scores, const int32_t *c
     const int mode = !divide ? kExBoundary : (opt.compare == NMS_COMPARE_GT ? kExDivideGt : kExDivideGe);
     const bool iou = opt.measure == NMS_MEASURE_IOU;
     const bool aux = flags != 0;
+    if (opt.rule == NMS_RULE_GREEDY && n_max <= kChunk && (long long)frames * n_max >= kGreedyFusedBoxes) {
+        // large batches under the greedy rule: the mask-free walk, one workgroup per frame
+        const NmsThetaConst th = nms_make_theta_const(threshold);
+        const FusedVariant v = {ranked_score, ranked_class, boundary, opt.pixel_offset, flags};
+        begin_launch();
+#define NMS_LAUNCH_WALK(IOU_, MODE_, AUX_)                                                          \
+    greedy_fused_kernel<true, IOU_, MODE_, AUX_><<<dim3(frames), dim3(kFusedWaves * 64), 0, s>>>(   \
+        w.sorted5, w.order, counts, n_max, n_pad, th, v, keep_out)
+#define NMS_LAUNCH_WALK_MODE(IOU_, AUX_)                                                  \
+    do {                                                                                  \
+        if (mode == kExBoundary) NMS_LAUNCH_WALK(IOU_, kExBoundary, AUX_);                \
+        else if (mode == kExDivideGe) NMS_LAUNCH_WALK(IOU_, kExDivideGe, AUX_);           \
+        else NMS_LAUNCH_WALK(IOU_, kExDivideGt, AUX_);                                    \
+    } while (0)
+        if (iou) {
+            if (aux) NMS_LAUNCH_WALK_MODE(true, true); else NMS_LAUNCH_WALK_MODE(true, false);
+        } else {
+            if (aux) NMS_LAUNCH_WALK_MODE(false, true); else NMS_LAUNCH_WALK_MODE(false, false);
+        }
+#undef NMS_LAUNCH_WALK_MODE
+#undef NMS_LAUNCH_WALK
+        return launch_status();
+    }
     begin_launch();
 #define NMS_LAUNCH_EX(IOU_, MODE_, AUX_)                                                                          \
     map_tile_ex_kernel<IOU_, MODE_, AUX_><<<grid, dim3(kMapWaves * 64), 0, s>>>(                                 \

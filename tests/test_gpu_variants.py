@@ -127,6 +127,45 @@ def test_batched_ragged_with_labels(nms, oracle):
         assert np.array_equal(got, want), f"{opts}: {(got != want).sum()} differing keep bits"
 
 
+def test_large_batch_greedy_takes_the_mask_free_walk(nms, oracle):
+    """frames * n_max >= 128 * 4096 under the greedy rule: one workgroup per frame, survivors only
+    as outranking boxes.  Every measure / compare / ties / offset / labels combination, ragged
+    counts, and thresholds that take the literal division."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    rng = np.random.default_rng(15)
+    n_max, F = 1024, 520
+    counts = rng.integers(0, n_max + 1, F).astype(np.int32)
+    counts[:8] = [0, 1, 63, 64, 65, 1023, 1024, 512]
+    boxes = np.zeros((F, n_max, 4), np.float32)
+    scores = np.zeros((F, n_max), np.float32)
+    for f in range(F):
+        boxes[f], scores[f] = random_frame(5000 + f, n_max, extent=500, max_side=100, integer=(f % 2 == 0), score_levels=150)
+    classes = rng.integers(0, 3, (F, n_max)).astype(np.int32)
+    dev = ExFrames(nms, boxes, scores, classes, counts)
+
+    def want_for(theta, opts):
+        out = np.zeros((F, n_max), np.uint8)
+
+        def one(f):
+            n = int(counts[f])
+            if n:
+                out[f, :n] = oracle.keep_ex(boxes[f, :n], scores[f, :n], np.float32(theta), rule="greedy",
+                                            measure=opts["measure"], compare=opts["compare"], ties=opts["ties"],
+                                            pixel_offset=opts["pixel_offset"],
+                                            classes=classes[f, :n] if opts["labelled"] else None)
+        with ThreadPoolExecutor(max_workers=16) as pool:
+            list(pool.map(one, range(F)))
+        return out
+
+    greedy = [o for o in GRID if o["rule"] == "greedy"]
+    for theta, grid in ((0.4, greedy), (0.0, greedy[::5]), (1.5, greedy[1::7]), (0.5, greedy[::3])):
+        for opts in grid:
+            want = want_for(theta, opts)
+            got = dev.run(theta, opts)
+            assert np.array_equal(got, want), f"{opts} theta={theta}: {(got != want).sum()} differing keep bits"
+
+
 def test_defaults_equal_the_default_path(nms, oracle):
     w = make_config(2)
     classes = np.zeros((w.frames, w.n), np.int32)
