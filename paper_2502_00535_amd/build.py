@@ -7,7 +7,9 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 SOURCES = [os.path.join(_HERE, "csrc", "nms_kernels.hip")]
 HEADERS = [os.path.join(_HERE, "csrc", "nms_pair.h"),
-           os.path.join(os.path.dirname(_HERE), "include", "nms.h")]
+           os.path.join(os.path.dirname(_HERE), "include", "nms.h"),
+           *sorted(os.path.join(_HERE, "csrc", "kernels", f)
+                   for f in os.listdir(os.path.join(_HERE, "csrc", "kernels")) if f.endswith(".h"))]
 LIBRARY = os.path.join(_HERE, "libnms_mi355x.so")
 
 # -ffp-contract=off: the pair test must round every operation on its own (the one

@@ -1,0 +1,179 @@
+// Part of nms_kernels.hip (included there, inside its anonymous namespace): map step: pair tests on the ranked lower triangle, mask-writing and fused (row reduction folded in) forms.
+#pragma once
+
+// ----------------------------------------------------------------------------- map
+
+// Work unit of the map step: one column tile tc (64 outranking boxes, held in registers)
+// against a "super-row" of kSuper consecutive victim tile rows, i.e. up to kSuper tiles of
+// the ranked lower triangle.  Super-row sr has min(kSuper*(sr+1), T) units (tc = 0 .. last
+// tile row of the super-row), so the units before super-row sr number
+// kSuper * sr*(sr+1)/2.  Linear unit index -> (sr, tc) by integer square root.
+// kSuper = 4 amortises the per-lane set-up over 256 rows and is used when the launch has
+// plenty of units; kSuper = 1 (one tile per wavefront) keeps small launches balanced.
+template <int kSuper>
+__device__ __forceinline__ void triangle_unit(int g, int &sr, int &tc)
+{
+    // largest sr with kSuper*sr*(sr+1)/2 <= g
+    int r = (int)((__fsqrt_rn(1.0f + (8.0f / kSuper) * (float)g) - 1.0f) * 0.5f);
+    while (kSuper * r * (r + 1) / 2 > g) --r;
+    while (kSuper * (r + 1) * (r + 2) / 2 <= g) ++r;
+    sr = r;
+    tc = g - kSuper * r * (r + 1) / 2;
+}
+
+// Number of units for T tile rows.
+inline int triangle_units(int T, int super)
+{
+    const int SR = (T + super - 1) / super;
+    return SR == 0 ? 0 : super * (SR - 1) * SR / 2 + T;
+}
+
+constexpr int kMapWaves = 4;  // wavefronts (tiles) per workgroup
+
+// State a wavefront carries through the 64 rows of a tile.
+struct TileState {
+    unsigned lane_hit = 0;           // fused form: lane r = 1 when row r has an eliminator in this tile
+    unsigned w_lo = 0, w_hi = 0;     // mask form: lane r collects the 64-bit word of row r
+};
+
+// The 64 rows of a tile: victim r (wave-uniform, fetched with scalar loads) against
+// the 64 outranking boxes held one per lane.  The ballot of the compare is the
+// elimination word of row r.  Rows go in 4 groups of 16 in a real loop, so that at
+// most 64 victim SGPRs are live at a time.
+// Which evaluation of the pair test a tile uses.
+enum { kPairExact = 0, kPairFast = 1, kPairFastYScaled = 2 };
+
+// For kPairFastYScaled, vb/cb hold y * NMS_YSCALE, c_T is NMS_YSCALE * T and y_one is
+// NMS_YSCALE in a vector register.
+template <int PAIR, bool WRITE_MASK, bool DIAG>
+__device__ __forceinline__ void tile_sweep(const float4 *__restrict__ vb, const float4 cb, float c_area, float c_T,
+                                           float y_one, const NmsThetaConst &th, int lane, TileState &st)
+{
+    // Rows go in groups of kGroup: the group's victims are fetched together (their scalar
+    // loads issue back to back) and its words are formed without any branch in between.
+    constexpr int kGroup = WRITE_MASK ? 8 : 16;
+#pragma unroll 1
+    for (int grp = 0; grp < kTile / kGroup; ++grp) {
+        const float4 *__restrict__ vg = vb + kGroup * grp;
+        unsigned grp_bits = 0;  // wave-uniform: bit k = row kGroup*grp+k has an eliminator
+        unsigned long long words[kGroup];
+#pragma unroll
+        for (int k = 0; k < kGroup; ++k) {
+            const int r = kGroup * grp + k;
+            const float4 v = vg[k];
+            bool hit;
+            if (PAIR == kPairFastYScaled)
+                hit = nms_eliminates_fast_yscaled(v.x, v.y, v.z, v.w, cb.x, cb.y, cb.z, cb.w, c_T, y_one);
+            else if (PAIR == kPairFast)
+                hit = nms_eliminates_fast(v.x, v.y, v.z, v.w, cb.x, cb.y, cb.z, cb.w, c_T);
+            else
+                hit = nms_eliminates_exact(v.x, v.y, v.z, v.w, cb.x, cb.y, cb.z, cb.w, c_area, th.theta);
+            unsigned long long word = __ballot(hit);
+            if (DIAG) word &= (1ull << r) - 1ull;  // only better-ranked boxes eliminate
+            words[k] = word;
+            grp_bits |= (word != 0 ? 1u : 0u) << k;
+        }
+        if (WRITE_MASK) {
+            // lane r collects the word of row r.  Most rows of most tiles have no eliminator:
+            // the move sits behind a wave-uniform branch.
+#pragma unroll
+            for (int k = 0; k < kGroup; ++k) {
+                if (words[k] != 0) {
+                    const int r = kGroup * grp + k;
+                    const bool mine = (lane == r);
+                    st.w_lo = mine ? (unsigned)words[k] : st.w_lo;
+                    st.w_hi = mine ? (unsigned)(words[k] >> 32) : st.w_hi;
+                }
+            }
+        } else {
+            st.lane_hit |= ((lane >> 4) == grp) ? ((grp_bits >> (lane & 15)) & 1u) : 0u;
+        }
+    }
+}
+
+// One wavefront = one unit: a column tile against up to kSuper victim tiles, so the
+// per-lane set-up (loads, threshold) is paid once per 4 x 64 rows.  WRITE_MASK: store each tile's 64 words (mask
+// layout of nms.h).  Otherwise: fold the row reduction in and clear keep_out of every
+// victim that some lane eliminates (keep_out was preset to 1 by the rank step; all
+// writers store the same 0, so concurrent tiles need no atomics).
+template <bool FAST, bool WRITE_MASK, int kSuper>
+__global__ void __launch_bounds__(kMapWaves * 64)
+map_tile_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ counts, int n_max, int n_pad,
+                int tiles, int tile_blocks, int frames, int xcd_frames, NmsThetaConst th,
+                unsigned long long *__restrict__ mask, const int32_t *__restrict__ order,
+                uint8_t *__restrict__ keep_out, const float4 *__restrict__ ysc, const unsigned *__restrict__ ytile)
+{
+    const int lane = threadIdx.x & 63;
+    int f, bx;
+    if (xcd_frames) {
+        // Workgroups are dealt to the 8 XCDs round-robin by linear id, and each XCD has its
+        // own L2.  Give all tiles of a frame to one XCD (frame f -> XCD f mod 8) so that the
+        // frame's box table is fetched from HBM once instead of once per XCD.
+        const int slot = blockIdx.x >> 3;
+        f = (slot / tile_blocks) * 8 + (int)(blockIdx.x & 7);
+        bx = slot % tile_blocks;
+        if (f >= frames) return;
+    } else {
+        f = blockIdx.y;
+        bx = blockIdx.x;
+    }
+    const int g = __builtin_amdgcn_readfirstlane(bx * kMapWaves + (int)(threadIdx.x >> 6));
+    if (g >= tiles) return;
+    const int n_f = frame_count(counts, f, n_max);
+    int sr, tc;
+    triangle_unit<kSuper>(g, sr, tc);
+    const int tiles_f = (n_f + kTile - 1) / kTile;  // tile rows that hold boxes of this frame
+    int tr = kSuper * sr > tc ? kSuper * sr : tc;
+    int tr_end = kSuper * sr + kSuper < tiles_f ? kSuper * sr + kSuper : tiles_f;
+    if (tr >= tr_end) return;
+
+    const float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
+    const float4 *box4 = reinterpret_cast<const float4 *>(sorted_f);
+    const float *area = sorted_f + 4 * (size_t)n_pad;
+
+    // outranking box of this lane, and the float32 its intersections are compared with
+    const float4 cb = box4[tc * kTile + lane];
+    const float c_area = area[tc * kTile + lane];
+    const float c_T = FAST ? nms_pair_threshold(c_area, th.m) : 0.0f;
+
+    // y-scaled form (fast threshold, and the caller has the scaled table and the tile flags
+    // of the rank step: the whole-path calls do, the stand-alone map step does not): usable
+    // for a tile pair when the rank step flagged both tiles regular.  The pointers are formed
+    // unconditionally so that the victims' loads stay scalar loads.
+    constexpr bool kScaled = FAST;
+    const float4 *__restrict__ ysc4 = ysc + (size_t)f * n_pad;
+    const unsigned *__restrict__ ytile_f = ytile + (size_t)f * (n_pad / kTile);
+    bool c_regular = false;
+    if (kScaled && ysc != nullptr) c_regular = ytile_f[tc] != 0;
+    const float4 cbs = make_float4(cb.x, cb.y * NMS_YSCALE, cb.z, cb.w * NMS_YSCALE);
+    const float c_Ts = c_T * NMS_YSCALE;
+    float y_one;  // NMS_YSCALE in a vector register (opaque to the compiler so it stays there)
+    asm volatile("v_mov_b32 %0, 0x38800000" : "=v"(y_one));
+
+    for (; tr < tr_end; ++tr) {
+        TileState st;
+        if (kScaled && c_regular && ytile_f[tr] != 0) {
+            const float4 *vb = ysc4 + tr * kTile;  // victims: wave-uniform addresses -> scalar loads
+            if (tr == tc)
+                tile_sweep<kPairFastYScaled, WRITE_MASK, true>(vb, cbs, c_area, c_Ts, y_one, th, lane, st);
+            else
+                tile_sweep<kPairFastYScaled, WRITE_MASK, false>(vb, cbs, c_area, c_Ts, y_one, th, lane, st);
+        } else {
+            const float4 *vb = box4 + tr * kTile;
+            if (tr == tc)
+                tile_sweep<FAST ? kPairFast : kPairExact, WRITE_MASK, true>(vb, cb, c_area, c_T, y_one, th, lane, st);
+            else
+                tile_sweep<FAST ? kPairFast : kPairExact, WRITE_MASK, false>(vb, cb, c_area, c_T, y_one, th, lane, st);
+        }
+
+        const int row = tr * kTile + lane;
+        if (WRITE_MASK) {
+            unsigned long long out = ((unsigned long long)st.w_hi << 32) | st.w_lo;
+            if (row >= n_f) out = 0;  // padding rows of the last tile
+            mask[(size_t)f * ((size_t)(n_pad / kTile) * n_pad) + (size_t)tc * n_pad + row] = out;
+        } else {
+            if (st.lane_hit && row < n_f)
+                keep_out[(size_t)f * n_max + order[(size_t)f * n_max + row]] = 0;
+        }
+    }
+}

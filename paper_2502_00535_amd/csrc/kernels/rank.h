@@ -1,0 +1,264 @@
+// Part of nms_kernels.hip (included there, inside its anonymous namespace): rank step: radix sort of a chunk in LDS, merge of several chunks.
+#pragma once
+
+// ----------------------------------------------------------------------------- rank
+
+// Unique ascending 64-bit key: better score first, then lower index.
+__device__ __forceinline__ unsigned long long rank_key(float score, unsigned idx)
+{
+    unsigned u = __float_as_uint(score);
+    if (u == 0x80000000u) u = 0u;  // -0.0 ties with +0.0
+    unsigned asc = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    return ((unsigned long long)(~asc) << 32) | idx;
+}
+
+// Rank-ordered row r: the box and its area, and (fused path only, ysc != nullptr) the same
+// box with y multiplied by NMS_YSCALE.  Returns whether the box may use the y-scaled form.
+__device__ __forceinline__ bool emit_ranked_box(const float4 b, int idx, int r, int n_pad,
+                                               int32_t *order_f, float *sorted_f, float4 *ysc_f)
+{
+    order_f[r] = idx;
+    reinterpret_cast<float4 *>(sorted_f)[r] = b;
+    sorted_f[4 * (size_t)n_pad + r] = nms_box_area(b.x, b.y, b.z, b.w);
+    if (ysc_f != nullptr) ysc_f[r] = make_float4(b.x, b.y * NMS_YSCALE, b.z, b.w * NMS_YSCALE);
+    return nms_y_regular(b.y) && nms_y_regular(b.w);
+}
+
+__device__ __forceinline__ void emit_padding_row(int r, int n_pad, float *sorted_f, float4 *ysc_f)
+{
+    reinterpret_cast<float4 *>(sorted_f)[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+    sorted_f[4 * (size_t)n_pad + r] = 1.0f;  // the one-pixel box (0,0,0,0): never divides by zero
+    if (ysc_f != nullptr) ysc_f[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+// Inclusive prefix sum over the 64 lanes of a wavefront with DPP: shifts by 1, 2, 4, 8 inside
+// each row of 16 lanes (lanes shifted in from outside a row read 0), then lane 15 of each row
+// broadcast into the next row (rows 1 and 3), then lane 31 into rows 2 and 3.
+__device__ __forceinline__ unsigned wave_inclusive_sum(unsigned x)
+{
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, true);  // row_shr:1
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, true);  // row_shr:2
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, true);  // row_shr:4
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, true);  // row_shr:8
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false); // row_bcast:15 into rows 1, 3
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false); // row_bcast:31 into rows 2, 3
+    return x;
+}
+
+// Stable LSD radix sort of the P = 4 * blockDim.x (key, index) pairs of a workgroup, eight
+// bits per pass, four passes.  Element e = 256 * wave + 64 * q + lane is register q of its
+// thread.  Stability is what makes 32-bit keys enough: elements start in index order, so
+// equal scores keep the lower index first (the tie rule) without the index taking part in
+// any compare.  Per pass:
+//   - every wavefront ranks its 256 elements among themselves: for q = 0..3 in turn, the
+//     lanes that hold the same digit find each other with eight ballots, take their place
+//     after the elements of earlier q with that digit (running per-wavefront histogram in
+//     LDS, touched by its own wavefront only) and the group's first lane bumps the histogram;
+//   - the histograms are turned into start offsets per (digit, wavefront): column sums,
+//     then one wavefront scans the 256 digit totals;
+//   - every element goes to start + place in `buf`, and the threads read their elements back.
+// After the last pass `buf` holds ((key << 32) | index) in sorted order.
+__device__ __forceinline__ void radix_rank_chunk(unsigned (&key)[4], unsigned (&idx)[4], const int (&e)[4],
+                                                 unsigned long long *buf, unsigned *hist, unsigned *tot,
+                                                 unsigned *dbase)
+{
+    const int tid = threadIdx.x;
+    const int nth = blockDim.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int W = nth >> 6;
+    unsigned *myhist = hist + wave * 256;
+#pragma unroll 1
+    for (int shift = 0; shift < 32; shift += 8) {
+        for (int i = lane; i < 256; i += 64) myhist[i] = 0;
+        unsigned place[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const unsigned d = (key[q] >> shift) & 255u;
+            unsigned m_lo = ~0u, m_hi = ~0u;  // lanes whose digit equals mine
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                const unsigned all = 0u - ((d >> b) & 1u);  // all ones if my bit b is set
+                const unsigned long long set = __ballot(all != 0);
+                m_lo &= ~((unsigned)set ^ all);
+                m_hi &= ~((unsigned)(set >> 32) ^ all);
+            }
+            const unsigned below = __builtin_amdgcn_mbcnt_hi(m_hi, __builtin_amdgcn_mbcnt_lo(m_lo, 0u));
+            const unsigned total = __popc(m_lo) + __popc(m_hi);
+            const unsigned base = myhist[d];
+            if (below == 0) myhist[d] = base + total;
+            place[q] = base + below;
+        }
+        __syncthreads();
+        for (int d = tid; d < 256; d += nth) {
+            // the counts of digit d in every wavefront (all reads issued together), then their running sums
+            unsigned t[kChunk / 256];
+#pragma unroll
+            for (int w = 0; w < kChunk / 256; ++w) t[w] = w < W ? hist[w * 256 + d] : 0u;
+            unsigned run = 0;
+#pragma unroll
+            for (int w = 0; w < kChunk / 256; ++w) {
+                if (w < W) hist[w * 256 + d] = run;
+                run += t[w];
+            }
+            tot[d] = run;
+        }
+        __syncthreads();
+        if (wave == 0) {
+            const unsigned a0 = tot[4 * lane], a1 = tot[4 * lane + 1], a2 = tot[4 * lane + 2], a3 = tot[4 * lane + 3];
+            const unsigned sum = a0 + a1 + a2 + a3;
+            const unsigned incl = wave_inclusive_sum(sum);
+            const unsigned excl = incl - sum;
+            dbase[4 * lane] = excl;
+            dbase[4 * lane + 1] = excl + a0;
+            dbase[4 * lane + 2] = excl + a0 + a1;
+            dbase[4 * lane + 3] = excl + a0 + a1 + a2;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const unsigned d = (key[q] >> shift) & 255u;
+            const unsigned dest = dbase[d] + myhist[d] + place[q];
+            buf[dest] = ((unsigned long long)key[q] << 32) | idx[q];
+        }
+        __syncthreads();
+        if (shift < 24) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const unsigned long long v = buf[e[q]];
+                key[q] = (unsigned)(v >> 32);
+                idx[q] = (unsigned)v;
+            }
+        }
+    }
+}
+
+// One workgroup ranks one chunk of up to kChunk boxes of one frame: P = 4 * blockDim.x
+// elements (P a multiple of 256, 256..4096), four per thread, sorted by radix_rank_chunk.
+// With a single chunk the kernel also writes order / sorted5 (and, for the fused path,
+// presets keep_out); with several chunks it leaves the chunk's sorted keys in `keys_ws`
+// for the merge kernel.
+__global__ void __launch_bounds__(1024)
+rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ scores,
+                  const int32_t *__restrict__ counts, int n_max, int n_pad, int n_chunks,
+                  int32_t *__restrict__ order, float *__restrict__ sorted5,
+                  unsigned long long *__restrict__ keys_ws, uint8_t *__restrict__ keep_preset,
+                  float4 *__restrict__ ysc, unsigned *__restrict__ ytile)
+{
+    __shared__ unsigned long long keys[kChunk];
+    __shared__ unsigned hist[(kChunk / 256) * 256];  // one row of 256 digit counts per wavefront
+    __shared__ unsigned tot[256];
+    __shared__ unsigned dbase[256];
+    const int f = blockIdx.y;
+    const int chunk = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int nth = blockDim.x;
+    const int lane = tid & 63;
+    const int n_f = frame_count(counts, f, n_max);
+    const int base = chunk * kChunk;
+    int cnt = n_f - base;
+    cnt = cnt < 0 ? 0 : (cnt > kChunk ? kChunk : cnt);
+    const float *scores_f = scores + (size_t)f * n_max;
+    int e[4];
+    unsigned long long K[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        e[q] = (tid >> 6) * 256 + q * 64 + lane;
+        K[q] = (e[q] < cnt) ? rank_key(scores_f[base + e[q]], (unsigned)(base + e[q])) : kSentinel;
+    }
+
+    unsigned key32[4], index[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        key32[q] = (unsigned)(K[q] >> 32);
+        index[q] = (unsigned)K[q];
+    }
+    radix_rank_chunk(key32, index, e, keys, hist, tot, dbase);  // ends with a barrier; keys[] is sorted
+
+    const float *boxes_f = boxes + (size_t)f * n_max * 4;
+    int32_t *order_f = order + (size_t)f * n_max;
+    float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
+    float4 *ysc_f = ysc ? ysc + (size_t)f * n_pad : nullptr;
+    unsigned *ytile_f = ytile ? ytile + (size_t)f * (n_pad / kTile) : nullptr;
+    if (n_chunks == 1) {
+        // n_pad <= 4 * nth: at most four ranks per thread, r = tid + q * nth (a wavefront covers 64
+        // consecutive ranks = one tile per q).  The four gathers are issued before anything is
+        // stored, so the thread waits for memory once, not once per rank.
+        float4 b[4];
+        int idx[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int r = tid + q * nth;
+            idx[q] = r < n_f ? (int)(unsigned)keys[r] : -1;
+            b[q] = idx[q] >= 0 ? reinterpret_cast<const float4 *>(boxes_f)[idx[q]] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int r = tid + q * nth;
+            if (r < n_pad) {  // uniform per wavefront (n_pad and nth are multiples of 64)
+                bool regular = true;
+                if (idx[q] >= 0)
+                    regular = emit_ranked_box(b[q], idx[q], r, n_pad, order_f, sorted_f, ysc_f);
+                else
+                    emit_padding_row(r, n_pad, sorted_f, ysc_f);
+                if (ytile_f != nullptr) {
+                    const unsigned long long irregular = __ballot(!regular);
+                    if (lane == 0) ytile_f[r / kTile] = irregular == 0 ? 1u : 0u;
+                }
+            }
+        }
+    } else {
+        unsigned long long *kw = keys_ws + (size_t)f * n_pad + base;
+        for (int i = tid; i < cnt; i += nth) kw[i] = keys[i];
+        // the merge kernel scatters rows, so it can only clear tile flags: preset them here
+        if (ytile_f != nullptr && chunk == 0)
+            for (int t = tid; t < n_pad / kTile; t += nth) ytile_f[t] = 1u;
+    }
+    if (keep_preset != nullptr) {
+        // fused path: every real box starts as a survivor, slots beyond the count are 0
+        uint8_t *kp = keep_preset + (size_t)f * n_max;
+        const int hi = (base + kChunk < n_max) ? base + kChunk : n_max;
+        for (int i = base + tid; i < hi; i += nth) kp[i] = (i < n_f) ? 1 : 0;
+    }
+}
+
+// Several chunks: the rank of a key is its position inside its own chunk plus the
+// number of smaller keys in every other chunk (keys are unique, so ranks are too).
+__global__ void __launch_bounds__(256)
+rank_merge_kernel(const float *__restrict__ boxes, const int32_t *__restrict__ counts, int n_max, int n_pad,
+                  int n_chunks, const unsigned long long *__restrict__ keys_ws,
+                  int32_t *__restrict__ order, float *__restrict__ sorted5,
+                  float4 *__restrict__ ysc, unsigned *__restrict__ ytile)
+{
+    const int f = blockIdx.y;
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n_pad) return;
+    const int n_f = frame_count(counts, f, n_max);
+    float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
+    float4 *ysc_f = ysc ? ysc + (size_t)f * n_pad : nullptr;
+    if (e >= n_f) {
+        emit_padding_row(e, n_pad, sorted_f, ysc_f);
+        return;
+    }
+    const unsigned long long *kw = keys_ws + (size_t)f * n_pad;
+    const unsigned long long key = kw[e];
+    const int own = e / kChunk;
+    int rank = e - own * kChunk;
+    for (int c = 0; c < n_chunks; ++c) {
+        if (c == own) continue;
+        const int base = c * kChunk;
+        int cnt = n_f - base;
+        cnt = cnt < 0 ? 0 : (cnt > kChunk ? kChunk : cnt);
+        int lo = 0, hi = cnt;  // first position whose key is not smaller
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (kw[base + mid] < key) lo = mid + 1; else hi = mid;
+        }
+        rank += lo;
+    }
+    const int idx = (int)(unsigned)key;
+    const bool regular = emit_ranked_box(reinterpret_cast<const float4 *>(boxes + (size_t)f * n_max * 4)[idx], idx, rank,
+                                         n_pad, order + (size_t)f * n_max, sorted_f, ysc_f);
+    // tile flags were preset to 1 by the chunk kernel; concurrent writers all store 0
+    if (ytile != nullptr && !regular) ytile[(size_t)f * (n_pad / kTile) + rank / kTile] = 0u;
+}

@@ -1,0 +1,125 @@
+// Part of nms_kernels.hip (included there, inside its anonymous namespace): map step with the selectable measure / compare / ties / offset / labels.
+#pragma once
+
+// ----------------------------------------------------------------------------- map with options
+
+// Rank-ordered scores and class labels (victims of a row are fetched with scalar loads, so
+// the map kernel wants them contiguous in rank order like the box table).
+__global__ void __launch_bounds__(256)
+gather_ranked_kernel(const int32_t *__restrict__ order, const float *__restrict__ scores,
+                     const int32_t *__restrict__ classes, const int32_t *__restrict__ counts, int n_max, int n_pad,
+                     float *__restrict__ ranked_score, int32_t *__restrict__ ranked_class)
+{
+    const int f = blockIdx.y;
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= n_pad) return;
+    const int n_f = frame_count(counts, f, n_max);
+    const bool real = r < n_f;
+    const int idx = real ? order[(size_t)f * n_max + r] : 0;
+    ranked_score[(size_t)f * n_pad + r] = real ? scores[(size_t)f * n_max + idx] : -INFINITY;
+    if (classes != nullptr) ranked_class[(size_t)f * n_pad + r] = real ? classes[(size_t)f * n_max + idx] : 0;
+}
+
+// The map step with the selectable measure / compare / tie / label / offset variants, one
+// wavefront per 64x64 tile of the ranked lower triangle, mask layout as in map_tile_kernel.
+// The denominator changes per pair under intersection-over-union, so there is no per-box
+// threshold to precompute; the division and the compare are still decided without dividing:
+//     RN(inter / d) >= theta  <=>  inter >= m * d     m = rounding boundary just below theta
+//     RN(inter / d) >  theta  <=>  inter >= m' * d    m' = rounding boundary just above theta
+// (d > 0; equality with m*d or m'*d cannot occur, by the same argument as in nms_pair.h).  m and m'
+// have 25 significant bits and d 24, so the product is exact in float64 and the compare is
+// done there.  Thresholds outside [2^-40, 2^20] take the literal float32 division (kExDivide).
+// Rank order puts equal scores next to each other, so "ties ignored" is the extra test
+// score_c > score_r on the pairs the triangle already holds.
+// IOU: the measure.  MODE: how the threshold is decided (above).  AUX: the launch uses the
+// rank-ordered scores and / or labels (ties ignored, labels given).
+template <bool IOU, int MODE, bool AUX>
+__global__ void __launch_bounds__(kMapWaves * 64)
+map_tile_ex_kernel(const float *__restrict__ sorted5, const float *__restrict__ ranked_score,
+                   const int32_t *__restrict__ ranked_class, const int32_t *__restrict__ counts, int n_max, int n_pad,
+                   int tiles, float theta, double boundary, float offset, int flags,
+                   unsigned long long *__restrict__ mask)
+{
+    const int lane = threadIdx.x & 63;
+    const int f = blockIdx.y;
+    const int g = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * kMapWaves + (threadIdx.x >> 6)));
+    if (g >= tiles) return;
+    const int n_f = frame_count(counts, f, n_max);
+    int tr, tc;
+    triangle_unit<1>(g, tr, tc);
+    if (tr * kTile >= n_f) return;
+
+    const float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
+    const float4 *box4 = reinterpret_cast<const float4 *>(sorted_f);
+    const float *score_f = ranked_score + (size_t)f * n_pad;
+    const int32_t *class_f = ranked_class + (size_t)f * n_pad;  // unwritten (but allocated) when no labels were given
+    const bool ties_ignore = (flags & kExTiesIgnore) != 0;
+    const bool labelled = (flags & kExClasses) != 0;
+
+    const int c = tc * kTile + lane;
+    const float4 cb = box4[c];
+    const float c_area = ((cb.z - cb.x) + offset) * ((cb.w - cb.y) + offset);
+    const float c_score = AUX ? score_f[c] : 0.0f;
+    const int c_class = AUX ? class_f[c] : 0;
+    const float c_T = (MODE == kExBoundary && !IOU) ? nms_pair_threshold(c_area, boundary) : 0.0f;
+
+    const float4 *__restrict__ vb = box4 + tr * kTile;  // wave-uniform addresses: scalar loads
+    const float *__restrict__ vs = score_f + tr * kTile;
+    const int32_t *__restrict__ vc = class_f + tr * kTile;
+    unsigned w_lo = 0, w_hi = 0;
+    constexpr int kGroup = 8;
+#pragma unroll 1
+    for (int grp = 0; grp < kTile / kGroup; ++grp) {
+        // a group's victims are fetched together, its words formed without a branch in between
+        float4 v[kGroup];
+        float v_score[kGroup];
+        int v_class[kGroup];
+#pragma unroll
+        for (int k = 0; k < kGroup; ++k) {
+            v[k] = vb[kGroup * grp + k];
+            v_score[k] = AUX ? vs[kGroup * grp + k] : 0.0f;
+            v_class[k] = AUX ? vc[kGroup * grp + k] : 0;
+        }
+        unsigned long long words[kGroup];
+#pragma unroll
+        for (int k = 0; k < kGroup; ++k) {
+            const int r = kGroup * grp + k;
+            const float iw = fmaxf(0.0f, (fminf(v[k].z, cb.z) - fmaxf(v[k].x, cb.x)) + offset);
+            const float ih = fmaxf(0.0f, (fminf(v[k].w, cb.w) - fmaxf(v[k].y, cb.y)) + offset);
+            const float inter = iw * ih;
+            float denom = c_area;
+            if (IOU) {
+                const float v_area = ((v[k].z - v[k].x) + offset) * ((v[k].w - v[k].y) + offset);
+                denom = (v_area + c_area) - inter;
+            }
+            bool hit;
+            if (MODE == kExBoundary && !IOU)
+                hit = inter >= c_T;  // the denominator is the lane's own area: one float32 threshold per box, as in nms_pair.h
+            else if (MODE == kExBoundary)
+                hit = (double)inter >= boundary * (double)denom;
+            else if (MODE == kExDivideGe)
+                hit = !(inter / denom < theta);
+            else
+                hit = inter / denom > theta;
+            if (AUX) {
+                hit = hit && (!ties_ignore || c_score > v_score[k]);
+                hit = hit && (!labelled || c_class == v_class[k]);
+            }
+            unsigned long long word = __ballot(hit);
+            if (tr == tc) word &= (1ull << r) - 1ull;  // only better-ranked boxes eliminate
+            words[k] = word;
+        }
+#pragma unroll
+        for (int k = 0; k < kGroup; ++k) {
+            if (words[k] != 0) {  // wave-uniform
+                const bool mine = (lane == kGroup * grp + k);
+                w_lo = mine ? (unsigned)words[k] : w_lo;
+                w_hi = mine ? (unsigned)(words[k] >> 32) : w_hi;
+            }
+        }
+    }
+    const int row = tr * kTile + lane;
+    unsigned long long out = ((unsigned long long)w_hi << 32) | w_lo;
+    if (row >= n_f) out = 0;
+    mask[(size_t)f * ((size_t)(n_pad / kTile) * n_pad) + (size_t)tc * n_pad + row] = out;
+}
