@@ -50,6 +50,25 @@ __global__ void k_addclamp(float *out, float a, float sb, int iters) { BODY("v_a
 __global__ void k_subclamp(float *out, float a, float sb, int iters) { BODY("v_sub_f32_e64 %0, %1, %0 clamp") }
 __global__ void k_rcp(float *out, float a, float sb, int iters) { BODY("v_rcp_f32 %0, %0") }
 
+// float64 instructions (the variants' exact threshold compare uses a convert, a multiply and a compare)
+#define BODYD(INSTR) \
+    double x0 = threadIdx.x, x1 = x0 + 1, x2 = x0 + 2, x3 = x0 + 3, x4 = x0 + 4, x5 = x0 + 5, x6 = x0 + 6, x7 = x0 + 7; \
+    const double ad = a; \
+    for (int i = 0; i < iters; ++i) { \
+        _Pragma("unroll") for (int u = 0; u < 8; ++u) { \
+            asm volatile(INSTR : "+v"(x0) : "v"(ad), "v"(a) : "vcc"); asm volatile(INSTR : "+v"(x1) : "v"(ad), "v"(a) : "vcc"); \
+            asm volatile(INSTR : "+v"(x2) : "v"(ad), "v"(a) : "vcc"); asm volatile(INSTR : "+v"(x3) : "v"(ad), "v"(a) : "vcc"); \
+            asm volatile(INSTR : "+v"(x4) : "v"(ad), "v"(a) : "vcc"); asm volatile(INSTR : "+v"(x5) : "v"(ad), "v"(a) : "vcc"); \
+            asm volatile(INSTR : "+v"(x6) : "v"(ad), "v"(a) : "vcc"); asm volatile(INSTR : "+v"(x7) : "v"(ad), "v"(a) : "vcc"); \
+        } \
+    } \
+    out[blockIdx.x * blockDim.x + threadIdx.x] = (float)(x0 + x1 + x2 + x3 + x4 + x5 + x6 + x7);
+
+__global__ void k_mul64(float *out, float a, float sb, int iters) { BODYD("v_mul_f64 %0, %1, %0") }
+__global__ void k_fma64(float *out, float a, float sb, int iters) { BODYD("v_fma_f64 %0, %1, %0, %0") }
+__global__ void k_cmpf64(float *out, float a, float sb, int iters) { BODYD("v_cmp_ge_f64 vcc, %1, %0") }
+__global__ void k_cvt64(float *out, float a, float sb, int iters) { BODYD("v_cvt_f64_f32 %0, %2") }
+
 typedef void (*kern_t)(float *, float, float, int);
 
 int main()
@@ -66,6 +85,7 @@ int main()
         {"v_max_f32", k_max, 1}, {"v_mul_f32", k_mul, 1}, {"v_sub_f32", k_sub, 1}, {"v_fma_f32", k_fma, 1}, {"v_fmac_f32", k_fmac, 1},
         {"v_cmp vcc", k_cmp, 1}, {"v_cmp sgpr", k_cmp64, 1}, {"v_mov_b32", k_mov, 1}, {"v_and_b32", k_and, 1}, {"v_max3_f32", k_max3, 1},
         {"v_add_u32", k_pkadd, 1}, {"v_rcp_f32", k_rcp, 1}, {"v_min_i32", k_mini, 1}, {"v_max_u32", k_maxu, 1}, {"v_add_f32 1.0", k_addc, 1}, {"v_and_or_b32", k_andor, 1}, {"v_fma_f32 3src", k_fma3, 1}, {"v_mul_f32 |abs|", k_mulabs, 1}, {"v_cndmask", k_cnd, 1}, {"v_add_f32 clamp", k_addclamp, 1}, {"v_sub_f32 clamp", k_subclamp, 1},
+        {"v_mul_f64", k_mul64, 1}, {"v_fma_f64", k_fma64, 1}, {"v_cmp_ge_f64", k_cmpf64, 1}, {"v_cvt_f64_f32", k_cvt64, 1},
     };
     const int iters = 2000;
     hipEvent_t e0, e1;
