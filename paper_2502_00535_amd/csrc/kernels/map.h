@@ -79,6 +79,7 @@ __device__ __forceinline__ void tile_sweep(const float4 *__restrict__ vb, const 
 #pragma unroll
             for (int k = 0; k < kGroup; ++k) {
                 if (words[k] != 0) {
+                    asm volatile("" ::: "memory");  // keeps this a branch (otherwise the move is made for every row)
                     const int r = kGroup * grp + k;
                     const bool mine = (lane == r);
                     st.w_lo = mine ? (unsigned)words[k] : st.w_lo;

@@ -3,12 +3,15 @@
 
 // ----------------------------------------------------------------------------- map with options
 
-// Rank-ordered scores and class labels (victims of a row are fetched with scalar loads, so
-// the map kernel wants them contiguous in rank order like the box table).
+// Rank-ordered scores, class labels and areas under the chosen pixel offset (victims of a row
+// are fetched with scalar loads, so the map kernel wants them contiguous in rank order like
+// the box table).
 __global__ void __launch_bounds__(256)
 gather_ranked_kernel(const int32_t *__restrict__ order, const float *__restrict__ scores,
-                     const int32_t *__restrict__ classes, const int32_t *__restrict__ counts, int n_max, int n_pad,
-                     float *__restrict__ ranked_score, int32_t *__restrict__ ranked_class)
+                     const int32_t *__restrict__ classes, const int32_t *__restrict__ counts,
+                     const float *__restrict__ sorted5, float offset, int n_max, int n_pad,
+                     float *__restrict__ ranked_score, int32_t *__restrict__ ranked_class,
+                     float *__restrict__ ranked_area)
 {
     const int f = blockIdx.y;
     const int r = blockIdx.x * blockDim.x + threadIdx.x;
@@ -18,6 +21,9 @@ gather_ranked_kernel(const int32_t *__restrict__ order, const float *__restrict_
     const int idx = real ? order[(size_t)f * n_max + r] : 0;
     ranked_score[(size_t)f * n_pad + r] = real ? scores[(size_t)f * n_max + idx] : -INFINITY;
     if (classes != nullptr) ranked_class[(size_t)f * n_pad + r] = real ? classes[(size_t)f * n_max + idx] : 0;
+    // area under the chosen pixel offset (the box table's own area column is the offset-1 one)
+    const float4 b = reinterpret_cast<const float4 *>(sorted5 + (size_t)f * 5 * n_pad)[r];
+    ranked_area[(size_t)f * n_pad + r] = ((b.z - b.x) + offset) * ((b.w - b.y) + offset);
 }
 
 // The map step with the selectable measure / compare / tie / label / offset variants, one
@@ -33,93 +39,116 @@ gather_ranked_kernel(const int32_t *__restrict__ order, const float *__restrict_
 // score_c > score_r on the pairs the triangle already holds.
 // IOU: the measure.  MODE: how the threshold is decided (above).  AUX: the launch uses the
 // rank-ordered scores and / or labels (ties ignored, labels given).
-template <bool IOU, int MODE, bool AUX>
+// Work units and their mapping to workgroups are those of map_tile_kernel: one column tile
+// against kSuper victim tiles per wavefront, frames pinned to XCDs on batches.
+template <bool IOU, int MODE, bool AUX, int kSuper>
 __global__ void __launch_bounds__(kMapWaves * 64)
 map_tile_ex_kernel(const float *__restrict__ sorted5, const float *__restrict__ ranked_score,
-                   const int32_t *__restrict__ ranked_class, const int32_t *__restrict__ counts, int n_max, int n_pad,
-                   int tiles, float theta, double boundary, float offset, int flags,
-                   unsigned long long *__restrict__ mask)
+                   const int32_t *__restrict__ ranked_class, const float *__restrict__ ranked_area,
+                   const int32_t *__restrict__ counts, int n_max, int n_pad,
+                   int tiles, int tile_blocks, int frames, int xcd_frames, float theta, double boundary, float offset,
+                   int flags, unsigned long long *__restrict__ mask)
 {
     const int lane = threadIdx.x & 63;
-    const int f = blockIdx.y;
-    const int g = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * kMapWaves + (threadIdx.x >> 6)));
+    int f, bx;
+    if (xcd_frames) {  // frame f runs entirely on XCD f mod 8 (see map_tile_kernel)
+        const int slot = blockIdx.x >> 3;
+        f = (slot / tile_blocks) * 8 + (int)(blockIdx.x & 7);
+        bx = slot % tile_blocks;
+        if (f >= frames) return;
+    } else {
+        f = blockIdx.y;
+        bx = blockIdx.x;
+    }
+    const int g = __builtin_amdgcn_readfirstlane(bx * kMapWaves + (int)(threadIdx.x >> 6));
     if (g >= tiles) return;
     const int n_f = frame_count(counts, f, n_max);
-    int tr, tc;
-    triangle_unit<1>(g, tr, tc);
-    if (tr * kTile >= n_f) return;
+    int sr, tc;
+    triangle_unit<kSuper>(g, sr, tc);
+    const int tiles_f = (n_f + kTile - 1) / kTile;
+    int tr = kSuper * sr > tc ? kSuper * sr : tc;
+    const int tr_end = kSuper * sr + kSuper < tiles_f ? kSuper * sr + kSuper : tiles_f;
+    if (tr >= tr_end) return;
 
     const float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
     const float4 *box4 = reinterpret_cast<const float4 *>(sorted_f);
     const float *score_f = ranked_score + (size_t)f * n_pad;
     const int32_t *class_f = ranked_class + (size_t)f * n_pad;  // unwritten (but allocated) when no labels were given
+    const float *area_f = ranked_area + (size_t)f * n_pad;
     const bool ties_ignore = (flags & kExTiesIgnore) != 0;
     const bool labelled = (flags & kExClasses) != 0;
 
     const int c = tc * kTile + lane;
     const float4 cb = box4[c];
-    const float c_area = ((cb.z - cb.x) + offset) * ((cb.w - cb.y) + offset);
+    const float c_area = area_f[c];
+    float off = offset;  // in a vector register: an add with a scalar-register source issues at half rate
+    asm volatile("" : "+v"(off));
     const float c_score = AUX ? score_f[c] : 0.0f;
     const int c_class = AUX ? class_f[c] : 0;
     const float c_T = (MODE == kExBoundary && !IOU) ? nms_pair_threshold(c_area, boundary) : 0.0f;
 
-    const float4 *__restrict__ vb = box4 + tr * kTile;  // wave-uniform addresses: scalar loads
-    const float *__restrict__ vs = score_f + tr * kTile;
-    const int32_t *__restrict__ vc = class_f + tr * kTile;
-    unsigned w_lo = 0, w_hi = 0;
-    constexpr int kGroup = 8;
+    for (; tr < tr_end; ++tr) {
+        const float4 *__restrict__ vb = box4 + tr * kTile;  // wave-uniform addresses: scalar loads
+        const float *__restrict__ vs = score_f + tr * kTile;
+        const int32_t *__restrict__ vc = class_f + tr * kTile;
+        const float *__restrict__ va = area_f + tr * kTile;
+        unsigned w_lo = 0, w_hi = 0;
+        constexpr int kGroup = 8;
 #pragma unroll 1
-    for (int grp = 0; grp < kTile / kGroup; ++grp) {
-        // a group's victims are fetched together, its words formed without a branch in between
-        float4 v[kGroup];
-        float v_score[kGroup];
-        int v_class[kGroup];
+        for (int grp = 0; grp < kTile / kGroup; ++grp) {
+            // a group's victims are fetched together, its words formed without a branch in between
+            float4 v[kGroup];
+            float v_score[kGroup];
+            int v_class[kGroup];
+            float v_area[kGroup];
 #pragma unroll
-        for (int k = 0; k < kGroup; ++k) {
-            v[k] = vb[kGroup * grp + k];
-            v_score[k] = AUX ? vs[kGroup * grp + k] : 0.0f;
-            v_class[k] = AUX ? vc[kGroup * grp + k] : 0;
-        }
-        unsigned long long words[kGroup];
+            for (int k = 0; k < kGroup; ++k) {
+                v[k] = vb[kGroup * grp + k];
+                v_area[k] = IOU ? va[kGroup * grp + k] : 0.0f;
+                v_score[k] = AUX ? vs[kGroup * grp + k] : 0.0f;
+                v_class[k] = AUX ? vc[kGroup * grp + k] : 0;
+            }
+            unsigned long long words[kGroup];
 #pragma unroll
-        for (int k = 0; k < kGroup; ++k) {
-            const int r = kGroup * grp + k;
-            const float iw = fmaxf(0.0f, (fminf(v[k].z, cb.z) - fmaxf(v[k].x, cb.x)) + offset);
-            const float ih = fmaxf(0.0f, (fminf(v[k].w, cb.w) - fmaxf(v[k].y, cb.y)) + offset);
-            const float inter = iw * ih;
-            float denom = c_area;
-            if (IOU) {
-                const float v_area = ((v[k].z - v[k].x) + offset) * ((v[k].w - v[k].y) + offset);
-                denom = (v_area + c_area) - inter;
+            for (int k = 0; k < kGroup; ++k) {
+                const int r = kGroup * grp + k;
+                // with a positive threshold boundary one floor is enough: a negative width times a
+                // floored height is <= 0 and can reach neither T nor boundary * (a positive union)
+                float iw = (fminf(v[k].z, cb.z) - fmaxf(v[k].x, cb.x)) + off;
+                if (MODE != kExBoundary) iw = fmaxf(0.0f, iw);
+                const float ih = fmaxf(0.0f, (fminf(v[k].w, cb.w) - fmaxf(v[k].y, cb.y)) + off);
+                const float inter = iw * ih;
+                const float denom = IOU ? (v_area[k] + c_area) - inter : c_area;
+                bool hit;
+                if (MODE == kExBoundary && !IOU)
+                    hit = inter >= c_T;  // the denominator is the lane's own area: one float32 threshold per box, as in nms_pair.h
+                else if (MODE == kExBoundary)
+                    hit = (double)inter >= boundary * (double)denom;
+                else if (MODE == kExDivideGe)
+                    hit = !(inter / denom < theta);
+                else
+                    hit = inter / denom > theta;
+                if (AUX) {
+                    hit = hit && (!ties_ignore || c_score > v_score[k]);
+                    hit = hit && (!labelled || c_class == v_class[k]);
+                }
+                unsigned long long word = __ballot(hit);
+                if (tr == tc) word &= (1ull << r) - 1ull;  // only better-ranked boxes eliminate
+                words[k] = word;
             }
-            bool hit;
-            if (MODE == kExBoundary && !IOU)
-                hit = inter >= c_T;  // the denominator is the lane's own area: one float32 threshold per box, as in nms_pair.h
-            else if (MODE == kExBoundary)
-                hit = (double)inter >= boundary * (double)denom;
-            else if (MODE == kExDivideGe)
-                hit = !(inter / denom < theta);
-            else
-                hit = inter / denom > theta;
-            if (AUX) {
-                hit = hit && (!ties_ignore || c_score > v_score[k]);
-                hit = hit && (!labelled || c_class == v_class[k]);
-            }
-            unsigned long long word = __ballot(hit);
-            if (tr == tc) word &= (1ull << r) - 1ull;  // only better-ranked boxes eliminate
-            words[k] = word;
-        }
 #pragma unroll
-        for (int k = 0; k < kGroup; ++k) {
-            if (words[k] != 0) {  // wave-uniform
-                const bool mine = (lane == kGroup * grp + k);
-                w_lo = mine ? (unsigned)words[k] : w_lo;
-                w_hi = mine ? (unsigned)(words[k] >> 32) : w_hi;
+            for (int k = 0; k < kGroup; ++k) {
+                if (words[k] != 0) {  // wave-uniform
+                    asm volatile("" ::: "memory");  // keeps this a branch (otherwise the move is made for every row)
+                    const bool mine = (lane == kGroup * grp + k);
+                    w_lo = mine ? (unsigned)words[k] : w_lo;
+                    w_hi = mine ? (unsigned)(words[k] >> 32) : w_hi;
+                }
             }
         }
+        const int row = tr * kTile + lane;
+        unsigned long long out = ((unsigned long long)w_hi << 32) | w_lo;
+        if (row >= n_f) out = 0;
+        mask[(size_t)f * ((size_t)(n_pad / kTile) * n_pad) + (size_t)tc * n_pad + row] = out;
     }
-    const int row = tr * kTile + lane;
-    unsigned long long out = ((unsigned long long)w_hi << 32) | w_lo;
-    if (row >= n_f) out = 0;
-    mask[(size_t)f * ((size_t)(n_pad / kTile) * n_pad) + (size_t)tc * n_pad + row] = out;
 }

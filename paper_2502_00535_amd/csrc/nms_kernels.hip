@@ -492,7 +492,7 @@ size_t nms_ex_workspace_bytes(int n_max, int frames)
     int st;
     if (!sizes_ok(n_max, frames, &st)) return 0;
     return nms_greedy_workspace_bytes(n_max, frames)
-         + 2 * align256((size_t)frames * nms_padded_n(n_max) * sizeof(float));  // ranked scores, ranked labels
+         + 3 * align256((size_t)frames * nms_padded_n(n_max) * sizeof(float));  // ranked scores, labels, areas
 }
 
 int nms_run_ex_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
@@ -519,18 +519,26 @@ int nms_run_ex_batched(const float *boxes, const float *scores, const int32_t *c
     float *ranked_score = reinterpret_cast<float *>(p);
     p += align256((size_t)frames * n_pad * sizeof(float));
     int32_t *ranked_class = reinterpret_cast<int32_t *>(p);
+    p += align256((size_t)frames * n_pad * sizeof(int32_t));
+    float *ranked_area = reinterpret_cast<float *>(p);
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     st = rank_launch(boxes, scores, counts, n_max, frames, w.order, w.sorted5, w.keys, nullptr, nullptr, nullptr, s);
     if (st != NMS_OK) return st;
     begin_launch();
     gather_ranked_kernel<<<dim3((n_pad + 255) / 256, frames), dim3(256), 0, s>>>(
-        w.order, scores, opt.classes, counts, n_max, n_pad, ranked_score, ranked_class);
+        w.order, scores, opt.classes, counts, w.sorted5, opt.pixel_offset, n_max, n_pad, ranked_score, ranked_class,
+        ranked_area);
     st = launch_status();
     if (st != NMS_OK) return st;
 
-    const int tiles = triangle_units(n_pad / kTile, 1);
-    const dim3 grid((tiles + kMapWaves - 1) / kMapWaves, frames);
+    // work units and grid as in map_launch
+    const int T = n_pad / kTile;
+    const bool super4 = (long long)frames * triangle_units(T, 4) >= 16384;
+    const int tiles = triangle_units(T, super4 ? 4 : 1);
+    const int tile_blocks = (tiles + kMapWaves - 1) / kMapWaves;
+    const int xcd_frames = frames >= 8 ? 1 : 0;
+    const dim3 grid = xcd_frames ? dim3((unsigned)(((frames + 7) / 8) * 8 * tile_blocks)) : dim3(tile_blocks, frames);
     // rounding boundary of the division next to theta, exact in float64: below theta for ">=", above it for ">"
     double boundary = 0.0;
     bool divide = true;
@@ -571,10 +579,15 @@ int nms_run_ex_batched(const float *boxes, const float *scores, const int32_t *c
         return launch_status();
     }
     begin_launch();
-#define NMS_LAUNCH_EX(IOU_, MODE_, AUX_)                                                                          \
-    map_tile_ex_kernel<IOU_, MODE_, AUX_><<<grid, dim3(kMapWaves * 64), 0, s>>>(                                 \
-        w.sorted5, ranked_score, ranked_class, counts, n_max, n_pad, tiles, threshold, boundary, opt.pixel_offset, \
-        flags, mask)
+#define NMS_LAUNCH_EX_SUPER(IOU_, MODE_, AUX_, SUPER_)                                                            \
+    map_tile_ex_kernel<IOU_, MODE_, AUX_, SUPER_><<<grid, dim3(kMapWaves * 64), 0, s>>>(                          \
+        w.sorted5, ranked_score, ranked_class, ranked_area, counts, n_max, n_pad, tiles, tile_blocks, frames,     \
+        xcd_frames, threshold, boundary, opt.pixel_offset, flags, mask)
+#define NMS_LAUNCH_EX(IOU_, MODE_, AUX_)                                                  \
+    do {                                                                                  \
+        if (super4) NMS_LAUNCH_EX_SUPER(IOU_, MODE_, AUX_, 4);                            \
+        else NMS_LAUNCH_EX_SUPER(IOU_, MODE_, AUX_, 1);                                   \
+    } while (0)
 #define NMS_LAUNCH_EX_MODE(IOU_, AUX_)                                                    \
     do {                                                                                  \
         if (mode == kExBoundary) NMS_LAUNCH_EX(IOU_, kExBoundary, AUX_);                  \
@@ -587,6 +600,7 @@ int nms_run_ex_batched(const float *boxes, const float *scores, const int32_t *c
         if (aux) NMS_LAUNCH_EX_MODE(false, true); else NMS_LAUNCH_EX_MODE(false, false);
     }
 #undef NMS_LAUNCH_EX_MODE
+#undef NMS_LAUNCH_EX_SUPER
 #undef NMS_LAUNCH_EX
     st = launch_status();
     if (st != NMS_OK) return st;

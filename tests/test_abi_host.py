@@ -161,8 +161,8 @@ def test_options_argument_errors(nms):
     assert call(ok(), ws=ctypes.c_void_p(0x1008)) == nms.NMS_ERR_WORKSPACE
     assert call(ok(), n=0) == nms.NMS_OK
     assert call(None, n=0) == nms.NMS_OK
-    # mask + ranked scores + ranked labels on top of the fused path's workspace
-    assert nms.nms_ex_workspace_bytes(1024, 2) == nms.nms_greedy_workspace_bytes(1024, 2) + 2 * (2 * 1024 * 4)
+    # mask + ranked scores + ranked labels + ranked areas on top of the fused path's workspace
+    assert nms.nms_ex_workspace_bytes(1024, 2) == nms.nms_greedy_workspace_bytes(1024, 2) + 3 * (2 * 1024 * 4)
     assert nms.nms_ex_workspace_bytes(-1, 2) == 0
 
 
