@@ -14,8 +14,6 @@ from fractions import Fraction
 
 import numpy as np
 
-from pins import f32_round
-
 VARIANT_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "variants")
 DEFAULTS = {"rule": "paper", "measure": "outranking_area", "compare": "ge", "ties": "index", "offset": "1",
             "classes": "off"}
@@ -85,6 +83,8 @@ def pin_variant_golden(oracle):
 def exact_eliminates_ex(boxes, scores, classes, theta, j, i, measure, compare, ties, offset):
     """Does j eliminate i under the options?  Integer coordinates: every add, subtract
     and multiply is exact in float32, only the final division rounds."""
+    from pins import f32_round  # here, not at the top: pins imports this module to extend ALL_PINS
+
     sj, si = Fraction(float(scores[j])), Fraction(float(scores[i]))
     if ties == "ignore":
         if not sj > si:
