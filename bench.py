@@ -341,6 +341,27 @@ def main():
         extra["paper_matrix_form"] = mform
         del Bm, Vm
 
+        # -------------------------------------------------------------- the detection counts of the paper's discrete-GPU table
+        # (its latencies there: 0.107 / 0.324 / 1.313 ms on a GTX 1060 and 0.024 / 0.088 / 0.430 ms on a Tesla T4)
+        sizes = {}
+        for n_t in (200, 1027, 2895):
+            bt = b1[:n_t].contiguous()
+            st_ = s1[:n_t].contiguous()
+            kt = torch.empty(n_t, dtype=torch.uint8, device=dev)
+            wt = torch.empty(nms.nms_workspace_bytes(n_t, 1), dtype=torch.uint8, device=dev)
+            plan_t = nms.RunPlan(bt, st_, None, n_t, 1, w1.theta, kt, wt)
+            lat_t = []
+            for _ in range(30):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                plan_t()
+                torch.cuda.synchronize()
+                lat_t.append((time.perf_counter() - t0) * 1e6)
+            lat_t.sort()
+            sizes[str(n_t)] = {"kernel_us_back_to_back": round(event_ms(plan_t, 200) * 1e3, 2),
+                               "sync_call_us_median": round(lat_t[len(lat_t) // 2], 2)}
+        extra["single_frame_at_the_papers_detection_counts"] = sizes
+
     if args.calibrate_copy:
         src = torch.empty(64 << 20, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
