@@ -23,8 +23,9 @@
  * Conventions for every entry point
  *   - Pointers are DEVICE pointers unless a parameter says "host".  `stream` is a
  *     hipStream_t passed as void* (NULL = the default stream).
- *   - Calls only enqueue work on `stream` and return; they never allocate device
- *     memory, never synchronise, and keep no state (except nms_init's pool, below).
+ *   - Calls only enqueue kernels on `stream` and return; they never allocate device
+ *     memory, never synchronise, issue no memset or copy, and keep no state (except
+ *     nms_init's pool, below), so they may be captured in a HIP graph.
  *   - The caller owns every buffer.  Buffers must stay valid until the stream has
  *     passed the call.  Inputs are never written.
  *   - Return value: NMS_OK or a negative nms_status.  Arguments are validated on the

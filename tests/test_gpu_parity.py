@@ -364,3 +364,55 @@ def test_pool_entry_point_and_side_stream(nms, oracle):
         plan()
         torch.cuda.synchronize()
         assert np.array_equal(keep3.cpu().numpy(), want)
+
+
+def test_calls_can_be_captured_in_a_hip_graph(nms, oracle):
+    """The entry points only enqueue kernels on the caller's stream (no allocation, no
+    synchronisation, no memset), so a caller may capture them in a HIP graph.  The graph is
+    replayed several times with new inputs written into the same buffers and eager work in
+    between; every replay must give what the oracle gives for the inputs of that replay."""
+    import torch
+
+    n, F = 700, 12
+    frames = [random_frame(4300 + f, n, extent=300, max_side=90, integer=(f % 2 == 0), score_levels=50) for f in range(3 * F)]
+    dev = torch.device("cuda:0")
+    boxes = torch.zeros((F, n, 4), dtype=torch.float32, device=dev)
+    scores = torch.zeros((F, n), dtype=torch.float32, device=dev)
+    keep = torch.zeros((F, n), dtype=torch.uint8, device=dev)
+    keep_g = torch.zeros((F, n), dtype=torch.uint8, device=dev)
+    keep_x = torch.zeros((F, n), dtype=torch.uint8, device=dev)
+    ws = torch.zeros(nms.nms_workspace_bytes(n, F), dtype=torch.uint8, device=dev)
+    ws_g = torch.zeros(nms.nms_greedy_workspace_bytes(n, F), dtype=torch.uint8, device=dev)
+    ws_x = torch.zeros(nms.nms_ex_workspace_bytes(n, F), dtype=torch.uint8, device=dev)
+    theta = 0.4
+
+    def enqueue():
+        nms.nms_run_ranked_batched(boxes, scores, None, n, F, theta, keep, ws)
+        nms.nms_run_greedy_batched(boxes, scores, None, n, F, theta, keep_g, ws_g)
+        nms.nms_run_ex_batched(boxes, scores, None, n, F, theta, keep_x, ws_x, rule="greedy", measure="iou", pixel_offset=0.0)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        enqueue()  # warm-up outside the capture
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            enqueue()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        b = np.stack([frames[rep * F + f][0] for f in range(F)])
+        s = np.stack([frames[rep * F + f][1] for f in range(F)])
+        boxes.copy_(torch.from_numpy(b))
+        scores.copy_(torch.from_numpy(s))
+        keep.fill_(9), keep_g.fill_(9), keep_x.fill_(9)
+        (boxes.sum() + scores.sum()).item()  # eager work and a synchronisation between replays
+        graph.replay()
+        torch.cuda.synchronize()
+        want = oracle_keep_frames(oracle, b, s, np.float32(theta))
+        want_g = oracle_keep_frames(oracle, b, s, np.float32(theta), rule="greedy")
+        want_x = np.stack([oracle.keep_ex(b[f], s[f], np.float32(theta), rule="greedy", measure="iou", pixel_offset=0.0)
+                           for f in range(F)])
+        assert np.array_equal(keep.cpu().numpy(), want), f"replay {rep}: paper rule"
+        assert np.array_equal(keep_g.cpu().numpy(), want_g), f"replay {rep}: greedy rule"
+        assert np.array_equal(keep_x.cpu().numpy(), want_x), f"replay {rep}: variants"
