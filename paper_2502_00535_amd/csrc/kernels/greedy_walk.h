@@ -10,14 +10,20 @@
 // the pair grid.  Worth it when a batch has about as many frames as the chip has compute
 // units, since each frame is walked sequentially.
 //
-// A wavefront owns the tiles wave, wave + 16, wave + 32, wave + 48 and keeps their boxes in
-// registers, lane = row; one wave-uniform 64-bit word per owned tile says which rows are
-// eliminated (or do not exist).  For tile t = 0, 1, ...:
-//   - its owner settles it: the rows still alive are visited in rank order; each one visited
-//     is a survivor, is broadcast from its lane (v_readlane), eliminates the later rows of the
-//     tile that it hits, and is appended to a list in LDS;
-//   - barrier; every wavefront tests its later tiles against the list, one survivor at a
-//     time (broadcast from the lane that read it from LDS), all 64 rows per instruction.
+// The rows that are left (at first all of them) are numbered in rank order and cut into tiles
+// of 64; wavefront w owns the tiles w, w + 16, w + 32, w + 48 and keeps their boxes in
+// registers, lane = row, with one wave-uniform 64-bit word per tile for the rows that are out.
+// Round t settles tile t: its owner first applies the survivors of tile t-1 ("list t-1", in
+// LDS) to that tile alone, then visits the rows still alive in rank order -- each one visited
+// is a survivor, is broadcast from its lane (v_readlane) and eliminates the later rows of
+// the tile that it hits -- and writes list t; meanwhile the other wavefronts apply list t-1 to
+// all their tiles (the owner does so after settling).  One LDS-only barrier ends the round.
+//
+// Most rows that die do so early (on configuration 4 more than half of the rows are out after
+// the first two tiles), and a tile costs the same with one row alive as with 64.  So the walk
+// runs in stages of 2, 4, 8, ... tiles; after a stage the rows still alive are compacted (their
+// rank numbers through LDS, their boxes gathered again from the table) into fewer tiles and
+// the walk starts over on them.  The last stage begins once 16 tiles or fewer are left.
 constexpr int kFusedWaves = 16;
 constexpr int kFusedOwned = NMS_SORT_CHUNK / kTile / kFusedWaves;  // 4
 constexpr long long kGreedyFusedBoxes = 128ll * 4096;  // nms_run_greedy_batched takes this route from frames * n_max boxes on
@@ -85,99 +91,203 @@ __device__ __forceinline__ FusedCandidate broadcast_candidate(const FusedCandida
     return c;
 }
 
+constexpr int kWalkChunk = 4;  // survivors fetched from LDS at a time
+
 template <bool EX, bool IOU, int MODE, bool AUX>
 __global__ void __launch_bounds__(kFusedWaves * 64)
 greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ order,
                     const int32_t *__restrict__ counts, int n_max, int n_pad, NmsThetaConst th, FusedVariant opt,
                     uint8_t *__restrict__ keep_out)
 {
-    __shared__ FusedCandidate list_s[2][kTile];  // survivors of tile t in buffer t & 1
+    constexpr bool kUseT = MODE == kExBoundary && !IOU;  // the list carries T, else the area
+    __shared__ float4 box_s[2][kTile];                   // list t in buffer t & 1
+    __shared__ float aux_s[2][kTile];
+    __shared__ float score_s[2][kTile];
+    __shared__ int label_s[2][kTile];
     __shared__ int count_s[2];
+    __shared__ int alive_s[NMS_SORT_CHUNK / kTile];  // compaction: rows alive per tile
+    __shared__ int ids_s[NMS_SORT_CHUNK];            // compaction: rank numbers of the rows left
     const int f = blockIdx.x;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int n_f = frame_count(counts, f, n_max);
-    const int tiles_f = (n_f + kTile - 1) / kTile;
     const float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
     const float4 *box4 = reinterpret_cast<const float4 *>(sorted_f);
     const float *area = sorted_f + 4 * (size_t)n_pad;
     uint8_t *keep_f = keep_out + (size_t)f * n_max;
     const int32_t *order_f = order + (size_t)f * n_max;
 
-    // the owned tiles: boxes (also in their role as outranking boxes) and the rows that are out
-    float4 vb[kFusedOwned];
-    FusedCandidate self[kFusedOwned];
-    unsigned long long out[kFusedOwned];  // wave-uniform; bit r: row r is eliminated, settled or does not exist
-#pragma unroll
-    for (int i = 0; i < kFusedOwned; ++i) {
-        const int tr = wave + kFusedWaves * i;
-        const bool has = tr < tiles_f;
-        const int r = has ? tr * kTile + lane : 0;  // rows of a partial last tile beyond n_f are padding rows of the table
-        vb[i] = box4[r];
-        FusedCandidate me;
-        me.x1 = vb[i].x, me.y1 = vb[i].y, me.x2 = vb[i].z, me.y2 = vb[i].w;
-        me.area = EX ? ((vb[i].z - vb[i].x) + opt.offset) * ((vb[i].w - vb[i].y) + opt.offset) : area[r];
-        me.T = MODE == kExBoundary ? nms_pair_threshold(me.area, EX ? opt.boundary : th.m) : 0.0f;
-        me.score = AUX ? opt.ranked_score[(size_t)f * n_pad + r] : 0.0f;
-        me.label = (AUX && (opt.flags & kExClasses)) ? opt.ranked_label[(size_t)f * n_pad + r] : 0;
-        self[i] = me;
-        const int first = tr * kTile;
-        out[i] = !has ? ~0ull : (first + kTile <= n_f ? 0ull : ~0ull << (n_f - first));
-    }
+    for (int i = (int)threadIdx.x; i < n_max; i += blockDim.x) keep_f[i] = 0;  // survivors are marked as they are found
 
-    for (int t = 0; t < tiles_f; ++t) {
-        const int buf = t & 1;
-        if (wave == (t & (kFusedWaves - 1))) {
-            // settle tile t = owned tile number t / 16
-            float4 v = vb[0];
-            FusedCandidate mine = self[0];
-            unsigned long long todo = ~out[0];
+    // The owned tiles that are not settled yet, the next one to settle in slot 0 (after a tile is
+    // settled the others move down one slot).
+    float4 vb[kFusedOwned];
+    FusedCandidate self[kFusedOwned];     // the same rows in their role as outranking boxes
+    int rank_of[kFusedOwned];             // rank number of the lane's row
+    unsigned long long out[kFusedOwned];  // wave-uniform; bit r: row r is eliminated or does not exist
+    int left = 0;                         // owned tiles not settled yet
+    int tn = 0;                           // number of the tile in slot 0 (the others follow in steps of 16)
+    int n_cur = n_f;                      // rows in the current numbering
+
+    // (re)load the owned tiles of the current numbering; `compacted`: rank numbers come from ids_s
+    auto load_tiles = [&](bool compacted) __attribute__((always_inline)) {
+        left = 0;
+        tn = wave;
 #pragma unroll
-            for (int i = 1; i < kFusedOwned; ++i) {
-                if ((t >> 4) == i) {  // wave-uniform
-                    v = vb[i];
-                    mine = self[i];
-                    todo = ~out[i];
+        for (int i = 0; i < kFusedOwned; ++i) {
+            const int first = (wave + kFusedWaves * i) * kTile;
+            const bool has = first < n_cur;
+            left += has ? 1 : 0;
+            const int q = first + lane;
+            const bool real = q < n_cur;
+            const int r = real ? (compacted ? ids_s[q] : q) : 0;  // rows that do not exist read row 0 and are marked out
+            rank_of[i] = r;
+            vb[i] = box4[r];
+            FusedCandidate me;
+            me.x1 = vb[i].x, me.y1 = vb[i].y, me.x2 = vb[i].z, me.y2 = vb[i].w;
+            me.area = EX ? ((vb[i].z - vb[i].x) + opt.offset) * ((vb[i].w - vb[i].y) + opt.offset) : area[r];
+            me.T = MODE == kExBoundary ? nms_pair_threshold(me.area, EX ? opt.boundary : th.m) : 0.0f;
+            me.score = AUX ? opt.ranked_score[(size_t)f * n_pad + r] : 0.0f;
+            me.label = (AUX && (opt.flags & kExClasses)) ? opt.ranked_label[(size_t)f * n_pad + r] : 0;
+            self[i] = me;
+            out[i] = !has ? ~0ull : (first + kTile <= n_cur ? 0ull : ~0ull << (n_cur - first));
+        }
+    };
+    load_tiles(false);
+    __syncthreads();  // the zero fill is complete before any survivor's byte is written
+
+    // Survivor k of the list in buffer `buf`, the same one in every lane (a broadcast read).
+    auto entry = [&](int buf, int k) __attribute__((always_inline)) {
+        FusedCandidate c;
+        const float4 b = box_s[buf][k];
+        c.x1 = b.x, c.y1 = b.y, c.x2 = b.z, c.y2 = b.w;
+        c.T = kUseT ? aux_s[buf][k] : 0.0f;
+        c.area = kUseT ? 0.0f : aux_s[buf][k];
+        c.score = AUX ? score_s[buf][k] : 0.0f;
+        c.label = AUX ? label_s[buf][k] : 0;
+        return c;
+    };
+    // The list in buffer `buf` against the tiles in slots 0 .. N-1; the next survivors are
+    // fetched while the current ones are tested, and a full chunk has no branch inside.
+    auto apply_slots = [&](auto slots, int buf) __attribute__((always_inline)) {
+        constexpr int N = decltype(slots)::value;
+        const int count = __builtin_amdgcn_readfirstlane(count_s[buf]);
+        if (count == 0) return;
+        FusedCandidate next[kWalkChunk];
+#pragma unroll
+        for (int u = 0; u < kWalkChunk; ++u) next[u] = entry(buf, u < count ? u : count - 1);
+        for (int k0 = 0; k0 < count; k0 += kWalkChunk) {
+            FusedCandidate cand[kWalkChunk];
+#pragma unroll
+            for (int u = 0; u < kWalkChunk; ++u) cand[u] = next[u];
+            if (k0 + kWalkChunk < count) {
+#pragma unroll
+                for (int u = 0; u < kWalkChunk; ++u) {
+                    const int k = k0 + kWalkChunk + u;
+                    next[u] = entry(buf, k < count ? k : count - 1);
                 }
             }
-            unsigned long long kept = 0;
-            int count = 0;
-            while (todo != 0) {
-                const int c = (int)__builtin_ctzll(todo);  // best-ranked row still alive: a survivor
-                todo &= todo - 1ull;
-                kept |= 1ull << c;
-                const FusedCandidate cand = broadcast_candidate(mine, c);
-                const bool hit = fused_hit<EX, IOU, MODE, AUX>(v, mine.area, mine.score, mine.label, cand, th.theta, opt) &&
-                                 lane > c;
-                todo &= ~__ballot(hit);
-                if (lane == 0) list_s[buf][count] = cand;
-                ++count;
-            }
-            if (lane == 0) count_s[buf] = count;
-            const int r = t * kTile + lane;
-            if (r < n_f) keep_f[order_f[r]] = (uint8_t)((kept >> lane) & 1ull);
+            if (k0 + kWalkChunk <= count) {
 #pragma unroll
-            for (int i = 0; i < kFusedOwned; ++i)
-                if ((t >> 4) == i) out[i] = ~0ull;
+                for (int u = 0; u < kWalkChunk; ++u) {
+#pragma unroll
+                    for (int i = 0; i < N; ++i)
+                        out[i] |= __ballot(fused_hit<EX, IOU, MODE, AUX>(vb[i], self[i].area, self[i].score, self[i].label,
+                                                                          cand[u], th.theta, opt));
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < kWalkChunk - 1; ++u) {
+                    if (k0 + u < count) {  // wave-uniform
+#pragma unroll
+                        for (int i = 0; i < N; ++i)
+                            out[i] |= __ballot(fused_hit<EX, IOU, MODE, AUX>(vb[i], self[i].area, self[i].score,
+                                                                              self[i].label, cand[u], th.theta, opt));
+                    }
+                }
+            }
+        }
+    };
+    auto apply = [&](int slots, int buf) __attribute__((always_inline)) {  // the same for a number of slots known at run time
+        if (slots == 1) apply_slots(std::integral_constant<int, 1>(), buf);
+        else if (slots == 2) apply_slots(std::integral_constant<int, 2>(), buf);
+        else if (slots == 3) apply_slots(std::integral_constant<int, 3>(), buf);
+        else if (slots >= 4) apply_slots(std::integral_constant<int, 4>(), buf);
+    };
+    static_assert(kFusedOwned == 4, "apply() dispatches on up to four slots");
+
+    for (int stage_tiles = 2;; stage_tiles *= 2) {
+        const int tiles_cur = (n_cur + kTile - 1) / kTile;
+        const int rounds = (tiles_cur <= kFusedWaves || stage_tiles >= tiles_cur) ? tiles_cur : stage_tiles;
+        for (int t = 0; t < rounds; ++t) {
+            const int pending = (t - 1) & 1;  // buffer of list t-1 (there is none in a stage's first round)
+            if (wave == (t & (kFusedWaves - 1))) {
+                // settle tile t (slot 0): list t-1 against it first, then the rows still alive in
+                // rank order, each one visited is a survivor
+                __builtin_amdgcn_s_setprio(3);
+                if (t > 0) apply_slots(std::integral_constant<int, 1>(), pending);
+                const float4 v = vb[0];
+                const FusedCandidate mine = self[0];
+                unsigned long long todo = ~out[0];
+                unsigned long long kept = 0;
+                while (todo != 0) {
+                    const int c = (int)__builtin_ctzll(todo);
+                    todo &= todo - 1ull;
+                    kept |= 1ull << c;
+                    const FusedCandidate cand = broadcast_candidate(mine, c);
+                    const bool hit = fused_hit<EX, IOU, MODE, AUX>(v, mine.area, mine.score, mine.label, cand, th.theta, opt) &&
+                                     lane > c;
+                    todo &= ~__ballot(hit);
+                }
+                const bool is_kept = (kept >> lane) & 1ull;
+                if (is_kept) {  // survivor number k of the tile is entry k of list t
+                    const int k = __builtin_popcountll(kept & ((1ull << lane) - 1ull));
+                    box_s[t & 1][k] = v;
+                    aux_s[t & 1][k] = kUseT ? mine.T : mine.area;
+                    if (AUX) score_s[t & 1][k] = mine.score;
+                    if (AUX) label_s[t & 1][k] = mine.label;
+                }
+                if (lane == 0) count_s[t & 1] = __builtin_popcountll(kept);
+                __builtin_amdgcn_s_setprio(0);
+                if (is_kept) keep_f[order_f[rank_of[0]]] = 1;
+#pragma unroll
+                for (int i = 0; i + 1 < kFusedOwned; ++i) {
+                    vb[i] = vb[i + 1];
+                    self[i] = self[i + 1];
+                    rank_of[i] = rank_of[i + 1];
+                    out[i] = out[i + 1];
+                }
+                --left;
+                tn += kFusedWaves;
+            }
+            if (t > 0) apply(left, pending);
+            lds_barrier();
+        }
+        if (rounds == tiles_cur) break;  // every tile is settled
+
+        // End of a stage: the last list against everything that is left, then the rows still
+        // alive move together.  Tile `rounds + j` of the old numbering reports its count in
+        // alive_s[j]; a prefix sum gives every tile its place in ids_s.
+        apply(left, (rounds - 1) & 1);
+        const int tiles_left = tiles_cur - rounds;
+#pragma unroll
+        for (int i = 0; i < kFusedOwned; ++i) {
+            if (i < left && lane == 0) alive_s[tn - rounds + kFusedWaves * i] = __builtin_popcountll(~out[i]);
         }
         lds_barrier();
-        // the survivors of tile t against the later owned tiles that still have a row alive
-        const int count = __builtin_amdgcn_readfirstlane(count_s[buf]);
-        bool any = false;
+        const unsigned mine_alive = lane < tiles_left ? (unsigned)alive_s[lane] : 0u;
+        const unsigned incl = wave_inclusive_sum(mine_alive);
+        const int total = __builtin_amdgcn_readlane((int)incl, 63);
 #pragma unroll
-        for (int i = 0; i < kFusedOwned; ++i) any = any || (wave + kFusedWaves * i > t && out[i] != ~0ull);
-        if (count > 0 && any) {
-            const FusedCandidate held = list_s[buf][lane < count ? lane : 0];  // lane k holds survivor k
-            for (int k = 0; k < count; ++k) {
-                const FusedCandidate cand = broadcast_candidate(held, k);
-#pragma unroll
-                for (int i = 0; i < kFusedOwned; ++i) {
-                    if (wave + kFusedWaves * i > t && out[i] != ~0ull)  // wave-uniform
-                        out[i] |= __ballot(fused_hit<EX, IOU, MODE, AUX>(vb[i], self[i].area, self[i].score, self[i].label,
-                                                                          cand, th.theta, opt));
-                }
+        for (int i = 0; i < kFusedOwned; ++i) {
+            if (i < left) {  // wave-uniform
+                const int base = __builtin_amdgcn_readlane((int)(incl - mine_alive), tn - rounds + kFusedWaves * i);
+                const unsigned long long alive = ~out[i];
+                if ((alive >> lane) & 1ull) ids_s[base + __builtin_popcountll(alive & ((1ull << lane) - 1ull))] = rank_of[i];
             }
         }
+        lds_barrier();
+        n_cur = total;
+        load_tiles(true);
     }
-    for (int i = n_f + (int)threadIdx.x; i < n_max; i += blockDim.x) keep_f[i] = 0;  // slots beyond the count
 }

@@ -20,6 +20,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <type_traits>
+
 #include "../../include/nms.h"
 #include "nms_pair.h"
 
