@@ -92,6 +92,7 @@ __device__ __forceinline__ FusedCandidate broadcast_candidate(const FusedCandida
 }
 
 constexpr int kWalkChunk = 4;  // survivors fetched from LDS at a time
+constexpr int kWalkLists = 4;  // lists kept in LDS: the one being written, the one being applied, the one before (see below)
 
 template <bool EX, bool IOU, int MODE, bool AUX>
 __global__ void __launch_bounds__(kFusedWaves * 64)
@@ -100,11 +101,11 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
                     uint8_t *__restrict__ keep_out)
 {
     constexpr bool kUseT = MODE == kExBoundary && !IOU;  // the list carries T, else the area
-    __shared__ float4 box_s[2][kTile];                   // list t in buffer t & 1
-    __shared__ float aux_s[2][kTile];
-    __shared__ float score_s[2][kTile];
-    __shared__ int label_s[2][kTile];
-    __shared__ int count_s[2];
+    __shared__ float4 box_s[kWalkLists][kTile];          // list t in buffer t % kWalkLists
+    __shared__ float aux_s[kWalkLists][kTile];
+    __shared__ float score_s[kWalkLists][kTile];
+    __shared__ int label_s[kWalkLists][kTile];
+    __shared__ int count_s[kWalkLists];
     __shared__ int alive_s[NMS_SORT_CHUNK / kTile];  // compaction: rows alive per tile
     __shared__ int ids_s[NMS_SORT_CHUNK];            // compaction: rank numbers of the rows left
     const int f = blockIdx.x;
@@ -167,33 +168,25 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
         c.label = AUX ? label_s[buf][k] : 0;
         return c;
     };
-    // The list in buffer `buf` against the tiles in slots 0 .. N-1; the next survivors are
-    // fetched while the current ones are tested, and a full chunk has no branch inside.
+    // The list in buffer `buf` against the tiles in slots 0 .. N-1.  Survivors are fetched four
+    // at a time into two sets of registers in turn, the next four while the current four are
+    // tested; a full chunk has no branch inside.
     auto apply_slots = [&](auto slots, int buf) __attribute__((always_inline)) {
         constexpr int N = decltype(slots)::value;
         const int count = __builtin_amdgcn_readfirstlane(count_s[buf]);
         if (count == 0) return;
-        FusedCandidate next[kWalkChunk];
+        auto fetch = [&](FusedCandidate (&c)[kWalkChunk], int k0) __attribute__((always_inline)) {
 #pragma unroll
-        for (int u = 0; u < kWalkChunk; ++u) next[u] = entry(buf, u < count ? u : count - 1);
-        for (int k0 = 0; k0 < count; k0 += kWalkChunk) {
-            FusedCandidate cand[kWalkChunk];
-#pragma unroll
-            for (int u = 0; u < kWalkChunk; ++u) cand[u] = next[u];
-            if (k0 + kWalkChunk < count) {
-#pragma unroll
-                for (int u = 0; u < kWalkChunk; ++u) {
-                    const int k = k0 + kWalkChunk + u;
-                    next[u] = entry(buf, k < count ? k : count - 1);
-                }
-            }
+            for (int u = 0; u < kWalkChunk; ++u) c[u] = entry(buf, k0 + u < count ? k0 + u : count - 1);
+        };
+        auto test = [&](const FusedCandidate (&c)[kWalkChunk], int k0) __attribute__((always_inline)) {
             if (k0 + kWalkChunk <= count) {
 #pragma unroll
                 for (int u = 0; u < kWalkChunk; ++u) {
 #pragma unroll
                     for (int i = 0; i < N; ++i)
                         out[i] |= __ballot(fused_hit<EX, IOU, MODE, AUX>(vb[i], self[i].area, self[i].score, self[i].label,
-                                                                          cand[u], th.theta, opt));
+                                                                          c[u], th.theta, opt));
                 }
             } else {
 #pragma unroll
@@ -202,10 +195,19 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
 #pragma unroll
                         for (int i = 0; i < N; ++i)
                             out[i] |= __ballot(fused_hit<EX, IOU, MODE, AUX>(vb[i], self[i].area, self[i].score,
-                                                                              self[i].label, cand[u], th.theta, opt));
+                                                                              self[i].label, c[u], th.theta, opt));
                     }
                 }
             }
+        };
+        FusedCandidate even[kWalkChunk], odd[kWalkChunk];
+        fetch(even, 0);
+        for (int k0 = 0; k0 < count; k0 += 2 * kWalkChunk) {
+            if (k0 + kWalkChunk < count) fetch(odd, k0 + kWalkChunk);
+            test(even, k0);
+            if (k0 + kWalkChunk >= count) break;
+            if (k0 + 2 * kWalkChunk < count) fetch(even, k0 + 2 * kWalkChunk);
+            test(odd, k0 + kWalkChunk);
         }
     };
     auto apply = [&](int slots, int buf) __attribute__((always_inline)) {  // the same for a number of slots known at run time
@@ -216,11 +218,12 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
     };
     static_assert(kFusedOwned == 4, "apply() dispatches on up to four slots");
 
+    bool owes = false;  // this wavefront settled a tile in the round before and has not yet applied that round's list to its other tiles
     for (int stage_tiles = 2;; stage_tiles *= 2) {
         const int tiles_cur = (n_cur + kTile - 1) / kTile;
         const int rounds = (tiles_cur <= kFusedWaves || stage_tiles >= tiles_cur) ? tiles_cur : stage_tiles;
         for (int t = 0; t < rounds; ++t) {
-            const int pending = (t - 1) & 1;  // buffer of list t-1 (there is none in a stage's first round)
+            const int pending = (t - 1) & (kWalkLists - 1);  // buffer of list t-1 (there is none in a stage's first round)
             if (wave == (t & (kFusedWaves - 1))) {
                 // settle tile t (slot 0): list t-1 against it first, then the rows still alive in
                 // rank order, each one visited is a survivor
@@ -240,14 +243,15 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
                     todo &= ~__ballot(hit);
                 }
                 const bool is_kept = (kept >> lane) & 1ull;
+                const int into = t & (kWalkLists - 1);
                 if (is_kept) {  // survivor number k of the tile is entry k of list t
                     const int k = __builtin_popcountll(kept & ((1ull << lane) - 1ull));
-                    box_s[t & 1][k] = v;
-                    aux_s[t & 1][k] = kUseT ? mine.T : mine.area;
-                    if (AUX) score_s[t & 1][k] = mine.score;
-                    if (AUX) label_s[t & 1][k] = mine.label;
+                    box_s[into][k] = v;
+                    aux_s[into][k] = kUseT ? mine.T : mine.area;
+                    if (AUX) score_s[into][k] = mine.score;
+                    if (AUX) label_s[into][k] = mine.label;
                 }
-                if (lane == 0) count_s[t & 1] = __builtin_popcountll(kept);
+                if (lane == 0) count_s[into] = __builtin_popcountll(kept);
                 __builtin_amdgcn_s_setprio(0);
                 if (is_kept) keep_f[order_f[rank_of[0]]] = 1;
 #pragma unroll
@@ -259,8 +263,12 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
                 }
                 --left;
                 tn += kFusedWaves;
+                owes = t > 0;  // list t-1 against its other tiles waits until the next round, so that this round is not held up
+            } else {
+                if (owes) apply(left, (t - 2) & (kWalkLists - 1));
+                owes = false;
+                if (t > 0) apply(left, pending);
             }
-            if (t > 0) apply(left, pending);
             lds_barrier();
         }
         if (rounds == tiles_cur) break;  // every tile is settled
@@ -268,7 +276,9 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
         // End of a stage: the last list against everything that is left, then the rows still
         // alive move together.  Tile `rounds + j` of the old numbering reports its count in
         // alive_s[j]; a prefix sum gives every tile its place in ids_s.
-        apply(left, (rounds - 1) & 1);
+        if (owes) apply(left, (rounds - 2) & (kWalkLists - 1));
+        owes = false;
+        apply(left, (rounds - 1) & (kWalkLists - 1));
         const int tiles_left = tiles_cur - rounds;
 #pragma unroll
         for (int i = 0; i < kFusedOwned; ++i) {
