@@ -219,16 +219,18 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
     static_assert(kFusedOwned == 4, "apply() dispatches on up to four slots");
 
     bool owes = false;  // this wavefront settled a tile in the round before and has not yet applied that round's list to its other tiles
+    int g = 0;          // rounds so far over all stages: round g writes list g, into buffer g % kWalkLists
     for (int stage_tiles = 2;; stage_tiles *= 2) {
         const int tiles_cur = (n_cur + kTile - 1) / kTile;
         const int rounds = (tiles_cur <= kFusedWaves || stage_tiles >= tiles_cur) ? tiles_cur : stage_tiles;
-        for (int t = 0; t < rounds; ++t) {
-            const int pending = (t - 1) & (kWalkLists - 1);  // buffer of list t-1 (there is none in a stage's first round)
+        for (int t = 0; t < rounds; ++t, ++g) {
+            const int pending = (g - 1) & (kWalkLists - 1);  // buffer of the list before (there is none in the very first round)
+            const bool stage_ends = t == rounds - 1 && rounds != tiles_cur;
             if (wave == (t & (kFusedWaves - 1))) {
-                // settle tile t (slot 0): list t-1 against it first, then the rows still alive in
-                // rank order, each one visited is a survivor
+                // settle tile t (slot 0): the list before against it first, then the rows still
+                // alive in rank order, each one visited is a survivor
                 __builtin_amdgcn_s_setprio(3);
-                if (t > 0) apply_slots(std::integral_constant<int, 1>(), pending);
+                if (g > 0) apply_slots(std::integral_constant<int, 1>(), pending);
                 const float4 v = vb[0];
                 const FusedCandidate mine = self[0];
                 unsigned long long todo = ~out[0];
@@ -243,7 +245,7 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
                     todo &= ~__ballot(hit);
                 }
                 const bool is_kept = (kept >> lane) & 1ull;
-                const int into = t & (kWalkLists - 1);
+                const int into = g & (kWalkLists - 1);
                 if (is_kept) {  // survivor number k of the tile is entry k of list t
                     const int k = __builtin_popcountll(kept & ((1ull << lane) - 1ull));
                     box_s[into][k] = v;
@@ -263,22 +265,23 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
                 }
                 --left;
                 tn += kFusedWaves;
-                owes = t > 0;  // list t-1 against its other tiles waits until the next round, so that this round is not held up
+                // the list before against its other tiles waits until the next round, so that this
+                // round is not held up -- unless the rows are about to be handed out anew
+                owes = g > 0 && !stage_ends;
+                if (g > 0 && stage_ends) apply(left, pending);
             } else {
-                if (owes) apply(left, (t - 2) & (kWalkLists - 1));
+                if (owes) apply(left, (g - 2) & (kWalkLists - 1));
                 owes = false;
-                if (t > 0) apply(left, pending);
+                if (g > 0) apply(left, pending);
             }
             lds_barrier();
         }
         if (rounds == tiles_cur) break;  // every tile is settled
 
-        // End of a stage: the last list against everything that is left, then the rows still
-        // alive move together.  Tile `rounds + j` of the old numbering reports its count in
+        // End of a stage: the rows still alive move together (the list just written has not been
+        // applied yet; it holds boxes, not row numbers, and is applied in the next stage's first
+        // round like any other).  Tile `rounds + j` of the old numbering reports its count in
         // alive_s[j]; a prefix sum gives every tile its place in ids_s.
-        if (owes) apply(left, (rounds - 2) & (kWalkLists - 1));
-        owes = false;
-        apply(left, (rounds - 1) & (kWalkLists - 1));
         const int tiles_left = tiles_cur - rounds;
 #pragma unroll
         for (int i = 0; i < kFusedOwned; ++i) {
