@@ -76,6 +76,16 @@ __device__ __forceinline__ bool fused_hit(const float4 v, float v_area, float v_
     return hit;
 }
 
+// Bitwise OR over each row of 16 lanes, in the row's last lane.
+__device__ __forceinline__ unsigned row_or16(unsigned x)
+{
+    x |= (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, true);  // row_shr:1
+    x |= (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, true);  // row_shr:2
+    x |= (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, true);  // row_shr:4
+    x |= (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, true);  // row_shr:8
+    return x;
+}
+
 // Lane `src` (wave-uniform) of a per-lane candidate, as a wave-uniform value.
 __device__ __forceinline__ FusedCandidate broadcast_candidate(const FusedCandidate &mine, int src)
 {
@@ -101,11 +111,14 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
                     uint8_t *__restrict__ keep_out)
 {
     constexpr bool kUseT = MODE == kExBoundary && !IOU;  // the list carries T, else the area
-    __shared__ float4 box_s[kWalkLists][kTile];          // list t in buffer t % kWalkLists
-    __shared__ float aux_s[kWalkLists][kTile];
-    __shared__ float score_s[kWalkLists][kTile];
-    __shared__ int label_s[kWalkLists][kTile];
+    constexpr int kTileBuf = kWalkLists;                 // one more buffer of the same layout: the rows of the tile being settled
+    __shared__ float4 box_s[kWalkLists + 1][kTile];      // list t in buffer t % kWalkLists
+    __shared__ float aux_s[kWalkLists + 1][kTile];
+    __shared__ float score_s[kWalkLists + 1][kTile];
+    __shared__ int label_s[kWalkLists + 1][kTile];
     __shared__ int count_s[kWalkLists];
+    __shared__ unsigned long long part_s[kFusedWaves];   // rows of the tile being settled that a wavefront's share of the list before eliminates
+    __shared__ unsigned long long hitters_s[kTile];      // per row of that tile: the better-ranked rows of the tile that eliminate it
     __shared__ int alive_s[NMS_SORT_CHUNK / kTile];  // compaction: rows alive per tile
     __shared__ int ids_s[NMS_SORT_CHUNK];            // compaction: rank numbers of the rows left
     const int f = blockIdx.x;
@@ -218,35 +231,74 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
     };
     static_assert(kFusedOwned == 4, "apply() dispatches on up to four slots");
 
+    // the rows of slot 0 into LDS for the round that settles them
+    auto post_tile = [&]() __attribute__((always_inline)) {
+        box_s[kTileBuf][lane] = vb[0];
+        aux_s[kTileBuf][lane] = kUseT ? self[0].T : self[0].area;
+        if (AUX) score_s[kTileBuf][lane] = self[0].score;
+        if (AUX) label_s[kTileBuf][lane] = self[0].label;
+    };
+
     bool owes = false;  // this wavefront settled a tile in the round before and has not yet applied that round's list to its other tiles
     int g = 0;          // rounds so far over all stages: round g writes list g, into buffer g % kWalkLists
     for (int stage_tiles = 2;; stage_tiles *= 2) {
         const int tiles_cur = (n_cur + kTile - 1) / kTile;
         const int rounds = (tiles_cur <= kFusedWaves || stage_tiles >= tiles_cur) ? tiles_cur : stage_tiles;
+        if (wave == 0) post_tile();  // tile 0 of this numbering
+        lds_barrier();
         for (int t = 0; t < rounds; ++t, ++g) {
             const int pending = (g - 1) & (kWalkLists - 1);  // buffer of the list before (there is none in the very first round)
             const bool stage_ends = t == rounds - 1 && rounds != tiles_cur;
+            // All wavefronts, a share each, on the tile being settled (its rows are in LDS, lane =
+            // row): the survivors of the list before against it, and for each of its rows the
+            // better-ranked rows of the tile itself that eliminate it.
+            {
+                const FusedCandidate row = entry(kTileBuf, lane);
+                const float4 row_box = make_float4(row.x1, row.y1, row.x2, row.y2);
+                const int count = g > 0 ? __builtin_amdgcn_readfirstlane(count_s[pending]) : 0;
+                unsigned long long part = 0;
+                for (int k = wave; k < count; k += kFusedWaves)
+                    part |= __ballot(fused_hit<EX, IOU, MODE, AUX>(row_box, row.area, row.score, row.label, entry(pending, k),
+                                                                    th.theta, opt));
+                if (lane == 0) part_s[wave] = part;
+                FusedCandidate victim[kTile / kFusedWaves];
+#pragma unroll
+                for (int j = 0; j < kTile / kFusedWaves; ++j) victim[j] = entry(kTileBuf, wave + kFusedWaves * j);
+#pragma unroll
+                for (int j = 0; j < kTile / kFusedWaves; ++j) {
+                    const int r = wave + kFusedWaves * j;
+                    const bool hit = fused_hit<EX, IOU, MODE, AUX>(make_float4(victim[j].x1, victim[j].y1, victim[j].x2, victim[j].y2),
+                                                                   victim[j].area, victim[j].score, victim[j].label, row,
+                                                                   th.theta, opt) &&
+                                     lane < r;
+                    const unsigned long long hitters = __ballot(hit);
+                    if (lane == 0) hitters_s[r] = hitters;
+                }
+            }
+            lds_barrier();
             if (wave == (t & (kFusedWaves - 1))) {
-                // settle tile t (slot 0): the list before against it first, then the rows still
-                // alive in rank order, each one visited is a survivor
+                // Settle tile t (slot 0).  A row survives iff it is alive and no surviving
+                // better-ranked row of the tile eliminates it; iterated from "every alive row
+                // survives" this settles one more row per pass at least, in practice a few passes.
                 __builtin_amdgcn_s_setprio(3);
-                if (g > 0) apply_slots(std::integral_constant<int, 1>(), pending);
+                const unsigned long long share = part_s[lane & (kFusedWaves - 1)];
+                const unsigned dead_lo = row_or16((unsigned)share), dead_hi = row_or16((unsigned)(share >> 32));
+                const unsigned long long dead =
+                    out[0] | ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)dead_hi, kFusedWaves - 1) << 32) |
+                    (unsigned)__builtin_amdgcn_readlane((int)dead_lo, kFusedWaves - 1);
+                const unsigned long long hitters = hitters_s[lane];
+                const bool alive = ((~dead >> lane) & 1ull) != 0;
+                unsigned long long kept = ~dead;
+                for (int pass = 0; pass < kTile; ++pass) {
+                    const unsigned long long next = __ballot(alive && (hitters & kept) == 0);
+                    if (next == kept) break;
+                    kept = next;
+                }
                 const float4 v = vb[0];
                 const FusedCandidate mine = self[0];
-                unsigned long long todo = ~out[0];
-                unsigned long long kept = 0;
-                while (todo != 0) {
-                    const int c = (int)__builtin_ctzll(todo);
-                    todo &= todo - 1ull;
-                    kept |= 1ull << c;
-                    const FusedCandidate cand = broadcast_candidate(mine, c);
-                    const bool hit = fused_hit<EX, IOU, MODE, AUX>(v, mine.area, mine.score, mine.label, cand, th.theta, opt) &&
-                                     lane > c;
-                    todo &= ~__ballot(hit);
-                }
                 const bool is_kept = (kept >> lane) & 1ull;
                 const int into = g & (kWalkLists - 1);
-                if (is_kept) {  // survivor number k of the tile is entry k of list t
+                if (is_kept) {  // survivor number k of the tile is entry k of the list
                     const int k = __builtin_popcountll(kept & ((1ull << lane) - 1ull));
                     box_s[into][k] = v;
                     aux_s[into][k] = kUseT ? mine.T : mine.area;
@@ -270,6 +322,7 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
                 owes = g > 0 && !stage_ends;
                 if (g > 0 && stage_ends) apply(left, pending);
             } else {
+                if (t + 1 < rounds && wave == ((t + 1) & (kFusedWaves - 1))) post_tile();  // the next round's tile
                 if (owes) apply(left, (g - 2) & (kWalkLists - 1));
                 owes = false;
                 if (g > 0) apply(left, pending);
