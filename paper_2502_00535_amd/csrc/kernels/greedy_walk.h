@@ -102,7 +102,7 @@ __device__ __forceinline__ FusedCandidate broadcast_candidate(const FusedCandida
 }
 
 constexpr int kWalkChunk = 4;  // survivors fetched from LDS at a time
-constexpr int kWalkLists = 4;  // lists kept in LDS: the one being written, the one being applied, the one before (see below)
+constexpr int kWalkLists = 2;  // lists kept in LDS: the one being written and the one being applied
 
 template <bool EX, bool IOU, int MODE, bool AUX>
 __global__ void __launch_bounds__(kFusedWaves * 64)
@@ -239,7 +239,6 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
         if (AUX) label_s[kTileBuf][lane] = self[0].label;
     };
 
-    bool owes = false;  // this wavefront settled a tile in the round before and has not yet applied that round's list to its other tiles
     int g = 0;          // rounds so far over all stages: round g writes list g, into buffer g % kWalkLists
     for (int stage_tiles = 2;; stage_tiles *= 2) {
         const int tiles_cur = (n_cur + kTile - 1) / kTile;
@@ -248,7 +247,6 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
         lds_barrier();
         for (int t = 0; t < rounds; ++t, ++g) {
             const int pending = (g - 1) & (kWalkLists - 1);  // buffer of the list before (there is none in the very first round)
-            const bool stage_ends = t == rounds - 1 && rounds != tiles_cur;
             // All wavefronts, a share each, on the tile being settled (its rows are in LDS, lane =
             // row): the survivors of the list before against it, and for each of its rows the
             // better-ranked rows of the tile itself that eliminate it.
@@ -317,16 +315,10 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
                 }
                 --left;
                 tn += kFusedWaves;
-                // the list before against its other tiles waits until the next round, so that this
-                // round is not held up -- unless the rows are about to be handed out anew
-                owes = g > 0 && !stage_ends;
-                if (g > 0 && stage_ends) apply(left, pending);
-            } else {
-                if (t + 1 < rounds && wave == ((t + 1) & (kFusedWaves - 1))) post_tile();  // the next round's tile
-                if (owes) apply(left, (g - 2) & (kWalkLists - 1));
-                owes = false;
-                if (g > 0) apply(left, pending);
+            } else if (t + 1 < rounds && wave == ((t + 1) & (kFusedWaves - 1))) {
+                post_tile();  // the next round's tile
             }
+            if (g > 0) apply(left, pending);  // the list before against the tiles that are left
             lds_barrier();
         }
         if (rounds == tiles_cur) break;  // every tile is settled
