@@ -162,15 +162,15 @@ int nms_run_direct_batched(const float *boxes, const float *scores, const int32_
  *   nms_run_greedy_batched    rank + map + greedy sweep; needs the mask in its workspace:
  *                             >= nms_greedy_workspace_bytes(n_max, frames) bytes, 256-byte aligned.
  *                             Batches of frames of at most NMS_SORT_CHUNK boxes with
- *                             frames * n_max >= 128 * 4096 take the route below instead (same
+ *                             frames * n_max >= 32 * 4096 take the route below instead (same
  *                             result, bit for bit).
- *   nms_run_greedy_fused_batched   rank, then one workgroup per frame walks the tile columns
- *                             in rank order and tests only victims that are still alive against
- *                             boxes that survived: no mask, and most of the pair grid is never
- *                             evaluated.  n_max <= NMS_SORT_CHUNK (else NMS_ERR_TOO_LARGE);
- *                             workspace >= nms_workspace_bytes(n_max, frames).  Frames are
- *                             walked sequentially, so it pays when the batch has about as many
- *                             frames as the chip has compute units.
+ *   nms_run_greedy_fused_batched   rank, then one workgroup per frame walks the frame in rank
+ *                             order, 64 rows a round, and tests only rows that are still alive
+ *                             against boxes that survived; the rows left are packed together
+ *                             after 2, 4, 8 ... rounds.  No mask, and most of the pair grid is
+ *                             never evaluated.  n_max <= NMS_SORT_CHUNK (else NMS_ERR_TOO_LARGE);
+ *                             workspace >= nms_workspace_bytes(n_max, frames).  A frame is one
+ *                             compute unit's work, so it pays from a few dozen frames on.
  */
 int nms_reduce_greedy(const uint64_t *mask, const int32_t *order, int n, uint8_t *keep_out, void *stream);
 int nms_reduce_greedy_batched(const uint64_t *mask, const int32_t *order, const int32_t *counts, int n_max,

@@ -26,7 +26,7 @@
 // the walk starts over on them.  The last stage begins once 16 tiles or fewer are left.
 constexpr int kFusedWaves = 16;
 constexpr int kFusedOwned = NMS_SORT_CHUNK / kTile / kFusedWaves;  // 4
-constexpr long long kGreedyFusedBoxes = 128ll * 4096;  // nms_run_greedy_batched takes this route from frames * n_max boxes on
+constexpr long long kGreedyFusedBoxes = 32ll * 4096;  // nms_run_greedy_batched takes this route from frames * n_max boxes on
 
 struct FusedCandidate {  // a survivor as an outranking box (fields a variant does not use are never read)
     float x1, y1, x2, y2, area, T, score;
@@ -84,21 +84,6 @@ __device__ __forceinline__ unsigned row_or16(unsigned x)
     x |= (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, true);  // row_shr:4
     x |= (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, true);  // row_shr:8
     return x;
-}
-
-// Lane `src` (wave-uniform) of a per-lane candidate, as a wave-uniform value.
-__device__ __forceinline__ FusedCandidate broadcast_candidate(const FusedCandidate &mine, int src)
-{
-    FusedCandidate c;
-    c.x1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mine.x1), src));
-    c.y1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mine.y1), src));
-    c.x2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mine.x2), src));
-    c.y2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mine.y2), src));
-    c.area = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mine.area), src));
-    c.T = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mine.T), src));
-    c.score = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mine.score), src));
-    c.label = __builtin_amdgcn_readlane(mine.label, src);
-    return c;
 }
 
 constexpr int kWalkChunk = 4;  // survivors fetched from LDS at a time

@@ -50,6 +50,29 @@ def test_long_chains(nms, oracle):
         check(nms, oracle, boxes[::-1].copy()[None], scores[::-1].copy()[None], 0.5)
 
 
+def test_walk_extremes(nms, oracle):
+    """What the mask-free walk's packing of the rows that are left can meet: nothing ever
+    eliminated (every stage repacks all rows), everything eliminated by the first box (nothing
+    left after the first stage), and exactly the better half surviving."""
+    rng = np.random.default_rng(79)
+    for n in (4096, 3000, 1100):
+        side = 64
+        gx, gy = np.meshgrid(np.arange(side), np.arange(side))
+        cells = np.stack([gx.ravel() * 40.0, gy.ravel() * 40.0], 1)[rng.permutation(side * side)[:n]]
+        disjoint = np.concatenate([cells, cells + 30.0], 1).astype(np.float32)
+        scores = rng.permutation(n).astype(np.float32) / n
+        want = check(nms, oracle, disjoint[None], scores[None], 0.5)
+        assert want.sum() == n
+        same = np.tile(np.array([[10, 10, 90, 70]], np.float32), (n, 1))
+        want = check(nms, oracle, same[None], scores[None], 0.5)
+        assert want.sum() == 1
+        half = disjoint.copy()
+        half[n // 2:] = half[:n - n // 2]            # each box of the second half repeats one of the first
+        scores2 = np.concatenate([1.0 + scores[:n // 2], scores[n // 2:] * 0.5]).astype(np.float32)
+        want = check(nms, oracle, half[None], scores2[None], 0.5)
+        assert want[0, :n // 2].all() and not want[0, n // 2:].any()
+
+
 def test_batched_ragged(nms, oracle):
     rng = np.random.default_rng(77)
     n_max, F = 500, 48

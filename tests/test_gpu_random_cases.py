@@ -27,7 +27,7 @@ def random_batch(rng, case):
         F, n_max = int(rng.integers(1, 4)), int(rng.integers(1500, 6000))
     elif shape == 1:    # many short frames
         F, n_max = int(rng.integers(20, 120)), int(rng.integers(1, 400))
-    elif shape == 2:    # enough boxes for the greedy rule's mask-free walk (frames * n_max >= 128 * 4096)
+    elif shape == 2:    # enough boxes for the greedy rule's mask-free walk (frames * n_max well above its threshold)
         n_max = int(rng.integers(600, 1400))
         F = (128 * 4096) // n_max + int(rng.integers(1, 20))
     else:               # around the tile and chunk borders

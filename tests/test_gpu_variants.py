@@ -128,7 +128,7 @@ def test_batched_ragged_with_labels(nms, oracle):
 
 
 def test_large_batch_greedy_takes_the_mask_free_walk(nms, oracle):
-    """frames * n_max >= 128 * 4096 under the greedy rule: one workgroup per frame, survivors only
+    """A batch large enough for the greedy rule's mask-free walk: one workgroup per frame, survivors only
     as outranking boxes.  Every measure / compare / ties / offset / labels combination, ragged
     counts, and thresholds that take the literal division."""
     from concurrent.futures import ThreadPoolExecutor
