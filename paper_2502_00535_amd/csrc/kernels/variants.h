@@ -41,13 +41,17 @@ gather_ranked_kernel(const int32_t *__restrict__ order, const float *__restrict_
 // rank-ordered scores and / or labels (ties ignored, labels given).
 // Work units and their mapping to workgroups are those of map_tile_kernel: one column tile
 // against kSuper victim tiles per wavefront, frames pinned to XCDs on batches.
-template <bool IOU, int MODE, bool AUX, int kSuper>
+// WRITE_MASK: store the tiles' words for a reduce step (the greedy sweep needs them).
+// Otherwise the row reduction of the paper's rule is folded in as in map_tile_kernel: keep_out
+// was preset to 1 by the rank step and every victim with an eliminator gets a 0.
+template <bool IOU, int MODE, bool AUX, int kSuper, bool WRITE_MASK>
 __global__ void __launch_bounds__(kMapWaves * 64)
 map_tile_ex_kernel(const float *__restrict__ sorted5, const float *__restrict__ ranked_score,
                    const int32_t *__restrict__ ranked_class, const float *__restrict__ ranked_area,
                    const int32_t *__restrict__ counts, int n_max, int n_pad,
                    int tiles, int tile_blocks, int frames, int xcd_frames, float theta, double boundary, float offset,
-                   int flags, unsigned long long *__restrict__ mask)
+                   int flags, unsigned long long *__restrict__ mask, const int32_t *__restrict__ order,
+                   uint8_t *__restrict__ keep_out)
 {
     const int lane = threadIdx.x & 63;
     int f, bx;
@@ -87,12 +91,15 @@ map_tile_ex_kernel(const float *__restrict__ sorted5, const float *__restrict__ 
     const int c_class = AUX ? class_f[c] : 0;
     const float c_T = (MODE == kExBoundary && !IOU) ? nms_pair_threshold(c_area, boundary) : 0.0f;
 
-    for (; tr < tr_end; ++tr) {
+    // one tile; DIAG: the tile on the diagonal, where only better-ranked boxes of the tile eliminate
+    auto tile = [&](auto on_diagonal) __attribute__((always_inline)) {
+        constexpr bool DIAG = decltype(on_diagonal)::value;
         const float4 *__restrict__ vb = box4 + tr * kTile;  // wave-uniform addresses: scalar loads
         const float *__restrict__ vs = score_f + tr * kTile;
         const int32_t *__restrict__ vc = class_f + tr * kTile;
         const float *__restrict__ va = area_f + tr * kTile;
         unsigned w_lo = 0, w_hi = 0;
+        unsigned lane_hit = 0;  // fused form: lane r = 1 when row r has an eliminator in this tile
         constexpr int kGroup = 8;
 #pragma unroll 1
         for (int grp = 0; grp < kTile / kGroup; ++grp) {
@@ -109,6 +116,7 @@ map_tile_ex_kernel(const float *__restrict__ sorted5, const float *__restrict__ 
                 v_class[k] = AUX ? vc[kGroup * grp + k] : 0;
             }
             unsigned long long words[kGroup];
+            unsigned grp_bits = 0;  // wave-uniform: bit k = row kGroup*grp+k has an eliminator
 #pragma unroll
             for (int k = 0; k < kGroup; ++k) {
                 const int r = kGroup * grp + k;
@@ -133,22 +141,35 @@ map_tile_ex_kernel(const float *__restrict__ sorted5, const float *__restrict__ 
                     hit = hit && (!labelled || c_class == v_class[k]);
                 }
                 unsigned long long word = __ballot(hit);
-                if (tr == tc) word &= (1ull << r) - 1ull;  // only better-ranked boxes eliminate
+                if (DIAG) word &= (1ull << r) - 1ull;
                 words[k] = word;
+                grp_bits |= (unsigned)((word | (0ull - word)) >> 63) << k;  // (word != 0) << k in scalar arithmetic
             }
+            if (WRITE_MASK) {
 #pragma unroll
-            for (int k = 0; k < kGroup; ++k) {
-                if (words[k] != 0) {  // wave-uniform
-                    asm volatile("" ::: "memory");  // keeps this a branch (otherwise the move is made for every row)
-                    const bool mine = (lane == kGroup * grp + k);
-                    w_lo = mine ? (unsigned)words[k] : w_lo;
-                    w_hi = mine ? (unsigned)(words[k] >> 32) : w_hi;
+                for (int k = 0; k < kGroup; ++k) {
+                    if (words[k] != 0) {  // wave-uniform
+                        asm volatile("" ::: "memory");  // keeps this a branch (otherwise the move is made for every row)
+                        const bool mine = (lane == kGroup * grp + k);
+                        w_lo = mine ? (unsigned)words[k] : w_lo;
+                        w_hi = mine ? (unsigned)(words[k] >> 32) : w_hi;
+                    }
                 }
+            } else {
+                lane_hit |= ((lane / kGroup) == grp) ? ((grp_bits >> (lane % kGroup)) & 1u) : 0u;
             }
         }
         const int row = tr * kTile + lane;
-        unsigned long long out = ((unsigned long long)w_hi << 32) | w_lo;
-        if (row >= n_f) out = 0;
-        mask[(size_t)f * ((size_t)(n_pad / kTile) * n_pad) + (size_t)tc * n_pad + row] = out;
+        if (WRITE_MASK) {
+            unsigned long long out = ((unsigned long long)w_hi << 32) | w_lo;
+            if (row >= n_f) out = 0;
+            mask[(size_t)f * ((size_t)(n_pad / kTile) * n_pad) + (size_t)tc * n_pad + row] = out;
+        } else {
+            if (lane_hit && row < n_f) keep_out[(size_t)f * n_max + order[(size_t)f * n_max + row]] = 0;
+        }
+    };
+    for (; tr < tr_end; ++tr) {
+        if (tr == tc) tile(std::true_type());
+        else tile(std::false_type());
     }
 }

@@ -525,7 +525,10 @@ int nms_run_ex_batched(const float *boxes, const float *scores, const int32_t *c
     float *ranked_area = reinterpret_cast<float *>(p);
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    st = rank_launch(boxes, scores, counts, n_max, frames, w.order, w.sorted5, w.keys, nullptr, nullptr, nullptr, s);
+    // under the paper's rule the row reduction is folded into the map kernel: keep_out starts at 1
+    const bool fold = opt.rule == NMS_RULE_PAPER;
+    st = rank_launch(boxes, scores, counts, n_max, frames, w.order, w.sorted5, w.keys, fold ? keep_out : nullptr, nullptr,
+                     nullptr, s);
     if (st != NMS_OK) return st;
     begin_launch();
     gather_ranked_kernel<<<dim3((n_pad + 255) / 256, frames), dim3(256), 0, s>>>(
@@ -581,14 +584,19 @@ int nms_run_ex_batched(const float *boxes, const float *scores, const int32_t *c
         return launch_status();
     }
     begin_launch();
-#define NMS_LAUNCH_EX_SUPER(IOU_, MODE_, AUX_, SUPER_)                                                            \
-    map_tile_ex_kernel<IOU_, MODE_, AUX_, SUPER_><<<grid, dim3(kMapWaves * 64), 0, s>>>(                          \
+#define NMS_LAUNCH_EX_SUPER(IOU_, MODE_, AUX_, SUPER_, MASK_)                                                     \
+    map_tile_ex_kernel<IOU_, MODE_, AUX_, SUPER_, MASK_><<<grid, dim3(kMapWaves * 64), 0, s>>>(                   \
         w.sorted5, ranked_score, ranked_class, ranked_area, counts, n_max, n_pad, tiles, tile_blocks, frames,     \
-        xcd_frames, threshold, boundary, opt.pixel_offset, flags, mask)
+        xcd_frames, threshold, boundary, opt.pixel_offset, flags, mask, w.order, keep_out)
 #define NMS_LAUNCH_EX(IOU_, MODE_, AUX_)                                                  \
     do {                                                                                  \
-        if (super4) NMS_LAUNCH_EX_SUPER(IOU_, MODE_, AUX_, 4);                            \
-        else NMS_LAUNCH_EX_SUPER(IOU_, MODE_, AUX_, 1);                                   \
+        if (fold) {                                                                       \
+            if (super4) NMS_LAUNCH_EX_SUPER(IOU_, MODE_, AUX_, 4, false);                 \
+            else NMS_LAUNCH_EX_SUPER(IOU_, MODE_, AUX_, 1, false);                        \
+        } else {                                                                          \
+            if (super4) NMS_LAUNCH_EX_SUPER(IOU_, MODE_, AUX_, 4, true);                  \
+            else NMS_LAUNCH_EX_SUPER(IOU_, MODE_, AUX_, 1, true);                         \
+        }                                                                                 \
     } while (0)
 #define NMS_LAUNCH_EX_MODE(IOU_, AUX_)                                                    \
     do {                                                                                  \
@@ -606,11 +614,9 @@ int nms_run_ex_batched(const float *boxes, const float *scores, const int32_t *c
 #undef NMS_LAUNCH_EX
     st = launch_status();
     if (st != NMS_OK) return st;
-    if (opt.rule == NMS_RULE_GREEDY)
-        return nms_reduce_greedy_batched(reinterpret_cast<const uint64_t *>(mask), w.order, counts, n_max, frames,
-                                         keep_out, stream);
-    return nms_reduce_batched(reinterpret_cast<const uint64_t *>(mask), w.order, counts, n_max, frames, keep_out,
-                              stream);
+    if (fold) return NMS_OK;
+    return nms_reduce_greedy_batched(reinterpret_cast<const uint64_t *>(mask), w.order, counts, n_max, frames,
+                                     keep_out, stream);
 }
 
 int nms_map_matrix(const float *boxes, const float *scores, int n, int capacity, float threshold,
