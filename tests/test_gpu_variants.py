@@ -48,16 +48,27 @@ class ExFrames:
         return self.keep.cpu().numpy()
 
 
-def oracle_ex(oracle, boxes, scores, classes, theta, opts, counts=None):
+def oracle_ex(oracle, boxes, scores, classes, theta, opts, counts=None, workers=1):
+    """oracle.keep_ex frame by frame (on host threads when workers > 1: the C call releases the GIL)."""
+    from concurrent.futures import ThreadPoolExecutor
+
     F, n_max = scores.shape
     out = np.zeros((F, n_max), np.uint8)
-    for f in range(F):
+
+    def one(f):
         n = n_max if counts is None else int(np.clip(counts[f], 0, n_max))
         if n:
             out[f, :n] = oracle.keep_ex(boxes[f, :n], scores[f, :n], np.float32(theta), rule=opts["rule"],
                                         measure=opts["measure"], compare=opts["compare"], ties=opts["ties"],
                                         pixel_offset=opts["pixel_offset"],
                                         classes=classes[f, :n] if opts["labelled"] else None)
+
+    if workers > 1:
+        with ThreadPoolExecutor(max_workers=workers) as pool:
+            list(pool.map(one, range(F)))
+    else:
+        for f in range(F):
+            one(f)
     return out
 
 
@@ -162,6 +173,31 @@ def test_large_batch_greedy_takes_the_mask_free_walk(nms, oracle):
     for theta, grid in ((0.4, greedy), (0.0, greedy[::5]), (1.5, greedy[1::7]), (0.5, greedy[::3])):
         for opts in grid:
             want = want_for(theta, opts)
+            got = dev.run(theta, opts)
+            assert np.array_equal(got, want), f"{opts} theta={theta}: {(got != want).sum()} differing keep bits"
+
+
+def test_walk_repacks_rows_under_every_option(nms, oracle):
+    """Long frames (up to 4096 boxes, 40 of them: the mask-free walk's route) so that the walk
+    repacks the rows that are left several times; scores, labels and areas of the repacked rows
+    are fetched again, which every measure / compare / ties / offset / labels combination under
+    the greedy rule has to survive.  Ragged counts around the repacking's borders."""
+    rng = np.random.default_rng(16)
+    n_max, F = 4096, 40
+    counts = rng.integers(1025, n_max + 1, F).astype(np.int32)
+    counts[:10] = [4096, 4095, 1025, 1088, 1089, 2048, 3000, 0, 64, 1024]
+    boxes = np.zeros((F, n_max, 4), np.float32)
+    scores = np.zeros((F, n_max), np.float32)
+    for f in range(F):
+        boxes[f], scores[f] = random_frame(5600 + f, n_max, extent=700 + 40 * f, max_side=140, integer=(f % 2 == 0),
+                                           score_levels=300)
+    classes = rng.integers(0, 3, (F, n_max)).astype(np.int32)
+    dev = ExFrames(nms, boxes, scores, classes, counts)
+    greedy = [o for o in GRID if o["rule"] == "greedy"]
+    for theta, grid in ((0.4, greedy), (0.0, greedy[::9]), (0.6, greedy[::4])):
+        for opts in grid:
+            print(f"case theta={theta} {opts}", flush=True)
+            want = oracle_ex(oracle, boxes, scores, classes, theta, opts, counts, workers=16)
             got = dev.run(theta, opts)
             assert np.array_equal(got, want), f"{opts} theta={theta}: {(got != want).sum()} differing keep bits"
 
