@@ -252,7 +252,9 @@ def main():
         ws_ex = torch.empty(nms.nms_ex_workspace_bytes(w.n, w.frames), dtype=torch.uint8, device=dev)
         keep_ex = torch.empty((w.frames, w.n), dtype=torch.uint8, device=dev)
         variants = {}
-        for label, kw in (("defaults", {}), ("iou_greedy_offset0", dict(rule="greedy", measure="iou", pixel_offset=0.0)),
+        # "defaults" is routed to nms_run_batched; "strict_compare" is the variants' kernel in its plainest form
+        for label, kw in (("defaults", {}), ("strict_compare", dict(compare="gt")),
+                          ("iou_greedy_offset0", dict(rule="greedy", measure="iou", pixel_offset=0.0)),
                           ("iou_paper_rule", dict(measure="iou"))):
             fn = lambda: nms.nms_run_ex_batched(d["boxes"], d["scores"], None, w.n, w.frames, w.theta, keep_ex, ws_ex, **kw)
             ms_v = time_steps(fn, steps3, 2)

@@ -199,7 +199,10 @@ int nms_run_greedy_fused_batched(const float *boxes, const float *scores, const 
  *            then x2 > x1 and y2 > y1 is an unchecked precondition).  Other values: NMS_ERR_INVALID_ARG.
  *   classes  NULL, or device int32 [frames][n_max]: only boxes with equal labels interact.
  * float32, one rounding per operation, in the order written above; the division is IEEE.
- * nms_run_ex_batched: rank, map into a mask (workspace), then the reduce of the chosen rule.
+ * nms_run_ex_batched: rank, then the map step with the options; the paper's rule has its row
+ * reduction folded into that kernel, the greedy rule takes the sweep on a mask (workspace) or,
+ * on large batches, the mask-free walk.  With every option at its default the call is
+ * nms_run_batched / nms_run_greedy_batched.
  *   options    HOST pointer, read before the call returns; NULL = all defaults
  *   workspace  >= nms_ex_workspace_bytes(n_max, frames) bytes, 256-byte aligned
  */

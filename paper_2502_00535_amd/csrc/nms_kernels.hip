@@ -471,8 +471,8 @@ int nms_run_greedy_batched(const float *boxes, const float *scores, const int32_
     if (!boxes || !scores || !keep_out) return NMS_ERR_INVALID_ARG;
     if (!workspace || ws_bytes < nms_greedy_workspace_bytes(n_max, frames) || ((uintptr_t)workspace & 255))
         return NMS_ERR_WORKSPACE;
-    // batches with a frame for (nearly) every compute unit: one workgroup walks each frame, no mask
-    // (measured crossover against rank + mask + sweep: 128 frames of 4096 boxes, 256 of 2048)
+    // batches with a few dozen frames or more: one workgroup walks each frame, no mask
+    // (measured crossover against rank + mask + sweep: 32 frames of 4096 boxes, 64 of 2048)
     if (n_max <= kChunk && (long long)frames * n_max >= kGreedyFusedBoxes)
         return run_greedy_fused(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace,
                                 static_cast<hipStream_t>(stream));
@@ -512,6 +512,13 @@ int nms_run_ex_batched(const float *boxes, const float *scores, const int32_t *c
     if (!boxes || !scores || !keep_out) return NMS_ERR_INVALID_ARG;
     if (!workspace || ws_bytes < nms_ex_workspace_bytes(n_max, frames) || ((uintptr_t)workspace & 255))
         return NMS_ERR_WORKSPACE;
+    // every option at its default: the default paths compute the same thing with fewer instructions
+    if (opt.measure == NMS_MEASURE_OUTRANKING_AREA && opt.compare == NMS_COMPARE_GE && opt.ties == NMS_TIES_BY_INDEX &&
+        opt.pixel_offset == 1.0f && opt.classes == nullptr) {
+        if (opt.rule == NMS_RULE_PAPER)
+            return nms_run_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, ws_bytes, stream);
+        return nms_run_greedy_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, ws_bytes, stream);
+    }
 
     const int n_pad = nms_padded_n(n_max);
     const RunWorkspace w = carve_workspace(workspace, n_max, frames);
