@@ -73,6 +73,21 @@ def test_walk_extremes(nms, oracle):
         assert want[0, :n // 2].all() and not want[0, n // 2:].any()
 
 
+def test_coordinates_beyond_the_scaled_form(nms, oracle):
+    """y coordinates above 8190 (and tiny ones) keep tiles out of the y-scaled form of the pair
+    test: the map step then mixes the scaled and the unscaled form tile by tile, and the greedy
+    reduce and the walk have to agree with it."""
+    n = 3000
+    boxes, scores = random_frame(7100, n, extent=30000, max_side=2500, integer=False, score_levels=400)
+    check(nms, oracle, boxes[None], scores[None], 0.3)
+    mixed = boxes.copy()
+    mixed[::7, [1, 3]] *= np.float32(2.0 ** -70)      # some boxes with tiny y extents
+    check(nms, oracle, mixed[None], scores[None], 0.3)
+    many = np.stack([boxes if f % 3 else boxes % np.float32(6000.0) for f in range(48)])
+    many[:, :, 2:] = np.maximum(many[:, :, 2:], many[:, :, :2])   # keep x2 >= x1, y2 >= y1 after the wrap
+    check(nms, oracle, many, np.tile(scores, (48, 1)), 0.3)
+
+
 def test_batched_ragged(nms, oracle):
     rng = np.random.default_rng(77)
     n_max, F = 500, 48
