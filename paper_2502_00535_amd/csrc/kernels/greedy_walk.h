@@ -7,17 +7,20 @@
 // wavefronts) per frame, no mask in memory.  Under this rule a box that is eliminated
 // neither eliminates others nor needs any further test, so only the SURVIVORS are ever used
 // as outranking boxes: about 600 of 4096 on frames like configuration 4, i.e. a seventh of
-// the pair grid.  Worth it when a batch has about as many frames as the chip has compute
-// units, since each frame is walked sequentially.
+// the pair grid.  A frame is one compute unit's work, so the route pays from a few dozen
+// frames on.
 //
 // The rows that are left (at first all of them) are numbered in rank order and cut into tiles
 // of 64; wavefront w owns the tiles w, w + 16, w + 32, w + 48 and keeps their boxes in
 // registers, lane = row, with one wave-uniform 64-bit word per tile for the rows that are out.
-// Round t settles tile t: its owner first applies the survivors of tile t-1 ("list t-1", in
-// LDS) to that tile alone, then visits the rows still alive in rank order -- each one visited
-// is a survivor, is broadcast from its lane (v_readlane) and eliminates the later rows of
-// the tile that it hits -- and writes list t; meanwhile the other wavefronts apply list t-1 to
-// all their tiles (the owner does so after settling).  One LDS-only barrier ends the round.
+// Round t settles tile t, whose rows its owner has put into LDS:
+//   - all wavefronts, a share each: the survivors of tile t-1 ("list t-1", in LDS) against the
+//     tile, and for each row of the tile the better-ranked rows of the tile itself that
+//     eliminate it (one 64-bit word per row); barrier;
+//   - the owner combines the shares and finds the tile's survivors as the fixed point of
+//     "alive, and not eliminated by a surviving better-ranked row of the tile", writes them
+//     to LDS as list t and marks them in keep_out; meanwhile every wavefront applies list t-1
+//     to all its other tiles; barrier.
 //
 // Most rows that die do so early (on configuration 4 more than half of the rows are out after
 // the first two tiles), and a tile costs the same with one row alive as with 64.  So the walk
@@ -155,7 +158,8 @@ greedy_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict
     load_tiles(false);
     __syncthreads();  // the zero fill is complete before any survivor's byte is written
 
-    // Survivor k of the list in buffer `buf`, the same one in every lane (a broadcast read).
+    // Entry k of buffer `buf` (a list's survivor, or a row of the tile being settled).  With a
+    // wave-uniform k every lane gets the same entry (a broadcast read); with k = lane, its own.
     auto entry = [&](int buf, int k) __attribute__((always_inline)) {
         FusedCandidate c;
         const float4 b = box_s[buf][k];
