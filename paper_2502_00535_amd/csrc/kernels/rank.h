@@ -51,7 +51,7 @@ __device__ __forceinline__ unsigned wave_inclusive_sum(unsigned x)
 // equal scores keep the lower index first (the tie rule) without the index taking part in
 // any compare.  Per pass:
 //   - every wavefront ranks its 256 elements among themselves: for q = 0..3 in turn, the
-//     lanes that hold the same digit find each other with eight ballots, take their place
+//     lanes that hold the same digit find each other (see below), take their place
 //     after the elements of earlier q with that digit (running per-wavefront histogram in
 //     LDS, touched by its own wavefront only) and the group's first lane bumps the histogram;
 //   - the histograms are turned into start offsets per (digit, wavefront): column sums,
@@ -60,7 +60,7 @@ __device__ __forceinline__ unsigned wave_inclusive_sum(unsigned x)
 // After the last pass `buf` holds ((key << 32) | index) in sorted order.
 __device__ __forceinline__ void radix_rank_chunk(unsigned (&key)[4], unsigned (&idx)[4], const int (&e)[4],
                                                  unsigned long long *buf, unsigned *hist, unsigned *tot,
-                                                 unsigned *dbase)
+                                                 unsigned *dbase, unsigned long long *match)
 {
     const int tid = threadIdx.x;
     const int nth = blockDim.x;
@@ -68,6 +68,13 @@ __device__ __forceinline__ void radix_rank_chunk(unsigned (&key)[4], unsigned (&
     const int wave = tid >> 6;
     const int W = nth >> 6;
     unsigned *myhist = hist + wave * 256;
+    // The lanes that hold the same digit find each other through a table of 256 lane masks per
+    // wavefront: every lane ORs its bit into the entry of its digit (an LDS atomic; OR does not
+    // care in which order) and reads the entry back.  The group's first lane clears the entry
+    // again, so the table is all zero between uses.  (A wavefront's LDS instructions execute in
+    // order, so no barrier is needed inside a wavefront.)
+    unsigned long long *mymatch = match + wave * 256;
+    for (int i = lane; i < 256; i += 64) mymatch[i] = 0ull;
 #pragma unroll 1
     for (int shift = 0; shift < 32; shift += 8) {
         for (int i = lane; i < 256; i += 64) myhist[i] = 0;
@@ -75,18 +82,16 @@ __device__ __forceinline__ void radix_rank_chunk(unsigned (&key)[4], unsigned (&
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const unsigned d = (key[q] >> shift) & 255u;
-            unsigned m_lo = ~0u, m_hi = ~0u;  // lanes whose digit equals mine
-#pragma unroll
-            for (int b = 0; b < 8; ++b) {
-                const unsigned all = 0u - ((d >> b) & 1u);  // all ones if my bit b is set
-                const unsigned long long set = __ballot(all != 0);
-                m_lo &= ~((unsigned)set ^ all);
-                m_hi &= ~((unsigned)(set >> 32) ^ all);
-            }
+            __hip_atomic_fetch_or(&mymatch[d], 1ull << lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+            const unsigned long long m = __hip_atomic_load(&mymatch[d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);  // lanes whose digit equals mine
+            const unsigned m_lo = (unsigned)m, m_hi = (unsigned)(m >> 32);
             const unsigned below = __builtin_amdgcn_mbcnt_hi(m_hi, __builtin_amdgcn_mbcnt_lo(m_lo, 0u));
             const unsigned total = __popc(m_lo) + __popc(m_hi);
             const unsigned base = myhist[d];
-            if (below == 0) myhist[d] = base + total;
+            if (below == 0) {
+                myhist[d] = base + total;
+                __hip_atomic_store(&mymatch[d], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+            }
             place[q] = base + below;
         }
         __syncthreads();
@@ -138,17 +143,22 @@ __device__ __forceinline__ void radix_rank_chunk(unsigned (&key)[4], unsigned (&
 // With a single chunk the kernel also writes order / sorted5 (and, for the fused path,
 // presets keep_out); with several chunks it leaves the chunk's sorted keys in `keys_ws`
 // for the merge kernel.
-__global__ void __launch_bounds__(1024)
+// STAGE (single chunk): the boxes are fetched in input order, coalesced, together with the
+// scores, wait in registers while the sort runs and change hands through LDS afterwards --
+// instead of a second, dependent round trip to memory for a gather by rank.
+template <int P, bool STAGE>
+__global__ void __launch_bounds__(P / 4)
 rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ scores,
                   const int32_t *__restrict__ counts, int n_max, int n_pad, int n_chunks,
                   int32_t *__restrict__ order, float *__restrict__ sorted5,
                   unsigned long long *__restrict__ keys_ws, uint8_t *__restrict__ keep_preset,
                   float4 *__restrict__ ysc, unsigned *__restrict__ ytile)
 {
-    __shared__ unsigned long long keys[kChunk];
-    __shared__ unsigned hist[(kChunk / 256) * 256];  // one row of 256 digit counts per wavefront
+    __shared__ unsigned long long keys[P];
+    __shared__ unsigned hist[(P / 256) * 256];  // one row of 256 digit counts per wavefront
     __shared__ unsigned tot[256];
     __shared__ unsigned dbase[256];
+    __shared__ float4 stage[STAGE ? P : P / 2];  // during the sort: the wavefronts' digit-match tables (P / 256 x 256 x 8 bytes)
     const int f = blockIdx.y;
     const int chunk = blockIdx.x;
     const int tid = threadIdx.x;
@@ -159,12 +169,15 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
     int cnt = n_f - base;
     cnt = cnt < 0 ? 0 : (cnt > kChunk ? kChunk : cnt);
     const float *scores_f = scores + (size_t)f * n_max;
+    const float *boxes_f = boxes + (size_t)f * n_max * 4;
     int e[4];
     unsigned long long K[4];
+    float4 mine[4];  // STAGE: box e[q] of the input
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         e[q] = (tid >> 6) * 256 + q * 64 + lane;
         K[q] = (e[q] < cnt) ? rank_key(scores_f[base + e[q]], (unsigned)(base + e[q])) : kSentinel;
+        if (STAGE) mine[q] = (e[q] < cnt) ? reinterpret_cast<const float4 *>(boxes_f)[e[q]] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
 
     unsigned key32[4], index[4];
@@ -173,24 +186,25 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
         key32[q] = (unsigned)(K[q] >> 32);
         index[q] = (unsigned)K[q];
     }
-    radix_rank_chunk(key32, index, e, keys, hist, tot, dbase);  // ends with a barrier; keys[] is sorted
+    radix_rank_chunk(key32, index, e, keys, hist, tot, dbase, reinterpret_cast<unsigned long long *>(stage));  // ends with a barrier; keys[] is sorted
 
-    const float *boxes_f = boxes + (size_t)f * n_max * 4;
     int32_t *order_f = order + (size_t)f * n_max;
     float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
     float4 *ysc_f = ysc ? ysc + (size_t)f * n_pad : nullptr;
     unsigned *ytile_f = ytile ? ytile + (size_t)f * (n_pad / kTile) : nullptr;
-    if (n_chunks == 1) {
+    if (STAGE) {
         // n_pad <= 4 * nth: at most four ranks per thread, r = tid + q * nth (a wavefront covers 64
-        // consecutive ranks = one tile per q).  The four gathers are issued before anything is
-        // stored, so the thread waits for memory once, not once per rank.
+        // consecutive ranks = one tile per q).
+#pragma unroll
+        for (int q = 0; q < 4; ++q) stage[e[q]] = mine[q];
+        __syncthreads();
         float4 b[4];
         int idx[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int r = tid + q * nth;
             idx[q] = r < n_f ? (int)(unsigned)keys[r] : -1;
-            b[q] = idx[q] >= 0 ? reinterpret_cast<const float4 *>(boxes_f)[idx[q]] : make_float4(0.f, 0.f, 0.f, 0.f);
+            b[q] = stage[idx[q] >= 0 ? idx[q] : 0];
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {

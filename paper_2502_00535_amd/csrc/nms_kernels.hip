@@ -99,8 +99,16 @@ int rank_launch(const float *boxes, const float *scores, const int32_t *counts, 
     while (threads < 1024 && threads * 4 < widest) threads <<= 1;
     auto *keys_ws = static_cast<unsigned long long *>(workspace);
     begin_launch();
-    rank_chunk_kernel<<<dim3(n_chunks, frames), dim3(threads), 0, stream>>>(
-        boxes, scores, counts, n_max, n_pad, n_chunks, order, sorted5, keys_ws, keep_preset, ysc, ytile);
+#define NMS_LAUNCH_RANK(P_, STAGE_)                                                                    \
+    rank_chunk_kernel<P_, STAGE_><<<dim3(n_chunks, frames), dim3(P_ / 4), 0, stream>>>(                \
+        boxes, scores, counts, n_max, n_pad, n_chunks, order, sorted5, keys_ws, keep_preset, ysc, ytile)
+    if (n_chunks > 1) NMS_LAUNCH_RANK(4096, false);
+    else if (threads == 64) NMS_LAUNCH_RANK(256, true);
+    else if (threads == 128) NMS_LAUNCH_RANK(512, true);
+    else if (threads == 256) NMS_LAUNCH_RANK(1024, true);
+    else if (threads == 512) NMS_LAUNCH_RANK(2048, true);
+    else NMS_LAUNCH_RANK(4096, true);
+#undef NMS_LAUNCH_RANK
     int st = launch_status();
     if (st != NMS_OK || n_chunks == 1) return st;
     begin_launch();
