@@ -364,6 +364,30 @@ def main():
                                "sync_call_us_median": round(lat_t[len(lat_t) // 2], 2)}
         extra["single_frame_at_the_papers_detection_counts"] = sizes
 
+        # -------------------------------------------------------------- single frames replayed from a HIP graph
+        # (the calls only enqueue kernels, so a caller can take the per-call launch cost out: 100 calls
+        # of nms_run_batched on one frame captured once, then replayed)
+        graphed = {}
+        for idx in (0, 1):
+            wg = make_config(idx)
+            dg = upload(wg)
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            graph = torch.cuda.CUDAGraph()
+            calls = 100
+            with torch.cuda.stream(side):
+                plan_g = nms.RunPlan(dg["boxes"], dg["scores"], None, wg.n, wg.frames, wg.theta, dg["keep"], dg["ws"])
+                plan_g()
+                side.synchronize()
+                with torch.cuda.graph(graph, stream=side):
+                    for _ in range(calls):
+                        plan_g()
+            torch.cuda.synchronize()
+            us = time_steps(graph.replay, 20, 3) * 1e3 / calls
+            graphed[wg.name] = {"us_per_frame": round(us, 3), "calls_per_graph": calls}
+            del dg
+        extra["single_frame_calls_replayed_from_a_hip_graph"] = graphed
+
     if args.calibrate_copy:
         src = torch.empty(64 << 20, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
