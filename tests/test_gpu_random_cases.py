@@ -50,7 +50,7 @@ def random_batch(rng, case):
     return boxes, scores, counts, theta
 
 
-@pytest.mark.parametrize("case", range(16))
+@pytest.mark.parametrize("case", range(32))
 def test_default_rule_and_greedy_rule(nms, oracle, case):
     rng = np.random.default_rng(9000 + case)
     boxes, scores, counts, theta = random_batch(rng, case)
@@ -65,7 +65,7 @@ def test_default_rule_and_greedy_rule(nms, oracle, case):
     assert np.array_equal(via_steps, want_g) and np.array_equal(one_call, want_g)
 
 
-@pytest.mark.parametrize("case", range(12))
+@pytest.mark.parametrize("case", range(24))
 def test_variants(nms, oracle, case):
     rng = np.random.default_rng(9500 + case)
     boxes, scores, counts, theta = random_batch(rng, case)
