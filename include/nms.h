@@ -62,13 +62,17 @@ extern "C" {
 #define NMS_TILE 64              /* boxes per tile = wavefront width */
 #define NMS_MAX_N 65536          /* largest n (and n_max) accepted */
 #define NMS_MAX_FRAMES 65535     /* largest batch accepted */
+#define NMS_MAX_MAP_WORKGROUPS 16777215  /* frames (rounded up to 8) x ceil(work units of a frame / 4) must not exceed this:
+                                            the pair-test step of a batch is one launch.  A frame of n boxes has about
+                                            (n/64)^2 / 8 work units; the limit only binds above some 5,600 boxes per frame
+                                            (about 8,000 frames of 16,384 boxes, 500 of 65,536) */
 #define NMS_SORT_CHUNK 4096      /* boxes ranked by one workgroup in LDS */
 #define NMS_MAX_MATRIX 16384     /* largest capacity of the byte-matrix form (256 MiB of B) */
 
 typedef enum {
     NMS_OK = 0,
     NMS_ERR_INVALID_ARG = -1,   /* null pointer, negative size, NaN threshold */
-    NMS_ERR_TOO_LARGE = -2,     /* n > NMS_MAX_N or frames > NMS_MAX_FRAMES */
+    NMS_ERR_TOO_LARGE = -2,     /* n > NMS_MAX_N, frames > NMS_MAX_FRAMES, or the batch exceeds NMS_MAX_MAP_WORKGROUPS */
     NMS_ERR_WORKSPACE = -3,     /* workspace missing, misaligned or too small; nms_run without nms_init */
     NMS_ERR_LAUNCH = -4         /* the HIP runtime refused a launch */
 } nms_status;

@@ -63,6 +63,12 @@ inline bool sizes_ok(int n_max, int frames, int *status)
 {
     if (n_max < 0 || frames < 0) { *status = NMS_ERR_INVALID_ARG; return false; }
     if (n_max > NMS_MAX_N || frames > NMS_MAX_FRAMES) { *status = NMS_ERR_TOO_LARGE; return false; }
+    // the map step is one launch of 256-thread workgroups, and a launch holds fewer than 2^32 threads
+    const int T = nms_padded_n(n_max) / kTile;
+    const bool super4 = (long long)frames * triangle_units(T, 4) >= 16384;
+    const long long tile_blocks = (triangle_units(T, super4 ? 4 : 1) + kMapWaves - 1) / kMapWaves;
+    const long long blocks = frames >= 8 ? (long long)((frames + 7) / 8) * 8 * tile_blocks : tile_blocks;
+    if (blocks > NMS_MAX_MAP_WORKGROUPS) { *status = NMS_ERR_TOO_LARGE; return false; }
     return true;
 }
 

@@ -111,6 +111,24 @@ def test_argument_errors_before_launch(nms):
     assert L.nms_run_batched(null, null, null, 64, 0, 0.5, null, null, 0, null) == nms.NMS_OK
 
 
+def test_batches_beyond_one_map_launch_are_refused(nms):
+    """The pair-test step of a batch is a single launch of 256-thread workgroups; a batch whose
+    launch would not fit the grid is refused up front (before anything is enqueued), and its
+    workspace size is reported as 0 like that of any other invalid size."""
+    L = nms.lib
+    p = ctypes.c_void_p(0x1000)
+    null = None
+    big = 1 << 62
+    assert L.nms_workspace_bytes(16384, 8064) > 0
+    assert L.nms_workspace_bytes(16384, 8072) == 0
+    assert L.nms_run_batched(p, p, null, 16384, 8072, 0.5, p, p, big, null) == nms.NMS_ERR_TOO_LARGE
+    assert L.nms_overlap_mask_batched(p, null, 16384, 8072, 0.5, p, null) == nms.NMS_ERR_TOO_LARGE
+    assert L.nms_run_greedy_batched(p, p, null, 65536, 512, 0.5, p, p, big, null) == nms.NMS_ERR_TOO_LARGE
+    assert L.nms_workspace_bytes(65536, 504) > 0
+    # frames of at most 4096 boxes are never affected
+    assert L.nms_workspace_bytes(4096, 65535) > 0
+
+
 def test_matrix_form_argument_errors(nms):
     L = nms.lib
     p = ctypes.c_void_p(0x1000)
