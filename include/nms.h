@@ -229,6 +229,19 @@ int nms_run_ex_batched(const float *boxes, const float *scores, const int32_t *c
                        void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * The paper's rule with work skipped that cannot change the result (section "Algorithm
+ * Correctness": V_i is the AND over all j, so it is settled by the first j that eliminates i):
+ * a victim that has met an eliminator is dropped from all further tests, while it goes on
+ * eliminating others.  Same keep vector as nms_run_batched, bit for bit, from a fraction of the
+ * pair tests on clustered detections; one workgroup per frame, so it pays on batches of about
+ * as many frames as the chip has compute units or more.  n_max <= NMS_SORT_CHUNK (else
+ * NMS_ERR_TOO_LARGE); workspace >= nms_workspace_bytes(n_max, frames), 256-byte aligned.
+ * Arguments, layout, ownership and errors as nms_run_batched.
+ */
+int nms_run_early_exit_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                               float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * The paper's own data layout, for measuring its form on this hardware: the boolean
  * matrix B as capacity x capacity BYTES over the UNSORTED input (Algorithm 1, one
  * matrix element per ordered pair, the score guard evaluated per pair), and

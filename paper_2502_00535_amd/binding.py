@@ -24,7 +24,7 @@ EXPORTS = (
     "nms_sort", "nms_sort_batched", "nms_overlap_mask", "nms_overlap_mask_batched",
     "nms_reduce", "nms_reduce_batched", "nms_run_ws", "nms_run_batched", "nms_run_ranked_batched", "nms_run_direct_batched",
     "nms_run_batched_profiled", "nms_reduce_greedy", "nms_reduce_greedy_batched",
-    "nms_greedy_workspace_bytes", "nms_run_greedy_batched", "nms_run_greedy_fused_batched", "nms_map_matrix", "nms_reduce_matrix",
+    "nms_greedy_workspace_bytes", "nms_run_greedy_batched", "nms_run_greedy_fused_batched", "nms_run_early_exit_batched", "nms_map_matrix", "nms_reduce_matrix",
     "nms_ex_workspace_bytes", "nms_run_ex_batched",
     "nms_init", "nms_shutdown", "nms_run", "nms_host_pair_test",
 )
@@ -110,6 +110,8 @@ def _load() -> ctypes.CDLL:
     L.nms_run_greedy_batched.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp, sz, vp]
     L.nms_run_greedy_fused_batched.restype = i32
     L.nms_run_greedy_fused_batched.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp, sz, vp]
+    L.nms_run_early_exit_batched.restype = i32
+    L.nms_run_early_exit_batched.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp, sz, vp]
     L.nms_run_batched_profiled.restype = i32
     L.nms_run_batched_profiled.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp, sz, vp, ctypes.POINTER(vp)]
     L.nms_map_matrix.restype = i32
@@ -327,6 +329,14 @@ def nms_run_greedy_batched(boxes, scores, counts, n_max, frames, threshold, keep
                                       _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
                                       _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream)),
            "nms_run_greedy_batched")
+
+
+def nms_run_early_exit_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib.nms_run_early_exit_batched(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
+                                          _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
+                                          _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream)),
+           "nms_run_early_exit_batched")
 
 
 def nms_run_greedy_fused_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, stream=None):

@@ -45,6 +45,7 @@ __device__ __forceinline__ int frame_count(const int32_t *counts, int f, int n_m
 #include "kernels/greedy_sweep.h"
 #include "kernels/greedy_walk.h"
 #include "kernels/variants.h"
+#include "kernels/early_exit.h"
 #include "kernels/matrix_form.h"
 
 // ----------------------------------------------------------------------------- host side
@@ -457,6 +458,33 @@ static int run_greedy_fused(const float *boxes, const float *scores, const int32
     else
         greedy_fused_kernel<false, false, kExDivideGe, false><<<dim3(frames), dim3(kFusedWaves * 64), 0, s>>>(
             w.sorted5, w.order, counts, n_max, n_pad, th, none, keep_out);
+    return launch_status();
+}
+
+int nms_run_early_exit_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                               float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream)
+{
+    int st;
+    if (!sizes_ok(n_max, frames, &st)) return st;
+    if (n_max > kChunk) return NMS_ERR_TOO_LARGE;
+    if (is_nan(threshold)) return NMS_ERR_INVALID_ARG;
+    if (n_max == 0 || frames == 0) return NMS_OK;
+    if (!boxes || !scores || !keep_out) return NMS_ERR_INVALID_ARG;
+    if (!workspace || ws_bytes < nms_workspace_bytes(n_max, frames) || ((uintptr_t)workspace & 255))
+        return NMS_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const RunWorkspace w = carve_workspace(workspace, n_max, frames);
+    st = rank_launch(boxes, scores, counts, n_max, frames, w.order, w.sorted5, w.keys, nullptr, nullptr, nullptr, s);
+    if (st != NMS_OK) return st;
+    const NmsThetaConst th = nms_make_theta_const(threshold);
+    const int n_pad = nms_padded_n(n_max);
+    begin_launch();
+    if (th.fast)
+        early_exit_kernel<true><<<dim3(frames), dim3(kEarlyWaves * 64), 0, s>>>(w.sorted5, w.order, counts, n_max, n_pad, th,
+                                                                                  keep_out);
+    else
+        early_exit_kernel<false><<<dim3(frames), dim3(kEarlyWaves * 64), 0, s>>>(w.sorted5, w.order, counts, n_max, n_pad, th,
+                                                                                   keep_out);
     return launch_status();
 }
 

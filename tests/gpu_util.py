@@ -57,8 +57,8 @@ class DeviceFrames:
         return self.keep.cpu().numpy()
 
     def fused(self, theta, want=None):
-        """nms_run_batched (automatic route).  With `want`, the ranked and the direct route
-        are run as well and all three must equal it bit for bit."""
+        """nms_run_batched (automatic route).  With `want`, the ranked, the direct and the
+        early-exit route are run as well and all must equal it bit for bit."""
         self.keep.fill_(77)
         self.nms.nms_run_batched(self.boxes, self.scores, self.counts, self.n_max, self.F, theta, self.keep, self.run_ws)
         self.torch.cuda.synchronize()
@@ -76,6 +76,14 @@ class DeviceFrames:
                 self.torch.cuda.synchronize()
                 direct = self.keep.cpu().numpy()
                 assert np.array_equal(direct, want), f"direct route: {(direct != want).sum()} differing keep bits"
+            if 0 < self.n_max <= 4096:
+                # the same rule with eliminated victims dropped from further tests (one workgroup per frame)
+                self.keep.fill_(77)
+                self.nms.nms_run_early_exit_batched(self.boxes, self.scores, self.counts, self.n_max, self.F, theta, self.keep,
+                                                    self.run_ws)
+                self.torch.cuda.synchronize()
+                early = self.keep.cpu().numpy()
+                assert np.array_equal(early, want), f"early-exit route: {(early != want).sum()} differing keep bits"
         return got
 
     def greedy(self, theta):

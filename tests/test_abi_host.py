@@ -184,6 +184,22 @@ def test_options_argument_errors(nms):
     assert nms.nms_ex_workspace_bytes(-1, 2) == 0
 
 
+def test_early_exit_argument_errors(nms):
+    L = nms.lib
+    p = ctypes.c_void_p(0x1000)
+    big = 1 << 30
+    assert L.nms_run_early_exit_batched(p, p, None, 4097, 2, 0.5, p, p, big, None) == nms.NMS_ERR_TOO_LARGE
+    assert L.nms_run_early_exit_batched(p, p, None, -1, 2, 0.5, p, p, big, None) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_run_early_exit_batched(p, p, None, 64, 2, float("nan"), p, p, big, None) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_run_early_exit_batched(None, p, None, 64, 2, 0.5, p, p, big, None) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_run_early_exit_batched(p, None, None, 64, 2, 0.5, p, p, big, None) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_run_early_exit_batched(p, p, None, 64, 2, 0.5, None, p, big, None) == nms.NMS_ERR_INVALID_ARG
+    assert L.nms_run_early_exit_batched(p, p, None, 64, 2, 0.5, p, None, 0, None) == nms.NMS_ERR_WORKSPACE
+    assert L.nms_run_early_exit_batched(p, p, None, 64, 2, 0.5, p, p, 100, None) == nms.NMS_ERR_WORKSPACE
+    assert L.nms_run_early_exit_batched(p, p, None, 64, 2, 0.5, p, ctypes.c_void_p(0x1010), big, None) == nms.NMS_ERR_WORKSPACE
+    assert L.nms_run_early_exit_batched(None, None, None, 0, 2, 0.5, None, None, 0, None) == nms.NMS_OK
+
+
 def test_greedy_fused_argument_errors(nms):
     L = nms.lib
     p = ctypes.c_void_p(0x1000)
