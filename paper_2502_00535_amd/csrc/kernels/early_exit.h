@@ -13,9 +13,10 @@
 //   * the victims still undecided are a LIST in LDS, in rank order (an entry is the byte offset
 //     of the victim's box in the staged table);
 //   * the outranking boxes ("candidates") are taken in stages [0,128), [128,256), [256,512) ...:
-//     a stage's work is cut into items of (two candidate tiles = 128 boxes, one in each lane of
-//     two register sets) x (32 consecutive list entries, read from LDS as broadcasts), dealt
-//     round-robin to the wavefronts, so every wavefront has work in every stage however few
+//     a stage's work is cut into items of (four candidate tiles, a box in each lane of as many
+//     register sets) x (16 consecutive list entries, read from LDS as broadcasts, so a victim is
+//     fetched once for 256 pair tests) -- two tiles x 32 entries in the first, narrow stages --, handed out
+//     to the wavefronts through a counter, so every wavefront has work in every stage however few
 //     victims are left; the compare's lane mask != 0 is "this victim has an eliminator";
 //   * after a stage the victims ranked before its end that are still alive are survivors, the
 //     other alive ones are packed to the front of the list, and a table start[t] = number of
@@ -30,8 +31,8 @@
 constexpr int kEarlyWaves = 16;
 constexpr int kEarlyThreads = kEarlyWaves * 64;
 constexpr int kEarlyFirstStage = 128;                 // candidates of the first stage; each further stage doubles the bound
-constexpr int kEarlyItemVictims = 32;                 // list entries of a work item (eight reads of four entries)
-constexpr int kEarlyGroup = 2 * kTile;                // candidates of a work item: two tiles
+constexpr int kEarlyItemVictims = 32;                 // most list entries of a work item
+constexpr int kEarlyItemPairs = 2 * kEarlyItemVictims; // a work item is 64 x this many pair tests: K tiles x 128 / K entries
 constexpr int kEarlyTiles = NMS_SORT_CHUNK / kTile;   // 64
 
 struct EarlyShared {
@@ -41,6 +42,7 @@ struct EarlyShared {
     uint8_t dead[NMS_SORT_CHUNK];                  // by list position: an eliminator was found in this stage
     int start[kEarlyTiles + 1];                    // start[t] = list entries ranked before 64 t
     int count[4 * kEarlyWaves];                    // packing: entries that go on, per 64 list positions
+    int next_item;                                 // the stage's next work item that no wavefront has taken
     int irregular;                                 // some y coordinate rules out the y-scaled form
 };
 
@@ -52,43 +54,126 @@ __device__ __forceinline__ bool early_hit(const float4 v, const float4 cb, float
     return nms_eliminates_exact(v.x, v.y, v.z, v.w, cb.x, cb.y, cb.z, cb.w, aux, theta);
 }
 
-// Lanes 0 .. d-1 (the candidates of a tile that outrank a victim d ranks past the tile's first).
-__device__ __forceinline__ unsigned long long early_below(int d)
+// One work item: the list entries [V jb, V jb + V), V = 128 / K, against the K candidate tiles held in
+// cb[], aux[].  DIAG: some of the victims are ranked within or before the group, or some of the
+// group's tiles do not exist (only the first `tiles` do), so a lane counts only when its
+// candidate outranks the victim: its entry value (at0 + 1024 i for tile i) is below the victim's.
+template <int PAIR, bool DIAG, int K>
+__device__ __forceinline__ void early_item(EarlyShared &sh, int jb, int m, const float4 (&cb)[K], const float (&aux)[K],
+                                           int at0, int tiles, float theta, float y_one, int lane)
 {
-    return d <= 0 ? 0ull : (d >= 64 ? ~0ull : (1ull << d) - 1ull);
-}
-
-// One work item: the list entries [32 jb, 32 jb + 32) against the candidates c_lo .. c_lo+127
-// held in (cb0, aux0), (cb1, aux1).  DIAG: some of the victims are ranked within or before the
-// group, so each compare mask is cut down to the candidates that outrank the victim (and to
-// nothing for a second tile that does not exist).
-template <int PAIR, bool DIAG>
-__device__ __forceinline__ void early_item(EarlyShared &sh, int jb, int m, int c_lo, bool second, const float4 cb0,
-                                           float aux0, const float4 cb1, float aux1, float theta, float y_one, int lane)
-{
-    const int4 *entries = reinterpret_cast<const int4 *>(sh.list + kEarlyItemVictims * jb);
-    int4 e[kEarlyItemVictims / 4];
+    constexpr int V = kEarlyItemPairs / K;
+    const int4 *entries = reinterpret_cast<const int4 *>(sh.list + V * jb);
+    constexpr int kReads = V / 4;
+    unsigned word = 0;  // wave-uniform: bit k = entry V jb + k has an eliminator
+    // Every lane reads the same address: broadcasts.  Entries are read two steps ahead and the
+    // four victims of step c+1 are fetched before those of step c are tested (the scheduling
+    // barriers keep the compiler from sinking the reads to their first use, where every one of
+    // them would be waited for in full).
+    int4 e[3];
+    e[0] = entries[0];
+    e[1] = entries[1];
+    float4 v[2][4];
+    auto fetch = [&](float4 (&dst)[4], const int4 &ent) __attribute__((always_inline)) {
+        const char *base = reinterpret_cast<const char *>(sh.box);
+        dst[0] = *reinterpret_cast<const float4 *>(base + ent.x);
+        dst[1] = *reinterpret_cast<const float4 *>(base + ent.y);
+        dst[2] = *reinterpret_cast<const float4 *>(base + ent.z);
+        dst[3] = *reinterpret_cast<const float4 *>(base + ent.w);
+    };
+    fetch(v[0], e[0]);
 #pragma unroll
-    for (int c = 0; c < kEarlyItemVictims / 4; ++c) e[c] = entries[c];  // same address in every lane: broadcasts
-    unsigned word = 0;  // wave-uniform: bit k = entry 32 jb + k has an eliminator
-#pragma unroll
-    for (int c = 0; c < kEarlyItemVictims / 4; ++c) {
-        const int off[4] = {e[c].x, e[c].y, e[c].z, e[c].w};
+    for (int c = 0; c < kReads; ++c) {
+        if (c + 2 < kReads) e[(c + 2) % 3] = entries[c + 2];
+        if (c + 1 < kReads) fetch(v[(c + 1) & 1], e[(c + 1) % 3]);
+        __builtin_amdgcn_sched_barrier(0);
+        const int off[4] = {e[c % 3].x, e[c % 3].y, e[c % 3].z, e[c % 3].w};
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const float4 v = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(sh.box) + off[u]);
-            unsigned long long h0 = __ballot(early_hit<PAIR>(v, cb0, aux0, theta, y_one));
-            unsigned long long h1 = __ballot(early_hit<PAIR>(v, cb1, aux1, theta, y_one));
-            if (DIAG) {
-                const int r = __builtin_amdgcn_readfirstlane(off[u]) >> 4;
-                h0 &= early_below(r - c_lo);
-                h1 &= second ? early_below(r - c_lo - kTile) : 0ull;
+            unsigned long long any = 0ull;
+            float4 vu = v[c & 1][u];
+            // ties this victim's arithmetic to its place between the scheduling barriers (on its own
+            // it has no order with respect to them, and instruction selection emits it far ahead)
+            asm volatile("" : "+v"(vu.x), "+v"(vu.y), "+v"(vu.z), "+v"(vu.w));
+#pragma unroll
+            for (int i = 0; i < K; ++i) {
+                unsigned long long h = __ballot(early_hit<PAIR>(vu, cb[i], aux[i], theta, y_one));
+                if (DIAG) {
+                    h &= __ballot(at0 < off[u] - 16 * kTile * i);
+                    h = i < tiles ? h : 0ull;
+                }
+                any |= h;
             }
-            word |= ((h0 | h1) != 0ull ? 1u : 0u) << (4 * c + u);
+            // word |= (any != 0) << (4 c + u), written out so that it too stays here and the lane
+            // masks are used up at once (left to itself the compiler keeps all of them for later)
+            unsigned bit;
+            asm volatile("s_cmp_lg_u64 %[any], 0\n\t"
+                         "s_cselect_b32 %[bit], %[k], 0\n\t"
+                         "s_or_b32 %[word], %[word], %[bit]"
+                         : [word] "+s"(word), [bit] "=&s"(bit)
+                         : [any] "s"(any), [k] "n"(1u << (4 * c + u))
+                         : "scc");
+            __builtin_amdgcn_sched_barrier(0);  // one victim at a time: mixing their chains only costs registers
         }
     }
-    const int pos = kEarlyItemVictims * jb + lane;
-    if (lane < kEarlyItemVictims && ((word >> lane) & 1u) != 0u && pos < m) sh.dead[pos] = 1;
+    const int pos = V * jb + lane;
+    if (lane < V && ((word >> lane) & 1u) != 0u && pos < m) sh.dead[pos] = 1;
+}
+
+// The work items of one stage (candidates [lo, hi), list of m entries) in groups of K tiles.
+template <int PAIR, int K>
+__device__ __forceinline__ void early_stage_items(EarlyShared &sh, int lo, int hi, int m, float theta, float y_one,
+                                                  int lane, int wave)
+{
+    constexpr int V = kEarlyItemPairs / K;
+    const int groups = ((hi - lo) / kTile + K - 1) / K;  // <= 32
+
+    // lane = candidate group: where its victims begin, where those begin that all its lanes outrank, its items
+    int p0 = 0, p1 = 0, items = 0;
+    if (lane < groups) {
+        const int t0 = lo / kTile + K * lane;
+        p0 = sh.start[t0];
+        p1 = sh.start[t0 + K < kEarlyTiles ? t0 + K : kEarlyTiles];
+        items = (m + V - 1) / V - p0 / V;
+        items = p0 >= m ? 0 : items;
+    }
+    const int incl = (int)wave_inclusive_sum((unsigned)items);
+    const int total = __builtin_amdgcn_readlane(incl, 63);
+    int g_held = -1;
+    float4 cb[K];
+    float aux[K];
+    int at0 = 0;
+#pragma unroll
+    for (int i = 0; i < K; ++i) {
+        cb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        aux[i] = 0.f;
+    }
+    // items are handed out through a counter (the first one of each wavefront is its own number):
+    // an item that straddles the group costs more than one past it, and counts rarely divide evenly
+    for (int it = wave; it < total;) {
+        int next = 0;
+        if (lane == 0) next = __hip_atomic_fetch_add(&sh.next_item, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        const int g = __builtin_amdgcn_readfirstlane(__builtin_popcountll(__ballot(incl <= it)));
+        const int jb = __builtin_amdgcn_readlane(p0, g) / V + (it - __builtin_amdgcn_readlane(incl - items, g));
+        const int p1_g = __builtin_amdgcn_readlane(p1, g);
+        const int c_lo = lo + K * kTile * g;
+        const int tiles = (hi - c_lo) / kTile < K ? (hi - c_lo) / kTile : K;  // of the group that exist
+        if (g != g_held) {
+#pragma unroll
+            for (int i = 0; i < K; ++i) {
+                const int c = i < tiles ? c_lo + kTile * i + lane : lane;
+                cb[i] = sh.box[c];
+                aux[i] = sh.aux[c];
+            }
+            at0 = 16 * (c_lo + lane);
+            g_held = g;
+        }
+        if (V * jb < p1_g || tiles < K)
+            early_item<PAIR, true, K>(sh, jb, m, cb, aux, at0, tiles, theta, y_one, lane);
+        else
+            early_item<PAIR, false, K>(sh, jb, m, cb, aux, at0, tiles, theta, y_one, lane);
+        it = __builtin_amdgcn_readfirstlane(next);
+    }
 }
 
 // The stages of one frame; the table is staged, sh.list / sh.dead / sh.start describe the
@@ -106,41 +191,10 @@ __device__ __forceinline__ void early_exit_frame(EarlyShared &sh, int n_f, float
     for (int bound = kEarlyFirstStage;; bound *= 2) {
         const int hi = bound < staged ? bound : staged;
         const bool last = hi >= n_f;
-        const int groups = ((hi - lo) / kTile + 1) / 2;  // <= 32
-
-        // lane = candidate group: where its victims begin, where those begin that all its lanes outrank, its items
-        int p0 = 0, p1 = 0, items = 0;
-        if (lane < groups) {
-            const int t0 = lo / kTile + 2 * lane;
-            p0 = sh.start[t0];
-            p1 = sh.start[t0 + 2 < kEarlyTiles ? t0 + 2 : kEarlyTiles];
-            items = (m + kEarlyItemVictims - 1) / kEarlyItemVictims - p0 / kEarlyItemVictims;
-            items = p0 >= m ? 0 : items;
-        }
-        const int incl = (int)wave_inclusive_sum((unsigned)items);
-        const int total = __builtin_amdgcn_readlane(incl, 63);
-        int g_held = -1;
-        float4 cb0 = make_float4(0.f, 0.f, 0.f, 0.f), cb1 = cb0;
-        float aux0 = 0.f, aux1 = 0.f;
-        for (int it = wave; it < total; it += kEarlyWaves) {
-            const int g = __builtin_amdgcn_readfirstlane(__builtin_popcountll(__ballot(incl <= it)));
-            const int jb = __builtin_amdgcn_readlane(p0, g) / kEarlyItemVictims + (it - __builtin_amdgcn_readlane(incl - items, g));
-            const int p1_g = __builtin_amdgcn_readlane(p1, g);
-            const int c_lo = lo + kEarlyGroup * g;
-            const bool second = c_lo + kTile < hi;
-            if (g != g_held) {
-                cb0 = sh.box[c_lo + lane];
-                aux0 = sh.aux[c_lo + lane];
-                const int c1 = second ? c_lo + kTile + lane : lane;
-                cb1 = sh.box[c1];
-                aux1 = sh.aux[c1];
-                g_held = g;
-            }
-            if (kEarlyItemVictims * jb < p1_g || !second)
-                early_item<PAIR, true>(sh, jb, m, c_lo, second, cb0, aux0, cb1, aux1, theta, y_one, lane);
-            else
-                early_item<PAIR, false>(sh, jb, m, c_lo, second, cb0, aux0, cb1, aux1, theta, y_one, lane);
-        }
+        if (hi - lo >= 4 * kTile)
+            early_stage_items<PAIR, 4>(sh, lo, hi, m, theta, y_one, lane, wave);
+        else
+            early_stage_items<PAIR, 2>(sh, lo, hi, m, theta, y_one, lane, wave);
         lds_barrier();
 
         // Entries still alive: those ranked before `hi` have met every better-ranked box and
@@ -173,6 +227,7 @@ __device__ __forceinline__ void early_exit_frame(EarlyShared &sh, int n_f, float
             if (on[j]) sh.list[base + __builtin_popcountll(on_mask[j] & ((1ull << lane) - 1ull))] = entry[j];
         }
         if (tid < kEarlyItemVictims) sh.list[m_new + tid] = 0;
+        if (tid == 0) sh.next_item = kEarlyWaves;
         if (m_new == 0) break;
         lds_barrier();
         // start[t] = entries ranked before 64 t: entry i opens every tile after its predecessor's up to its own
@@ -193,17 +248,21 @@ __device__ __forceinline__ void early_exit_frame(EarlyShared &sh, int n_f, float
     }
 }
 
-// FAST: the division-free forms of nms_pair.h (the y-scaled one when every y coordinate of the
-// frame allows it), else the literal division.
-template <bool FAST>
+// PAIR: which evaluation of the pair test (nms_pair.h).  The y-scaled form needs every y
+// coordinate of a frame to allow it: the kernel of that form reports per frame, in
+// irregular[f], whether it had to leave the frame alone, and the kernel of the plain fast form,
+// launched after it, takes exactly those frames.  (Two kernels rather than one with both forms:
+// the register allocation of each stays free of spills.)
+template <int PAIR>
 __global__ void __launch_bounds__(kEarlyThreads)
 early_exit_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ order,
                   const int32_t *__restrict__ counts, int n_max, int n_pad, NmsThetaConst th,
-                  uint8_t *__restrict__ keep_out)
+                  uint8_t *__restrict__ keep_out, int *__restrict__ irregular)
 {
     __shared__ EarlyShared sh;
     const int f = blockIdx.x;
     const int tid = (int)threadIdx.x;
+    if (PAIR == kPairFast && irregular[f] == 0) return;
     const int n_f = frame_count(counts, f, n_max);
     const float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
     const float4 *box4 = reinterpret_cast<const float4 *>(sorted_f);
@@ -211,35 +270,38 @@ early_exit_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__
     uint8_t *keep_f = keep_out + (size_t)f * n_max;
     const int32_t *order_f = order + (size_t)f * n_max;
 
-    for (int i = tid; i < n_max; i += kEarlyThreads) keep_f[i] = 0;  // survivors are marked as they are found
-    if (tid == 0) sh.irregular = 0;
-    __syncthreads();  // also: the zero fill is complete before any survivor is marked
-    const int staged = (n_f + kTile - 1) / kTile * kTile;  // padding rows of the table included
-    bool irregular = false;
-    for (int r = tid; r < staged; r += kEarlyThreads) {
-        const float4 b = box4[r];
-        sh.box[r] = b;
-        sh.aux[r] = FAST ? nms_pair_threshold(area[r], th.m) : area[r];
-        irregular |= !(nms_y_regular(b.y) && nms_y_regular(b.w));
+    if (tid == 0) {
+        sh.irregular = 0;
+        sh.next_item = kEarlyWaves;
     }
-    if (FAST && irregular) sh.irregular = 1;
+    lds_barrier();
+    const int staged = (n_f + kTile - 1) / kTile * kTile;  // padding rows of the table included
+    bool odd = false;
+    for (int r = tid; r < staged; r += kEarlyThreads) {
+        float4 b = box4[r];
+        float a = PAIR == kPairExact ? area[r] : nms_pair_threshold(area[r], th.m);
+        if (PAIR == kPairFastYScaled) {
+            odd |= !(nms_y_regular(b.y) && nms_y_regular(b.w));
+            b.y *= NMS_YSCALE;
+            b.w *= NMS_YSCALE;
+            a *= NMS_YSCALE;
+        }
+        sh.box[r] = b;
+        sh.aux[r] = a;
+    }
+    if (odd) sh.irregular = 1;
     for (int i = tid; i < NMS_SORT_CHUNK + kEarlyItemVictims; i += kEarlyThreads) sh.list[i] = i < n_f ? 16 * i : 0;
     reinterpret_cast<int *>(sh.dead)[tid] = 0;
     if (tid <= kEarlyTiles) sh.start[tid] = kTile * tid < n_f ? kTile * tid : n_f;
     lds_barrier();
+    if (PAIR == kPairFastYScaled) {
+        const int leave = sh.irregular;
+        if (tid == 0) irregular[f] = leave;
+        if (leave != 0) return;
+    }
+    for (int i = tid; i < n_max; i += kEarlyThreads) keep_f[i] = 0;  // survivors are marked as they are found
+    __syncthreads();  // the zero fill is complete before any survivor is marked
     float y_one;  // NMS_YSCALE in a vector register (opaque to the compiler so it stays there)
     asm volatile("v_mov_b32 %0, 0x38800000" : "=v"(y_one));
-    if (FAST && sh.irregular == 0) {
-        for (int r = tid; r < staged; r += kEarlyThreads) {  // the rows this thread staged itself
-            float4 b = sh.box[r];
-            b.y *= NMS_YSCALE;
-            b.w *= NMS_YSCALE;
-            sh.box[r] = b;
-            sh.aux[r] *= NMS_YSCALE;
-        }
-        lds_barrier();
-        early_exit_frame<kPairFastYScaled>(sh, n_f, th.theta, y_one, order_f, keep_f);
-    } else {
-        early_exit_frame<FAST ? kPairFast : kPairExact>(sh, n_f, th.theta, y_one, order_f, keep_f);
-    }
+    early_exit_frame<PAIR>(sh, n_f, th.theta, y_one, order_f, keep_f);
 }
