@@ -40,6 +40,7 @@ struct EarlyShared {
     float aux[NMS_SORT_CHUNK];                     // T, NMS_YSCALE * T, or the area
     int list[NMS_SORT_CHUNK + kEarlyItemVictims];  // undecided victims: 16 * rank, ascending; zeros behind the end
     uint8_t dead[NMS_SORT_CHUNK];                  // by list position: an eliminator was found in this stage
+    uint16_t order[NMS_SORT_CHUNK];                // rank -> index in the input (so that marking a survivor is a plain store)
     int start[kEarlyTiles + 1];                    // start[t] = list entries ranked before 64 t
     int count[4 * kEarlyWaves];                    // packing: entries that go on, per 64 list positions
     int next_item;                                 // the stage's next work item that no wavefront has taken
@@ -180,7 +181,7 @@ __device__ __forceinline__ void early_stage_items(EarlyShared &sh, int lo, int h
 // initial list (every rank) and keep_f is zero.
 template <int PAIR>
 __device__ __forceinline__ void early_exit_frame(EarlyShared &sh, int n_f, float theta, float y_one,
-                                                 const int32_t *__restrict__ order_f, uint8_t *__restrict__ keep_f)
+                                                 uint8_t *__restrict__ keep_f)
 {
     const int tid = (int)threadIdx.x;
     const int lane = tid & 63;
@@ -211,7 +212,7 @@ __device__ __forceinline__ void early_exit_frame(EarlyShared &sh, int n_f, float
             const bool alive = valid && sh.dead[valid ? i : 0] == 0;
             if (valid) sh.dead[i] = 0;
             const int r = entry[j] >> 4;
-            if (alive && r < hi) keep_f[order_f[r]] = 1;
+            if (alive && r < hi) keep_f[sh.order[r]] = 1;
             on[j] = alive && r >= hi;
             on_mask[j] = __ballot(on[j]);
             if (lane == 0) sh.count[kEarlyWaves * j + wave] = __builtin_popcountll(on_mask[j]);
@@ -288,6 +289,7 @@ early_exit_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__
         }
         sh.box[r] = b;
         sh.aux[r] = a;
+        sh.order[r] = (uint16_t)(r < n_f ? order_f[r] : 0);
     }
     if (odd) sh.irregular = 1;
     for (int i = tid; i < NMS_SORT_CHUNK + kEarlyItemVictims; i += kEarlyThreads) sh.list[i] = i < n_f ? 16 * i : 0;
@@ -303,5 +305,5 @@ early_exit_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__
     __syncthreads();  // the zero fill is complete before any survivor is marked
     float y_one;  // NMS_YSCALE in a vector register (opaque to the compiler so it stays there)
     asm volatile("v_mov_b32 %0, 0x38800000" : "=v"(y_one));
-    early_exit_frame<PAIR>(sh, n_f, th.theta, y_one, order_f, keep_f);
+    early_exit_frame<PAIR>(sh, n_f, th.theta, y_one, keep_f);
 }

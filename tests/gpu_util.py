@@ -86,6 +86,13 @@ class DeviceFrames:
                 assert np.array_equal(early, want), f"early-exit route: {(early != want).sum()} differing keep bits"
         return got
 
+    def early_exit(self, theta):
+        """nms_run_early_exit_batched alone."""
+        self.keep.fill_(77)
+        self.nms.nms_run_early_exit_batched(self.boxes, self.scores, self.counts, self.n_max, self.F, theta, self.keep, self.run_ws)
+        self.torch.cuda.synchronize()
+        return self.keep.cpu().numpy()
+
     def greedy(self, theta):
         """Greedy rule two ways: nms_reduce_greedy_batched on the mask of the step calls, and
         the one-call nms_run_greedy_batched.  Returns both keep arrays."""
