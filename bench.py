@@ -76,6 +76,7 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="workload configuration of the headline number (0..4)")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-early-exit", action="store_true", help="skip the timing of nms_run_early_exit_batched")
     ap.add_argument("--cpu-sample-frames", type=int, default=256)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device copies (a known-size kernel to scale HBM counters by)")
@@ -177,6 +178,21 @@ def main():
         "us_per_frame": round(ms_per_step * 1e3 / w.frames, 3),
         "survivors": int(keep_gpu.sum()),
     }
+
+    # -------------------------------------------------------------- the paper's rule, eliminated victims skipped
+    # (same keep vector as nms_run_batched from a fraction of the pair tests: quoted in frames/s,
+    # never in pair tests/s -- the headline counts pairs that are evaluated, all of them)
+    if w.n <= 4096 and not args.no_early_exit:
+        keep_e = torch.empty((w.frames, w.n), dtype=torch.uint8, device=dev)
+        ms_e = time_steps(lambda: nms.nms_run_early_exit_batched(d["boxes"], d["scores"], None, w.n, w.frames, w.theta,
+                                                                 keep_e, d["ws"]), max(5, K // 5), 2)
+        extra["early_exit_route"] = {
+            "nms_run_early_exit_batched_ms_per_step": round(ms_e, 4),
+            "frames_per_s": round(w.frames / (ms_e * 1e-3), 1),
+            "equals_nms_run_batched": bool(torch.equal(keep_e, d["keep"])),
+            "speedup_over_all_pairs": round(ms_per_step / ms_e, 3),
+        }
+        del keep_e
 
     # ------------------------------------------------------------------ three-step (mask) pipeline on the same workload
     if not args.no_extra:

@@ -40,7 +40,7 @@ struct EarlyShared {
     float aux[NMS_SORT_CHUNK];                     // T, NMS_YSCALE * T, or the area
     int list[NMS_SORT_CHUNK + kEarlyItemVictims];  // undecided victims: 16 * rank, ascending; zeros behind the end
     uint8_t dead[NMS_SORT_CHUNK];                  // by list position: an eliminator was found in this stage
-    uint16_t order[NMS_SORT_CHUNK];                // rank -> index in the input (so that marking a survivor is a plain store)
+    uint8_t survives[NMS_SORT_CHUNK];              // by rank; written out through `order` when the frame is done
     int start[kEarlyTiles + 1];                    // start[t] = list entries ranked before 64 t
     int count[4 * kEarlyWaves];                    // packing: entries that go on, per 64 list positions
     int next_item;                                 // the stage's next work item that no wavefront has taken
@@ -57,11 +57,11 @@ __device__ __forceinline__ bool early_hit(const float4 v, const float4 cb, float
 
 // One work item: the list entries [V jb, V jb + V), V = 128 / K, against the K candidate tiles held in
 // cb[], aux[].  DIAG: some of the victims are ranked within or before the group, or some of the
-// group's tiles do not exist (only the first `tiles` do), so a lane counts only when its
-// candidate outranks the victim: its entry value (at0 + 1024 i for tile i) is below the victim's.
+// group's tiles do not exist, so a lane counts only when its candidate outranks the victim: its
+// entry value (at0 + 1024 i for tile i) is below the victim's.
 template <int PAIR, bool DIAG, int K>
 __device__ __forceinline__ void early_item(EarlyShared &sh, int jb, int m, const float4 (&cb)[K], const float (&aux)[K],
-                                           int at0, int tiles, float theta, float y_one, int lane)
+                                           int at0, float theta, float y_one, int lane)
 {
     constexpr int V = kEarlyItemPairs / K;
     const int4 *entries = reinterpret_cast<const int4 *>(sh.list + V * jb);
@@ -99,10 +99,9 @@ __device__ __forceinline__ void early_item(EarlyShared &sh, int jb, int m, const
 #pragma unroll
             for (int i = 0; i < K; ++i) {
                 unsigned long long h = __ballot(early_hit<PAIR>(vu, cb[i], aux[i], theta, y_one));
-                if (DIAG) {
-                    h &= __ballot(at0 < off[u] - 16 * kTile * i);
-                    h = i < tiles ? h : 0ull;
-                }
+                // (a tile of the group that does not exist lies at or beyond the end of the frame:
+                // no victim is ranked behind any of its lanes, so this test takes it out as well)
+                if (DIAG) h &= __ballot(at0 < off[u] - 16 * kTile * i);
                 any |= h;
             }
             // word |= (any != 0) << (4 c + u), written out so that it too stays here and the lane
@@ -170,18 +169,18 @@ __device__ __forceinline__ void early_stage_items(EarlyShared &sh, int lo, int h
             g_held = g;
         }
         if (V * jb < p1_g || tiles < K)
-            early_item<PAIR, true, K>(sh, jb, m, cb, aux, at0, tiles, theta, y_one, lane);
+            early_item<PAIR, true, K>(sh, jb, m, cb, aux, at0, theta, y_one, lane);
         else
-            early_item<PAIR, false, K>(sh, jb, m, cb, aux, at0, tiles, theta, y_one, lane);
+            early_item<PAIR, false, K>(sh, jb, m, cb, aux, at0, theta, y_one, lane);
         it = __builtin_amdgcn_readfirstlane(next);
     }
 }
 
 // The stages of one frame; the table is staged, sh.list / sh.dead / sh.start describe the
-// initial list (every rank) and keep_f is zero.
+// initial list (every rank) and sh.survives is zero.
 template <int PAIR>
 __device__ __forceinline__ void early_exit_frame(EarlyShared &sh, int n_f, float theta, float y_one,
-                                                 uint8_t *__restrict__ keep_f)
+                                                 const int32_t *__restrict__ order_f, uint8_t *__restrict__ keep_f)
 {
     const int tid = (int)threadIdx.x;
     const int lane = tid & 63;
@@ -202,17 +201,22 @@ __device__ __forceinline__ void early_exit_frame(EarlyShared &sh, int n_f, float
         // survive; the others go on, packed to the front.  64 consecutive list positions report
         // how many go on in count[]; a prefix sum gives each its place.
         int entry[4];
+        uint8_t gone[4];
         bool on[4];
         unsigned long long on_mask[4];
 #pragma unroll
+        for (int j = 0; j < 4; ++j) {  // all reads first: they do not wait for each other
+            const int i = tid + kEarlyThreads * j;
+            entry[j] = sh.list[i < m ? i : 0];
+            gone[j] = sh.dead[i < m ? i : 0];
+        }
+#pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int i = tid + kEarlyThreads * j;
-            const bool valid = i < m;
-            entry[j] = valid ? sh.list[i] : 0;
-            const bool alive = valid && sh.dead[valid ? i : 0] == 0;
-            if (valid) sh.dead[i] = 0;
+            const bool alive = i < m && gone[j] == 0;
+            if (i < m) sh.dead[i] = 0;
             const int r = entry[j] >> 4;
-            if (alive && r < hi) keep_f[sh.order[r]] = 1;
+            if (alive && r < hi) sh.survives[r] = 1;
             on[j] = alive && r >= hi;
             on_mask[j] = __ballot(on[j]);
             if (lane == 0) sh.count[kEarlyWaves * j + wave] = __builtin_popcountll(on_mask[j]);
@@ -247,6 +251,8 @@ __device__ __forceinline__ void early_exit_frame(EarlyShared &sh, int n_f, float
         m = m_new;
         lo = hi;
     }
+    lds_barrier();  // every survivor is marked
+    for (int r = tid; r < n_f; r += kEarlyThreads) keep_f[order_f[r]] = sh.survives[r];  // `order` is a permutation: each byte once
 }
 
 // PAIR: which evaluation of the pair test (nms_pair.h).  The y-scaled form needs every y
@@ -289,11 +295,11 @@ early_exit_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__
         }
         sh.box[r] = b;
         sh.aux[r] = a;
-        sh.order[r] = (uint16_t)(r < n_f ? order_f[r] : 0);
     }
     if (odd) sh.irregular = 1;
     for (int i = tid; i < NMS_SORT_CHUNK + kEarlyItemVictims; i += kEarlyThreads) sh.list[i] = i < n_f ? 16 * i : 0;
     reinterpret_cast<int *>(sh.dead)[tid] = 0;
+    reinterpret_cast<int *>(sh.survives)[tid] = 0;
     if (tid <= kEarlyTiles) sh.start[tid] = kTile * tid < n_f ? kTile * tid : n_f;
     lds_barrier();
     if (PAIR == kPairFastYScaled) {
@@ -301,9 +307,8 @@ early_exit_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__
         if (tid == 0) irregular[f] = leave;
         if (leave != 0) return;
     }
-    for (int i = tid; i < n_max; i += kEarlyThreads) keep_f[i] = 0;  // survivors are marked as they are found
-    __syncthreads();  // the zero fill is complete before any survivor is marked
     float y_one;  // NMS_YSCALE in a vector register (opaque to the compiler so it stays there)
     asm volatile("v_mov_b32 %0, 0x38800000" : "=v"(y_one));
-    early_exit_frame<PAIR>(sh, n_f, th.theta, y_one, keep_f);
+    for (int i = n_f + tid; i < n_max; i += kEarlyThreads) keep_f[i] = 0;
+    early_exit_frame<PAIR>(sh, n_f, th.theta, y_one, order_f, keep_f);
 }
