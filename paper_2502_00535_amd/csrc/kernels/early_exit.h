@@ -255,21 +255,18 @@ __device__ __forceinline__ void early_exit_frame(EarlyShared &sh, int n_f, float
     for (int r = tid; r < n_f; r += kEarlyThreads) keep_f[order_f[r]] = sh.survives[r];  // `order` is a permutation: each byte once
 }
 
-// PAIR: which evaluation of the pair test (nms_pair.h).  The y-scaled form needs every y
-// coordinate of a frame to allow it: the kernel of that form reports per frame, in
-// irregular[f], whether it had to leave the frame alone, and the kernel of the plain fast form,
-// launched after it, takes exactly those frames.  (Two kernels rather than one with both forms:
-// the register allocation of each stays free of spills.)
+// PAIR: kPairFastYScaled (the division-free form of nms_pair.h; a frame with a y coordinate
+// outside the y-scaled form's range is staged again as it is and takes the plain fast form) or
+// kPairExact (the literal division, for thresholds outside the fast form's range).
 template <int PAIR>
 __global__ void __launch_bounds__(kEarlyThreads)
 early_exit_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ order,
                   const int32_t *__restrict__ counts, int n_max, int n_pad, NmsThetaConst th,
-                  uint8_t *__restrict__ keep_out, int *__restrict__ irregular)
+                  uint8_t *__restrict__ keep_out)
 {
     __shared__ EarlyShared sh;
     const int f = blockIdx.x;
     const int tid = (int)threadIdx.x;
-    if (PAIR == kPairFast && irregular[f] == 0) return;
     const int n_f = frame_count(counts, f, n_max);
     const float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
     const float4 *box4 = reinterpret_cast<const float4 *>(sorted_f);
@@ -302,13 +299,18 @@ early_exit_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__
     reinterpret_cast<int *>(sh.survives)[tid] = 0;
     if (tid <= kEarlyTiles) sh.start[tid] = kTile * tid < n_f ? kTile * tid : n_f;
     lds_barrier();
-    if (PAIR == kPairFastYScaled) {
-        const int leave = sh.irregular;
-        if (tid == 0) irregular[f] = leave;
-        if (leave != 0) return;
-    }
     float y_one;  // NMS_YSCALE in a vector register (opaque to the compiler so it stays there)
     asm volatile("v_mov_b32 %0, 0x38800000" : "=v"(y_one));
     for (int i = n_f + tid; i < n_max; i += kEarlyThreads) keep_f[i] = 0;
+    if (PAIR == kPairFastYScaled && sh.irregular != 0) {
+        // some y coordinate is outside the scaled form's range: the table again, as it is, and the plain form
+        for (int r = tid; r < staged; r += kEarlyThreads) {  // the rows this thread staged itself
+            sh.box[r] = box4[r];
+            sh.aux[r] = nms_pair_threshold(area[r], th.m);
+        }
+        lds_barrier();
+        early_exit_frame<kPairFast>(sh, n_f, th.theta, y_one, order_f, keep_f);
+        return;
+    }
     early_exit_frame<PAIR>(sh, n_f, th.theta, y_one, order_f, keep_f);
 }

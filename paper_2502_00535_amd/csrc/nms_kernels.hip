@@ -478,17 +478,13 @@ int nms_run_early_exit_batched(const float *boxes, const float *scores, const in
     if (st != NMS_OK) return st;
     const NmsThetaConst th = nms_make_theta_const(threshold);
     const int n_pad = nms_padded_n(n_max);
-    int *irregular = reinterpret_cast<int *>(w.ytile);  // per frame: the y-scaled form left it to the plain one
     begin_launch();
-    if (th.fast) {
+    if (th.fast)
         early_exit_kernel<kPairFastYScaled><<<dim3(frames), dim3(kEarlyThreads), 0, s>>>(w.sorted5, w.order, counts, n_max, n_pad,
-                                                                                         th, keep_out, irregular);
-        early_exit_kernel<kPairFast><<<dim3(frames), dim3(kEarlyThreads), 0, s>>>(w.sorted5, w.order, counts, n_max, n_pad, th,
-                                                                                  keep_out, irregular);
-    } else {
+                                                                                         th, keep_out);
+    else
         early_exit_kernel<kPairExact><<<dim3(frames), dim3(kEarlyThreads), 0, s>>>(w.sorted5, w.order, counts, n_max, n_pad, th,
-                                                                                   keep_out, irregular);
-    }
+                                                                                   keep_out);
     return launch_status();
 }
 
