@@ -41,6 +41,7 @@ struct EarlyShared {
     int list[NMS_SORT_CHUNK + kEarlyItemVictims];  // undecided victims: 16 * rank, ascending; zeros behind the end
     uint8_t dead[NMS_SORT_CHUNK];                  // by list position: an eliminator was found in this stage
     uint8_t survives[NMS_SORT_CHUNK];              // by rank; written out through `order` when the frame is done
+    uint16_t order[NMS_SORT_CHUNK];                // rank -> index in the input
     int start[kEarlyTiles + 1];                    // start[t] = list entries ranked before 64 t
     int count[4 * kEarlyWaves];                    // packing: entries that go on, per 64 list positions
     int next_item;                                 // the stage's next work item that no wavefront has taken
@@ -180,7 +181,7 @@ __device__ __forceinline__ void early_stage_items(EarlyShared &sh, int lo, int h
 // initial list (every rank) and sh.survives is zero.
 template <int PAIR>
 __device__ __forceinline__ void early_exit_frame(EarlyShared &sh, int n_f, float theta, float y_one,
-                                                 const int32_t *__restrict__ order_f, uint8_t *__restrict__ keep_f)
+                                                 uint8_t *__restrict__ keep_f)
 {
     const int tid = (int)threadIdx.x;
     const int lane = tid & 63;
@@ -252,7 +253,7 @@ __device__ __forceinline__ void early_exit_frame(EarlyShared &sh, int n_f, float
         lo = hi;
     }
     lds_barrier();  // every survivor is marked
-    for (int r = tid; r < n_f; r += kEarlyThreads) keep_f[order_f[r]] = sh.survives[r];  // `order` is a permutation: each byte once
+    for (int r = tid; r < n_f; r += kEarlyThreads) keep_f[sh.order[r]] = sh.survives[r];  // `order` is a permutation: each byte once
 }
 
 // PAIR: kPairFastYScaled (the division-free form of nms_pair.h; a frame with a y coordinate
@@ -292,6 +293,7 @@ early_exit_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__
         }
         sh.box[r] = b;
         sh.aux[r] = a;
+        sh.order[r] = (uint16_t)(r < n_f ? order_f[r] : 0);
     }
     if (odd) sh.irregular = 1;
     for (int i = tid; i < NMS_SORT_CHUNK + kEarlyItemVictims; i += kEarlyThreads) sh.list[i] = i < n_f ? 16 * i : 0;
@@ -309,8 +311,101 @@ early_exit_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__
             sh.aux[r] = nms_pair_threshold(area[r], th.m);
         }
         lds_barrier();
-        early_exit_frame<kPairFast>(sh, n_f, th.theta, y_one, order_f, keep_f);
+        early_exit_frame<kPairFast>(sh, n_f, th.theta, y_one, keep_f);
         return;
     }
-    early_exit_frame<PAIR>(sh, n_f, th.theta, y_one, order_f, keep_f);
+    early_exit_frame<PAIR>(sh, n_f, th.theta, y_one, keep_f);
+}
+
+// The same with the rank step inside (frames of more than 2048 boxes, where the rank kernel
+// would run with this kernel's 1024 threads anyway): scores and boxes are fetched in input
+// order, sorted in LDS (radix_rank_chunk of rank.h), and go from the registers straight into the
+// staged table -- no order / box table in memory, no second launch.  The LDS of the rank step is
+// the LDS of the list afterwards.
+struct EarlyRankShared {
+    unsigned long long keys[NMS_SORT_CHUNK];
+    unsigned hist[NMS_SORT_CHUNK];  // one row of 256 digit counts per wavefront
+    unsigned tot[256];
+    unsigned dbase[256];
+    float4 stage[NMS_SORT_CHUNK];   // during the sort: the wavefronts' digit-match tables
+};
+
+template <int PAIR>
+__global__ void __launch_bounds__(kEarlyThreads)
+early_exit_ranked_kernel(const float *__restrict__ boxes, const float *__restrict__ scores,
+                         const int32_t *__restrict__ counts, int n_max, NmsThetaConst th, uint8_t *__restrict__ keep_out)
+{
+    constexpr size_t kBytes = sizeof(EarlyShared) > sizeof(EarlyRankShared) ? sizeof(EarlyShared) : sizeof(EarlyRankShared);
+    __shared__ __align__(16) unsigned char raw[kBytes];
+    EarlyShared &sh = *reinterpret_cast<EarlyShared *>(raw);
+    EarlyRankShared &rk = *reinterpret_cast<EarlyRankShared *>(raw);
+    const int f = blockIdx.x;
+    const int tid = (int)threadIdx.x;
+    const int lane = tid & 63;
+    const int n_f = frame_count(counts, f, n_max);
+    const float *scores_f = scores + (size_t)f * n_max;
+    const float4 *boxes_f = reinterpret_cast<const float4 *>(boxes + (size_t)f * n_max * 4);
+    uint8_t *keep_f = keep_out + (size_t)f * n_max;
+
+    int e[4];
+    unsigned key32[4], index[4];
+    float4 mine[4];  // box e[q] of the input
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        e[q] = (tid >> 6) * 256 + q * 64 + lane;
+        const unsigned long long key = e[q] < n_f ? rank_key(scores_f[e[q]], (unsigned)e[q]) : kSentinel;
+        key32[q] = (unsigned)(key >> 32);
+        index[q] = (unsigned)key;
+        mine[q] = e[q] < n_f ? boxes_f[e[q]] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    radix_rank_chunk(key32, index, e, rk.keys, rk.hist, rk.tot, rk.dbase, reinterpret_cast<unsigned long long *>(rk.stage));  // ends with a barrier
+#pragma unroll
+    for (int q = 0; q < 4; ++q) rk.stage[e[q]] = mine[q];
+    __syncthreads();
+    float4 b[4];  // the box of rank tid + 1024 q, or the padding row (0,0,0,0) of area 1, which eliminates nothing
+    int idx[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int r = tid + kEarlyThreads * q;
+        idx[q] = r < n_f ? (int)(unsigned)rk.keys[r] : 0;
+        b[q] = r < n_f ? rk.stage[idx[q]] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    bool odd = false;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) odd |= !(nms_y_regular(b[q].y) && nms_y_regular(b[q].w));
+    // (a barrier: everything of the rank step is in registers from here on, its LDS is free)
+    const bool scaled = PAIR == kPairFastYScaled && __syncthreads_or(odd ? 1 : 0) == 0;
+    if (PAIR != kPairFastYScaled) __syncthreads();
+
+    const int staged = (n_f + kTile - 1) / kTile * kTile;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int r = tid + kEarlyThreads * q;
+        if (r < staged) {
+            const float area = nms_box_area(b[q].x, b[q].y, b[q].z, b[q].w);
+            float a = PAIR == kPairExact ? area : nms_pair_threshold(area, th.m);
+            float4 bs = b[q];
+            if (scaled) {
+                bs.y *= NMS_YSCALE;
+                bs.w *= NMS_YSCALE;
+                a *= NMS_YSCALE;
+            }
+            sh.box[r] = bs;
+            sh.aux[r] = a;
+            sh.order[r] = (uint16_t)idx[q];
+        }
+    }
+    if (tid == 0) sh.next_item = kEarlyWaves;
+    for (int i = tid; i < NMS_SORT_CHUNK + kEarlyItemVictims; i += kEarlyThreads) sh.list[i] = i < n_f ? 16 * i : 0;
+    reinterpret_cast<int *>(sh.dead)[tid] = 0;
+    reinterpret_cast<int *>(sh.survives)[tid] = 0;
+    if (tid <= kEarlyTiles) sh.start[tid] = kTile * tid < n_f ? kTile * tid : n_f;
+    for (int i = n_f + tid; i < n_max; i += kEarlyThreads) keep_f[i] = 0;
+    lds_barrier();
+    float y_one;  // NMS_YSCALE in a vector register (opaque to the compiler so it stays there)
+    asm volatile("v_mov_b32 %0, 0x38800000" : "=v"(y_one));
+    if (PAIR == kPairFastYScaled && !scaled)
+        early_exit_frame<kPairFast>(sh, n_f, th.theta, y_one, keep_f);
+    else
+        early_exit_frame<PAIR>(sh, n_f, th.theta, y_one, keep_f);
 }

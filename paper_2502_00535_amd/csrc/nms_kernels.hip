@@ -473,10 +473,21 @@ int nms_run_early_exit_batched(const float *boxes, const float *scores, const in
     if (!workspace || ws_bytes < nms_workspace_bytes(n_max, frames) || ((uintptr_t)workspace & 255))
         return NMS_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const NmsThetaConst th = nms_make_theta_const(threshold);
+    if (n_max > kChunk / 2) {
+        // the rank step would run with the same 1024 threads per frame: it is part of the kernel
+        begin_launch();
+        if (th.fast)
+            early_exit_ranked_kernel<kPairFastYScaled><<<dim3(frames), dim3(kEarlyThreads), 0, s>>>(boxes, scores, counts, n_max, th,
+                                                                                                    keep_out);
+        else
+            early_exit_ranked_kernel<kPairExact><<<dim3(frames), dim3(kEarlyThreads), 0, s>>>(boxes, scores, counts, n_max, th,
+                                                                                              keep_out);
+        return launch_status();
+    }
     const RunWorkspace w = carve_workspace(workspace, n_max, frames);
     st = rank_launch(boxes, scores, counts, n_max, frames, w.order, w.sorted5, w.keys, nullptr, nullptr, nullptr, s);
     if (st != NMS_OK) return st;
-    const NmsThetaConst th = nms_make_theta_const(threshold);
     const int n_pad = nms_padded_n(n_max);
     begin_launch();
     if (th.fast)
