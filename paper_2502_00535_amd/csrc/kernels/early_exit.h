@@ -177,17 +177,32 @@ __device__ __forceinline__ void early_stage_items(EarlyShared &sh, int lo, int h
     }
 }
 
-// The stages of one frame; the table is staged, sh.list / sh.dead / sh.start describe the
-// initial list (every rank) and sh.survives is zero.
+// The initial list of a workgroup's victims, ranks part + parts * i for i < m0, with its start[] table.
+__device__ __forceinline__ void early_initial_list(EarlyShared &sh, int m0, int part, int parts)
+{
+    const int tid = (int)threadIdx.x;
+    for (int i = tid; i < NMS_SORT_CHUNK + kEarlyItemVictims; i += kEarlyThreads) sh.list[i] = i < m0 ? 16 * (part + parts * i) : 0;
+    reinterpret_cast<int *>(sh.dead)[tid] = 0;
+    reinterpret_cast<int *>(sh.survives)[tid] = 0;
+    if (tid <= kEarlyTiles) {
+        const int before = kTile * tid > part ? (kTile * tid - part + parts - 1) / parts : 0;  // entries ranked before 64 tid
+        sh.start[tid] = before < m0 ? before : m0;
+    }
+}
+
+// The stages of one frame for the victims of one workgroup: the ranks part, part + parts,
+// part + 2 parts ... (victims do not depend on each other, so a frame can be shared out; every
+// workgroup needs all the frame's boxes as candidates).  The table is staged, sh.list / sh.dead /
+// sh.start describe the initial list of m0 entries and sh.survives is zero.
 template <int PAIR>
-__device__ __forceinline__ void early_exit_frame(EarlyShared &sh, int n_f, float theta, float y_one,
-                                                 uint8_t *__restrict__ keep_f)
+__device__ __forceinline__ void early_exit_frame(EarlyShared &sh, int n_f, int m0, int part, int parts, float theta,
+                                                 float y_one, uint8_t *__restrict__ keep_f)
 {
     const int tid = (int)threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int staged = (n_f + kTile - 1) / kTile * kTile;
-    int m = n_f;  // list length
+    int m = m0;  // list length
     int lo = 0;
     for (int bound = kEarlyFirstStage;; bound *= 2) {
         const int hi = bound < staged ? bound : staged;
@@ -253,7 +268,10 @@ __device__ __forceinline__ void early_exit_frame(EarlyShared &sh, int n_f, float
         lo = hi;
     }
     lds_barrier();  // every survivor is marked
-    for (int r = tid; r < n_f; r += kEarlyThreads) keep_f[sh.order[r]] = sh.survives[r];  // `order` is a permutation: each byte once
+    for (int i = tid; i < m0; i += kEarlyThreads) {  // `order` is a permutation: each byte once
+        const int r = part + parts * i;
+        keep_f[sh.order[r]] = sh.survives[r];
+    }
 }
 
 // PAIR: kPairFastYScaled (the division-free form of nms_pair.h; a frame with a y coordinate
@@ -262,13 +280,15 @@ __device__ __forceinline__ void early_exit_frame(EarlyShared &sh, int n_f, float
 template <int PAIR>
 __global__ void __launch_bounds__(kEarlyThreads)
 early_exit_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ order,
-                  const int32_t *__restrict__ counts, int n_max, int n_pad, NmsThetaConst th,
+                  const int32_t *__restrict__ counts, int n_max, int n_pad, int parts, NmsThetaConst th,
                   uint8_t *__restrict__ keep_out)
 {
     __shared__ EarlyShared sh;
-    const int f = blockIdx.x;
+    const int f = blockIdx.x / parts;
+    const int part = blockIdx.x % parts;  // this workgroup's share of the frame's victims
     const int tid = (int)threadIdx.x;
     const int n_f = frame_count(counts, f, n_max);
+    const int m0 = n_f > part ? (n_f - part + parts - 1) / parts : 0;
     const float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
     const float4 *box4 = reinterpret_cast<const float4 *>(sorted_f);
     const float *area = sorted_f + 4 * (size_t)n_pad;
@@ -296,14 +316,12 @@ early_exit_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__
         sh.order[r] = (uint16_t)(r < n_f ? order_f[r] : 0);
     }
     if (odd) sh.irregular = 1;
-    for (int i = tid; i < NMS_SORT_CHUNK + kEarlyItemVictims; i += kEarlyThreads) sh.list[i] = i < n_f ? 16 * i : 0;
-    reinterpret_cast<int *>(sh.dead)[tid] = 0;
-    reinterpret_cast<int *>(sh.survives)[tid] = 0;
-    if (tid <= kEarlyTiles) sh.start[tid] = kTile * tid < n_f ? kTile * tid : n_f;
+    early_initial_list(sh, m0, part, parts);
     lds_barrier();
     float y_one;  // NMS_YSCALE in a vector register (opaque to the compiler so it stays there)
     asm volatile("v_mov_b32 %0, 0x38800000" : "=v"(y_one));
-    for (int i = n_f + tid; i < n_max; i += kEarlyThreads) keep_f[i] = 0;
+    if (part == 0)
+        for (int i = n_f + tid; i < n_max; i += kEarlyThreads) keep_f[i] = 0;
     if (PAIR == kPairFastYScaled && sh.irregular != 0) {
         // some y coordinate is outside the scaled form's range: the table again, as it is, and the plain form
         for (int r = tid; r < staged; r += kEarlyThreads) {  // the rows this thread staged itself
@@ -311,10 +329,10 @@ early_exit_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__
             sh.aux[r] = nms_pair_threshold(area[r], th.m);
         }
         lds_barrier();
-        early_exit_frame<kPairFast>(sh, n_f, th.theta, y_one, keep_f);
+        early_exit_frame<kPairFast>(sh, n_f, m0, part, parts, th.theta, y_one, keep_f);
         return;
     }
-    early_exit_frame<PAIR>(sh, n_f, th.theta, y_one, keep_f);
+    early_exit_frame<PAIR>(sh, n_f, m0, part, parts, th.theta, y_one, keep_f);
 }
 
 // The same with the rank step inside (frames of more than 2048 boxes, where the rank kernel
@@ -396,16 +414,13 @@ early_exit_ranked_kernel(const float *__restrict__ boxes, const float *__restric
         }
     }
     if (tid == 0) sh.next_item = kEarlyWaves;
-    for (int i = tid; i < NMS_SORT_CHUNK + kEarlyItemVictims; i += kEarlyThreads) sh.list[i] = i < n_f ? 16 * i : 0;
-    reinterpret_cast<int *>(sh.dead)[tid] = 0;
-    reinterpret_cast<int *>(sh.survives)[tid] = 0;
-    if (tid <= kEarlyTiles) sh.start[tid] = kTile * tid < n_f ? kTile * tid : n_f;
+    early_initial_list(sh, n_f, 0, 1);
     for (int i = n_f + tid; i < n_max; i += kEarlyThreads) keep_f[i] = 0;
     lds_barrier();
     float y_one;  // NMS_YSCALE in a vector register (opaque to the compiler so it stays there)
     asm volatile("v_mov_b32 %0, 0x38800000" : "=v"(y_one));
     if (PAIR == kPairFastYScaled && !scaled)
-        early_exit_frame<kPairFast>(sh, n_f, th.theta, y_one, keep_f);
+        early_exit_frame<kPairFast>(sh, n_f, n_f, 0, 1, th.theta, y_one, keep_f);
     else
-        early_exit_frame<PAIR>(sh, n_f, th.theta, y_one, keep_f);
+        early_exit_frame<PAIR>(sh, n_f, n_f, 0, 1, th.theta, y_one, keep_f);
 }

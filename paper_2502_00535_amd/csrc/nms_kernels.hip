@@ -474,7 +474,11 @@ int nms_run_early_exit_batched(const float *boxes, const float *scores, const in
         return NMS_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const NmsThetaConst th = nms_make_theta_const(threshold);
-    if (n_max > kChunk / 2) {
+    // Fewer frames than compute units: a frame's victims are shared out among `parts` workgroups
+    // (each stages the whole frame), which then need the ranked table in memory.
+    int parts = 1;
+    while (parts < 16 && frames * parts * 2 <= 256) parts *= 2;
+    if (parts == 1 && n_max > kChunk / 2) {
         // the rank step would run with the same 1024 threads per frame: it is part of the kernel
         begin_launch();
         if (th.fast)
@@ -491,11 +495,11 @@ int nms_run_early_exit_batched(const float *boxes, const float *scores, const in
     const int n_pad = nms_padded_n(n_max);
     begin_launch();
     if (th.fast)
-        early_exit_kernel<kPairFastYScaled><<<dim3(frames), dim3(kEarlyThreads), 0, s>>>(w.sorted5, w.order, counts, n_max, n_pad,
-                                                                                         th, keep_out);
+        early_exit_kernel<kPairFastYScaled><<<dim3(frames * parts), dim3(kEarlyThreads), 0, s>>>(w.sorted5, w.order, counts, n_max,
+                                                                                                 n_pad, parts, th, keep_out);
     else
-        early_exit_kernel<kPairExact><<<dim3(frames), dim3(kEarlyThreads), 0, s>>>(w.sorted5, w.order, counts, n_max, n_pad, th,
-                                                                                   keep_out);
+        early_exit_kernel<kPairExact><<<dim3(frames * parts), dim3(kEarlyThreads), 0, s>>>(w.sorted5, w.order, counts, n_max, n_pad,
+                                                                                           parts, th, keep_out);
     return launch_status();
 }
 

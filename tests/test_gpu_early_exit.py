@@ -92,7 +92,7 @@ def test_single_eliminator_at_every_stage_bound(nms, oracle):
 
 def test_frames_that_leave_the_scaled_form(nms, oracle):
     """A batch in which some frames have y coordinates outside the y-scaled form's range (above
-    8190, or tiny): those are left by the first kernel and taken by the second."""
+    8190, or tiny): those are staged again unscaled and take the plain form of the pair test."""
     n, F = 2100, 24
     base_b, base_s = random_frame(9300, n, extent=3000, max_side=300, integer=False, score_levels=500)
     boxes = np.tile(base_b[None], (F, 1, 1))
@@ -133,6 +133,28 @@ def test_score_ties(nms, oracle):
     scores[::97] = np.float32(-0.0)
     boxes[1::2] = boxes[::2]
     check(nms, oracle, boxes[None], scores[None], 0.5)
+
+
+@pytest.mark.parametrize("frames", [3, 16, 17, 33, 64, 65, 128, 129, 200])
+def test_frames_shared_out_among_workgroups(nms, oracle, frames):
+    """Batches of fewer frames than the chip has compute units: a frame's victims are shared out
+    among 16, 8, 4 or 2 workgroups (ranks part, part + parts, ...), ragged counts included (some
+    shares then stay empty)."""
+    print(f"case frames={frames}", flush=True)
+    n = 1500
+    rng = np.random.default_rng(frames)
+    boxes = np.zeros((frames, n, 4), np.float32)
+    scores = np.zeros((frames, n), np.float32)
+    for f in range(min(frames, 12)):
+        boxes[f], scores[f] = random_frame(9600 + f, n, extent=900, max_side=140, integer=(f % 2 == 0), score_levels=300)
+    for f in range(12, frames):
+        p = rng.permutation(n)
+        boxes[f], scores[f] = boxes[f % 12][p], scores[f % 12][p]
+    counts = rng.integers(0, n + 1, frames).astype(np.int32)
+    counts[:3] = [n, 5, 0]
+    want = check(nms, oracle, boxes, scores, 0.45, counts)
+    assert 0 < want.sum() < want.size
+    check(nms, oracle, boxes[:, :700], scores[:, :700], 0.6)
 
 
 @pytest.mark.parametrize("index", [0, 1, 2, 4])
