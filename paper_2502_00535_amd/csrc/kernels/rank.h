@@ -165,9 +165,10 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
     const int nth = blockDim.x;
     const int lane = tid & 63;
     const int n_f = frame_count(counts, f, n_max);
-    const int base = chunk * kChunk;
+    constexpr int kSpan = STAGE ? kChunk : P;  // boxes per chunk: several chunks are P boxes each
+    const int base = chunk * kSpan;
     int cnt = n_f - base;
-    cnt = cnt < 0 ? 0 : (cnt > kChunk ? kChunk : cnt);
+    cnt = cnt < 0 ? 0 : (cnt > kSpan ? kSpan : cnt);
     const float *scores_f = scores + (size_t)f * n_max;
     const float *boxes_f = boxes + (size_t)f * n_max * 4;
     int e[4];
@@ -231,13 +232,19 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
     if (keep_preset != nullptr) {
         // fused path: every real box starts as a survivor, slots beyond the count are 0
         uint8_t *kp = keep_preset + (size_t)f * n_max;
-        const int hi = (base + kChunk < n_max) ? base + kChunk : n_max;
+        const int hi = (base + kSpan < n_max) ? base + kSpan : n_max;
         for (int i = base + tid; i < hi; i += nth) kp[i] = (i < n_f) ? 1 : 0;
     }
 }
 
-// Several chunks: the rank of a key is its position inside its own chunk plus the
-// number of smaller keys in every other chunk (keys are unique, so ranks are too).
+// Several chunks (of kMergeChunk boxes): the rank of a key is its position inside its own chunk
+// plus the number of smaller keys in every other chunk (keys are unique, so ranks are too).
+// The binary searches in the other chunks advance together, kMergeBatch chunks at a time, a
+// fixed number of steps: the loads of one step do not depend on each other, so a thread waits
+// for log2(chunk) + 1 round trips to memory however many chunks there are.
+constexpr int kMergeChunk = 1024;
+constexpr int kMergeBatch = 16;
+
 __global__ void __launch_bounds__(256)
 rank_merge_kernel(const float *__restrict__ boxes, const int32_t *__restrict__ counts, int n_max, int n_pad,
                   int n_chunks, const unsigned long long *__restrict__ keys_ws,
@@ -246,29 +253,44 @@ rank_merge_kernel(const float *__restrict__ boxes, const int32_t *__restrict__ c
 {
     const int f = blockIdx.y;
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= n_pad) return;
     const int n_f = frame_count(counts, f, n_max);
+    const unsigned long long *kw = keys_ws + (size_t)f * n_pad;
+    if (e >= n_pad) return;
     float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
     float4 *ysc_f = ysc ? ysc + (size_t)f * n_pad : nullptr;
     if (e >= n_f) {
         emit_padding_row(e, n_pad, sorted_f, ysc_f);
         return;
     }
-    const unsigned long long *kw = keys_ws + (size_t)f * n_pad;
     const unsigned long long key = kw[e];
-    const int own = e / kChunk;
-    int rank = e - own * kChunk;
-    for (int c = 0; c < n_chunks; ++c) {
-        if (c == own) continue;
-        const int base = c * kChunk;
-        int cnt = n_f - base;
-        cnt = cnt < 0 ? 0 : (cnt > kChunk ? kChunk : cnt);
-        int lo = 0, hi = cnt;  // first position whose key is not smaller
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (kw[base + mid] < key) lo = mid + 1; else hi = mid;
+    const int own = e / kMergeChunk;
+    int rank = e - own * kMergeChunk;
+    for (int c0 = 0; c0 < n_chunks; c0 += kMergeBatch) {
+        int below[kMergeBatch];  // keys of chunk c0 + k known to be smaller than `key`
+        int cnt[kMergeBatch];
+#pragma unroll
+        for (int k = 0; k < kMergeBatch; ++k) {
+            const int c = c0 + k;
+            int left = n_f - c * kMergeChunk;
+            left = left < 0 ? 0 : (left > kMergeChunk ? kMergeChunk : left);
+            cnt[k] = (c < n_chunks && c != own) ? left : 0;
+            below[k] = 0;
         }
-        rank += lo;
+        // below += step whenever the key `step` places further on is still smaller: no branches, and
+        // a probe that would leave the chunk reads this thread's own key instead (never smaller)
+#pragma unroll 1
+        for (int step = kMergeChunk; step > 0; step >>= 1) {
+            unsigned long long probe[kMergeBatch];
+#pragma unroll
+            for (int k = 0; k < kMergeBatch; ++k) {
+                const int at = below[k] + step;
+                probe[k] = kw[at <= cnt[k] ? (c0 + k) * kMergeChunk + at - 1 : e];
+            }
+#pragma unroll
+            for (int k = 0; k < kMergeBatch; ++k) below[k] += probe[k] < key ? step : 0;
+        }
+#pragma unroll
+        for (int k = 0; k < kMergeBatch; ++k) rank += below[k];
     }
     const int idx = (int)(unsigned)key;
     const bool regular = emit_ranked_box(reinterpret_cast<const float4 *>(boxes + (size_t)f * n_max * 4)[idx], idx, rank,

@@ -100,7 +100,8 @@ int rank_launch(const float *boxes, const float *scores, const int32_t *counts, 
                 hipStream_t stream)
 {
     const int n_pad = nms_padded_n(n_max);
-    const int n_chunks = (n_max + kChunk - 1) / kChunk;
+    // one chunk up to kChunk boxes; beyond that, chunks of kMergeChunk (more workgroups, shorter sorts) and a merge
+    const int n_chunks = n_max <= kChunk ? 1 : (n_max + kMergeChunk - 1) / kMergeChunk;
     int threads = 64;  // four keys per thread, at least one wavefront
     const int widest = n_max < kChunk ? n_max : kChunk;
     while (threads < 1024 && threads * 4 < widest) threads <<= 1;
@@ -109,7 +110,7 @@ int rank_launch(const float *boxes, const float *scores, const int32_t *counts, 
 #define NMS_LAUNCH_RANK(P_, STAGE_)                                                                    \
     rank_chunk_kernel<P_, STAGE_><<<dim3(n_chunks, frames), dim3(P_ / 4), 0, stream>>>(                \
         boxes, scores, counts, n_max, n_pad, n_chunks, order, sorted5, keys_ws, keep_preset, ysc, ytile)
-    if (n_chunks > 1) NMS_LAUNCH_RANK(4096, false);
+    if (n_chunks > 1) NMS_LAUNCH_RANK(kMergeChunk, false);
     else if (threads == 64) NMS_LAUNCH_RANK(256, true);
     else if (threads == 128) NMS_LAUNCH_RANK(512, true);
     else if (threads == 256) NMS_LAUNCH_RANK(1024, true);
