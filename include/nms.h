@@ -236,10 +236,11 @@ int nms_run_ex_batched(const float *boxes, const float *scores, const int32_t *c
  * pair tests on clustered detections (a quarter on 4096-box frames of SSD-style anchors).  One
  * workgroup per frame, which ranks the frame, keeps its boxes and the list of undecided victims in
  * LDS and takes the outranking boxes in stages of doubling width (with fewer frames than compute
- * units a frame's victims are shared out among up to 16 workgroups); it pays from about 2^29 pair
- * slots per batch (frames * n_max^2) on.  n_max <= NMS_SORT_CHUNK (else
- * NMS_ERR_TOO_LARGE); workspace >= nms_workspace_bytes(n_max, frames), 256-byte aligned (used
- * for the rank step's tables when n_max <= NMS_SORT_CHUNK / 2; required in either case).
+ * units a frame's victims are shared out among several workgroups; frames beyond NMS_SORT_CHUNK
+ * boxes always are, and their workgroups fetch the outranking boxes from the ranked table in
+ * memory); it pays from about 2^29 pair slots per batch (frames * n_max^2) on.  Sizes as
+ * nms_run_batched; workspace >= nms_workspace_bytes(n_max, frames), 256-byte aligned (used
+ * for the rank step's tables unless the rank step runs inside the kernel; required in either case).
  * Arguments, layout, ownership and errors as nms_run_batched.
  */
 int nms_run_early_exit_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,

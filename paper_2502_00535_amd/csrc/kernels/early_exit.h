@@ -42,10 +42,20 @@ struct EarlyShared {
     uint8_t dead[NMS_SORT_CHUNK];                  // by list position: an eliminator was found in this stage
     uint8_t survives[NMS_SORT_CHUNK];              // by rank; written out through `order` when the frame is done
     uint16_t order[NMS_SORT_CHUNK];                // rank -> index in the input
-    int start[kEarlyTiles + 1];                    // start[t] = list entries ranked before 64 t
+    int start[NMS_MAX_N / kTile + 1];              // start[t] = list entries ranked before 64 t
     int count[4 * kEarlyWaves];                    // packing: entries that go on, per 64 list positions
     int next_item;                                 // the stage's next work item that no wavefront has taken
     int irregular;                                 // some y coordinate rules out the y-scaled form
+};
+
+// Frames beyond NMS_SORT_CHUNK boxes ("wide"): the table does not fit LDS.  A workgroup stages only
+// its own victims (rank part + parts * i at position i; a list entry is 16 i) and fetches the
+// candidate tiles of an item from the ranked table in memory.
+struct EarlyWide {
+    const float4 *box4;  // ranked boxes
+    const float *area;   // and their areas
+    double m;            // rounding boundary below the threshold (fast form)
+    int part, parts;
 };
 
 template <int PAIR>
@@ -59,10 +69,11 @@ __device__ __forceinline__ bool early_hit(const float4 v, const float4 cb, float
 // One work item: the list entries [V jb, V jb + V), V = 128 / K, against the K candidate tiles held in
 // cb[], aux[].  DIAG: some of the victims are ranked within or before the group, or some of the
 // group's tiles do not exist, so a lane counts only when its candidate outranks the victim: its
-// entry value (at0 + 1024 i for tile i) is below the victim's.
-template <int PAIR, bool DIAG, int K>
+// entry value (at0 + 1024 i for tile i) is below the victim's (16 x the victim's rank: the entry
+// itself, or worked out from it when the list holds positions of a staged share, WIDE).
+template <int PAIR, bool DIAG, int K, bool WIDE>
 __device__ __forceinline__ void early_item(EarlyShared &sh, int jb, int m, const float4 (&cb)[K], const float (&aux)[K],
-                                           int at0, float theta, float y_one, int lane)
+                                           int at0, int part, int parts, float theta, float y_one, int lane)
 {
     constexpr int V = kEarlyItemPairs / K;
     const int4 *entries = reinterpret_cast<const int4 *>(sh.list + V * jb);
@@ -102,7 +113,7 @@ __device__ __forceinline__ void early_item(EarlyShared &sh, int jb, int m, const
                 unsigned long long h = __ballot(early_hit<PAIR>(vu, cb[i], aux[i], theta, y_one));
                 // (a tile of the group that does not exist lies at or beyond the end of the frame:
                 // no victim is ranked behind any of its lanes, so this test takes it out as well)
-                if (DIAG) h &= __ballot(at0 < off[u] - 16 * kTile * i);
+                if (DIAG) h &= __ballot(at0 < (WIDE ? off[u] * parts + 16 * part : off[u]) - 16 * kTile * i);
                 any |= h;
             }
             // word |= (any != 0) << (4 c + u), written out so that it too stays here and the lane
@@ -122,19 +133,19 @@ __device__ __forceinline__ void early_item(EarlyShared &sh, int jb, int m, const
 }
 
 // The work items of one stage (candidates [lo, hi), list of m entries) in groups of K tiles.
-template <int PAIR, int K>
-__device__ __forceinline__ void early_stage_items(EarlyShared &sh, int lo, int hi, int m, float theta, float y_one,
-                                                  int lane, int wave)
+template <int PAIR, int K, bool WIDE>
+__device__ __forceinline__ void early_stage_items(EarlyShared &sh, const EarlyWide &wide, int lo, int hi, int m, int tiles_all,
+                                                  float theta, float y_one, int lane, int wave)
 {
     constexpr int V = kEarlyItemPairs / K;
-    const int groups = ((hi - lo) / kTile + K - 1) / K;  // <= 32
+    const int groups = ((hi - lo) / kTile + K - 1) / K;  // <= 64
 
     // lane = candidate group: where its victims begin, where those begin that all its lanes outrank, its items
     int p0 = 0, p1 = 0, items = 0;
     if (lane < groups) {
         const int t0 = lo / kTile + K * lane;
         p0 = sh.start[t0];
-        p1 = sh.start[t0 + K < kEarlyTiles ? t0 + K : kEarlyTiles];
+        p1 = sh.start[t0 + K < tiles_all ? t0 + K : tiles_all];
         items = (m + V - 1) / V - p0 / V;
         items = p0 >= m ? 0 : items;
     }
@@ -163,30 +174,39 @@ __device__ __forceinline__ void early_stage_items(EarlyShared &sh, int lo, int h
 #pragma unroll
             for (int i = 0; i < K; ++i) {
                 const int c = i < tiles ? c_lo + kTile * i + lane : lane;
-                cb[i] = sh.box[c];
-                aux[i] = sh.aux[c];
+                if (WIDE) {
+                    cb[i] = wide.box4[c];
+                    const float a = wide.area[c];
+                    aux[i] = PAIR == kPairExact ? a : nms_pair_threshold(a, wide.m);
+                } else {
+                    cb[i] = sh.box[c];
+                    aux[i] = sh.aux[c];
+                }
             }
             at0 = 16 * (c_lo + lane);
             g_held = g;
         }
         if (V * jb < p1_g || tiles < K)
-            early_item<PAIR, true, K>(sh, jb, m, cb, aux, at0, theta, y_one, lane);
+            early_item<PAIR, true, K, WIDE>(sh, jb, m, cb, aux, at0, wide.part, wide.parts, theta, y_one, lane);
         else
-            early_item<PAIR, false, K>(sh, jb, m, cb, aux, at0, theta, y_one, lane);
+            early_item<PAIR, false, K, WIDE>(sh, jb, m, cb, aux, at0, wide.part, wide.parts, theta, y_one, lane);
         it = __builtin_amdgcn_readfirstlane(next);
     }
 }
 
-// The initial list of a workgroup's victims, ranks part + parts * i for i < m0, with its start[] table.
-__device__ __forceinline__ void early_initial_list(EarlyShared &sh, int m0, int part, int parts)
+// The initial list of a workgroup's victims, ranks part + parts * i for i < m0 (entry: 16 x the rank,
+// or 16 i when only the share is staged), with its start[] table over the frame's tiles_all tiles.
+template <bool WIDE>
+__device__ __forceinline__ void early_initial_list(EarlyShared &sh, int m0, int part, int parts, int tiles_all)
 {
     const int tid = (int)threadIdx.x;
-    for (int i = tid; i < NMS_SORT_CHUNK + kEarlyItemVictims; i += kEarlyThreads) sh.list[i] = i < m0 ? 16 * (part + parts * i) : 0;
+    for (int i = tid; i < NMS_SORT_CHUNK + kEarlyItemVictims; i += kEarlyThreads)
+        sh.list[i] = i < m0 ? 16 * (WIDE ? i : part + parts * i) : 0;
     reinterpret_cast<int *>(sh.dead)[tid] = 0;
     reinterpret_cast<int *>(sh.survives)[tid] = 0;
-    if (tid <= kEarlyTiles) {
-        const int before = kTile * tid > part ? (kTile * tid - part + parts - 1) / parts : 0;  // entries ranked before 64 tid
-        sh.start[tid] = before < m0 ? before : m0;
+    for (int t = tid; t <= tiles_all; t += kEarlyThreads) {
+        const int before = kTile * t > part ? (kTile * t - part + parts - 1) / parts : 0;  // entries ranked before 64 t
+        sh.start[t] = before < m0 ? before : m0;
     }
 }
 
@@ -194,23 +214,28 @@ __device__ __forceinline__ void early_initial_list(EarlyShared &sh, int m0, int 
 // part + 2 parts ... (victims do not depend on each other, so a frame can be shared out; every
 // workgroup needs all the frame's boxes as candidates).  The table is staged, sh.list / sh.dead /
 // sh.start describe the initial list of m0 entries and sh.survives is zero.
-template <int PAIR>
-__device__ __forceinline__ void early_exit_frame(EarlyShared &sh, int n_f, int m0, int part, int parts, float theta,
-                                                 float y_one, uint8_t *__restrict__ keep_f)
+// WIDE: see EarlyWide (order_f: rank -> input index, in memory); otherwise `wide` only carries part / parts.
+template <int PAIR, bool WIDE>
+__device__ __forceinline__ void early_exit_frame(EarlyShared &sh, const EarlyWide &wide, int n_f, int m0, float theta, float y_one,
+                                                 const int32_t *__restrict__ order_f, uint8_t *__restrict__ keep_f)
 {
     const int tid = (int)threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int part = wide.part, parts = wide.parts;
     const int staged = (n_f + kTile - 1) / kTile * kTile;
+    const int tiles_all = staged / kTile;
+    auto rank_of = [&](int entry) __attribute__((always_inline)) { return WIDE ? part + parts * (entry >> 4) : entry >> 4; };
     int m = m0;  // list length
     int lo = 0;
-    for (int bound = kEarlyFirstStage;; bound *= 2) {
+    // stages double in width, up to 64 groups of four tiles (a lane per group)
+    for (int bound = kEarlyFirstStage;; bound = 2 * bound < bound + 64 * 4 * kTile ? 2 * bound : bound + 64 * 4 * kTile) {
         const int hi = bound < staged ? bound : staged;
         const bool last = hi >= n_f;
         if (hi - lo >= 4 * kTile)
-            early_stage_items<PAIR, 4>(sh, lo, hi, m, theta, y_one, lane, wave);
+            early_stage_items<PAIR, 4, WIDE>(sh, wide, lo, hi, m, tiles_all, theta, y_one, lane, wave);
         else
-            early_stage_items<PAIR, 2>(sh, lo, hi, m, theta, y_one, lane, wave);
+            early_stage_items<PAIR, 2, WIDE>(sh, wide, lo, hi, m, tiles_all, theta, y_one, lane, wave);
         lds_barrier();
 
         // Entries still alive: those ranked before `hi` have met every better-ranked box and
@@ -231,8 +256,8 @@ __device__ __forceinline__ void early_exit_frame(EarlyShared &sh, int n_f, int m
             const int i = tid + kEarlyThreads * j;
             const bool alive = i < m && gone[j] == 0;
             if (i < m) sh.dead[i] = 0;
-            const int r = entry[j] >> 4;
-            if (alive && r < hi) sh.survives[r] = 1;
+            const int r = rank_of(entry[j]);
+            if (alive && r < hi) sh.survives[entry[j] >> 4] = 1;
             on[j] = alive && r >= hi;
             on_mask[j] = __ballot(on[j]);
             if (lane == 0) sh.count[kEarlyWaves * j + wave] = __builtin_popcountll(on_mask[j]);
@@ -256,11 +281,11 @@ __device__ __forceinline__ void early_exit_frame(EarlyShared &sh, int n_f, int m
         for (int j = 0; j < 4; ++j) {
             const int i = tid + kEarlyThreads * j;
             if (i < m_new) {
-                const int t_cur = sh.list[i] >> 10;
-                const int t_prev = i > 0 ? sh.list[i - 1] >> 10 : -1;
+                const int t_cur = rank_of(sh.list[i]) >> 6;
+                const int t_prev = i > 0 ? rank_of(sh.list[i - 1]) >> 6 : -1;
                 for (int t = t_prev + 1; t <= t_cur; ++t) sh.start[t] = i;
                 if (i == m_new - 1)
-                    for (int t = t_cur + 1; t <= kEarlyTiles; ++t) sh.start[t] = m_new;
+                    for (int t = t_cur + 1; t <= tiles_all; ++t) sh.start[t] = m_new;
             }
         }
         lds_barrier();
@@ -270,7 +295,8 @@ __device__ __forceinline__ void early_exit_frame(EarlyShared &sh, int n_f, int m
     lds_barrier();  // every survivor is marked
     for (int i = tid; i < m0; i += kEarlyThreads) {  // `order` is a permutation: each byte once
         const int r = part + parts * i;
-        keep_f[sh.order[r]] = sh.survives[r];
+        if (WIDE) keep_f[order_f[r]] = sh.survives[i];
+        else keep_f[sh.order[r]] = sh.survives[r];
     }
 }
 
@@ -316,10 +342,11 @@ early_exit_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__
         sh.order[r] = (uint16_t)(r < n_f ? order_f[r] : 0);
     }
     if (odd) sh.irregular = 1;
-    early_initial_list(sh, m0, part, parts);
+    early_initial_list<false>(sh, m0, part, parts, staged / kTile);
     lds_barrier();
     float y_one;  // NMS_YSCALE in a vector register (opaque to the compiler so it stays there)
     asm volatile("v_mov_b32 %0, 0x38800000" : "=v"(y_one));
+    const EarlyWide share = {nullptr, nullptr, 0.0, part, parts};
     if (part == 0)
         for (int i = n_f + tid; i < n_max; i += kEarlyThreads) keep_f[i] = 0;
     if (PAIR == kPairFastYScaled && sh.irregular != 0) {
@@ -329,10 +356,37 @@ early_exit_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__
             sh.aux[r] = nms_pair_threshold(area[r], th.m);
         }
         lds_barrier();
-        early_exit_frame<kPairFast>(sh, n_f, m0, part, parts, th.theta, y_one, keep_f);
+        early_exit_frame<kPairFast, false>(sh, share, n_f, m0, th.theta, y_one, nullptr, keep_f);
         return;
     }
-    early_exit_frame<PAIR>(sh, n_f, m0, part, parts, th.theta, y_one, keep_f);
+    early_exit_frame<PAIR, false>(sh, share, n_f, m0, th.theta, y_one, nullptr, keep_f);
+}
+
+// Frames beyond NMS_SORT_CHUNK boxes (see EarlyWide): parts >= n_max / NMS_SORT_CHUNK workgroups
+// per frame, each with the victims of ranks part, part + parts, ...; PAIR: kPairFast or kPairExact.
+template <int PAIR>
+__global__ void __launch_bounds__(kEarlyThreads)
+early_exit_wide_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ order,
+                       const int32_t *__restrict__ counts, int n_max, int n_pad, int parts, NmsThetaConst th,
+                       uint8_t *__restrict__ keep_out)
+{
+    __shared__ EarlyShared sh;
+    const int f = blockIdx.x / parts;
+    const int part = blockIdx.x % parts;
+    const int tid = (int)threadIdx.x;
+    const int n_f = frame_count(counts, f, n_max);
+    const int m0 = n_f > part ? (n_f - part + parts - 1) / parts : 0;  // <= NMS_SORT_CHUNK
+    const float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
+    const EarlyWide wide = {reinterpret_cast<const float4 *>(sorted_f), sorted_f + 4 * (size_t)n_pad, th.m, part, parts};
+    uint8_t *keep_f = keep_out + (size_t)f * n_max;
+
+    if (tid == 0) sh.next_item = kEarlyWaves;
+    for (int i = tid; i < m0; i += kEarlyThreads) sh.box[i] = wide.box4[part + parts * i];
+    early_initial_list<true>(sh, m0, part, parts, (n_f + kTile - 1) / kTile);
+    if (part == 0)
+        for (int i = n_f + tid; i < n_max; i += kEarlyThreads) keep_f[i] = 0;
+    lds_barrier();
+    early_exit_frame<PAIR, true>(sh, wide, n_f, m0, th.theta, 0.f, order + (size_t)f * n_max, keep_f);
 }
 
 // The same with the rank step inside (frames of more than 2048 boxes, where the rank kernel
@@ -414,13 +468,14 @@ early_exit_ranked_kernel(const float *__restrict__ boxes, const float *__restric
         }
     }
     if (tid == 0) sh.next_item = kEarlyWaves;
-    early_initial_list(sh, n_f, 0, 1);
+    early_initial_list<false>(sh, n_f, 0, 1, staged / kTile);
     for (int i = n_f + tid; i < n_max; i += kEarlyThreads) keep_f[i] = 0;
     lds_barrier();
     float y_one;  // NMS_YSCALE in a vector register (opaque to the compiler so it stays there)
     asm volatile("v_mov_b32 %0, 0x38800000" : "=v"(y_one));
+    const EarlyWide whole = {nullptr, nullptr, 0.0, 0, 1};
     if (PAIR == kPairFastYScaled && !scaled)
-        early_exit_frame<kPairFast>(sh, n_f, n_f, 0, 1, th.theta, y_one, keep_f);
+        early_exit_frame<kPairFast, false>(sh, whole, n_f, n_f, th.theta, y_one, nullptr, keep_f);
     else
-        early_exit_frame<PAIR>(sh, n_f, n_f, 0, 1, th.theta, y_one, keep_f);
+        early_exit_frame<PAIR, false>(sh, whole, n_f, n_f, th.theta, y_one, nullptr, keep_f);
 }

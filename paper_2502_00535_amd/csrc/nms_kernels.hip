@@ -467,7 +467,6 @@ int nms_run_early_exit_batched(const float *boxes, const float *scores, const in
 {
     int st;
     if (!sizes_ok(n_max, frames, &st)) return st;
-    if (n_max > kChunk) return NMS_ERR_TOO_LARGE;
     if (is_nan(threshold)) return NMS_ERR_INVALID_ARG;
     if (n_max == 0 || frames == 0) return NMS_OK;
     if (!boxes || !scores || !keep_out) return NMS_ERR_INVALID_ARG;
@@ -478,7 +477,7 @@ int nms_run_early_exit_batched(const float *boxes, const float *scores, const in
     // Fewer frames than compute units: a frame's victims are shared out among `parts` workgroups
     // (each stages the whole frame), which then need the ranked table in memory.
     int parts = 1;
-    while (parts < 16 && frames * parts * 2 <= 256) parts *= 2;
+    while (parts < (n_max > kChunk ? 256 : 16) && frames * parts * 2 <= 256) parts *= 2;
     if (parts == 1 && n_max > kChunk / 2) {
         // the rank step would run with the same 1024 threads per frame: it is part of the kernel
         begin_launch();
@@ -494,6 +493,18 @@ int nms_run_early_exit_batched(const float *boxes, const float *scores, const in
     st = rank_launch(boxes, scores, counts, n_max, frames, w.order, w.sorted5, w.keys, nullptr, nullptr, nullptr, s);
     if (st != NMS_OK) return st;
     const int n_pad = nms_padded_n(n_max);
+    if (n_max > kChunk) {
+        // the frame's table does not fit LDS: every workgroup stages its share of the victims only
+        while (parts * kChunk < n_max) parts *= 2;
+        begin_launch();
+        if (th.fast)
+            early_exit_wide_kernel<kPairFast><<<dim3(frames * parts), dim3(kEarlyThreads), 0, s>>>(w.sorted5, w.order, counts, n_max,
+                                                                                                   n_pad, parts, th, keep_out);
+        else
+            early_exit_wide_kernel<kPairExact><<<dim3(frames * parts), dim3(kEarlyThreads), 0, s>>>(w.sorted5, w.order, counts, n_max,
+                                                                                                    n_pad, parts, th, keep_out);
+        return launch_status();
+    }
     begin_launch();
     if (th.fast)
         early_exit_kernel<kPairFastYScaled><<<dim3(frames * parts), dim3(kEarlyThreads), 0, s>>>(w.sorted5, w.order, counts, n_max,

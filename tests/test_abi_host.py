@@ -188,7 +188,7 @@ def test_early_exit_argument_errors(nms):
     L = nms.lib
     p = ctypes.c_void_p(0x1000)
     big = 1 << 30
-    assert L.nms_run_early_exit_batched(p, p, None, 4097, 2, 0.5, p, p, big, None) == nms.NMS_ERR_TOO_LARGE
+    assert L.nms_run_early_exit_batched(p, p, None, 65537, 2, 0.5, p, p, big, None) == nms.NMS_ERR_TOO_LARGE
     assert L.nms_run_early_exit_batched(p, p, None, -1, 2, 0.5, p, p, big, None) == nms.NMS_ERR_INVALID_ARG
     assert L.nms_run_early_exit_batched(p, p, None, 64, 2, float("nan"), p, p, big, None) == nms.NMS_ERR_INVALID_ARG
     assert L.nms_run_early_exit_batched(None, p, None, 64, 2, 0.5, p, p, big, None) == nms.NMS_ERR_INVALID_ARG

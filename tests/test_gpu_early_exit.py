@@ -32,7 +32,7 @@ def check(nms, oracle, boxes, scores, theta, counts=None):
 
 
 @pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 127, 128, 129, 191, 192, 193, 255, 256, 257, 511, 513, 1000, 1025,
-                               2047, 2049, 3000, 4095, 4096])
+                               2047, 2049, 3000, 4095, 4096, 4097, 5000, 8191, 8193, 12345, 16384, 20000])
 def test_single_frame_lengths(nms, oracle, n):
     print(f"case n={n}", flush=True)
     boxes, scores = random_frame(9100 + n, n, extent=1500 if n > 600 else 300, max_side=90,
@@ -157,7 +157,7 @@ def test_frames_shared_out_among_workgroups(nms, oracle, frames):
     check(nms, oracle, boxes[:, :700], scores[:, :700], 0.6)
 
 
-@pytest.mark.parametrize("index", [0, 1, 2, 4])
+@pytest.mark.parametrize("index", [0, 1, 2, 3, 4])
 def test_configs_full_size(nms, oracle, index):
     print(f"case config={index}", flush=True)
     w = make_config(index)
@@ -165,14 +165,30 @@ def test_configs_full_size(nms, oracle, index):
     assert 0 < want.sum() < want.size
 
 
-def test_too_large_is_refused(nms):
-    import torch
+def test_wide_frames_batched(nms, oracle):
+    """Frames beyond 4096 boxes (only a workgroup's share of the victims is staged, candidates come
+    from the ranked table in memory): batches of 1, 3 and 40 frames with ragged counts, both forms
+    of the pair test."""
+    n = 6000
+    base_b, base_s = random_frame(9700, n, extent=2500, max_side=260, integer=False, score_levels=2000)
+    for frames, theta in ((1, 0.5), (3, 0.3), (40, 0.45), (3, 0.0), (2, 1.5)):
+        rng = np.random.default_rng(frames)
+        boxes = np.zeros((frames, n, 4), np.float32)
+        scores = np.zeros((frames, n), np.float32)
+        for f in range(frames):
+            p = rng.permutation(n)
+            boxes[f], scores[f] = base_b[p], base_s[p]
+        counts = rng.integers(0, n + 1, frames).astype(np.int32)
+        counts[0] = n
+        if frames > 2:
+            counts[1:3] = [4097, 100]
+        check(nms, oracle, boxes, scores, theta, counts)
+    b, s = staircase(9000)
+    assert check(nms, oracle, b[None], s[None], 0.5).sum() == 1
+    same = np.tile(np.array([[10, 10, 90, 70]], np.float32), (7000, 1))
+    sc = (np.arange(7000)[::-1] / 7000).astype(np.float32)
+    assert check(nms, oracle, same[None], sc[None], 0.5).sum() == 1
 
-    dev = torch.device("cuda:0")
-    n = 4097
-    b = torch.zeros((1, n, 4), device=dev)
-    s = torch.zeros((1, n), device=dev)
-    k = torch.zeros((1, n), dtype=torch.uint8, device=dev)
-    ws = torch.zeros(nms.nms_workspace_bytes(n, 1), dtype=torch.uint8, device=dev)
-    with pytest.raises(Exception):
-        nms.nms_run_early_exit_batched(b, s, None, n, 1, 0.5, k, ws)
+
+def test_sizes_beyond_the_limit_are_refused(nms):
+    assert nms.lib.nms_run_early_exit_batched(None, None, None, 65537, 1, 0.5, None, None, 0, None) == nms.NMS_ERR_TOO_LARGE
