@@ -1,4 +1,4 @@
-// Part of nms_kernels.hip (included there, inside its anonymous namespace): the paper's rule with eliminated victims dropped from further tests, one workgroup per frame.
+// Part of nms_kernels.hip (included there, inside its anonymous namespace): the paper's rule with eliminated victims dropped from further tests.
 #pragma once
 
 // ----------------------------------------------------------------------------- paper's rule, eliminated victims skipped
@@ -26,8 +26,11 @@
 // No pair is tested that involves a victim eliminated in an earlier stage; the result does not
 // depend on the stage bounds, only the amount of work does.
 //
-// A frame is one compute unit's work, so this route is for batches of about as many frames as
-// the chip has compute units or more.  Frames of at most NMS_SORT_CHUNK boxes.
+// Victims do not depend on each other, so with fewer frames than compute units a frame's victims
+// are shared out among several workgroups, each with a list of its own (ranks part, part + parts,
+// ...) and the whole frame staged as candidates.  Three kernels share the stages: the table staged
+// from the rank step's output (early_exit_kernel), the rank step inside (early_exit_ranked_kernel),
+// and frames beyond NMS_SORT_CHUNK boxes, whose table stays in memory (early_exit_wide_kernel).
 constexpr int kEarlyWaves = 16;
 constexpr int kEarlyThreads = kEarlyWaves * 64;
 constexpr int kEarlyFirstStage = 128;                 // candidates of the first stage; each further stage doubles the bound
