@@ -71,8 +71,8 @@ class HipEvents:
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=4, help="workload configuration of the headline number (0..4)")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -193,7 +193,7 @@ def main():
             nms.nms_overlap_mask_batched(sorted5, None, w.n, w.frames, w.theta, mask)
             nms.nms_reduce_batched(mask, order, None, w.n, w.frames, keep3)
 
-        steps3 = max(5, K // 5)
+        steps3 = min(100, max(5, K // 5))
         ms3 = time_steps(run_steps, steps3, 2)
         te = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
         split = [0.0, 0.0, 0.0]
@@ -397,7 +397,7 @@ def main():
     if not args.no_early_exit:
         keep_e = torch.empty((w.frames, w.n), dtype=torch.uint8, device=dev)
         ms_e = time_steps(lambda: nms.nms_run_early_exit_batched(d["boxes"], d["scores"], None, w.n, w.frames, w.theta,
-                                                                 keep_e, d["ws"]), max(5, K // 5), 2)
+                                                                 keep_e, d["ws"]), min(100, max(5, K // 5)), 2)
         extra["early_exit_route"] = {
             "nms_run_early_exit_batched_ms_per_step": round(ms_e, 4),
             "frames_per_s": round(w.frames / (ms_e * 1e-3), 1),
