@@ -26,7 +26,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 FLOPS_PER_PAIR = 13            # min,max,sub,add,max0 per axis (10) + mul + div + compare
-PEAK_FP32_VECTOR_TFLOPS = 157.3  # MI355X datasheet (packed FMA); see the design doc for the unpacked ceiling
+PEAK_FP32_VECTOR_TFLOPS = 157.3  # MI355X datasheet: 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz x 2 (every instruction an FMA)
 # Issue model of the pair-test kernel: per row of 64 pairs a SIMD issues 5 instructions of the
 # 4-cycle class (4 x v_min/v_max, v_cmp) and 5 of the 2-cycle class (2 x v_sub, 2 x v_add, v_mul);
 # cycle counts measured with the stand-alone probe (profiles/valu_issue_rates__gfx950.txt).
