@@ -232,7 +232,9 @@ __device__ __forceinline__ void early_exit_frame(EarlyShared &sh, const EarlyWid
     int m = m0;  // list length
     int lo = 0;
     // stages double in width, up to 64 groups of four tiles (a lane per group)
-    for (int bound = kEarlyFirstStage;; bound = 2 * bound < bound + 64 * 4 * kTile ? 2 * bound : bound + 64 * 4 * kTile) {
+    // a small share of a wide frame is cheap to test and every stage costs its barriers: wider steps
+    const int grow = WIDE && m0 <= 128 ? 4 : 2;
+    for (int bound = kEarlyFirstStage;; bound = grow * bound < bound + 64 * 4 * kTile ? grow * bound : bound + 64 * 4 * kTile) {
         const int hi = bound < staged ? bound : staged;
         const bool last = hi >= n_f;
         if (hi - lo >= 4 * kTile)
