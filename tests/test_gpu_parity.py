@@ -381,6 +381,8 @@ def test_calls_can_be_captured_in_a_hip_graph(nms, oracle):
     keep = torch.zeros((F, n), dtype=torch.uint8, device=dev)
     keep_g = torch.zeros((F, n), dtype=torch.uint8, device=dev)
     keep_x = torch.zeros((F, n), dtype=torch.uint8, device=dev)
+    keep_e = torch.zeros((F, n), dtype=torch.uint8, device=dev)
+    ws_e = torch.zeros(nms.nms_workspace_bytes(n, F), dtype=torch.uint8, device=dev)
     ws = torch.zeros(nms.nms_workspace_bytes(n, F), dtype=torch.uint8, device=dev)
     ws_g = torch.zeros(nms.nms_greedy_workspace_bytes(n, F), dtype=torch.uint8, device=dev)
     ws_x = torch.zeros(nms.nms_ex_workspace_bytes(n, F), dtype=torch.uint8, device=dev)
@@ -390,6 +392,7 @@ def test_calls_can_be_captured_in_a_hip_graph(nms, oracle):
         nms.nms_run_ranked_batched(boxes, scores, None, n, F, theta, keep, ws)
         nms.nms_run_greedy_batched(boxes, scores, None, n, F, theta, keep_g, ws_g)
         nms.nms_run_ex_batched(boxes, scores, None, n, F, theta, keep_x, ws_x, rule="greedy", measure="iou", pixel_offset=0.0)
+        nms.nms_run_early_exit_batched(boxes, scores, None, n, F, theta, keep_e, ws_e)
 
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -405,7 +408,7 @@ def test_calls_can_be_captured_in_a_hip_graph(nms, oracle):
         s = np.stack([frames[rep * F + f][1] for f in range(F)])
         boxes.copy_(torch.from_numpy(b))
         scores.copy_(torch.from_numpy(s))
-        keep.fill_(9), keep_g.fill_(9), keep_x.fill_(9)
+        keep.fill_(9), keep_g.fill_(9), keep_x.fill_(9), keep_e.fill_(9)
         (boxes.sum() + scores.sum()).item()  # eager work and a synchronisation between replays
         graph.replay()
         torch.cuda.synchronize()
@@ -414,5 +417,6 @@ def test_calls_can_be_captured_in_a_hip_graph(nms, oracle):
         want_x = np.stack([oracle.keep_ex(b[f], s[f], np.float32(theta), rule="greedy", measure="iou", pixel_offset=0.0)
                            for f in range(F)])
         assert np.array_equal(keep.cpu().numpy(), want), f"replay {rep}: paper rule"
+        assert np.array_equal(keep_e.cpu().numpy(), want), f"replay {rep}: paper rule, early-exit route"
         assert np.array_equal(keep_g.cpu().numpy(), want_g), f"replay {rep}: greedy rule"
         assert np.array_equal(keep_x.cpu().numpy(), want_x), f"replay {rep}: variants"
