@@ -143,10 +143,12 @@ __device__ __forceinline__ void early_stage_items(EarlyShared &sh, const EarlyWi
     constexpr int V = kEarlyItemPairs / K;
     const int groups = ((hi - lo) / kTile + K - 1) / K;  // <= 64
 
-    // lane = candidate group: where its victims begin, where those begin that all its lanes outrank, its items
+    // lane = candidate group, the last group in lane 0 (its items, most of which straddle the
+    // group and cost more, are handed out first; the stage ends on the cheap ones): where the
+    // group's victims begin, where those begin that all its lanes outrank, its items
     int p0 = 0, p1 = 0, items = 0;
     if (lane < groups) {
-        const int t0 = lo / kTile + K * lane;
+        const int t0 = lo / kTile + K * (groups - 1 - lane);
         p0 = sh.start[t0];
         p1 = sh.start[t0 + K < tiles_all ? t0 + K : tiles_all];
         items = (m + V - 1) / V - p0 / V;
@@ -168,9 +170,10 @@ __device__ __forceinline__ void early_stage_items(EarlyShared &sh, const EarlyWi
     for (int it = wave; it < total;) {
         int next = 0;
         if (lane == 0) next = __hip_atomic_fetch_add(&sh.next_item, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        const int g = __builtin_amdgcn_readfirstlane(__builtin_popcountll(__ballot(incl <= it)));
-        const int jb = __builtin_amdgcn_readlane(p0, g) / V + (it - __builtin_amdgcn_readlane(incl - items, g));
-        const int p1_g = __builtin_amdgcn_readlane(p1, g);
+        const int at = __builtin_amdgcn_readfirstlane(__builtin_popcountll(__ballot(incl <= it)));  // the group's lane
+        const int g = groups - 1 - at;
+        const int jb = __builtin_amdgcn_readlane(p0, at) / V + (it - __builtin_amdgcn_readlane(incl - items, at));
+        const int p1_g = __builtin_amdgcn_readlane(p1, at);
         const int c_lo = lo + K * kTile * g;
         const int tiles = (hi - c_lo) / kTile < K ? (hi - c_lo) / kTile : K;  // of the group that exist
         if (g != g_held) {
