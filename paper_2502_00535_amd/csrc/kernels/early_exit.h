@@ -235,8 +235,8 @@ __device__ __forceinline__ void early_exit_frame(EarlyShared &sh, const EarlyWid
     int m = m0;  // list length
     int lo = 0;
     // stages double in width, up to 64 groups of four tiles (a lane per group)
-    // a small share of a wide frame is cheap to test and every stage costs its barriers: wider steps
-    const int grow = WIDE && m0 <= 128 ? 4 : 2;
+    // a small share is cheap to test and every stage costs its barriers: wider steps
+    const int grow = (WIDE && m0 <= 128) || (!WIDE && m0 <= 256) ? 4 : 2;
     for (int bound = kEarlyFirstStage;; bound = grow * bound < bound + 64 * 4 * kTile ? grow * bound : bound + 64 * 4 * kTile) {
         const int hi = bound < staged ? bound : staged;
         const bool last = hi >= n_f;
