@@ -288,8 +288,8 @@ def test_configs_full_size(nms, oracle, index):
 
 
 def test_largest_frame(nms, oracle):
-    """n = NMS_MAX_N = 65536: sixteen rank chunks, a 512 MiB mask, sixteen blocks of the greedy
-    sweep; both rules, every keep bit.  (The two oracle runs take about half a minute; they run
+    """n = NMS_MAX_N = 65536: sixty-four rank chunks merged in four batches, a 512 MiB mask, sixteen
+    blocks of the greedy sweep, sixteen shares of the early-exit route; both rules, every keep bit.  (The two oracle runs take about half a minute; they run
     side by side on two host threads.)"""
     from concurrent.futures import ThreadPoolExecutor
 
@@ -303,7 +303,7 @@ def test_largest_frame(nms, oracle):
         want, want_g = fut.result(), fut_g.result()
     print("case n=65536: GPU running", flush=True)
     dev = DeviceFrames(nms, boxes[None], scores[None])
-    dev.fused(float(theta), want=want[None])   # automatic and ranked route (the direct one is skipped: 4.3 G pair slots)
+    dev.fused(float(theta), want=want[None])   # automatic, ranked and early-exit route (the direct one is skipped: 4.3 G pair slots)
     assert np.array_equal(dev.steps(float(theta))[0], want)
     via_steps, one_call = dev.greedy(float(theta))
     assert np.array_equal(via_steps[0], want_g) and np.array_equal(one_call[0], want_g)
