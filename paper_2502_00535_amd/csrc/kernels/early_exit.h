@@ -234,8 +234,8 @@ __device__ __forceinline__ void early_exit_frame(EarlyShared &sh, const EarlyWid
     auto rank_of = [&](int entry) __attribute__((always_inline)) { return WIDE ? part + parts * (entry >> 4) : entry >> 4; };
     int m = m0;  // list length
     int lo = 0;
-    // stages double in width, up to 64 groups of four tiles (a lane per group)
-    // a small share is cheap to test and every stage costs its barriers: wider steps
+    // Stages double in width, up to 64 groups of four tiles (a lane per group).  A small share is
+    // cheap to test and every stage costs its barriers: its stages grow fourfold.
     const int grow = (WIDE && m0 <= 128) || (!WIDE && m0 <= 256) ? 4 : 2;
     for (int bound = kEarlyFirstStage;; bound = grow * bound < bound + 64 * 4 * kTile ? grow * bound : bound + 64 * 4 * kTile) {
         const int hi = bound < staged ? bound : staged;
