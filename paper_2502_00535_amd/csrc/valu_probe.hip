@@ -49,6 +49,11 @@ __global__ void k_cnd(float *out, float a, float sb, int iters) { BODY("v_cndmas
 __global__ void k_addclamp(float *out, float a, float sb, int iters) { BODY("v_add_f32_e64 %0, 1.0, %0 clamp") }
 __global__ void k_subclamp(float *out, float a, float sb, int iters) { BODY("v_sub_f32_e64 %0, %1, %0 clamp") }
 __global__ void k_rcp(float *out, float a, float sb, int iters) { BODY("v_rcp_f32 %0, %0") }
+__global__ void k_fmaclamp(float *out, float a, float sb, int iters) { BODY("v_fma_f32 %0, %0, %1, %1 clamp") }
+__global__ void k_fmaxaa(float *out, float a, float sb, int iters) { BODY("v_fma_f32 %0, %0, %1, %1") }
+__global__ void k_fmaaxa(float *out, float a, float sb, int iters) { BODY("v_fma_f32 %0, %1, %0, %1") }
+__global__ void k_fmaxa1(float *out, float a, float sb, int iters) { BODY("v_fma_f32 %0, %0, %1, 1.0") }
+__global__ void k_madxa(float *out, float a, float sb, int iters) { BODY("v_fma_f32 %0, %1, %0, 1.0 clamp") }
 
 // float64 instructions (the variants' exact threshold compare uses a convert, a multiply and a compare)
 #define BODYD(INSTR) \
@@ -84,7 +89,7 @@ int main()
         {"v_add_f32 vv", k_add, 1}, {"v_add_f32 sv", k_add_s, 1}, {"v_min_f32 vv", k_min, 1}, {"v_min_f32 sv", k_min_s, 1},
         {"v_max_f32", k_max, 1}, {"v_mul_f32", k_mul, 1}, {"v_sub_f32", k_sub, 1}, {"v_fma_f32", k_fma, 1}, {"v_fmac_f32", k_fmac, 1},
         {"v_cmp vcc", k_cmp, 1}, {"v_cmp sgpr", k_cmp64, 1}, {"v_mov_b32", k_mov, 1}, {"v_and_b32", k_and, 1}, {"v_max3_f32", k_max3, 1},
-        {"v_add_u32", k_pkadd, 1}, {"v_rcp_f32", k_rcp, 1}, {"v_min_i32", k_mini, 1}, {"v_max_u32", k_maxu, 1}, {"v_add_f32 1.0", k_addc, 1}, {"v_and_or_b32", k_andor, 1}, {"v_fma_f32 3src", k_fma3, 1}, {"v_mul_f32 |abs|", k_mulabs, 1}, {"v_cndmask", k_cnd, 1}, {"v_add_f32 clamp", k_addclamp, 1}, {"v_sub_f32 clamp", k_subclamp, 1},
+        {"v_add_u32", k_pkadd, 1}, {"v_rcp_f32", k_rcp, 1}, {"v_min_i32", k_mini, 1}, {"v_max_u32", k_maxu, 1}, {"v_add_f32 1.0", k_addc, 1}, {"v_and_or_b32", k_andor, 1}, {"v_fma_f32 3src", k_fma3, 1}, {"v_mul_f32 |abs|", k_mulabs, 1}, {"v_cndmask", k_cnd, 1}, {"v_add_f32 clamp", k_addclamp, 1}, {"v_sub_f32 clamp", k_subclamp, 1}, {"v_fma_f32 x,a,a clamp", k_fmaclamp, 1}, {"v_fma_f32 x,a,a", k_fmaxaa, 1}, {"v_fma_f32 a,x,a", k_fmaaxa, 1}, {"v_fma_f32 x,a,1.0", k_fmaxa1, 1}, {"v_fma_f32 a,x,1.0 clamp", k_madxa, 1},
         {"v_mul_f64", k_mul64, 1}, {"v_fma_f64", k_fma64, 1}, {"v_cmp_ge_f64", k_cmpf64, 1}, {"v_cvt_f64_f32", k_cvt64, 1},
     };
     const int iters = 2000;
