@@ -293,9 +293,12 @@ int nms_run(const float *boxes, const float *scores, int n, float threshold,
 /*
  * Host-only test hook: evaluates, on the CPU, the exact arithmetic the device pair
  * test uses for "does the outranking box eliminate the victim" (all pointers HOST:
- * victim[4], outranking[4]).  Returns 1/0, or a negative status for a NaN threshold.
+ * victim[4], outranking[4]).  Every form of the test that a kernel may take for the pair is
+ * evaluated (plain fast form; y-scaled; scaled late); returns 1/0, NMS_HOST_FORMS_DISAGREE if
+ * they do not all give the same answer, or a negative status for a NaN threshold.
  * Lets the decision procedure be checked against plain division without a GPU.
  */
+#define NMS_HOST_FORMS_DISAGREE (-100)
 int nms_host_pair_test(const float *victim, const float *outranking, float threshold);
 
 #ifdef __cplusplus

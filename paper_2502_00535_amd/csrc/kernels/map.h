@@ -41,10 +41,11 @@ struct TileState {
 // elimination word of row r.  Rows go in 4 groups of 16 in a real loop, so that at
 // most 64 victim SGPRs are live at a time.
 // Which evaluation of the pair test a tile uses.
-enum { kPairExact = 0, kPairFast = 1, kPairFastYScaled = 2 };
+enum { kPairExact = 0, kPairFast = 1, kPairFastYScaled = 2, kPairFastLateScaled = 3 };
 
 // For kPairFastYScaled, vb/cb hold y * NMS_YSCALE, c_T is NMS_YSCALE * T and y_one is
-// NMS_YSCALE in a vector register.
+// NMS_YSCALE in a vector register; for kPairFastLateScaled vb/cb are the plain boxes, c_T and
+// y_one as for kPairFastYScaled.
 template <int PAIR, bool WRITE_MASK, bool DIAG>
 __device__ __forceinline__ void tile_sweep(const float4 *__restrict__ vb, const float4 cb, float c_area, float c_T,
                                            float y_one, const NmsThetaConst &th, int lane, TileState &st)
@@ -64,6 +65,8 @@ __device__ __forceinline__ void tile_sweep(const float4 *__restrict__ vb, const 
             bool hit;
             if (PAIR == kPairFastYScaled)
                 hit = nms_eliminates_fast_yscaled(v.x, v.y, v.z, v.w, cb.x, cb.y, cb.z, cb.w, c_T, y_one);
+            else if (PAIR == kPairFastLateScaled)
+                hit = nms_eliminates_fast_latescaled(v.x, v.y, v.z, v.w, cb.x, cb.y, cb.z, cb.w, c_T, y_one);
             else if (PAIR == kPairFast)
                 hit = nms_eliminates_fast(v.x, v.y, v.z, v.w, cb.x, cb.y, cb.z, cb.w, c_T);
             else
@@ -150,6 +153,12 @@ map_tile_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ c
     const float c_Ts = c_T * NMS_YSCALE;
     float y_one;  // NMS_YSCALE in a vector register (opaque to the compiler so it stays there)
     asm volatile("v_mov_b32 %0, 0x38800000" : "=v"(y_one));
+    // The mask-writing kernel without the table (the stand-alone map step), or on a tile outside
+    // the table's range: the late-scaled form, when every outranking box of this column tile is at
+    // most 2^14 high.  (Not in the fused kernel: the table form covers it, and the third variant
+    // cost it 1 % through its code size.)
+    constexpr bool kLate = FAST && WRITE_MASK;
+    const bool late_ok = kLate && __ballot(!nms_extent_fits_late_scaling(cb.y, cb.w)) == 0ull;
 
     for (; tr < tr_end; ++tr) {
         TileState st;
@@ -159,6 +168,12 @@ map_tile_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ c
                 tile_sweep<kPairFastYScaled, WRITE_MASK, true>(vb, cbs, c_area, c_Ts, y_one, th, lane, st);
             else
                 tile_sweep<kPairFastYScaled, WRITE_MASK, false>(vb, cbs, c_area, c_Ts, y_one, th, lane, st);
+        } else if (kLate && late_ok) {
+            const float4 *vb = box4 + tr * kTile;
+            if (tr == tc)
+                tile_sweep<kPairFastLateScaled, WRITE_MASK, true>(vb, cb, c_area, c_Ts, y_one, th, lane, st);
+            else
+                tile_sweep<kPairFastLateScaled, WRITE_MASK, false>(vb, cb, c_area, c_Ts, y_one, th, lane, st);
         } else {
             const float4 *vb = box4 + tr * kTile;
             if (tr == tc)

@@ -767,19 +767,24 @@ int nms_host_pair_test(const float *victim, const float *outranking, float thres
     if (!victim || !outranking || is_nan(threshold)) return NMS_ERR_INVALID_ARG;
     const NmsThetaConst th = nms_make_theta_const(threshold);
     const float a = nms_box_area(outranking[0], outranking[1], outranking[2], outranking[3]);
-    bool hit;
+    if (!th.fast)
+        return nms_eliminates_exact(victim[0], victim[1], victim[2], victim[3], outranking[0], outranking[1], outranking[2],
+                                    outranking[3], a, th.theta) ? 1 : 0;
+    // every fast form that the kernels may take for this pair; they have to agree
+    const float T = nms_pair_threshold(a, th.m);
+    const bool hit = nms_eliminates_fast(victim[0], victim[1], victim[2], victim[3],
+                                         outranking[0], outranking[1], outranking[2], outranking[3], T);
     const bool regular = nms_y_regular(victim[1]) && nms_y_regular(victim[3]) && nms_y_regular(outranking[1]) &&
                          nms_y_regular(outranking[3]);
-    if (th.fast && regular)  // what the fused kernel does for a pair of regular tiles
-        hit = nms_eliminates_fast_yscaled(victim[0], victim[1] * NMS_YSCALE, victim[2], victim[3] * NMS_YSCALE,
-                                          outranking[0], outranking[1] * NMS_YSCALE, outranking[2],
-                                          outranking[3] * NMS_YSCALE, nms_pair_threshold(a, th.m) * NMS_YSCALE, NMS_YSCALE);
-    else if (th.fast)
-        hit = nms_eliminates_fast(victim[0], victim[1], victim[2], victim[3],
-                                  outranking[0], outranking[1], outranking[2], outranking[3], nms_pair_threshold(a, th.m));
-    else
-        hit = nms_eliminates_exact(victim[0], victim[1], victim[2], victim[3],
-                                   outranking[0], outranking[1], outranking[2], outranking[3], a, th.theta);
+    if (regular &&  // what the fused kernel does for a pair of regular tiles
+        hit != nms_eliminates_fast_yscaled(victim[0], victim[1] * NMS_YSCALE, victim[2], victim[3] * NMS_YSCALE,
+                                           outranking[0], outranking[1] * NMS_YSCALE, outranking[2],
+                                           outranking[3] * NMS_YSCALE, T * NMS_YSCALE, NMS_YSCALE))
+        return NMS_HOST_FORMS_DISAGREE;
+    if (nms_extent_fits_late_scaling(outranking[1], outranking[3]) &&
+        hit != nms_eliminates_fast_latescaled(victim[0], victim[1], victim[2], victim[3], outranking[0], outranking[1],
+                                              outranking[2], outranking[3], T * NMS_YSCALE, NMS_YSCALE))
+        return NMS_HOST_FORMS_DISAGREE;
     return hit ? 1 : 0;
 }
 

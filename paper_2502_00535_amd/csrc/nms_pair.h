@@ -136,6 +136,32 @@ NMS_HD bool nms_eliminates_fast_yscaled(float vx1, float vy1s, float vx2, float 
     return iw * ihs >= c_Ts;
 }
 
+// ---- fast form, scaled late ------------------------------------------------------------
+// Where no y-scaled table exists (or a tile is outside its range) the half-rate floor can
+// still be avoided: ih = (min - max) + 1 as defined, then ih * NMS_YSCALE with the clamp
+// modifier (full rate) instead of max(0, ih).  Scaling by a power of two is exact, a negative
+// extent clamps to 0 as the floor would make it, and the product is compared with
+// NMS_YSCALE * T.  The clamp's upper end must not bite: ih never exceeds the outranking box's
+// own extent (y2_c - y1_c) + 1 (every step of both is monotone), so it is enough that this
+// extent is at most 2^14 -- a condition on the outranking box alone.  (An extent below 2^-112,
+// whose scaled value would leave the normal range, gives a product far below any T either way.)
+// Costs one full-rate instruction more than the y-scaled table form, one half-rate
+// instruction less than the plain fast form.
+NMS_HD bool nms_extent_fits_late_scaling(float cy1, float cy2)
+{
+    return (cy2 - cy1) + 1.0f <= 16384.0f;
+}
+
+// c_Ts = NMS_YSCALE * T, y_scale = NMS_YSCALE (a parameter for the same reason as y_one above).
+NMS_HD bool nms_eliminates_fast_latescaled(float vx1, float vy1, float vx2, float vy2,
+                                           float cx1, float cy1, float cx2, float cy2, float c_Ts, float y_scale)
+{
+    float iw = (fminf(vx2, cx2) - fmaxf(vx1, cx1)) + 1.0f;
+    float ih = (fminf(vy2, cy2) - fmaxf(vy1, cy1)) + 1.0f;
+    float ihs = fminf(fmaxf(ih * y_scale, 0.0f), 1.0f);  // folds into the multiply as its clamp modifier
+    return iw * ihs >= c_Ts;
+}
+
 // Area of a box, pixel-inclusive (Algorithm 1's first assignment, one extent per axis).
 NMS_HD float nms_box_area(float x1, float y1, float x2, float y2)
 {

@@ -184,3 +184,39 @@ def test_magnitudes_from_tiny_to_two_to_the_forty(nms):
             checked += 1
             hits += want
     assert checked > 30000 and 5000 < hits < checked - 5000
+
+
+def test_late_scaled_form_at_the_edge_of_its_range(nms):
+    """The form that multiplies the y extent by 2^-14 with a clamp instead of flooring it is taken
+    when the outranking box is at most 2^14 high (pixel-inclusive); the hook evaluates it next to
+    the plain fast form whenever it applies and reports a disagreement.  Heights on both sides of
+    the limit, victims taller and shorter than the outranking box, y far outside the y-scaled
+    table's range, extents that barely exist, thresholds at the overlap and its neighbours."""
+    rng = np.random.default_rng(314)
+    checked = hits = 0
+    for i in range(8000):
+        height = [16382.0, 16383.0, 16384.0, 16385.0, 12000.0, 40000.0, 3.0][i % 7]   # (y2 - y1); the extent is one more
+        cy1 = float(np.float32(rng.uniform(-60000, 60000)))
+        c = np.array([rng.uniform(-500, 500), cy1, rng.uniform(500, 900), cy1 + height], np.float32)
+        vh = rng.uniform(1, 50000)
+        vy1 = cy1 + rng.uniform(-1.0, 1.0) * height
+        v = np.array([rng.uniform(-500, 500), vy1, rng.uniform(500, 900), vy1 + vh], np.float32)
+        _, q = plain_decision(v, c, np.float32(0.5))
+        for theta in (np.float32(0.5), q, steps(q, 1), steps(q, -1)):
+            if not (theta >= 2.0 ** -40):
+                continue
+            want, _ = plain_decision(v, c, theta)
+            got = nms.nms_host_pair_test(v, c, float(theta))
+            assert got == want, f"v={v.tolist()} c={c.tolist()} theta={theta!r} got {got}"
+            checked += 1
+            hits += want
+    assert checked > 20000 and 2000 < hits < checked - 2000
+    # the victim spans the whole outranking box, which is exactly 2^14 high: the scaled extent is exactly 1
+    assert nms.nms_host_pair_test([0, -100, 99, 30000], [0, 0, 99, 16383], 1.0) == 1
+    assert nms.nms_host_pair_test([0, -100, 99, 30000], [0, 0, 99, 16383], float(np.nextafter(np.float32(1), np.float32(2)))) == 0
+    # extents that barely exist or do not
+    e = np.float32(1) - np.float32(2.0 ** -24)
+    for theta in (2.0 ** -30, 1e-6, 0.5):
+        assert nms.nms_host_pair_test([0, 0, 9, 100], [0, float(100 + e), 9, 200], theta) == plain_decision(
+            np.array([0, 0, 9, 100], np.float32), np.array([0, float(100 + e), 9, 200], np.float32), np.float32(theta))[0]
+        assert nms.nms_host_pair_test([0, 0, 9, 100], [0, 101, 9, 200], theta) == 0
