@@ -163,9 +163,10 @@ int map_launch(const float *sorted5, const int32_t *counts, int n_max, int frame
 {
     const int n_pad = nms_padded_n(n_max);
     const int T = n_pad / kTile;
-    // four tiles per wavefront when that still leaves every SIMD several wavefronts
+    // four (or two) tiles per wavefront when that still leaves every SIMD several wavefronts
     const bool super4 = (long long)frames * triangle_units(T, 4) >= 16384;
-    const int tiles = triangle_units(T, super4 ? 4 : 1);  // work units, one per wavefront
+    const bool super2 = !super4 && (long long)frames * triangle_units(T, 2) >= 16384;
+    const int tiles = triangle_units(T, super4 ? 4 : (super2 ? 2 : 1));  // work units, one per wavefront
     const NmsThetaConst th = nms_make_theta_const(threshold);
     const int tile_blocks = (tiles + kMapWaves - 1) / kMapWaves;
     // batches: one frame per XCD at a time (see the kernel); a few large frames: spread each over all XCDs
@@ -178,9 +179,9 @@ int map_launch(const float *sorted5, const int32_t *counts, int n_max, int frame
                                                                            tile_blocks, frames, xcd_frames, th,   \
                                                                            mask, order, keep_out, ysc, ytile)
     if (th.fast) {
-        if (super4) NMS_LAUNCH_MAP(true, 4); else NMS_LAUNCH_MAP(true, 1);
+        if (super4) NMS_LAUNCH_MAP(true, 4); else if (super2) NMS_LAUNCH_MAP(true, 2); else NMS_LAUNCH_MAP(true, 1);
     } else {
-        if (super4) NMS_LAUNCH_MAP(false, 4); else NMS_LAUNCH_MAP(false, 1);
+        if (super4) NMS_LAUNCH_MAP(false, 4); else if (super2) NMS_LAUNCH_MAP(false, 2); else NMS_LAUNCH_MAP(false, 1);
     }
 #undef NMS_LAUNCH_MAP
     return launch_status();
