@@ -241,9 +241,12 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
 // plus the number of smaller keys in every other chunk (keys are unique, so ranks are too).
 // The binary searches in the other chunks advance together, kMergeBatch chunks at a time, a
 // fixed number of steps: the loads of one step do not depend on each other, so a thread waits
-// for log2(chunk) + 1 round trips to memory however many chunks there are.
+// for log2(chunk) + 1 round trips to memory however many chunks there are.  Four neighbouring
+// lanes share an element (each takes every fourth chunk, the counts are summed across the four):
+// a single large frame then fills the chip with workgroups instead of a quarter of it.
 constexpr int kMergeChunk = 1024;
-constexpr int kMergeBatch = 16;
+constexpr int kMergeBatch = 16;   // chunks searched together by the four lanes of an element
+constexpr int kMergeLanes = 4;
 
 __global__ void __launch_bounds__(256)
 rank_merge_kernel(const float *__restrict__ boxes, const int32_t *__restrict__ counts, int n_max, int n_pad,
@@ -251,26 +254,29 @@ rank_merge_kernel(const float *__restrict__ boxes, const int32_t *__restrict__ c
                   int32_t *__restrict__ order, float *__restrict__ sorted5,
                   float4 *__restrict__ ysc, unsigned *__restrict__ ytile)
 {
+    constexpr int kMine = kMergeBatch / kMergeLanes;  // chunks of a batch per lane
     const int f = blockIdx.y;
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    const int thread = blockIdx.x * blockDim.x + threadIdx.x;
+    const int e = thread / kMergeLanes;   // n_pad is a multiple of 64: the four lanes of an element leave together
+    const int q = thread % kMergeLanes;
     const int n_f = frame_count(counts, f, n_max);
     const unsigned long long *kw = keys_ws + (size_t)f * n_pad;
     if (e >= n_pad) return;
     float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
     float4 *ysc_f = ysc ? ysc + (size_t)f * n_pad : nullptr;
     if (e >= n_f) {
-        emit_padding_row(e, n_pad, sorted_f, ysc_f);
+        if (q == 0) emit_padding_row(e, n_pad, sorted_f, ysc_f);
         return;
     }
     const unsigned long long key = kw[e];
     const int own = e / kMergeChunk;
-    int rank = e - own * kMergeChunk;
+    int rank = 0;
     for (int c0 = 0; c0 < n_chunks; c0 += kMergeBatch) {
-        int below[kMergeBatch];  // keys of chunk c0 + k known to be smaller than `key`
-        int cnt[kMergeBatch];
+        int below[kMine];  // keys of this lane's k-th chunk of the batch known to be smaller than `key`
+        int cnt[kMine];
 #pragma unroll
-        for (int k = 0; k < kMergeBatch; ++k) {
-            const int c = c0 + k;
+        for (int k = 0; k < kMine; ++k) {
+            const int c = c0 + kMergeLanes * k + q;
             int left = n_f - c * kMergeChunk;
             left = left < 0 ? 0 : (left > kMergeChunk ? kMergeChunk : left);
             cnt[k] = (c < n_chunks && c != own) ? left : 0;
@@ -280,18 +286,23 @@ rank_merge_kernel(const float *__restrict__ boxes, const int32_t *__restrict__ c
         // a probe that would leave the chunk reads this thread's own key instead (never smaller)
 #pragma unroll 1
         for (int step = kMergeChunk; step > 0; step >>= 1) {
-            unsigned long long probe[kMergeBatch];
+            unsigned long long probe[kMine];
 #pragma unroll
-            for (int k = 0; k < kMergeBatch; ++k) {
+            for (int k = 0; k < kMine; ++k) {
                 const int at = below[k] + step;
-                probe[k] = kw[at <= cnt[k] ? (c0 + k) * kMergeChunk + at - 1 : e];
+                probe[k] = kw[at <= cnt[k] ? (c0 + kMergeLanes * k + q) * kMergeChunk + at - 1 : e];
             }
 #pragma unroll
-            for (int k = 0; k < kMergeBatch; ++k) below[k] += probe[k] < key ? step : 0;
+            for (int k = 0; k < kMine; ++k) below[k] += probe[k] < key ? step : 0;
         }
 #pragma unroll
-        for (int k = 0; k < kMergeBatch; ++k) rank += below[k];
+        for (int k = 0; k < kMine; ++k) rank += below[k];
     }
+    rank += __shfl_xor(rank, 1);
+    rank += __shfl_xor(rank, 2);
+    if (kMergeLanes > 4) rank += __shfl_xor(rank, 4);
+    if (q != 0) return;
+    rank += e - own * kMergeChunk;
     const int idx = (int)(unsigned)key;
     const bool regular = emit_ranked_box(reinterpret_cast<const float4 *>(boxes + (size_t)f * n_max * 4)[idx], idx, rank,
                                          n_pad, order + (size_t)f * n_max, sorted_f, ysc_f);

@@ -120,7 +120,7 @@ int rank_launch(const float *boxes, const float *scores, const int32_t *counts, 
     int st = launch_status();
     if (st != NMS_OK || n_chunks == 1) return st;
     begin_launch();
-    rank_merge_kernel<<<dim3((n_pad + 255) / 256, frames), dim3(256), 0, stream>>>(
+    rank_merge_kernel<<<dim3((n_pad * kMergeLanes + 255) / 256, frames), dim3(256), 0, stream>>>(
         boxes, counts, n_max, n_pad, n_chunks, keys_ws, order, sorted5, ysc, ytile);
     return launch_status();
 }
