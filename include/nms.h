@@ -148,7 +148,7 @@ int nms_run_batched(const float *boxes, const float *scores, const int32_t *coun
  *   direct  one launch, no workspace: Algorithm 1 on the full n x n grid of the unsorted
  *           input with the score guard evaluated per pair, row AND finished in the
  *           workgroup.  About 2.5x the arithmetic, so it is chosen only where launch
- *           latency dominates (n_max <= 4096 and frames * n_max^2 <= 2^25).
+ *           latency dominates (n_max <= 4096 and frames * n_max^2 up to about 2^25).
  * Both give the same keep_out as nms_run_batched, bit for bit, for any sizes.
  */
 int nms_run_ranked_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,

@@ -128,9 +128,14 @@ int rank_launch(const float *boxes, const float *scores, const int32_t *counts, 
 // Frames small enough that launch latency, not arithmetic, decides: one launch of the
 // direct form instead of rank + map.  (Twice the pairs and two more compares per pair:
 // about 2.5x the VALU work of the ranked triangle.)
+// The crossover in GPU time sits near 2^25 pair slots per batch and moves with the frame size,
+// because the rank step it saves does (15 us at 1024 boxes, 23 us at 4096): measured 24 to 32
+// frames of 1024 boxes, 8 to 12 of 2048, 3 to 4 of 4096.
 inline bool use_direct_form(int n_max, int frames)
 {
-    return n_max <= 4096 && (long long)frames * n_max * n_max <= (1ll << 25);
+    const long long slots = (long long)frames * n_max * n_max;
+    const long long limit = n_max > 2048 ? (3ll << 24) : (n_max > 512 && n_max <= 1024 ? (3ll << 23) : (1ll << 25));
+    return n_max <= 4096 && slots <= limit;
 }
 
 int direct_launch(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
