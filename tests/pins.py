@@ -29,8 +29,8 @@ GOLDEN_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 # --------------------------------------------------------------------------- golden files
 
 def parse_golden(path):
-    case = {"boxes": [], "scores": [], "overlaps": [], "keep": None, "greedy": None,
-            "literal_keep": None, "theta": None, "path": path}
+    case = {"boxes": [], "scores": [], "overlaps": [], "overlaps_f32": [], "areas_f32": [], "keep": None,
+            "greedy": None, "literal_keep": None, "theta": None, "path": path}
     with open(path) as fh:
         for raw in fh:
             line = raw.split("#", 1)[0].strip()
@@ -46,9 +46,20 @@ def parse_golden(path):
             elif tok[0] == "box":
                 case["boxes"].append([float(v) for v in tok[1:5]])
                 case["scores"].append(float(tok[5]))
+                assert np.float32(case["boxes"][-1]).astype(np.float64).tolist() == case["boxes"][-1], \
+                    f"{path}: a coordinate is not a float32"
             elif tok[0] == "overlap":
                 p, q = tok[3].split("/")
                 case["overlaps"].append((int(tok[1]), int(tok[2]), int(p), int(q)))
+            elif tok[0] == "overlap_f32":
+                # the float32 the measure must come out as, written as a C99 hexadecimal literal
+                value = float.fromhex(tok[3])
+                assert float(np.float32(value)) == value, f"{path}: {tok[3]} is not a float32"
+                case["overlaps_f32"].append((int(tok[1]), int(tok[2]), np.float32(value)))
+            elif tok[0] == "area_f32":
+                value = float.fromhex(tok[2])
+                assert float(np.float32(value)) == value, f"{path}: {tok[2]} is not a float32"
+                case["areas_f32"].append((int(tok[1]), np.float32(value)))
             elif tok[0] in ("keep", "greedy", "literal_keep"):
                 case[tok[0]] = np.array([int(v) for v in tok[1:]], dtype=np.uint8)
             else:
@@ -74,6 +85,12 @@ def pin_golden(oracle):
             assert got == want, f"{name}: overlap({i}|{j}) = {got}, hand value {p}/{q}"
             assert oracle.outranks(s, j, i), f"{name}: {j} should outrank {i}"
             assert not oracle.outranks(s, i, j), f"{name}: {i} should not outrank {j}"
+        for (i, j, want) in case["overlaps_f32"]:
+            got = oracle.overlap(b[i], b[j])
+            assert got == want, f"{name}: overlap({i}|{j}) = {float(got).hex()}, hand value {float(want).hex()}"
+        for (i, want) in case["areas_f32"]:
+            got = oracle.area(b[i])
+            assert got == want, f"{name}: area({i}) = {float(got).hex()}, hand value {float(want).hex()}"
         keep = oracle.keep(b, s, th)
         assert keep.tolist() == case["keep"].tolist(), f"{name}: keep {keep.tolist()}"
         via_matrix = oracle.reduce(oracle.map(b, s, th))
@@ -94,23 +111,26 @@ def pin_golden(oracle):
 # --------------------------------------------------------------------------- exact rational model
 
 def f32_round(x: Fraction) -> Fraction:
-    """Round a non-negative rational to the nearest float32 (ties to even),
-    returned as a rational.  Normal range only."""
+    """Round a rational to the nearest float32 (ties to even), returned as a
+    rational.  Either sign; below the normal range the spacing stays 2^-149."""
     if x == 0:
         return Fraction(0)
-    assert x > 0
+    if x < 0:
+        return -f32_round(-x)
     e = 0
     while x >= Fraction(2) ** (e + 1):
         e += 1
     while x < Fraction(2) ** e:
         e -= 1
-    assert -126 <= e <= 127
+    e = max(e, -126)
     ulp = Fraction(2) ** (e - 23)
     k, rem = divmod(x, ulp)
     k = int(k)
     if rem > ulp / 2 or (rem == ulp / 2 and (k & 1)):
         k += 1
-    return k * ulp
+    out = k * ulp
+    assert out < Fraction(2) ** 128, "beyond the float32 range"
+    return out
 
 
 def exact_overlap(bi, bj) -> Fraction:
@@ -354,9 +374,10 @@ ALL_PINS = [
 
 
 def _with_variants():
-    from pins_variants import VARIANT_PINS  # imports f32_round from this module: resolved lazily
+    from pins_rounding import ROUNDING_PINS  # both import f32_round from this module: resolved lazily
+    from pins_variants import VARIANT_PINS
 
-    return VARIANT_PINS
+    return VARIANT_PINS + ROUNDING_PINS
 
 
 ALL_PINS = ALL_PINS + _with_variants()

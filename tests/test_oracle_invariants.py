@@ -1,8 +1,10 @@
 """Properties of the paper's rule that hold for every input (no GPU).
 
 Each property is checked on the oracle's output with the pair tests recomputed
-here in float32 numpy (a second, vectorised evaluation of the same definitions;
-it shares nothing with the oracle's C code).
+here in float32 numpy.  That recomputation repeats the formula, so it says nothing
+about the formula itself or its rounding order (tests/pins.py and
+tests/pins_rounding.py pin those against hand-worked values and an exact model);
+what this file adds are the properties: witnesses, containments, invariances.
 """
 import numpy as np
 import pytest
