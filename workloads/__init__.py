@@ -13,4 +13,5 @@ from .synth import (  # noqa: F401
     anchor_frame,
     make_config,
     random_frame,
+    scores_of_every_kind,
 )

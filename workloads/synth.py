@@ -187,6 +187,26 @@ def random_frame(seed, n, extent=256, max_side=64, integer=True, score_levels=0)
     return boxes, scores
 
 
+def scores_of_every_kind(seed, n):
+    """Scores as a detector may emit them before any squashing (raw logits): negative and
+    positive values over many magnitudes, both zeros, denormals of both signs, both
+    infinities, and exact ties among all of these.  No NaN."""
+    rng = np.random.default_rng(seed)
+    tiny = np.float32(1e-45)  # the smallest positive denormal
+    palette = np.array([0.0, -0.0, 1.0, -1.0, np.inf, -np.inf, tiny, -tiny, 3 * tiny, -3 * tiny, 1e-39, -1e-39,
+                        1.1754944e-38, -1.1754944e-38, 3.4028235e38, -3.4028235e38, 0.5, -0.5], np.float32)
+    kind = rng.integers(0, 4, n)
+    scores = np.empty(n, np.float32)
+    scores[:] = rng.normal(0.0, 4.0, n).astype(np.float32)                      # logits
+    wide = (rng.normal(0.0, 1.0, n) * np.exp2(rng.integers(-140, 120, n).astype(np.float64))).astype(np.float32)
+    scores[kind == 1] = wide[kind == 1]                                        # every magnitude incl. denormals
+    scores[kind == 2] = palette[rng.integers(0, palette.shape[0], n)][kind == 2]  # special values, many ties
+    tie = kind == 3                                                            # exact copies of other boxes' scores
+    scores[tie] = scores[rng.integers(0, n, n)][tie]
+    assert not np.any(np.isnan(scores))
+    return scores
+
+
 def make_config(index: int, frames: int | None = None) -> Workload:
     """Build configuration ``index`` (0..4).  ``frames`` truncates the batched
     configurations (2 and 4) to their first frames; it is ignored elsewhere."""
