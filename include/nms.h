@@ -68,6 +68,8 @@ extern "C" {
                                             (about 8,000 frames of 16,384 boxes, 500 of 65,536) */
 #define NMS_SORT_CHUNK 4096      /* boxes ranked by one workgroup in LDS */
 #define NMS_MAX_MATRIX 16384     /* largest capacity of the byte-matrix form (256 MiB of B) */
+#define NMS_STATIC_SCRATCH_BYTES 4194304  /* scratch that the library itself holds on every GPU it is loaded on (4 MiB),
+                                             used by nms_run_static_batched only */
 
 typedef enum {
     NMS_OK = 0,
@@ -289,6 +291,27 @@ int nms_init(int n_max, int frames_max, void *workspace, size_t ws_bytes);
 int nms_shutdown(void);
 int nms_run(const float *boxes, const float *scores, int n, float threshold,
             uint8_t *keep_out, void *stream);
+
+/*
+ * nms_run_batched for callers that cannot allocate or bring scratch: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace is a static
+ * device array of NMS_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, resident from
+ * the time the library is loaded there until the process ends); the call makes no allocation
+ * of any kind.  Same result as nms_run_batched, bit for bit; the caller still passes inputs
+ * and keep_out.
+ *   sizes    nms_workspace_bytes(n_max, frames) must not exceed NMS_STATIC_SCRATCH_BYTES, else
+ *            NMS_ERR_TOO_LARGE and nothing is enqueued.  That admits any single frame the library
+ *            takes (65,536 boxes: 3.0 MiB), 4 frames of 16,384 boxes, 25 of 4096, 102 of 1024.
+ *   sharing  every call on a GPU uses that GPU's one array, which keeps the previous call's
+ *            contents (nothing in it has to start at zero: each call writes what it reads).
+ *            Calls on the same GPU must therefore be ordered on one stream; calls that overlap
+ *            race.  Calls on different GPUs are independent (the current device selects the copy).
+ *   set-up   the first call on a device looks up the array's address (hipGetSymbolAddress,
+ *            once per device, under a lock); make that call outside graph capture.
+ * Other arguments, layout, ownership and errors as nms_run_batched.
+ */
+int nms_run_static_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                           float threshold, uint8_t *keep_out, void *stream);
 
 /*
  * Host-only test hook: evaluates, on the CPU, the exact arithmetic the device pair

@@ -17,7 +17,7 @@ _BINDING_NAMES = (
     "nms_reduce", "nms_reduce_batched", "nms_run_ws", "nms_run_batched", "nms_run_ranked_batched", "nms_run_direct_batched",
     "nms_run_batched_profiled", "nms_reduce_greedy", "nms_reduce_greedy_batched",
     "nms_greedy_workspace_bytes", "nms_run_greedy_batched", "nms_run_greedy_fused_batched", "nms_run_early_exit_batched", "nms_map_matrix", "nms_reduce_matrix", "nms_ex_workspace_bytes", "nms_run_ex_batched", "NmsOptions",
-    "nms_init", "nms_shutdown", "nms_run",
+    "nms_init", "nms_shutdown", "nms_run", "nms_run_static_batched", "NMS_STATIC_SCRATCH_BYTES",
 )
 
 __all__ = list(_BINDING_NAMES)

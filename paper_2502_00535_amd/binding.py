@@ -26,7 +26,7 @@ EXPORTS = (
     "nms_run_batched_profiled", "nms_reduce_greedy", "nms_reduce_greedy_batched",
     "nms_greedy_workspace_bytes", "nms_run_greedy_batched", "nms_run_greedy_fused_batched", "nms_run_early_exit_batched", "nms_map_matrix", "nms_reduce_matrix",
     "nms_ex_workspace_bytes", "nms_run_ex_batched",
-    "nms_init", "nms_shutdown", "nms_run", "nms_host_pair_test",
+    "nms_init", "nms_shutdown", "nms_run", "nms_run_static_batched", "nms_host_pair_test",
 )
 
 
@@ -128,6 +128,8 @@ def _load() -> ctypes.CDLL:
     L.nms_shutdown.argtypes = []
     L.nms_run.restype = i32
     L.nms_run.argtypes = [vp, vp, i32, f32, vp, vp]
+    L.nms_run_static_batched.restype = i32
+    L.nms_run_static_batched.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp]
     L.nms_host_pair_test.restype = i32
     L.nms_host_pair_test.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float), f32]
     return L
@@ -387,3 +389,13 @@ def nms_shutdown():
 def nms_run(boxes, scores, n, threshold, keep_out, stream=None):
     _check(lib.nms_run(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"), int(n),
                        float(threshold), _ptr(keep_out, "uint8", "keep_out"), _stream(stream)), "nms_run")
+
+
+NMS_STATIC_SCRATCH_BYTES = 4194304
+
+
+def nms_run_static_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, stream=None):
+    _check(lib.nms_run_static_batched(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
+                                      _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
+                                      _ptr(keep_out, "uint8", "keep_out"), _stream(stream)),
+           "nms_run_static_batched")

@@ -20,10 +20,16 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "../../include/nms.h"
 #include "nms_pair.h"
+
+// Scratch of nms_run_static_batched: one copy per GPU, held from the moment the library is
+// loaded on it until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; the address the kernels use is static_scratch_on_current_device().
+static __device__ __align__(256) unsigned char scratch[NMS_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -766,6 +772,47 @@ int nms_run(const float *boxes, const float *scores, int n, float threshold, uin
     if (n == 0) return NMS_OK;
     if (!g_pool.ws || n > g_pool.n_max) return NMS_ERR_WORKSPACE;
     return nms_run_batched(boxes, scores, nullptr, n, 1, threshold, keep_out, g_pool.ws, g_pool.bytes, stream);
+}
+
+// Device address of `scratch` on the current GPU, looked up once per device.
+static int static_scratch_on_current_device(void **out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex lock;
+    static void *address[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { g_last_hip_error = e; return NMS_ERR_LAUNCH; }
+    if (dev < 0 || dev >= kMaxDevices) return NMS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> hold(lock);
+    if (address[dev] == nullptr) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || p == nullptr) {
+            g_last_hip_error = e != hipSuccess ? e : hipErrorInvalidSymbol;
+            (void)hipGetLastError();
+            return NMS_ERR_LAUNCH;
+        }
+        address[dev] = p;
+    }
+    *out = address[dev];
+    return NMS_OK;
+}
+
+int nms_run_static_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                           float threshold, uint8_t *keep_out, void *stream)
+{
+    int st;
+    if (!sizes_ok(n_max, frames, &st)) return st;
+    if (is_nan(threshold)) return NMS_ERR_INVALID_ARG;
+    if (n_max == 0 || frames == 0) return NMS_OK;
+    if (!boxes || !scores || !keep_out) return NMS_ERR_INVALID_ARG;
+    if (nms_workspace_bytes(n_max, frames) > (size_t)NMS_STATIC_SCRATCH_BYTES) return NMS_ERR_TOO_LARGE;
+    void *ws = nullptr;
+    st = static_scratch_on_current_device(&ws);
+    if (st != NMS_OK) return st;
+    return run_routed(kRouteAuto, boxes, scores, counts, n_max, frames, threshold, keep_out, ws,
+                      (size_t)NMS_STATIC_SCRATCH_BYTES, stream, nullptr);
 }
 
 int nms_host_pair_test(const float *victim, const float *outranking, float threshold)
