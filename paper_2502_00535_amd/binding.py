@@ -140,21 +140,39 @@ lib = _load()
 
 # ------------------------------------------------------------------ marshalling helpers
 
-def _ptr(t, dtype_name: str | None, what: str):
-    """Device pointer of a contiguous CUDA/HIP tensor (None -> NULL)."""
+def _on_device(t) -> bool:
+    return t.is_cuda
+
+
+def _ptr(t, dtype_name: str | None, what: str, need: int = 0):
+    """Device pointer of a contiguous CUDA/HIP tensor (None -> NULL).  `need` is the number
+    of elements the library will read or write there: the C ABI takes bare pointers and
+    cannot know a buffer's size, so a tensor that is too small is refused here, before a
+    kernel could run past its end."""
     if t is None:
         return None
     import torch
 
     if not isinstance(t, torch.Tensor):
         raise TypeError(f"{what}: expected a torch tensor")
-    if not t.is_cuda:
+    if t.numel() < need:
+        raise ValueError(f"{what}: {t.numel()} elements, the call needs {need}")
+    if not _on_device(t):
         raise ValueError(f"{what}: tensor must live on the GPU")
     if not t.is_contiguous():
         raise ValueError(f"{what}: tensor must be contiguous")
     if dtype_name is not None and str(t.dtype) != f"torch.{dtype_name}":
         raise TypeError(f"{what}: expected dtype {dtype_name}, got {t.dtype}")
     return ctypes.c_void_p(t.data_ptr())
+
+
+def _sizes(n_max, frames):
+    """Element counts of the per-frame buffers for a batch: (frames * n_max, frames * n_pad,
+    frames * mask words); zeros when the library will refuse the sizes anyway."""
+    n_max, frames = int(n_max), int(frames)
+    if n_max < 0 or frames < 0:
+        return 0, 0, 0
+    return frames * n_max, frames * int(lib.nms_padded_n(n_max)), frames * int(lib.nms_mask_words(n_max))
 
 
 def _ws(t):
@@ -211,54 +229,62 @@ def nms_host_pair_test(victim, outranking, threshold: float) -> int:
 # ------------------------------------------------------------------ device entry points
 
 def nms_sort(boxes, scores, n, order, sorted5, workspace=None, stream=None):
+    fn_, fp_, fm_ = _sizes(n, 1)
     w, wb = _ws(workspace)
-    _check(lib.nms_sort(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"), int(n),
-                        _ptr(order, "int32", "order"), _ptr(sorted5, "float32", "sorted5"),
+    _check(lib.nms_sort(_ptr(boxes, "float32", "boxes", 4 * fn_), _ptr(scores, "float32", "scores", fn_), int(n),
+                        _ptr(order, "int32", "order", fn_), _ptr(sorted5, "float32", "sorted5", 5 * fp_),
                         w, wb, _stream(stream)), "nms_sort")
 
 
 def nms_sort_batched(boxes, scores, counts, n_max, frames, order, sorted5, workspace=None, stream=None):
+    fn_, fp_, fm_ = _sizes(n_max, frames)
     w, wb = _ws(workspace)
-    _check(lib.nms_sort_batched(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
-                                _ptr(counts, "int32", "counts"), int(n_max), int(frames),
-                                _ptr(order, "int32", "order"), _ptr(sorted5, "float32", "sorted5"),
+    _check(lib.nms_sort_batched(_ptr(boxes, "float32", "boxes", 4 * fn_), _ptr(scores, "float32", "scores", fn_),
+                                _ptr(counts, "int32", "counts", int(frames)), int(n_max), int(frames),
+                                _ptr(order, "int32", "order", fn_), _ptr(sorted5, "float32", "sorted5", 5 * fp_),
                                 w, wb, _stream(stream)), "nms_sort_batched")
 
 
 def nms_overlap_mask(sorted5, n, threshold, mask, stream=None):
-    _check(lib.nms_overlap_mask(_ptr(sorted5, "float32", "sorted5"), int(n), float(threshold),
-                                _ptr(mask, "int64", "mask"), _stream(stream)), "nms_overlap_mask")
+    fn_, fp_, fm_ = _sizes(n, 1)
+    _check(lib.nms_overlap_mask(_ptr(sorted5, "float32", "sorted5", 5 * fp_), int(n), float(threshold),
+                                _ptr(mask, "int64", "mask", fm_), _stream(stream)), "nms_overlap_mask")
 
 
 def nms_overlap_mask_batched(sorted5, counts, n_max, frames, threshold, mask, stream=None):
-    _check(lib.nms_overlap_mask_batched(_ptr(sorted5, "float32", "sorted5"), _ptr(counts, "int32", "counts"),
+    fn_, fp_, fm_ = _sizes(n_max, frames)
+    _check(lib.nms_overlap_mask_batched(_ptr(sorted5, "float32", "sorted5", 5 * fp_), _ptr(counts, "int32", "counts", int(frames)),
                                         int(n_max), int(frames), float(threshold),
-                                        _ptr(mask, "int64", "mask"), _stream(stream)), "nms_overlap_mask_batched")
+                                        _ptr(mask, "int64", "mask", fm_), _stream(stream)), "nms_overlap_mask_batched")
 
 
 def nms_reduce(mask, order, n, keep_out, stream=None):
-    _check(lib.nms_reduce(_ptr(mask, "int64", "mask"), _ptr(order, "int32", "order"), int(n),
-                          _ptr(keep_out, "uint8", "keep_out"), _stream(stream)), "nms_reduce")
+    fn_, fp_, fm_ = _sizes(n, 1)
+    _check(lib.nms_reduce(_ptr(mask, "int64", "mask", fm_), _ptr(order, "int32", "order", fn_), int(n),
+                          _ptr(keep_out, "uint8", "keep_out", fn_), _stream(stream)), "nms_reduce")
 
 
 def nms_reduce_batched(mask, order, counts, n_max, frames, keep_out, stream=None):
-    _check(lib.nms_reduce_batched(_ptr(mask, "int64", "mask"), _ptr(order, "int32", "order"),
-                                  _ptr(counts, "int32", "counts"), int(n_max), int(frames),
-                                  _ptr(keep_out, "uint8", "keep_out"), _stream(stream)), "nms_reduce_batched")
+    fn_, fp_, fm_ = _sizes(n_max, frames)
+    _check(lib.nms_reduce_batched(_ptr(mask, "int64", "mask", fm_), _ptr(order, "int32", "order", fn_),
+                                  _ptr(counts, "int32", "counts", int(frames)), int(n_max), int(frames),
+                                  _ptr(keep_out, "uint8", "keep_out", fn_), _stream(stream)), "nms_reduce_batched")
 
 
 def nms_run_ws(boxes, scores, n, threshold, keep_out, workspace, stream=None):
+    fn_, fp_, fm_ = _sizes(n, 1)
     w, wb = _ws(workspace)
-    _check(lib.nms_run_ws(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"), int(n),
-                          float(threshold), _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream)),
+    _check(lib.nms_run_ws(_ptr(boxes, "float32", "boxes", 4 * fn_), _ptr(scores, "float32", "scores", fn_), int(n),
+                          float(threshold), _ptr(keep_out, "uint8", "keep_out", fn_), w, wb, _stream(stream)),
            "nms_run_ws")
 
 
 def nms_run_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, stream=None):
+    fn_, fp_, fm_ = _sizes(n_max, frames)
     w, wb = _ws(workspace)
-    _check(lib.nms_run_batched(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
-                               _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
-                               _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream)), "nms_run_batched")
+    _check(lib.nms_run_batched(_ptr(boxes, "float32", "boxes", 4 * fn_), _ptr(scores, "float32", "scores", fn_),
+                               _ptr(counts, "int32", "counts", int(frames)), int(n_max), int(frames), float(threshold),
+                               _ptr(keep_out, "uint8", "keep_out", fn_), w, wb, _stream(stream)), "nms_run_batched")
 
 
 class RunPlan:
@@ -273,9 +299,10 @@ class RunPlan:
     def __init__(self, boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, stream=None):
         self._keepalive = (boxes, scores, counts, keep_out, workspace)
         w, wb = _ws(workspace)
-        self._args = (_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
-                      _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
-                      _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream))
+        fn_, _, _ = _sizes(n_max, frames)
+        self._args = (_ptr(boxes, "float32", "boxes", 4 * fn_), _ptr(scores, "float32", "scores", fn_),
+                      _ptr(counts, "int32", "counts", int(frames)), int(n_max), int(frames), float(threshold),
+                      _ptr(keep_out, "uint8", "keep_out", fn_), w, wb, _stream(stream))
         self._fn = lib.nms_run_batched
 
     def __call__(self):
@@ -285,39 +312,44 @@ class RunPlan:
 
 
 def nms_run_ranked_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, stream=None):
+    fn_, fp_, fm_ = _sizes(n_max, frames)
     w, wb = _ws(workspace)
-    _check(lib.nms_run_ranked_batched(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
-                                      _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
-                                      _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream)),
+    _check(lib.nms_run_ranked_batched(_ptr(boxes, "float32", "boxes", 4 * fn_), _ptr(scores, "float32", "scores", fn_),
+                                      _ptr(counts, "int32", "counts", int(frames)), int(n_max), int(frames), float(threshold),
+                                      _ptr(keep_out, "uint8", "keep_out", fn_), w, wb, _stream(stream)),
            "nms_run_ranked_batched")
 
 
 def nms_run_direct_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, stream=None):
-    _check(lib.nms_run_direct_batched(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
-                                      _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
-                                      _ptr(keep_out, "uint8", "keep_out"), _stream(stream)),
+    fn_, fp_, fm_ = _sizes(n_max, frames)
+    _check(lib.nms_run_direct_batched(_ptr(boxes, "float32", "boxes", 4 * fn_), _ptr(scores, "float32", "scores", fn_),
+                                      _ptr(counts, "int32", "counts", int(frames)), int(n_max), int(frames), float(threshold),
+                                      _ptr(keep_out, "uint8", "keep_out", fn_), _stream(stream)),
            "nms_run_direct_batched")
 
 
 def nms_run_batched_profiled(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, events, stream=None):
+    fn_, fp_, fm_ = _sizes(n_max, frames)
     """events: three raw hipEvent_t handles (ints) or None entries."""
     w, wb = _ws(workspace)
     ev = (ctypes.c_void_p * 3)(*[ctypes.c_void_p(e) if e else None for e in events])
-    _check(lib.nms_run_batched_profiled(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
-                                        _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
-                                        _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream), ev),
+    _check(lib.nms_run_batched_profiled(_ptr(boxes, "float32", "boxes", 4 * fn_), _ptr(scores, "float32", "scores", fn_),
+                                        _ptr(counts, "int32", "counts", int(frames)), int(n_max), int(frames), float(threshold),
+                                        _ptr(keep_out, "uint8", "keep_out", fn_), w, wb, _stream(stream), ev),
            "nms_run_batched_profiled")
 
 
 def nms_reduce_greedy(mask, order, n, keep_out, stream=None):
-    _check(lib.nms_reduce_greedy(_ptr(mask, "int64", "mask"), _ptr(order, "int32", "order"), int(n),
-                                 _ptr(keep_out, "uint8", "keep_out"), _stream(stream)), "nms_reduce_greedy")
+    fn_, fp_, fm_ = _sizes(n, 1)
+    _check(lib.nms_reduce_greedy(_ptr(mask, "int64", "mask", fm_), _ptr(order, "int32", "order", fn_), int(n),
+                                 _ptr(keep_out, "uint8", "keep_out", fn_), _stream(stream)), "nms_reduce_greedy")
 
 
 def nms_reduce_greedy_batched(mask, order, counts, n_max, frames, keep_out, stream=None):
-    _check(lib.nms_reduce_greedy_batched(_ptr(mask, "int64", "mask"), _ptr(order, "int32", "order"),
-                                         _ptr(counts, "int32", "counts"), int(n_max), int(frames),
-                                         _ptr(keep_out, "uint8", "keep_out"), _stream(stream)),
+    fn_, fp_, fm_ = _sizes(n_max, frames)
+    _check(lib.nms_reduce_greedy_batched(_ptr(mask, "int64", "mask", fm_), _ptr(order, "int32", "order", fn_),
+                                         _ptr(counts, "int32", "counts", int(frames)), int(n_max), int(frames),
+                                         _ptr(keep_out, "uint8", "keep_out", fn_), _stream(stream)),
            "nms_reduce_greedy_batched")
 
 
@@ -326,37 +358,43 @@ def nms_greedy_workspace_bytes(n_max: int, frames: int) -> int:
 
 
 def nms_run_greedy_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, stream=None):
+    fn_, fp_, fm_ = _sizes(n_max, frames)
     w, wb = _ws(workspace)
-    _check(lib.nms_run_greedy_batched(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
-                                      _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
-                                      _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream)),
+    _check(lib.nms_run_greedy_batched(_ptr(boxes, "float32", "boxes", 4 * fn_), _ptr(scores, "float32", "scores", fn_),
+                                      _ptr(counts, "int32", "counts", int(frames)), int(n_max), int(frames), float(threshold),
+                                      _ptr(keep_out, "uint8", "keep_out", fn_), w, wb, _stream(stream)),
            "nms_run_greedy_batched")
 
 
 def nms_run_early_exit_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, stream=None):
+    fn_, fp_, fm_ = _sizes(n_max, frames)
     w, wb = _ws(workspace)
-    _check(lib.nms_run_early_exit_batched(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
-                                          _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
-                                          _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream)),
+    _check(lib.nms_run_early_exit_batched(_ptr(boxes, "float32", "boxes", 4 * fn_), _ptr(scores, "float32", "scores", fn_),
+                                          _ptr(counts, "int32", "counts", int(frames)), int(n_max), int(frames), float(threshold),
+                                          _ptr(keep_out, "uint8", "keep_out", fn_), w, wb, _stream(stream)),
            "nms_run_early_exit_batched")
 
 
 def nms_run_greedy_fused_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, stream=None):
+    fn_, fp_, fm_ = _sizes(n_max, frames)
     w, wb = _ws(workspace)
-    _check(lib.nms_run_greedy_fused_batched(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
-                                            _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
-                                            _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream)),
+    _check(lib.nms_run_greedy_fused_batched(_ptr(boxes, "float32", "boxes", 4 * fn_), _ptr(scores, "float32", "scores", fn_),
+                                            _ptr(counts, "int32", "counts", int(frames)), int(n_max), int(frames), float(threshold),
+                                            _ptr(keep_out, "uint8", "keep_out", fn_), w, wb, _stream(stream)),
            "nms_run_greedy_fused_batched")
 
 
 def nms_map_matrix(boxes, scores, n, capacity, threshold, B, stream=None):
-    _check(lib.nms_map_matrix(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"), int(n),
-                              int(capacity), float(threshold), _ptr(B, "uint8", "B"), _stream(stream)),
+    cap = max(int(capacity), 0)
+    _check(lib.nms_map_matrix(_ptr(boxes, "float32", "boxes", 4 * max(int(n), 0)),
+                              _ptr(scores, "float32", "scores", max(int(n), 0)), int(n),
+                              int(capacity), float(threshold), _ptr(B, "uint8", "B", cap * cap), _stream(stream)),
            "nms_map_matrix")
 
 
 def nms_reduce_matrix(B, capacity, k, V, stream=None):
-    _check(lib.nms_reduce_matrix(_ptr(B, "uint8", "B"), int(capacity), int(k), _ptr(V, "uint8", "V"),
+    cap = max(int(capacity), 0)
+    _check(lib.nms_reduce_matrix(_ptr(B, "uint8", "B", cap * cap), int(capacity), int(k), _ptr(V, "uint8", "V", cap),
                                  _stream(stream)), "nms_reduce_matrix")
 
 
@@ -367,13 +405,14 @@ def nms_ex_workspace_bytes(n_max: int, frames: int) -> int:
 def nms_run_ex_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, rule="paper",
                        measure="outranking_area", compare="ge", ties="index", pixel_offset=1.0, classes=None,
                        stream=None):
+    fn_, fp_, fm_ = _sizes(n_max, frames)
     w, wb = _ws(workspace)
-    cls = _ptr(classes, "int32", "classes")
+    cls = _ptr(classes, "int32", "classes", fn_)
     opt = NmsOptions(RULES[rule], MEASURES[measure], COMPARES[compare], TIES[ties], float(pixel_offset), 0,
                      cls.value if cls is not None else None)
-    _check(lib.nms_run_ex_batched(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
-                                  _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
-                                  ctypes.byref(opt), _ptr(keep_out, "uint8", "keep_out"), w, wb, _stream(stream)),
+    _check(lib.nms_run_ex_batched(_ptr(boxes, "float32", "boxes", 4 * fn_), _ptr(scores, "float32", "scores", fn_),
+                                  _ptr(counts, "int32", "counts", int(frames)), int(n_max), int(frames), float(threshold),
+                                  ctypes.byref(opt), _ptr(keep_out, "uint8", "keep_out", fn_), w, wb, _stream(stream)),
            "nms_run_ex_batched")
 
 
@@ -387,15 +426,17 @@ def nms_shutdown():
 
 
 def nms_run(boxes, scores, n, threshold, keep_out, stream=None):
-    _check(lib.nms_run(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"), int(n),
-                       float(threshold), _ptr(keep_out, "uint8", "keep_out"), _stream(stream)), "nms_run")
+    fn_, fp_, fm_ = _sizes(n, 1)
+    _check(lib.nms_run(_ptr(boxes, "float32", "boxes", 4 * fn_), _ptr(scores, "float32", "scores", fn_), int(n),
+                       float(threshold), _ptr(keep_out, "uint8", "keep_out", fn_), _stream(stream)), "nms_run")
 
 
 NMS_STATIC_SCRATCH_BYTES = 4194304
 
 
 def nms_run_static_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, stream=None):
-    _check(lib.nms_run_static_batched(_ptr(boxes, "float32", "boxes"), _ptr(scores, "float32", "scores"),
-                                      _ptr(counts, "int32", "counts"), int(n_max), int(frames), float(threshold),
-                                      _ptr(keep_out, "uint8", "keep_out"), _stream(stream)),
+    fn_, fp_, fm_ = _sizes(n_max, frames)
+    _check(lib.nms_run_static_batched(_ptr(boxes, "float32", "boxes", 4 * fn_), _ptr(scores, "float32", "scores", fn_),
+                                      _ptr(counts, "int32", "counts", int(frames)), int(n_max), int(frames), float(threshold),
+                                      _ptr(keep_out, "uint8", "keep_out", fn_), _stream(stream)),
            "nms_run_static_batched")

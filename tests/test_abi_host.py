@@ -238,3 +238,97 @@ def test_binding_refuses_cpu_tensors(nms):
     t = torch.zeros(8, 4)
     with pytest.raises(ValueError):
         nms.nms_sort(t, torch.zeros(8), 8, torch.zeros(8, dtype=torch.int32), torch.zeros(5 * 64))
+
+
+class _NoDeviceCalls:
+    """Stands in for the loaded library: host-only helpers pass through, anything that would
+    enqueue work raises, so a test can never hand a host pointer to a kernel."""
+
+    HOST_ONLY = {"nms_padded_n", "nms_mask_words", "nms_workspace_bytes", "nms_sort_workspace_bytes",
+                 "nms_status_string", "nms_last_launch_error"}
+
+    def __init__(self, real):
+        self._real = real
+
+    def __getattr__(self, name):
+        if name in self.HOST_ONLY:
+            return getattr(self._real, name)
+
+        def refuse(*args):
+            raise RuntimeError(f"reached the library: {name}")
+
+        return refuse
+
+
+def test_binding_refuses_undersized_tensors(nms, monkeypatch):
+    """The C ABI takes bare pointers; the binding knows the tensors' sizes and refuses a buffer
+    that is too small for the call.  Run on host tensors with the device check switched off and
+    the library replaced by a stand-in that raises, so every argument's check is reached and
+    nothing can be launched."""
+    import torch
+
+    monkeypatch.setattr(nms, "_on_device", lambda t: True)
+    monkeypatch.setattr(nms, "lib", _NoDeviceCalls(nms.lib))
+    monkeypatch.setattr(nms, "_stream", lambda stream: None)
+
+    F, n = 3, 100
+    n_pad = nms.nms_padded_n(n)
+    ok = dict(boxes=torch.zeros((F, n, 4)), scores=torch.zeros((F, n)), keep=torch.zeros((F, n), dtype=torch.uint8),
+              counts=torch.zeros(F, dtype=torch.int32), order=torch.zeros((F, n), dtype=torch.int32),
+              sorted5=torch.zeros(F * 5 * n_pad), mask=torch.zeros(F * nms.nms_mask_words(n), dtype=torch.int64),
+              classes=torch.zeros((F, n), dtype=torch.int32))
+    small = dict(boxes=torch.zeros((F, n, 4))[:, :-1].contiguous(), scores=torch.zeros((F, n - 1)),
+                 keep=torch.zeros((F, n - 1), dtype=torch.uint8), counts=torch.zeros(F - 1, dtype=torch.int32),
+                 order=torch.zeros((F, n - 1), dtype=torch.int32), sorted5=torch.zeros(F * 5 * n_pad - 1),
+                 mask=torch.zeros(F * nms.nms_mask_words(n) - 1, dtype=torch.int64),
+                 classes=torch.zeros((F, n - 1), dtype=torch.int32))
+    ws = torch.zeros(8, dtype=torch.uint8)
+    def args(bad):
+        return {k: (small[k] if k == bad else ok[k]) for k in ok}
+
+    def run_batched(a):
+        nms.nms_run_batched(a["boxes"], a["scores"], a["counts"], n, F, 0.5, a["keep"], ws)
+
+    def run_static(a):
+        nms.nms_run_static_batched(a["boxes"], a["scores"], a["counts"], n, F, 0.5, a["keep"])
+
+    def run_direct(a):
+        nms.nms_run_direct_batched(a["boxes"], a["scores"], a["counts"], n, F, 0.5, a["keep"])
+
+    def run_ex(a):
+        nms.nms_run_ex_batched(a["boxes"], a["scores"], a["counts"], n, F, 0.5, a["keep"], ws, classes=a["classes"])
+
+    def sort_batched(a):
+        nms.nms_sort_batched(a["boxes"], a["scores"], a["counts"], n, F, a["order"], a["sorted5"])
+
+    def mask_batched(a):
+        nms.nms_overlap_mask_batched(a["sorted5"], a["counts"], n, F, 0.5, a["mask"])
+
+    def reduce_batched(a):
+        nms.nms_reduce_batched(a["mask"], a["order"], a["counts"], n, F, a["keep"])
+
+    def greedy_batched(a):
+        nms.nms_reduce_greedy_batched(a["mask"], a["order"], a["counts"], n, F, a["keep"])
+
+    cases = [(run_batched, ("boxes", "scores", "counts", "keep")), (run_static, ("boxes", "scores", "counts", "keep")),
+             (run_direct, ("boxes", "scores", "counts", "keep")), (run_ex, ("boxes", "scores", "counts", "keep", "classes")),
+             (sort_batched, ("boxes", "scores", "counts", "order", "sorted5")), (mask_batched, ("sorted5", "counts", "mask")),
+             (reduce_batched, ("mask", "order", "counts", "keep")), (greedy_batched, ("mask", "order", "counts", "keep"))]
+    for call, names in cases:
+        for bad in names:
+            with pytest.raises(ValueError, match="elements, the call needs"):
+                call(args(bad))
+        # with every tensor large enough the call goes through to the library
+        with pytest.raises(RuntimeError, match="reached the library"):
+            call(args(None))
+    with pytest.raises(ValueError, match="elements, the call needs"):
+        nms.RunPlan(ok["boxes"], ok["scores"], None, n, F + 1, 0.5, ok["keep"], ws)
+    with pytest.raises(ValueError, match="elements, the call needs"):
+        nms.nms_map_matrix(ok["boxes"], ok["scores"], 100, 128, 0.5, torch.zeros(128 * 127, dtype=torch.uint8))
+    with pytest.raises(ValueError, match="elements, the call needs"):
+        nms.nms_reduce_matrix(torch.zeros(128 * 128, dtype=torch.uint8), 128, 4, torch.zeros(127, dtype=torch.uint8))
+    # the single-frame calls
+    with pytest.raises(ValueError, match="elements, the call needs"):
+        nms.nms_run_ws(ok["boxes"], ok["scores"], F * n + 1, 0.5, ok["keep"], ws)
+    with pytest.raises(ValueError, match="elements, the call needs"):
+        nms.nms_run(ok["boxes"], ok["scores"], n, 0.5, torch.zeros(n - 1, dtype=torch.uint8))
