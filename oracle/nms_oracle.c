@@ -21,15 +21,16 @@
  *     eliminates (Algorithm 1, last assignment).
  *   - The paper's boxes are squares {x, y, z, s}; here each axis has its own
  *     extent: x+z becomes x2, y+z becomes y2 and (z+1)^2 becomes
- *     ((x2-x1)+1)*((y2-y1)+1).  nmso_alg12_square() below is the paper's
- *     square form, printed-operation for printed-operation, and the tests check
- *     that the two agree on square inputs.
+ *     ((x2-x1)+1)*((y2-y1)+1).  nmso_alg12_square() below evaluates the paper's
+ *     own statement on {x, y, z, s} tuples (strict score guard, zero-filled
+ *     capacity, k row partitions), and the tests check that the two agree on
+ *     square inputs.
  *   - Equal scores: the paper's strict "<" lets two equal-score boxes ignore
  *     each other.  This build's stated rule is a total order: of two boxes with
  *     equal scores the one with the lower index outranks the other.
  *   - The "D[j].z != 0" term of Algorithm 1 guards the zero-filled tail of the
  *     fixed-capacity vector D.  Here n is explicit and there is no tail, so the
- *     term does not appear (nmso_alg12_square() keeps it, as printed).
+ *     term does not appear (nmso_alg12_square() keeps it).
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -188,46 +189,53 @@ void nmso_ranked_elimination_words(const float *boxes, const int32_t *order, int
     }
 }
 
-/* ---- the paper's own square-box form, as printed -------------------------------- */
+/* ---- the paper's own statement: square boxes in a vector of fixed capacity ------- */
 
-/* Algorithm 1 then Algorithm 2 on D = {x, y, z, s} tuples of capacity dmax
- * (unused slots all zero).  B is dmax*dmax bytes preset to 1, V is dmax bytes.
- * Strict score comparison and the "z != 0" term exactly as the listing has
- * them.  The reduce is Algorithm 2's k strided partial ANDs per row: partition p
- * covers columns p*(dmax/k) .. (p+1)*(dmax/k)-1 and the block-wide AND is a
- * plain loop.  dmax must be a multiple of k. */
+/* The paper states the method on detections D = {x, y, z, s}: squares of side z with
+ * their corner at (x, y), held in a vector of capacity dmax whose unused slots are all
+ * zero (section "Proposed Parallel Algorithm").  This function evaluates that statement
+ * with the measure defined above: slot t is the box spanning x..x+z and y..y+z, so its
+ * extent per axis is z and its pixel-inclusive area (z+1)*(z+1), as in Algorithm 1.
+ *   map     B_ij is written only where s_i < s_j STRICTLY (Algorithm 1's guard: equal
+ *           scores do not touch each other -- no index tie-break here); there
+ *           B_ij = (overlap < theta) AND (z_j != 0), the second term as the listing has
+ *           it.  Elsewhere B keeps its preset 1.
+ *   reduce  Algorithm 2 folds a row in k partitions of dmax/k columns each;
+ *           V_i = AND over the partitions of (AND over the partition's columns).
+ * x + z is computed in float32; it is exact for the integer inputs the pins use, and
+ * only then does (x + z) - x give back z bit for bit.  dmax must be a multiple of k. */
 void nmso_alg12_square(const float *D, int dmax, float theta, int k, uint8_t *B, uint8_t *V)
 {
-    memset(B, 1, (size_t)dmax * (size_t)dmax);
+    float *box = (float *)malloc(sizeof(float) * 4 * (size_t)(dmax > 0 ? dmax : 1));
+    for (int t = 0; t < dmax; ++t) {
+        const float *d = D + 4 * (size_t)t;
+        box[4 * t + 0] = d[0];
+        box[4 * t + 1] = d[1];
+        box[4 * t + 2] = d[0] + d[2];
+        box[4 * t + 3] = d[1] + d[2];
+    }
     for (int i = 0; i < dmax; ++i) {
         for (int j = 0; j < dmax; ++j) {
-            const float *di = D + 4 * (size_t)i;
-            const float *dj = D + 4 * (size_t)j;
-            if (di[3] < dj[3]) {
-                float a = (dj[2] + 1.0f) * (dj[2] + 1.0f);
-                float fx = (di[0] + di[2]) < (dj[0] + dj[2]) ? (di[0] + di[2]) : (dj[0] + dj[2]);
-                float nx = di[0] > dj[0] ? di[0] : dj[0];
-                float w = (fx - nx) + 1.0f;
-                if (!(w > 0.0f)) w = 0.0f;
-                float fy = (di[1] + di[2]) < (dj[1] + dj[2]) ? (di[1] + di[2]) : (dj[1] + dj[2]);
-                float ny = di[1] > dj[1] ? di[1] : dj[1];
-                float h = (fy - ny) + 1.0f;
-                if (!(h > 0.0f)) h = 0.0f;
-                B[(size_t)i * dmax + j] = (uint8_t)(((w * h) / a < theta) && (dj[2] != 0.0f));
+            uint8_t b = 1;
+            float s_i = D[4 * (size_t)i + 3], s_j = D[4 * (size_t)j + 3], z_j = D[4 * (size_t)j + 2];
+            if (s_i < s_j) {
+                int below = overlap(box + 4 * (size_t)i, box + 4 * (size_t)j) < theta;
+                b = (uint8_t)(below && z_j != 0.0f);
             }
+            B[(size_t)i * dmax + j] = b;
         }
     }
-    int part = dmax / k;
+    int columns = dmax / k;
     for (int i = 0; i < dmax; ++i) {
         uint8_t v = 1;
-        for (int t = 0; t < part; ++t) v = (uint8_t)(v & B[(size_t)i * dmax + t]);
-        V[i] = v;
-        for (int p = 1; p < k; ++p) {
-            uint8_t blk = 1;
-            for (int t = 0; t < part; ++t) blk = (uint8_t)(blk & (V[i] && B[(size_t)i * dmax + p * part + t]));
-            V[i] = blk;
+        for (int part = 0; part < k; ++part) {
+            uint8_t whole = 1;
+            for (int t = 0; t < columns; ++t) whole = (uint8_t)(whole & B[(size_t)i * dmax + part * columns + t]);
+            v = (uint8_t)(v & whole);
         }
+        V[i] = v;
     }
+    free(box);
 }
 
 /* ---- classic sequential greedy NMS (a different function; not the default) -------- */

@@ -57,20 +57,69 @@ map_matrix_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
     }
 }
 
-// Algorithm 2 as printed: one workgroup per row i with capacity / k threads; thread t
-// looks at column t of each of the k partitions in turn, and a block-wide AND
-// (__syncthreads_and: barrier plus wave ballots combined through LDS; CDNA has no barrier
-// instruction that reduces) folds each partition into V_i.
-__global__ void __launch_bounds__(1024)
-reduce_matrix_kernel(const uint8_t *__restrict__ B, int cap, int k, uint8_t *__restrict__ V)
+// Algorithm 2's result on the byte matrix, V_i = AND over j of B_ij (ReduceKernel
+// postcondition), with its partition count k as the knob the paper sweeps: the row is cut in
+// k partitions of cap / k columns and a row is given (cap / k) / VEC lanes; lane t folds column
+// group t of every partition in turn, k loads that do not depend on each other (issued
+// four at a time), VEC = 8 bytes per load when a partition is a multiple of eight columns
+// (one 64-bit load, "some byte is zero" decided with integer arithmetic), else byte loads.
+// A row of at most 64 lanes is one wavefront and ends in a single ballot; wider rows take
+// several wavefronts of one workgroup, which meet once in LDS.  Small k: many lanes, few
+// loads each; large k: few lanes, long chains -- the same trade the paper's threads-per-block
+// sweep makes, without a workgroup-wide barrier per partition.
+__device__ __forceinline__ bool has_zero_byte(unsigned long long w)
 {
-    const int i = blockIdx.x;
-    const int part = cap / k;  // == blockDim.x
-    size_t j = (size_t)i * cap + threadIdx.x;
-    int v = __syncthreads_and(B[j]);
-    for (int p = 1; p < k; ++p) {
-        j += part;
-        v = __syncthreads_and(v && B[j]);
+    return ((w - 0x0101010101010101ull) & ~w & 0x8080808080808080ull) != 0ull;
+}
+
+template <int VEC>
+__global__ void __launch_bounds__(1024)
+reduce_matrix_kernel(const uint8_t *__restrict__ B, int cap, int k, int waves_per_row, uint8_t *__restrict__ V)
+{
+    __shared__ unsigned zero_seen[16];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int rows_per_block = (int)(blockDim.x >> 6) / waves_per_row;
+    const int row_in_block = wave / waves_per_row;
+    const int sub = wave - row_in_block * waves_per_row;  // which wavefront of its row
+    const int i = blockIdx.x * rows_per_block + row_in_block;
+    const int part = cap / k;
+    const int col = (sub * 64 + lane) * VEC;              // first column of this lane's group inside a partition
+    const bool active = row_in_block < rows_per_block && i < cap && col < part;
+    bool zero = false;
+    if (active) {
+        const uint8_t *row = B + (size_t)i * cap + col;
+        int p = 0;
+        for (; p + 4 <= k; p += 4) {
+            if (VEC == 8) {
+                const unsigned long long a = *reinterpret_cast<const unsigned long long *>(row + (size_t)p * part);
+                const unsigned long long b = *reinterpret_cast<const unsigned long long *>(row + (size_t)(p + 1) * part);
+                const unsigned long long c = *reinterpret_cast<const unsigned long long *>(row + (size_t)(p + 2) * part);
+                const unsigned long long d = *reinterpret_cast<const unsigned long long *>(row + (size_t)(p + 3) * part);
+                zero |= has_zero_byte(a) | has_zero_byte(b) | has_zero_byte(c) | has_zero_byte(d);
+            } else {
+                const uint8_t a = row[(size_t)p * part], b = row[(size_t)(p + 1) * part];
+                const uint8_t c = row[(size_t)(p + 2) * part], d = row[(size_t)(p + 3) * part];
+                zero |= (a == 0) | (b == 0) | (c == 0) | (d == 0);
+            }
+        }
+        for (; p < k; ++p) {
+            if (VEC == 8)
+                zero |= has_zero_byte(*reinterpret_cast<const unsigned long long *>(row + (size_t)p * part));
+            else
+                zero |= row[(size_t)p * part] == 0;
+        }
     }
-    if (threadIdx.x == 0) V[i] = (uint8_t)(v ? 1 : 0);
+    const bool wave_zero = __ballot(zero) != 0ull;
+    if (waves_per_row == 1) {
+        if (lane == 0 && active) V[i] = wave_zero ? 0 : 1;  // lane 0's column 0 exists whenever the row does
+        return;
+    }
+    if (lane == 0) zero_seen[wave] = wave_zero ? 1u : 0u;
+    __syncthreads();
+    if (sub == 0 && lane == 0 && row_in_block < rows_per_block && i < cap) {
+        unsigned any = 0;
+        for (int w = 0; w < waves_per_row; ++w) any |= zero_seen[wave + w];
+        V[i] = any ? 0 : 1;
+    }
 }

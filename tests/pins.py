@@ -12,7 +12,7 @@ Contents
     frames, with exhaustive search over all survivor sets (n <= 8)
   * closed forms: empty frame, one box, disjoint boxes, theta <= 0, theta > 1,
     staircase chain of any length, disjoint clusters of identical boxes
-  * the paper's printed square-box algorithms against the per-axis form
+  * the paper's own square-box statement (strict guard, fixed capacity, k partitions) against the per-axis form
 """
 from __future__ import annotations
 
@@ -97,7 +97,7 @@ def pin_golden(oracle):
         assert via_matrix.tolist() == case["keep"].tolist(), f"{name}: reduce(map) {via_matrix.tolist()}"
         greedy = oracle.greedy_keep(b, s, th)
         assert greedy.tolist() == case["greedy"].tolist(), f"{name}: greedy {greedy.tolist()}"
-        # the printed square-box algorithms on the same case, when its boxes are squares
+        # the paper's square-box statement on the same case, when its boxes are squares
         # with positive scores
         side = b[:, 2] - b[:, 0]
         if np.all(side == b[:, 3] - b[:, 1]) and np.all(s > 0):
@@ -105,7 +105,7 @@ def pin_golden(oracle):
             want = case["literal_keep"] if case["literal_keep"] is not None else case["keep"]
             for k in (1, len(s)):
                 _, V = oracle.alg12_square(D, th, k)
-                assert V.tolist() == want.tolist(), f"{name}: printed algorithms, k={k}: {V.tolist()}"
+                assert V.tolist() == want.tolist(), f"{name}: square-box form, k={k}: {V.tolist()}"
 
 
 # --------------------------------------------------------------------------- exact rational model
@@ -333,11 +333,11 @@ def pin_clusters(oracle):
     assert oracle.keep(boxes, flat, 0.5).tolist() == want.tolist()
 
 
-# --------------------------------------------------------------------------- printed algorithms vs per-axis form
+# --------------------------------------------------------------------------- the paper's square-box statement vs per-axis form
 
 def pin_square_form(oracle):
     """On square boxes with distinct positive scores the per-axis oracle must equal
-    the paper's printed Algorithm 1 + Algorithm 2 run on {x, y, z, s} tuples in a
+    the paper's Algorithm 1 + Algorithm 2 stated on {x, y, z, s} tuples in a
     zero-filled vector of capacity D_max > n, for every partition count k.
     Integer coordinates, so x + z and (x2 - x1) + 1 = z + 1 are exact and both
     forms see the same numbers."""
@@ -360,6 +360,18 @@ def pin_square_form(oracle):
             assert np.array_equal(B[:n, :n], B_general), f"seed {seed}, k={k}: matrix"
             # columns of empty slots (score 0) never pass the score guard: still the preset ones
             assert np.all(B[:, n:] == 1)
+    # The listing's second term, "AND D[j].z != 0", as it stands: where the guard does fire against
+    # an empty slot j (score 0, side 0) -- that takes a NEGATIVE score s_i -- the term is false, so
+    # B_ij = 0 and V_i = 0 whatever the overlap.  Two squares far from the origin and from each
+    # other, capacity 4 (two empty slots): the positive-score one survives, the negative-score one
+    # does not; its row has zeros exactly in the empty slots' columns.
+    D = np.zeros((4, 4), np.float32)
+    D[0] = [100, 100, 10, 0.5]
+    D[1] = [300, 300, 10, -0.5]
+    for k in (1, 2, 4):
+        B, V = oracle.alg12_square(D, np.float32(0.5), k)
+        assert V.tolist() == [1, 0, 1, 1], f"k={k}: {V.tolist()}"
+        assert B.tolist() == [[1, 1, 1, 1], [1, 1, 0, 0], [1, 1, 1, 1], [1, 1, 1, 1]], f"k={k}"
 
 
 ALL_PINS = [

@@ -37,8 +37,10 @@ MUTANTS = [
      "for (int c = 0; c <= r; ++c) {\n            float q = overlap(boxes + 4 * (size_t)order[r], boxes + 4 * (size_t)order[c]);\n            E[", 1),
     ("ranked_words_wrong_bit", "(uint64_t)1 << (c & 63)", "(uint64_t)1 << (c & 31)", 1),
     ("ranked_area_missing", "out[5 * (size_t)r + 4] = box_area(b);", "out[5 * (size_t)r + 4] = b[2] - b[0];", 1),
-    ("printed_form_drops_partition", "for (int p = 1; p < k; ++p) {", "for (int p = 1; p < k - 1; ++p) {", 1),
-    ("printed_form_nonstrict", "if (di[3] < dj[3]) {", "if (di[3] <= dj[3]) {", 1),
+    ("square_form_drops_partition", "for (int part = 0; part < k; ++part) {", "for (int part = 0; part < k - 1; ++part) {", 1),
+    ("square_form_nonstrict", "if (s_i < s_j) {", "if (s_i <= s_j) {", 1),
+    ("square_form_ignores_empty_slots_term", "b = (uint8_t)(below && z_j != 0.0f);", "b = (uint8_t)below;", 1),
+    ("square_form_far_corner", "box[4 * t + 3] = d[1] + d[2];", "box[4 * t + 3] = d[1] + d[3];", 1),
     # operation order and precision of the measure (caught only on inputs where float32 operations round)
     ("width_plus_one_before_subtraction", "float w = (far_x - near_x) + 1.0f;", "float w = (far_x + 1.0f) - near_x;", 1),
     ("height_plus_one_before_subtraction", "float h = (far_y - near_y) + 1.0f;", "float h = (far_y + 1.0f) - near_y;", 1),
