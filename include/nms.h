@@ -133,7 +133,12 @@ int nms_reduce_batched(const uint64_t *mask, const int32_t *order, const int32_t
 /*
  * The whole path in one call.  No mask is written to memory: the row AND is folded
  * into the pair tests, and the result is the same keep vector as steps 1-3 give.
- * The call picks the ranked or the direct route (below) by size.
+ * The call picks its route by size: direct (one launch) for small work, ranked (rank step +
+ * all pair tests of the ranked triangle) otherwise, and for large batches of frames of 1024
+ * boxes or more (frames * n_max^2 >= 2^29) the early-exit route (nms_run_early_exit_batched
+ * below), which returns the same bits from a fraction of the pair tests on clustered
+ * detections.  Callers that want every pair evaluated whatever the size (a fixed running
+ * time) call nms_run_ranked_batched.
  *   workspace >= nms_workspace_bytes(n or n_max, 1 or frames) bytes, 256-byte aligned
  *             (always required, whichever route is taken).
  * Two calls that share a workspace must be ordered on one stream.
@@ -144,7 +149,7 @@ int nms_run_batched(const float *boxes, const float *scores, const int32_t *coun
                     float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream);
 
 /*
- * The two routes that nms_run_batched chooses between, callable on their own.
+ * The two all-pairs routes that nms_run_batched chooses between, callable on their own.
  *   ranked  rank step, then pair tests on the ranked lower triangle (each pair once).
  *           Needs the workspace.  Chosen for batches and large frames.
  *   direct  one launch, no workspace: Algorithm 1 on the full n x n grid of the unsorted
@@ -252,8 +257,9 @@ int nms_run_early_exit_batched(const float *boxes, const float *scores, const in
  * The paper's own data layout, for measuring its form on this hardware: the boolean
  * matrix B as capacity x capacity BYTES over the UNSORTED input (Algorithm 1, one
  * matrix element per ordered pair, the score guard evaluated per pair), and
- * Algorithm 2's reduce with its k row partitions (one workgroup per row, capacity / k
- * threads, k block-wide ANDs).
+ * Algorithm 2's reduce with its k row partitions (a row gets capacity / k / 8 lanes --
+ * capacity / k when that is not a multiple of 8 --, each of which folds its columns of all k
+ * partitions; one combine per row instead of the paper's k block-wide ANDs).
  *   nms_map_matrix     B[i * capacity + j] = 0 iff j outranks i and overlap(i, j) >= theta,
  *                      else 1.  Every byte of B is written (the paper presets B to 1 with
  *                      a memset and rewrites the guarded entries; slots at or beyond n
@@ -262,14 +268,15 @@ int nms_run_early_exit_batched(const float *boxes, const float *scores, const in
  *   nms_reduce_matrix  V[i] = AND over j of B[i * capacity + j], for all capacity rows
  *                      (rows of unused slots give 1, as in the paper).
  *   n <= capacity <= NMS_MAX_MATRIX, capacity a multiple of 64; k >= 1 divides capacity and
- *   capacity / k <= 1024 (the workgroup size); otherwise NMS_ERR_INVALID_ARG.
+ *   capacity / k <= 1024; otherwise NMS_ERR_INVALID_ARG.
  */
 int nms_map_matrix(const float *boxes, const float *scores, int n, int capacity, float threshold,
                    uint8_t *B, void *stream);
 int nms_reduce_matrix(const uint8_t *B, int capacity, int k, uint8_t *V, void *stream);
 
 /*
- * Profiling variant of nms_run_batched: identical work, and in addition records the
+ * Profiling variant of the all-pairs routes (ranked or direct, chosen by size as in
+ * nms_run_batched; never the early-exit route): identical work, and in addition records the
  * caller's HIP events on `stream`.  `events` is a HOST array of three hipEvent_t
  * (each may be NULL = skip): [0] before the rank step, [1] between rank and map,
  * [2] after the map step ([1] directly follows [0] on the direct route, which has no

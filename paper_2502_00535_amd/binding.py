@@ -288,7 +288,7 @@ def nms_run_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, w
 
 
 class RunPlan:
-    """nms_run_batched with its arguments marshalled once.
+    """nms_run_batched (or another entry point with the same arguments) with its arguments marshalled once.
 
     For serving loops that call the library many times on the same buffers: the tensors
     are validated and their pointers taken at construction; each call is then a single
@@ -296,19 +296,26 @@ class RunPlan:
     current when it was built unless one is given.
     """
 
-    def __init__(self, boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, stream=None):
+    SAME_SIGNATURE = ("nms_run_batched", "nms_run_ranked_batched", "nms_run_early_exit_batched",
+                      "nms_run_greedy_batched", "nms_run_greedy_fused_batched")
+
+    def __init__(self, boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, stream=None,
+                 entry="nms_run_batched"):
+        if entry not in self.SAME_SIGNATURE:
+            raise ValueError(f"RunPlan: {entry} does not take nms_run_batched's arguments")
+        self._entry = entry
         self._keepalive = (boxes, scores, counts, keep_out, workspace)
         w, wb = _ws(workspace)
         fn_, _, _ = _sizes(n_max, frames)
         self._args = (_ptr(boxes, "float32", "boxes", 4 * fn_), _ptr(scores, "float32", "scores", fn_),
                       _ptr(counts, "int32", "counts", int(frames)), int(n_max), int(frames), float(threshold),
                       _ptr(keep_out, "uint8", "keep_out", fn_), w, wb, _stream(stream))
-        self._fn = lib.nms_run_batched
+        self._fn = getattr(lib, entry)
 
     def __call__(self):
         status = self._fn(*self._args)
         if status != NMS_OK:
-            raise NmsError(status, "nms_run_batched")
+            raise NmsError(status, self._entry)
 
 
 def nms_run_ranked_batched(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, stream=None):

@@ -49,24 +49,5 @@ def build_library(verbose: bool = False) -> str:
     return LIBRARY
 
 
-PROBE_SOURCE = os.path.join(_HERE, "csrc", "valu_probe.hip")
-PROBE_BINARY = os.path.join(_HERE, "valu_probe")
-
-
-def build_probe() -> str:
-    """The stand-alone VALU issue-rate probe (a measurement tool, not part of the library)."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wno-unused-command-line-argument", PROBE_SOURCE, "-o", PROBE_BINARY]
-    proc = subprocess.run(cmd, capture_output=True, text=True)
-    if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + proc.stdout + proc.stderr)
-    return PROBE_BINARY
-
-
 if __name__ == "__main__":
-    import sys
-
     print(build_library(verbose=True))
-    if "--probe" in sys.argv:
-        print(build_probe())

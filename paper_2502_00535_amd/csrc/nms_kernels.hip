@@ -339,7 +339,23 @@ inline RunWorkspace carve_workspace(void *workspace, int n_max, int frames)
     return w;
 }
 
-enum Route { kRouteAuto = 0, kRouteRanked = 1, kRouteDirect = 2 };
+// forward: defined with the early-exit entry point below
+static int early_exit_launch(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                             float threshold, uint8_t *keep_out, void *workspace, hipStream_t s);
+
+// Large batches of frames of a thousand boxes or more: the route that stops testing a victim
+// once it has an eliminator returns the same keep vector 1.3 to 3.3 times sooner on clustered
+// detections (what a detector emits) and 0.7 to 1.0 times as fast when almost nothing is
+// eliminated (measured on 32 to 1024 frames of 1024 to 4096 boxes).  Frames of 512 boxes or
+// fewer never gain: their stages are mostly barriers.
+inline bool use_early_exit(int n_max, int frames)
+{
+    return n_max >= 1024 && (long long)frames * n_max * n_max >= (1ll << 29);
+}
+
+// kRouteAuto: direct, ranked or early exit by size.  kRouteAllPairs: direct or ranked by size
+// (every pair of the ranked triangle is evaluated).
+enum Route { kRouteAuto = 0, kRouteRanked = 1, kRouteDirect = 2, kRouteAllPairs = 3 };
 
 static int run_routed(Route route, const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
                       float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream,
@@ -350,13 +366,16 @@ static int run_routed(Route route, const float *boxes, const float *scores, cons
     if (is_nan(threshold)) return NMS_ERR_INVALID_ARG;
     if (n_max == 0 || frames == 0) return NMS_OK;
     if (!boxes || !scores || !keep_out) return NMS_ERR_INVALID_ARG;
-    const bool direct = route == kRouteDirect || (route == kRouteAuto && use_direct_form(n_max, frames));
+    const bool by_size = route == kRouteAuto || route == kRouteAllPairs;
+    const bool direct = route == kRouteDirect || (by_size && use_direct_form(n_max, frames));
     if (route != kRouteDirect) {  // the automatic route validates the workspace whichever way it goes
         const size_t need = nms_workspace_bytes(n_max, frames);
         if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)) return NMS_ERR_WORKSPACE;
     }
 
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (route == kRouteAuto && !direct && use_early_exit(n_max, frames))
+        return early_exit_launch(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, s);
     auto mark = [&](int i) {
         if (!events || !events[i]) return true;
         const hipError_t e = hipEventRecord(static_cast<hipEvent_t>(events[i]), s);
@@ -384,7 +403,7 @@ int nms_run_batched_profiled(const float *boxes, const float *scores, const int3
                              float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream,
                              void *const *events)
 {
-    return run_routed(kRouteAuto, boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, ws_bytes,
+    return run_routed(kRouteAllPairs, boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, ws_bytes,
                       stream, events);
 }
 
@@ -474,17 +493,11 @@ static int run_greedy_fused(const float *boxes, const float *scores, const int32
     return launch_status();
 }
 
-int nms_run_early_exit_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
-                               float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream)
+// The paper's rule with decided victims skipped (kernels/early_exit.h); arguments already validated.
+static int early_exit_launch(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                             float threshold, uint8_t *keep_out, void *workspace, hipStream_t s)
 {
     int st;
-    if (!sizes_ok(n_max, frames, &st)) return st;
-    if (is_nan(threshold)) return NMS_ERR_INVALID_ARG;
-    if (n_max == 0 || frames == 0) return NMS_OK;
-    if (!boxes || !scores || !keep_out) return NMS_ERR_INVALID_ARG;
-    if (!workspace || ws_bytes < nms_workspace_bytes(n_max, frames) || ((uintptr_t)workspace & 255))
-        return NMS_ERR_WORKSPACE;
-    hipStream_t s = static_cast<hipStream_t>(stream);
     const NmsThetaConst th = nms_make_theta_const(threshold);
     // Fewer frames than compute units: a frame's victims are shared out among `parts` workgroups
     // (each stages the whole frame), which then need the ranked table in memory.
@@ -525,6 +538,21 @@ int nms_run_early_exit_batched(const float *boxes, const float *scores, const in
         early_exit_kernel<kPairExact><<<dim3(frames * parts), dim3(kEarlyThreads), 0, s>>>(w.sorted5, w.order, counts, n_max, n_pad,
                                                                                            parts, th, keep_out);
     return launch_status();
+}
+
+
+int nms_run_early_exit_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                               float threshold, uint8_t *keep_out, void *workspace, size_t ws_bytes, void *stream)
+{
+    int st;
+    if (!sizes_ok(n_max, frames, &st)) return st;
+    if (is_nan(threshold)) return NMS_ERR_INVALID_ARG;
+    if (n_max == 0 || frames == 0) return NMS_OK;
+    if (!boxes || !scores || !keep_out) return NMS_ERR_INVALID_ARG;
+    if (!workspace || ws_bytes < nms_workspace_bytes(n_max, frames) || ((uintptr_t)workspace & 255))
+        return NMS_ERR_WORKSPACE;
+    return early_exit_launch(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace,
+                             static_cast<hipStream_t>(stream));
 }
 
 int nms_run_greedy_fused_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
@@ -733,8 +761,18 @@ int nms_reduce_matrix(const uint8_t *B, int capacity, int k, uint8_t *V, void *s
     if (capacity % kTile != 0) return NMS_ERR_INVALID_ARG;
     if (capacity == 0) return NMS_OK;
     if (capacity % k != 0 || capacity / k > 1024 || !B || !V) return NMS_ERR_INVALID_ARG;
+    const int part = capacity / k;
+    const int vec = part % 8 == 0 ? 8 : 1;                       // bytes per load
+    const int waves_per_row = (part / vec + 63) / 64;             // 1 .. 16
+    const int block_waves = waves_per_row <= 4 ? 4 : waves_per_row;
+    const int rows_per_block = block_waves / waves_per_row;
+    const dim3 grid((capacity + rows_per_block - 1) / rows_per_block);
+    hipStream_t s = static_cast<hipStream_t>(stream);
     begin_launch();
-    reduce_matrix_kernel<<<dim3(capacity), dim3(capacity / k), 0, static_cast<hipStream_t>(stream)>>>(B, capacity, k, V);
+    if (vec == 8)
+        reduce_matrix_kernel<8><<<grid, dim3(block_waves * 64), 0, s>>>(B, capacity, k, waves_per_row, V);
+    else
+        reduce_matrix_kernel<1><<<grid, dim3(block_waves * 64), 0, s>>>(B, capacity, k, waves_per_row, V);
     return launch_status();
 }
 
