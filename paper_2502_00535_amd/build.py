@@ -6,7 +6,7 @@ import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 SOURCES = [os.path.join(_HERE, "csrc", "nms_kernels.hip")]
-HEADERS = [os.path.join(_HERE, "csrc", "nms_pair.h"),
+HEADERS = [os.path.join(_HERE, "csrc", "nms_pair.h"), os.path.join(_HERE, "csrc", "nms_host_logic.h"),
            os.path.join(os.path.dirname(_HERE), "include", "nms.h"),
            *sorted(os.path.join(_HERE, "csrc", "kernels", f)
                    for f in os.listdir(os.path.join(_HERE, "csrc", "kernels")) if f.endswith(".h"))]

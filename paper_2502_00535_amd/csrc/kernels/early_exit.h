@@ -433,7 +433,7 @@ early_exit_ranked_kernel(const float *__restrict__ boxes, const float *__restric
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         e[q] = (tid >> 6) * 256 + q * 64 + lane;
-        const unsigned long long key = e[q] < n_f ? rank_key(scores_f[e[q]], (unsigned)e[q]) : kSentinel;
+        const unsigned long long key = e[q] < n_f ? nms_rank_key(scores_f[e[q]], (unsigned)e[q]) : kSentinel;
         key32[q] = (unsigned)(key >> 32);
         index[q] = (unsigned)key;
         mine[q] = e[q] < n_f ? boxes_f[e[q]] : make_float4(0.f, 0.f, 0.f, 0.f);

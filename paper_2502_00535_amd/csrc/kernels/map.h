@@ -3,31 +3,7 @@
 
 // ----------------------------------------------------------------------------- map
 
-// Work unit of the map step: one column tile tc (64 outranking boxes, held in registers)
-// against a "super-row" of kSuper consecutive victim tile rows, i.e. up to kSuper tiles of
-// the ranked lower triangle.  Super-row sr has min(kSuper*(sr+1), T) units (tc = 0 .. last
-// tile row of the super-row), so the units before super-row sr number
-// kSuper * sr*(sr+1)/2.  Linear unit index -> (sr, tc) by integer square root.
-// kSuper = 4 amortises the per-lane set-up over 256 rows and is used when the launch has
-// plenty of units; kSuper = 1 (one tile per wavefront) keeps small launches balanced.
-template <int kSuper>
-__device__ __forceinline__ void triangle_unit(int g, int &sr, int &tc)
-{
-    // largest sr with kSuper*sr*(sr+1)/2 <= g
-    int r = (int)((__fsqrt_rn(1.0f + (8.0f / kSuper) * (float)g) - 1.0f) * 0.5f);
-    while (kSuper * r * (r + 1) / 2 > g) --r;
-    while (kSuper * (r + 1) * (r + 2) / 2 <= g) ++r;
-    sr = r;
-    tc = g - kSuper * r * (r + 1) / 2;
-}
-
-// Number of units for T tile rows.
-inline int triangle_units(int T, int super)
-{
-    const int SR = (T + super - 1) / super;
-    return SR == 0 ? 0 : super * (SR - 1) * SR / 2 + T;
-}
-
+// Work units and their numbering: nms_triangle_unit / nms_triangle_units in nms_host_logic.h.
 constexpr int kMapWaves = 4;  // wavefronts (tiles) per workgroup
 
 // State a wavefront carries through the 64 rows of a tile.
@@ -125,7 +101,7 @@ map_tile_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ c
     if (g >= tiles) return;
     const int n_f = frame_count(counts, f, n_max);
     int sr, tc;
-    triangle_unit<kSuper>(g, sr, tc);
+    nms_triangle_unit<kSuper>(g, sr, tc);
     const int tiles_f = (n_f + kTile - 1) / kTile;  // tile rows that hold boxes of this frame
     int tr = kSuper * sr > tc ? kSuper * sr : tc;
     int tr_end = kSuper * sr + kSuper < tiles_f ? kSuper * sr + kSuper : tiles_f;

@@ -3,14 +3,7 @@
 
 // ----------------------------------------------------------------------------- rank
 
-// Unique ascending 64-bit key: better score first, then lower index.
-__device__ __forceinline__ unsigned long long rank_key(float score, unsigned idx)
-{
-    unsigned u = __float_as_uint(score);
-    if (u == 0x80000000u) u = 0u;  // -0.0 ties with +0.0
-    unsigned asc = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-    return ((unsigned long long)(~asc) << 32) | idx;
-}
+// Sort keys: nms_rank_key in nms_host_logic.h (unique, ascending = better score first, then lower index).
 
 // Rank-ordered row r: the box and its area, and (fused path only, ysc != nullptr) the same
 // box with y multiplied by NMS_YSCALE.  Returns whether the box may use the y-scaled form.
@@ -177,7 +170,7 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         e[q] = (tid >> 6) * 256 + q * 64 + lane;
-        K[q] = (e[q] < cnt) ? rank_key(scores_f[base + e[q]], (unsigned)(base + e[q])) : kSentinel;
+        K[q] = (e[q] < cnt) ? nms_rank_key(scores_f[base + e[q]], (unsigned)(base + e[q])) : kSentinel;
         if (STAGE) mine[q] = (e[q] < cnt) ? reinterpret_cast<const float4 *>(boxes_f)[e[q]] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
 

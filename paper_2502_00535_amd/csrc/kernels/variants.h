@@ -68,7 +68,7 @@ map_tile_ex_kernel(const float *__restrict__ sorted5, const float *__restrict__ 
     if (g >= tiles) return;
     const int n_f = frame_count(counts, f, n_max);
     int sr, tc;
-    triangle_unit<kSuper>(g, sr, tc);
+    nms_triangle_unit<kSuper>(g, sr, tc);
     const int tiles_f = (n_f + kTile - 1) / kTile;
     int tr = kSuper * sr > tc ? kSuper * sr : tc;
     const int tr_end = kSuper * sr + kSuper < tiles_f ? kSuper * sr + kSuper : tiles_f;

@@ -25,6 +25,7 @@
 
 #include "../../include/nms.h"
 #include "nms_pair.h"
+#include "nms_host_logic.h"
 
 // Scratch of nms_run_static_batched: one copy per GPU, held from the moment the library is
 // loaded on it until the process ends.  In host code this name is only a handle for
@@ -64,7 +65,7 @@ struct Pool {
 };
 Pool g_pool;
 
-inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+inline size_t align256(size_t v) { return nms_align256(v); }
 
 inline bool sizes_ok(int n_max, int frames, int *status)
 {
@@ -72,8 +73,8 @@ inline bool sizes_ok(int n_max, int frames, int *status)
     if (n_max > NMS_MAX_N || frames > NMS_MAX_FRAMES) { *status = NMS_ERR_TOO_LARGE; return false; }
     // the map step is one launch of 256-thread workgroups, and a launch holds fewer than 2^32 threads
     const int T = nms_padded_n(n_max) / kTile;
-    const bool super4 = (long long)frames * triangle_units(T, 4) >= 16384;
-    const long long tile_blocks = (triangle_units(T, super4 ? 4 : 1) + kMapWaves - 1) / kMapWaves;
+    const bool super4 = (long long)frames * nms_triangle_units(T, 4) >= 16384;
+    const long long tile_blocks = (nms_triangle_units(T, super4 ? 4 : 1) + kMapWaves - 1) / kMapWaves;
     const long long blocks = frames >= 8 ? (long long)((frames + 7) / 8) * 8 * tile_blocks : tile_blocks;
     if (blocks > NMS_MAX_MAP_WORKGROUPS) { *status = NMS_ERR_TOO_LARGE; return false; }
     return true;
@@ -175,9 +176,9 @@ int map_launch(const float *sorted5, const int32_t *counts, int n_max, int frame
     const int n_pad = nms_padded_n(n_max);
     const int T = n_pad / kTile;
     // four (or two) tiles per wavefront when that still leaves every SIMD several wavefronts
-    const bool super4 = (long long)frames * triangle_units(T, 4) >= 16384;
-    const bool super2 = !super4 && (long long)frames * triangle_units(T, 2) >= 16384;
-    const int tiles = triangle_units(T, super4 ? 4 : (super2 ? 2 : 1));  // work units, one per wavefront
+    const bool super4 = (long long)frames * nms_triangle_units(T, 4) >= 16384;
+    const bool super2 = !super4 && (long long)frames * nms_triangle_units(T, 2) >= 16384;
+    const int tiles = nms_triangle_units(T, super4 ? 4 : (super2 ? 2 : 1));  // work units, one per wavefront
     const NmsThetaConst th = nms_make_theta_const(threshold);
     const int tile_blocks = (tiles + kMapWaves - 1) / kMapWaves;
     // batches: one frame per XCD at a time (see the kernel); a few large frames: spread each over all XCDs
@@ -245,12 +246,7 @@ size_t nms_workspace_bytes(int n_max, int frames)
 {
     int st;
     if (!sizes_ok(n_max, frames, &st)) return 0;
-    const size_t n_pad = (size_t)nms_padded_n(n_max);
-    return align256((size_t)frames * n_max * sizeof(int32_t))               // order
-         + align256((size_t)frames * 5 * n_pad * sizeof(float))             // sorted5
-         + align256((size_t)frames * n_pad * 4 * sizeof(float))             // y-scaled boxes
-         + align256((size_t)frames * (n_pad / kTile) * sizeof(unsigned))    // tile flags
-         + nms_sort_workspace_bytes(n_max, frames);                         // chunk keys
+    return nms_run_layout(n_max, nms_padded_n(n_max), frames, kChunk).end;
 }
 
 int nms_sort_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
@@ -322,20 +318,15 @@ struct RunWorkspace {
 
 inline RunWorkspace carve_workspace(void *workspace, int n_max, int frames)
 {
-    const size_t n_pad = (size_t)nms_padded_n(n_max);
+    const NmsRunLayout l = nms_run_layout(n_max, nms_padded_n(n_max), frames, kChunk);
+    char *base = static_cast<char *>(workspace);
     RunWorkspace w;
-    char *p = static_cast<char *>(workspace);
-    w.order = reinterpret_cast<int32_t *>(p);
-    p += align256((size_t)frames * n_max * sizeof(int32_t));
-    w.sorted5 = reinterpret_cast<float *>(p);
-    p += align256((size_t)frames * 5 * n_pad * sizeof(float));
-    w.ysc = reinterpret_cast<float4 *>(p);
-    p += align256((size_t)frames * n_pad * sizeof(float4));
-    w.ytile = reinterpret_cast<unsigned *>(p);
-    p += align256((size_t)frames * (n_pad / kTile) * sizeof(unsigned));
-    w.keys = p;
-    p += nms_sort_workspace_bytes(n_max, frames);
-    w.end = p;
+    w.order = reinterpret_cast<int32_t *>(base + l.order);
+    w.sorted5 = reinterpret_cast<float *>(base + l.sorted5);
+    w.ysc = reinterpret_cast<float4 *>(base + l.ysc);
+    w.ytile = reinterpret_cast<unsigned *>(base + l.ytile);
+    w.keys = base + l.keys;
+    w.end = base + l.end;
     return w;
 }
 
@@ -655,8 +646,8 @@ int nms_run_ex_batched(const float *boxes, const float *scores, const int32_t *c
 
     // work units and grid as in map_launch
     const int T = n_pad / kTile;
-    const bool super4 = (long long)frames * triangle_units(T, 4) >= 16384;
-    const int tiles = triangle_units(T, super4 ? 4 : 1);
+    const bool super4 = (long long)frames * nms_triangle_units(T, 4) >= 16384;
+    const int tiles = nms_triangle_units(T, super4 ? 4 : 1);
     const int tile_blocks = (tiles + kMapWaves - 1) / kMapWaves;
     const int xcd_frames = frames >= 8 ? 1 : 0;
     const dim3 grid = xcd_frames ? dim3((unsigned)(((frames + 7) / 8) * 8 * tile_blocks)) : dim3(tile_blocks, frames);
