@@ -308,7 +308,7 @@ int nms_run(const float *boxes, const float *scores, int n, float threshold,
  * and keep_out.
  *   sizes    nms_workspace_bytes(n_max, frames) must not exceed NMS_STATIC_SCRATCH_BYTES, else
  *            NMS_ERR_TOO_LARGE and nothing is enqueued.  That admits any single frame the library
- *            takes (65,536 boxes: 3.0 MiB), 4 frames of 16,384 boxes, 25 of 4096, 102 of 1024.
+ *            takes (65,536 boxes: 3.3 MiB), 4 frames of 16,384 boxes, 23 of 4096, 92 of 1024.
  *   sharing  every call on a GPU uses that GPU's one array, which keeps the previous call's
  *            contents (nothing in it has to start at zero: each call writes what it reads).
  *            Calls on the same GPU must therefore be ordered on one stream; calls that overlap

@@ -169,3 +169,120 @@ map_tile_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ c
         }
     }
 }
+
+// ----------------------------------------------------------------------------- fused map, lane = victim
+
+// The whole-path calls do not need the mask, only "does row r have an eliminator".  With the
+// roles exchanged -- lane = VICTIM r of a tile row (its box in registers), the outranking box c
+// wave-uniform, fetched with scalar loads together with its precomputed decision threshold -- the
+// compare's lane mask is, for one outranking box, the set of victims it eliminates, and the row
+// reduction is a running OR of those masks: one scalar instruction per 64 pair tests instead
+// of three (test for zero, select a bit, merge), and at the end lane r itself holds the answer
+// for row r, so a victim is written at most once per work unit and no threshold has to be worked
+// out per lane.  The ten VALU instructions of the pair test are the same.
+//
+// caux: per outranking box, NMS_YSCALE * T (written by the rank step; the unscaled forms multiply
+// it back up, a power of two) or, for thresholds that take the literal division, the area.
+// Wave-uniform reads of tables that a previous kernel wrote and this one never writes: through
+// the constant address space, so that they are scalar loads whatever else the kernel loads.
+typedef const __attribute__((address_space(4))) float *nms_uniform_float_ptr;
+
+template <int PAIR, bool DIAG>
+__device__ __forceinline__ unsigned long long fused_candidates(const float4 *__restrict__ cb,
+                                                               const float *__restrict__ caux, const float4 vb,
+                                                               float y_one, float theta)
+{
+    unsigned long long acc = 0;
+    constexpr int kGroup = 8;  // outranking boxes fetched together: 40 SGPRs
+#pragma unroll 1
+    for (int grp = 0; grp < kTile / kGroup; ++grp) {
+        const nms_uniform_float_ptr cg = (nms_uniform_float_ptr)(uintptr_t)(cb + kGroup * grp);
+        const nms_uniform_float_ptr ag = (nms_uniform_float_ptr)(uintptr_t)(caux + kGroup * grp);
+#pragma unroll
+        for (int k = 0; k < kGroup; ++k) {
+            const float4 c = make_float4(cg[4 * k], cg[4 * k + 1], cg[4 * k + 2], cg[4 * k + 3]);
+            const float a = ag[k];
+            bool hit;
+            if (PAIR == kPairFastYScaled)
+                hit = nms_eliminates_fast_yscaled(vb.x, vb.y, vb.z, vb.w, c.x, c.y, c.z, c.w, a, y_one);
+            else if (PAIR == kPairFast)
+                hit = nms_eliminates_fast(vb.x, vb.y, vb.z, vb.w, c.x, c.y, c.z, c.w, a * (1.0f / NMS_YSCALE));
+            else
+                hit = nms_eliminates_exact(vb.x, vb.y, vb.z, vb.w, c.x, c.y, c.z, c.w, a, theta);
+            unsigned long long word = __ballot(hit);
+            if (DIAG) {  // same tile: only victims ranked behind this box count
+                const int ci = kGroup * grp + k;
+                word &= ci == kTile - 1 ? 0ull : (~0ull << (ci + 1));
+            }
+            acc |= word;
+        }
+    }
+    return acc;
+}
+
+// One wavefront = one unit: a victim tile row tr against up to kSuper tiles of outranking boxes
+// tc <= tr.  Units are numbered as in nms_triangle_unit with both tile indices counted from the
+// far end (u = T-1-tr, v = T-1-tc, v >= u, the v of a unit share v / kSuper).  keep_out was preset
+// to 1 by the rank step; every writer stores 0, so concurrent units need no atomics.
+template <bool FAST, int kSuper>
+__global__ void __launch_bounds__(kMapWaves * 64)
+map_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ counts, int n_max, int n_pad,
+                 int tiles, int tile_blocks, int frames, int xcd_frames, NmsThetaConst th,
+                 const int32_t *__restrict__ order, uint8_t *__restrict__ keep_out,
+                 const float4 *__restrict__ ysc, const unsigned *__restrict__ ytile, const float *__restrict__ tsc)
+{
+    const int lane = threadIdx.x & 63;
+    int f, bx;
+    if (xcd_frames) {  // frame f runs entirely on XCD f mod 8 (see map_tile_kernel)
+        const int slot = blockIdx.x >> 3;
+        f = (slot / tile_blocks) * 8 + (int)(blockIdx.x & 7);
+        bx = slot % tile_blocks;
+        if (f >= frames) return;
+    } else {
+        f = blockIdx.y;
+        bx = blockIdx.x;
+    }
+    const int g = __builtin_amdgcn_readfirstlane(bx * kMapWaves + (int)(threadIdx.x >> 6));
+    if (g >= tiles) return;
+    const int n_f = frame_count(counts, f, n_max);
+    const int T = n_pad / kTile;
+    int sr, u;
+    nms_triangle_unit<kSuper>(g, sr, u);
+    const int tr = T - 1 - u;                       // victim tile row
+    const int tiles_f = (n_f + kTile - 1) / kTile;  // tile rows that hold boxes of this frame
+    if (tr >= tiles_f) return;
+    int v = kSuper * sr > u ? kSuper * sr : u;
+    const int v_end = kSuper * sr + kSuper < T ? kSuper * sr + kSuper : T;
+
+    const float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
+    const float4 *__restrict__ box4 = reinterpret_cast<const float4 *>(sorted_f);
+    const float *__restrict__ area = sorted_f + 4 * (size_t)n_pad;
+    const float4 *__restrict__ ysc4 = ysc + (size_t)f * n_pad;
+    const unsigned *__restrict__ ytile_f = ytile + (size_t)f * (n_pad / kTile);
+    const float *__restrict__ tsc_f = tsc + (size_t)f * n_pad;
+
+    const int row = tr * kTile + lane;
+    const float4 vbs = ysc4[row];  // this lane's victim, y scaled
+    const bool r_regular = FAST && ytile_f[tr] != 0;  // the rank step's flag: the tile may take the y-scaled form
+    float y_one;  // NMS_YSCALE in a vector register (opaque to the compiler so it stays there)
+    asm volatile("v_mov_b32 %0, 0x38800000" : "=v"(y_one));
+
+    unsigned long long acc = 0;
+    for (; v < v_end; ++v) {
+        const int tc = T - 1 - v;
+        if (r_regular && ytile_f[tc] != 0) {
+            if (tc == tr)
+                acc |= fused_candidates<kPairFastYScaled, true>(ysc4 + tc * kTile, tsc_f + tc * kTile, vbs, y_one, th.theta);
+            else
+                acc |= fused_candidates<kPairFastYScaled, false>(ysc4 + tc * kTile, tsc_f + tc * kTile, vbs, y_one, th.theta);
+        } else {
+            const float4 vb = box4[row];
+            const float *caux = FAST ? tsc_f + tc * kTile : area + tc * kTile;
+            if (tc == tr)
+                acc |= fused_candidates<FAST ? kPairFast : kPairExact, true>(box4 + tc * kTile, caux, vb, y_one, th.theta);
+            else
+                acc |= fused_candidates<FAST ? kPairFast : kPairExact, false>(box4 + tc * kTile, caux, vb, y_one, th.theta);
+        }
+    }
+    if (((acc >> lane) & 1ull) && row < n_f) keep_out[(size_t)f * n_max + order[(size_t)f * n_max + row]] = 0;
+}

@@ -7,21 +7,27 @@
 
 // Rank-ordered row r: the box and its area, and (fused path only, ysc != nullptr) the same
 // box with y multiplied by NMS_YSCALE.  Returns whether the box may use the y-scaled form.
+// The fused map kernel also gets, per box, the float32 that intersections with it are compared
+// with, already multiplied by NMS_YSCALE (tsc_f; m = the rounding boundary below the threshold,
+// 0 when the threshold takes the literal division and the table is not used).
 __device__ __forceinline__ bool emit_ranked_box(const float4 b, int idx, int r, int n_pad,
-                                               int32_t *order_f, float *sorted_f, float4 *ysc_f)
+                                               int32_t *order_f, float *sorted_f, float4 *ysc_f, float *tsc_f, double m)
 {
     order_f[r] = idx;
     reinterpret_cast<float4 *>(sorted_f)[r] = b;
-    sorted_f[4 * (size_t)n_pad + r] = nms_box_area(b.x, b.y, b.z, b.w);
+    const float area = nms_box_area(b.x, b.y, b.z, b.w);
+    sorted_f[4 * (size_t)n_pad + r] = area;
     if (ysc_f != nullptr) ysc_f[r] = make_float4(b.x, b.y * NMS_YSCALE, b.z, b.w * NMS_YSCALE);
+    if (tsc_f != nullptr) tsc_f[r] = nms_pair_threshold(area, m) * NMS_YSCALE;
     return nms_y_regular(b.y) && nms_y_regular(b.w);
 }
 
-__device__ __forceinline__ void emit_padding_row(int r, int n_pad, float *sorted_f, float4 *ysc_f)
+__device__ __forceinline__ void emit_padding_row(int r, int n_pad, float *sorted_f, float4 *ysc_f, float *tsc_f)
 {
     reinterpret_cast<float4 *>(sorted_f)[r] = make_float4(0.f, 0.f, 0.f, 0.f);
     sorted_f[4 * (size_t)n_pad + r] = 1.0f;  // the one-pixel box (0,0,0,0): never divides by zero
     if (ysc_f != nullptr) ysc_f[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (tsc_f != nullptr) tsc_f[r] = INFINITY;  // no intersection reaches it
 }
 
 // Inclusive prefix sum over the 64 lanes of a wavefront with DPP: shifts by 1, 2, 4, 8 inside
@@ -145,7 +151,7 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
                   const int32_t *__restrict__ counts, int n_max, int n_pad, int n_chunks,
                   int32_t *__restrict__ order, float *__restrict__ sorted5,
                   unsigned long long *__restrict__ keys_ws, uint8_t *__restrict__ keep_preset,
-                  float4 *__restrict__ ysc, unsigned *__restrict__ ytile)
+                  float4 *__restrict__ ysc, unsigned *__restrict__ ytile, float *__restrict__ tsc, double m)
 {
     __shared__ unsigned long long keys[P];
     __shared__ unsigned hist[(P / 256) * 256];  // one row of 256 digit counts per wavefront
@@ -185,6 +191,7 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
     int32_t *order_f = order + (size_t)f * n_max;
     float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
     float4 *ysc_f = ysc ? ysc + (size_t)f * n_pad : nullptr;
+    float *tsc_f = tsc ? tsc + (size_t)f * n_pad : nullptr;
     unsigned *ytile_f = ytile ? ytile + (size_t)f * (n_pad / kTile) : nullptr;
     if (STAGE) {
         // n_pad <= 4 * nth: at most four ranks per thread, r = tid + q * nth (a wavefront covers 64
@@ -206,9 +213,9 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
             if (r < n_pad) {  // uniform per wavefront (n_pad and nth are multiples of 64)
                 bool regular = true;
                 if (idx[q] >= 0)
-                    regular = emit_ranked_box(b[q], idx[q], r, n_pad, order_f, sorted_f, ysc_f);
+                    regular = emit_ranked_box(b[q], idx[q], r, n_pad, order_f, sorted_f, ysc_f, tsc_f, m);
                 else
-                    emit_padding_row(r, n_pad, sorted_f, ysc_f);
+                    emit_padding_row(r, n_pad, sorted_f, ysc_f, tsc_f);
                 if (ytile_f != nullptr) {
                     const unsigned long long irregular = __ballot(!regular);
                     if (lane == 0) ytile_f[r / kTile] = irregular == 0 ? 1u : 0u;
@@ -245,7 +252,7 @@ __global__ void __launch_bounds__(256)
 rank_merge_kernel(const float *__restrict__ boxes, const int32_t *__restrict__ counts, int n_max, int n_pad,
                   int n_chunks, const unsigned long long *__restrict__ keys_ws,
                   int32_t *__restrict__ order, float *__restrict__ sorted5,
-                  float4 *__restrict__ ysc, unsigned *__restrict__ ytile)
+                  float4 *__restrict__ ysc, unsigned *__restrict__ ytile, float *__restrict__ tsc, double m)
 {
     constexpr int kMine = kMergeBatch / kMergeLanes;  // chunks of a batch per lane
     const int f = blockIdx.y;
@@ -257,8 +264,9 @@ rank_merge_kernel(const float *__restrict__ boxes, const int32_t *__restrict__ c
     if (e >= n_pad) return;
     float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
     float4 *ysc_f = ysc ? ysc + (size_t)f * n_pad : nullptr;
+    float *tsc_f = tsc ? tsc + (size_t)f * n_pad : nullptr;
     if (e >= n_f) {
-        if (q == 0) emit_padding_row(e, n_pad, sorted_f, ysc_f);
+        if (q == 0) emit_padding_row(e, n_pad, sorted_f, ysc_f, tsc_f);
         return;
     }
     const unsigned long long key = kw[e];
@@ -298,7 +306,7 @@ rank_merge_kernel(const float *__restrict__ boxes, const int32_t *__restrict__ c
     rank += e - own * kMergeChunk;
     const int idx = (int)(unsigned)key;
     const bool regular = emit_ranked_box(reinterpret_cast<const float4 *>(boxes + (size_t)f * n_max * 4)[idx], idx, rank,
-                                         n_pad, order + (size_t)f * n_max, sorted_f, ysc_f);
+                                         n_pad, order + (size_t)f * n_max, sorted_f, ysc_f, tsc_f, m);
     // tile flags were preset to 1 by the chunk kernel; concurrent writers all store 0
     if (ytile != nullptr && !regular) ytile[(size_t)f * (n_pad / kTile) + rank / kTile] = 0u;
 }

@@ -58,6 +58,7 @@ struct NmsRunLayout {
     size_t sorted5;  // float [frames][5 * n_pad]      box table: rows (x1,y1,x2,y2), then areas
     size_t ysc;      // float4 [frames][n_pad]         boxes with y * 2^-14, rank order
     size_t ytile;    // uint32 [frames][n_pad / 64]    1 = every box of the tile may use the y-scaled form
+    size_t tsc;      // float [frames][n_pad]          per box, 2^-14 x the float32 its intersections are compared with
     size_t keys;     // uint64 [frames][n_pad]         chunk-sorted keys, only when n_max > sort_chunk
     size_t end;
 };
@@ -74,6 +75,8 @@ NMS_HD NmsRunLayout nms_run_layout(int n_max, int n_pad, int frames, int sort_ch
     p += nms_align256((size_t)frames * (size_t)n_pad * 4 * sizeof(float));
     l.ytile = p;
     p += nms_align256((size_t)frames * (size_t)(n_pad / 64) * sizeof(uint32_t));
+    l.tsc = p;
+    p += nms_align256((size_t)frames * (size_t)n_pad * sizeof(float));
     l.keys = p;
     if (n_max > sort_chunk) p += nms_align256((size_t)frames * (size_t)n_pad * sizeof(unsigned long long));
     l.end = p;

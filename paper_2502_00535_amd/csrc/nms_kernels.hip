@@ -104,7 +104,7 @@ inline int launch_status()
 
 int rank_launch(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
                 int32_t *order, float *sorted5, void *workspace, uint8_t *keep_preset, float4 *ysc, unsigned *ytile,
-                hipStream_t stream)
+                hipStream_t stream, float *tsc = nullptr, double m = 0.0)
 {
     const int n_pad = nms_padded_n(n_max);
     // one chunk up to kChunk boxes; beyond that, chunks of kMergeChunk (more workgroups, shorter sorts) and a merge
@@ -116,7 +116,7 @@ int rank_launch(const float *boxes, const float *scores, const int32_t *counts, 
     begin_launch();
 #define NMS_LAUNCH_RANK(P_, STAGE_)                                                                    \
     rank_chunk_kernel<P_, STAGE_><<<dim3(n_chunks, frames), dim3(P_ / 4), 0, stream>>>(                \
-        boxes, scores, counts, n_max, n_pad, n_chunks, order, sorted5, keys_ws, keep_preset, ysc, ytile)
+        boxes, scores, counts, n_max, n_pad, n_chunks, order, sorted5, keys_ws, keep_preset, ysc, ytile, tsc, m)
     if (n_chunks > 1) NMS_LAUNCH_RANK(kMergeChunk, false);
     else if (threads == 64) NMS_LAUNCH_RANK(256, true);
     else if (threads == 128) NMS_LAUNCH_RANK(512, true);
@@ -128,7 +128,7 @@ int rank_launch(const float *boxes, const float *scores, const int32_t *counts, 
     if (st != NMS_OK || n_chunks == 1) return st;
     begin_launch();
     rank_merge_kernel<<<dim3((n_pad * kMergeLanes + 255) / 256, frames), dim3(256), 0, stream>>>(
-        boxes, counts, n_max, n_pad, n_chunks, keys_ws, order, sorted5, ysc, ytile);
+        boxes, counts, n_max, n_pad, n_chunks, keys_ws, order, sorted5, ysc, ytile, tsc, m);
     return launch_status();
 }
 
@@ -312,6 +312,7 @@ struct RunWorkspace {
     float *sorted5;     // [frames][5 * n_pad]
     float4 *ysc;        // [frames][n_pad]       boxes with y * NMS_YSCALE, rank order
     unsigned *ytile;    // [frames][n_pad / 64]  1 = every box of the tile may use the y-scaled form
+    float *tsc;         // [frames][n_pad]       NMS_YSCALE * T per box (fused map kernel)
     void *keys;         // rank scratch (n_max > NMS_SORT_CHUNK only)
     char *end;
 };
@@ -325,9 +326,37 @@ inline RunWorkspace carve_workspace(void *workspace, int n_max, int frames)
     w.sorted5 = reinterpret_cast<float *>(base + l.sorted5);
     w.ysc = reinterpret_cast<float4 *>(base + l.ysc);
     w.ytile = reinterpret_cast<unsigned *>(base + l.ytile);
+    w.tsc = reinterpret_cast<float *>(base + l.tsc);
     w.keys = base + l.keys;
     w.end = base + l.end;
     return w;
+}
+
+// The fused map step (map_fused_kernel): work units and grid as in map_launch.
+static int fused_launch(const RunWorkspace &w, const int32_t *counts, int n_max, int frames, const NmsThetaConst &th,
+                        uint8_t *keep_out, hipStream_t stream)
+{
+    const int n_pad = nms_padded_n(n_max);
+    const int T = n_pad / kTile;
+    const bool super4 = (long long)frames * nms_triangle_units(T, 4) >= 16384;
+    const bool super2 = !super4 && (long long)frames * nms_triangle_units(T, 2) >= 16384;
+    const int tiles = nms_triangle_units(T, super4 ? 4 : (super2 ? 2 : 1));
+    const int tile_blocks = (tiles + kMapWaves - 1) / kMapWaves;
+    const int xcd_frames = frames >= 8 ? 1 : 0;
+    const dim3 grid = xcd_frames ? dim3((unsigned)(((frames + 7) / 8) * 8 * tile_blocks)) : dim3(tile_blocks, frames);
+    const dim3 block(kMapWaves * 64);
+    begin_launch();
+#define NMS_LAUNCH_FUSED(FAST_, SUPER_)                                                                        \
+    map_fused_kernel<FAST_, SUPER_><<<grid, block, 0, stream>>>(w.sorted5, counts, n_max, n_pad, tiles,        \
+                                                                tile_blocks, frames, xcd_frames, th, w.order,  \
+                                                                keep_out, w.ysc, w.ytile, w.tsc)
+    if (th.fast) {
+        if (super4) NMS_LAUNCH_FUSED(true, 4); else if (super2) NMS_LAUNCH_FUSED(true, 2); else NMS_LAUNCH_FUSED(true, 1);
+    } else {
+        if (super4) NMS_LAUNCH_FUSED(false, 4); else if (super2) NMS_LAUNCH_FUSED(false, 2); else NMS_LAUNCH_FUSED(false, 1);
+    }
+#undef NMS_LAUNCH_FUSED
+    return launch_status();
 }
 
 // forward: defined with the early-exit entry point below
@@ -382,10 +411,12 @@ static int run_routed(Route route, const float *boxes, const float *scores, cons
     }
 
     const RunWorkspace w = carve_workspace(workspace, n_max, frames);
-    st = rank_launch(boxes, scores, counts, n_max, frames, w.order, w.sorted5, w.keys, keep_out, w.ysc, w.ytile, s);
+    const NmsThetaConst th = nms_make_theta_const(threshold);
+    st = rank_launch(boxes, scores, counts, n_max, frames, w.order, w.sorted5, w.keys, keep_out, w.ysc, w.ytile, s,
+                     th.fast ? w.tsc : nullptr, th.m);
     if (st != NMS_OK) return st;
     if (!mark(1)) return NMS_ERR_LAUNCH;
-    st = map_launch<false>(w.sorted5, counts, n_max, frames, threshold, nullptr, w.order, keep_out, w.ysc, w.ytile, s);
+    st = fused_launch(w, counts, n_max, frames, th, keep_out, s);
     if (st != NMS_OK) return st;
     return mark(2) ? NMS_OK : NMS_ERR_LAUNCH;
 }

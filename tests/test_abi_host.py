@@ -54,11 +54,11 @@ def test_size_helpers(nms):
     assert nms.nms_sort_workspace_bytes(4096, 256) == 0
     assert nms.nms_sort_workspace_bytes(4097, 1) == 4160 * 8
     assert nms.nms_sort_workspace_bytes(16384, 2) == 2 * 16384 * 8
-    # order (int32) + box table (5 floats) + y-scaled boxes (4 floats) per padded box + one flag word per
-    # tile, 256-byte aligned parts
-    assert nms.nms_workspace_bytes(1024, 1) == 1024 * 4 + 1024 * 20 + 1024 * 16 + 256
-    assert nms.nms_workspace_bytes(16384, 1) == 16384 * 4 + 16384 * 20 + 16384 * 16 + 1024 + 16384 * 8
-    assert nms.nms_workspace_bytes(100, 3) == 1280 + 7680 + 6144 + 256  # 1200 -> 1280; 3*5*128*4; 3*128*16; 3*2*4 -> 256
+    # order (int32) + box table (5 floats) + y-scaled boxes (4 floats) + scaled threshold (1 float) per padded
+    # box + one flag word per tile, 256-byte aligned parts
+    assert nms.nms_workspace_bytes(1024, 1) == 1024 * 4 + 1024 * 20 + 1024 * 16 + 256 + 1024 * 4
+    assert nms.nms_workspace_bytes(16384, 1) == 16384 * 4 + 16384 * 20 + 16384 * 16 + 1024 + 16384 * 4 + 16384 * 8
+    assert nms.nms_workspace_bytes(100, 3) == 1280 + 7680 + 6144 + 256 + 1536  # 1200 -> 1280; 3*5*128*4; 3*128*16; 3*2*4 -> 256; 3*128*4
     assert nms.nms_greedy_workspace_bytes(1024, 2) == nms.nms_workspace_bytes(1024, 2) + 2 * 16 * 1024 * 8
     assert nms.nms_workspace_bytes(-1, 1) == 0 and nms.nms_workspace_bytes(1, 70000) == 0
 

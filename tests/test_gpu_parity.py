@@ -337,7 +337,11 @@ def test_pool_entry_point_and_side_stream(nms, oracle):
             nms.nms_run(dev.boxes, dev.scores, 1024, w.theta, dev.keep)
         side.synchronize()
         assert np.array_equal(dev.keep.cpu().numpy()[0], want)
-        with pytest.raises(nms.NmsError):
+        big = DeviceFrames(nms, np.zeros((1, 4096, 4), np.float32), np.zeros((1, 4096), np.float32))
+        with pytest.raises(nms.NmsError) as err:  # more boxes than the pool was registered for
+            nms.nms_run(big.boxes, big.scores, 4096, w.theta, big.keep)
+        assert err.value.status == nms.NMS_ERR_WORKSPACE
+        with pytest.raises(ValueError):           # and the binding refuses tensors smaller than n says
             nms.nms_run(dev.boxes, dev.scores, 4096, w.theta, dev.keep)
     finally:
         nms.nms_shutdown()

@@ -82,7 +82,7 @@ def test_limit_and_arguments(nms):
     import torch
 
     dev = torch.device("cuda:0")
-    n_max, F = 4096, 26  # 26 frames of 4096 boxes need more than the array holds
+    n_max, F = 4096, 24  # 24 frames of 4096 boxes need more than the array holds
     assert nms.nms_workspace_bytes(n_max, F) > nms.NMS_STATIC_SCRATCH_BYTES
     boxes = torch.zeros((F, n_max, 4), dtype=torch.float32, device=dev)
     scores = torch.zeros((F, n_max), dtype=torch.float32, device=dev)
@@ -97,6 +97,6 @@ def test_limit_and_arguments(nms):
     assert int(keep.min()) == 77  # nothing was enqueued
     # an empty batch is fine and touches nothing
     nms.nms_run_static_batched(boxes, scores, None, 0, 1, 0.5, keep)
-    nms.nms_run_static_batched(boxes, scores, None, n_max, 25, 0.5, keep)  # the largest 4096-box batch that fits
+    nms.nms_run_static_batched(boxes, scores, None, n_max, 23, 0.5, keep)  # the largest 4096-box batch that fits
     torch.cuda.synchronize()
-    assert int(keep[:25].max()) <= 1
+    assert int(keep[:23].max()) <= 1
