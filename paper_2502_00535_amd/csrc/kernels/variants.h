@@ -49,8 +49,8 @@ __global__ void __launch_bounds__(kMapWaves * 64)
 map_tile_ex_kernel(const float *__restrict__ sorted5, const float *__restrict__ ranked_score,
                    const int32_t *__restrict__ ranked_class, const float *__restrict__ ranked_area,
                    const int32_t *__restrict__ counts, int n_max, int n_pad,
-                   int tiles, int tile_blocks, int frames, int xcd_frames, float theta, double boundary, float offset,
-                   int flags, unsigned long long *__restrict__ mask, const int32_t *__restrict__ order,
+                   int tiles, int tile_blocks, int frames, int xcd_frames, float theta, double boundary,
+                   float boundary_lo, float offset, int flags, unsigned long long *__restrict__ mask, const int32_t *__restrict__ order,
                    uint8_t *__restrict__ keep_out)
 {
     const int lane = threadIdx.x & 63;
@@ -90,6 +90,31 @@ map_tile_ex_kernel(const float *__restrict__ sorted5, const float *__restrict__ 
     const float c_score = AUX ? score_f[c] : 0.0f;
     const int c_class = AUX ? class_f[c] : 0;
     const float c_T = (MODE == kExBoundary && !IOU) ? nms_pair_threshold(c_area, boundary) : 0.0f;
+    // Intersection over union, boundary form: the exact decision, inter >= boundary * denom, is a
+    // float64 compare behind two more float32 operations for the denominator.  Most pairs are
+    // nowhere near the threshold, so two float32 tests go first that can only err towards "maybe":
+    //   1. the union is never smaller than the outranking box's own area -- as float32 values,
+    //      denom >= c_area * (1 - 2^-22): the sum of the areas is at least the larger one, the
+    //      intersection at most the smaller one, two roundings -- so with
+    //      c_T1 = the float32 at or below boundary * c_area * (1 - 2^-21), worked out once per lane,
+    //      inter < c_T1 is a certain miss.  One compare, like the outranking-area measure.
+    //   2. rows in which some lane passed: with boundary_lo <= boundary * (1 - 2^-22),
+    //      RN(denom * boundary_lo) < boundary * denom for every denominator of at least 2^-40 (the
+    //      product's rounding error is 2^-24 relative), so inter < RN(denom * boundary_lo) is a certain
+    //      miss too.  The condition on the denominator is checked once per work unit on the lanes'
+    //      areas; a unit that fails it skips this test.
+    // Rows that still hold a "maybe" are decided exactly.
+    constexpr bool kPretest = IOU && MODE == kExBoundary;
+    const bool pretest = kPretest && __ballot(c_area < 0x1p-40f) == 0ull;
+    float c_lo = boundary_lo;  // in a vector register, like `off`
+    asm volatile("" : "+v"(c_lo));
+    float c_T1 = 0.0f;
+    if (kPretest) {
+        const double t = boundary * (double)c_area * (1.0 - 0x1p-21);
+        c_T1 = (float)t;
+        if ((double)c_T1 > t) c_T1 = __uint_as_float(__float_as_uint(c_T1) - 1u);  // next float32 down (t > 0)
+        if (!(c_T1 > 0.0f)) c_T1 = 0.0f;
+    }
 
     // one tile; DIAG: the tile on the diagonal, where only better-ranked boxes of the tile eliminate
     auto tile = [&](auto on_diagonal) __attribute__((always_inline)) {
@@ -126,25 +151,38 @@ map_tile_ex_kernel(const float *__restrict__ sorted5, const float *__restrict__ 
                 if (MODE != kExBoundary) iw = fmaxf(0.0f, iw);
                 const float ih = fmaxf(0.0f, (fminf(v[k].w, cb.w) - fmaxf(v[k].y, cb.y)) + off);
                 const float inter = iw * ih;
-                const float denom = IOU ? (v_area[k] + c_area) - inter : c_area;
                 bool hit;
                 if (MODE == kExBoundary && !IOU)
                     hit = inter >= c_T;  // the denominator is the lane's own area: one float32 threshold per box, as in nms_pair.h
                 else if (MODE == kExBoundary)
-                    hit = (double)inter >= boundary * (double)denom;
+                    hit = inter >= c_T1;  // certain miss below it (see above); decided further down otherwise
                 else if (MODE == kExDivideGe)
-                    hit = !(inter / denom < theta);
+                    hit = !(inter / (IOU ? (v_area[k] + c_area) - inter : c_area) < theta);
                 else
-                    hit = inter / denom > theta;
-                if (AUX) {
-                    hit = hit && (!ties_ignore || c_score > v_score[k]);
-                    hit = hit && (!labelled || c_class == v_class[k]);
-                }
+                    hit = inter / (IOU ? (v_area[k] + c_area) - inter : c_area) > theta;
                 unsigned long long word = __ballot(hit);
                 if (DIAG) word &= (1ull << r) - 1ull;
+                if (AUX && word != 0) {  // wave-uniform: scores and labels matter only where the boxes overlap enough
+                    asm volatile("" ::: "memory");  // keeps this a branch
+                    if (ties_ignore) word &= __ballot(c_score > v_score[k]);
+                    if (labelled) word &= __ballot(c_class == v_class[k]);
+                }
+                if (kPretest && word != 0) {  // wave-uniform: some pair of the row may reach the threshold
+                    asm volatile("" ::: "memory");  // keeps this a branch
+                    const float denom = (v_area[k] + c_area) - inter;
+                    unsigned long long maybe = word;
+                    if (pretest) maybe &= __ballot(inter >= denom * c_lo);
+                    if (maybe != 0) {
+                        asm volatile("" ::: "memory");
+                        maybe &= __ballot((double)inter >= boundary * (double)denom);
+                    }
+                    word = maybe;
+                }
                 words[k] = word;
-                grp_bits |= (unsigned)((word | (0ull - word)) >> 63) << k;  // (word != 0) << k in scalar arithmetic
             }
+#pragma unroll
+            for (int k = 0; k < kGroup; ++k)
+                grp_bits |= (unsigned)((words[k] | (0ull - words[k])) >> 63) << k;  // (word != 0) << k in scalar arithmetic
             if (WRITE_MASK) {
 #pragma unroll
                 for (int k = 0; k < kGroup; ++k) {

@@ -694,6 +694,13 @@ int nms_run_ex_batched(const float *boxes, const float *scores, const int32_t *c
         boundary = 0.5 * ((double)threshold + (double)other);
         divide = false;
     }
+    // a float32 at or below boundary * (1 - 2^-22): the factor of the variants kernel's first, float32 test
+    float boundary_lo = 0.0f;
+    if (!divide) {
+        const double want = boundary * (1.0 - 0x1p-22);
+        boundary_lo = (float)want;
+        if ((double)boundary_lo > want) boundary_lo = nextafterf(boundary_lo, 0.0f);
+    }
     const int flags = (opt.ties == NMS_TIES_IGNORE ? kExTiesIgnore : 0) | (opt.classes ? kExClasses : 0);
     const int mode = !divide ? kExBoundary : (opt.compare == NMS_COMPARE_GT ? kExDivideGt : kExDivideGe);
     const bool iou = opt.measure == NMS_MEASURE_IOU;
@@ -725,7 +732,7 @@ int nms_run_ex_batched(const float *boxes, const float *scores, const int32_t *c
 #define NMS_LAUNCH_EX_SUPER(IOU_, MODE_, AUX_, SUPER_, MASK_)                                                     \
     map_tile_ex_kernel<IOU_, MODE_, AUX_, SUPER_, MASK_><<<grid, dim3(kMapWaves * 64), 0, s>>>(                   \
         w.sorted5, ranked_score, ranked_class, ranked_area, counts, n_max, n_pad, tiles, tile_blocks, frames,     \
-        xcd_frames, threshold, boundary, opt.pixel_offset, flags, mask, w.order, keep_out)
+        xcd_frames, threshold, boundary, boundary_lo, opt.pixel_offset, flags, mask, w.order, keep_out)
 #define NMS_LAUNCH_EX(IOU_, MODE_, AUX_)                                                  \
     do {                                                                                  \
         if (fold) {                                                                       \
