@@ -90,6 +90,12 @@ int nms_padded_n(int n);                                  /* n rounded up to a m
 size_t nms_mask_words(int n);                             /* ceil(n/64) * nms_padded_n(n) */
 size_t nms_sort_workspace_bytes(int n_max, int frames);   /* scratch of nms_sort*: 0 when n_max <= NMS_SORT_CHUNK */
 size_t nms_workspace_bytes(int n_max, int frames);        /* scratch of nms_run_ws / nms_run_batched */
+/* Which kernels nms_run_batched launches for a batch shape: one of NMS_ROUTE_*; -1 on invalid sizes. */
+#define NMS_ROUTE_DIRECT 0
+#define NMS_ROUTE_ALL_PAIRS 1
+#define NMS_ROUTE_TWO_LAUNCH 2
+#define NMS_ROUTE_EARLY_EXIT 3
+int nms_route(int n_max, int frames);
 
 /*
  * Step 1 - rank.  The total order that Algorithm 1 evaluates per pair as
@@ -133,12 +139,17 @@ int nms_reduce_batched(const uint64_t *mask, const int32_t *order, const int32_t
 /*
  * The whole path in one call.  No mask is written to memory: the row AND is folded
  * into the pair tests, and the result is the same keep vector as steps 1-3 give.
- * The call picks its route by size: direct (one launch) for small work, ranked (rank step +
- * all pair tests of the ranked triangle) otherwise, and for large batches of frames of 1024
- * boxes or more (frames * n_max^2 >= 2^29) the early-exit route (nms_run_early_exit_batched
- * below), which returns the same bits from a fraction of the pair tests on clustered
- * detections.  Callers that want every pair evaluated whatever the size (a fixed running
- * time) call nms_run_ranked_batched.
+ * The call picks its route by size (nms_route() names it); every route returns the same bits:
+ *   NMS_ROUTE_DIRECT      small work (up to about 2^25 pair slots = frames * n_max^2): one launch.
+ *   NMS_ROUTE_ALL_PAIRS   rank step, then every pair test of the ranked triangle.
+ *   NMS_ROUTE_TWO_LAUNCH  frames beyond NMS_SORT_CHUNK boxes, 2^27 <= pair slots < 2^31: rank step,
+ *                         every victim against the best 2048 ranks, then only the victims still
+ *                         alive against the rest.
+ *   NMS_ROUTE_EARLY_EXIT  large batches (frames of 1024 to NMS_SORT_CHUNK boxes from 2^29 pair
+ *                         slots, larger frames from 2^31): nms_run_early_exit_batched below.
+ * The last two skip pair tests of victims that already have an eliminator, so their running
+ * time depends on the data.  Callers that want every pair evaluated whatever the size (a fixed
+ * running time) call nms_run_ranked_batched.
  *   workspace >= nms_workspace_bytes(n or n_max, 1 or frames) bytes, 256-byte aligned
  *             (always required, whichever route is taken).
  * Two calls that share a workspace must be ordered on one stream.

@@ -17,10 +17,11 @@ NMS_ERR_INVALID_ARG = -1
 NMS_ERR_TOO_LARGE = -2
 NMS_ERR_WORKSPACE = -3
 NMS_ERR_LAUNCH = -4
+NMS_ROUTE_DIRECT, NMS_ROUTE_ALL_PAIRS, NMS_ROUTE_TWO_LAUNCH, NMS_ROUTE_EARLY_EXIT = 0, 1, 2, 3
 
 EXPORTS = (
     "nms_status_string", "nms_version", "nms_last_launch_error", "nms_padded_n", "nms_mask_words",
-    "nms_sort_workspace_bytes", "nms_workspace_bytes",
+    "nms_sort_workspace_bytes", "nms_workspace_bytes", "nms_route",
     "nms_sort", "nms_sort_batched", "nms_overlap_mask", "nms_overlap_mask_batched",
     "nms_reduce", "nms_reduce_batched", "nms_run_ws", "nms_run_batched", "nms_run_ranked_batched", "nms_run_direct_batched",
     "nms_run_batched_profiled", "nms_reduce_greedy", "nms_reduce_greedy_batched",
@@ -80,6 +81,8 @@ def _load() -> ctypes.CDLL:
     L.nms_sort_workspace_bytes.argtypes = [i32, i32]
     L.nms_workspace_bytes.restype = sz
     L.nms_workspace_bytes.argtypes = [i32, i32]
+    L.nms_route.restype = i32
+    L.nms_route.argtypes = [i32, i32]
     L.nms_sort.restype = i32
     L.nms_sort.argtypes = [vp, vp, i32, vp, vp, vp, sz, vp]
     L.nms_sort_batched.restype = i32
@@ -218,6 +221,10 @@ def nms_sort_workspace_bytes(n_max: int, frames: int) -> int:
 
 def nms_workspace_bytes(n_max: int, frames: int) -> int:
     return int(lib.nms_workspace_bytes(int(n_max), int(frames)))
+
+
+def nms_route(n_max: int, frames: int) -> int:
+    return int(lib.nms_route(int(n_max), int(frames)))
 
 
 def nms_host_pair_test(victim, outranking, threshold: float) -> int:

@@ -187,15 +187,25 @@ map_tile_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ c
 // the constant address space, so that they are scalar loads whatever else the kernel loads.
 typedef const __attribute__((address_space(4))) float *nms_uniform_float_ptr;
 
-template <int PAIR, bool DIAG>
+// Which victims of the wavefront an outranking box may eliminate at all: every lane (the tile of
+// outranking boxes lies wholly before the victims), the lanes behind it in the same tile, or --
+// lanes that hold victims of arbitrary ranks -- the lanes whose victim is ranked behind it.
+enum { kMaskNone = 0, kMaskDiagonal = 1, kMaskByRank = 2 };
+
+// r_lane: rank of the lane's victim, c_base: rank of the tile's first outranking box (kMaskByRank only).
+// The tile's boxes are taken in groups of kFusedGroup, groups [grp_begin, grp_end).
+constexpr int kFusedGroup = 8;  // outranking boxes fetched together: 40 SGPRs
+
+template <int PAIR, int MASK>
 __device__ __forceinline__ unsigned long long fused_candidates(const float4 *__restrict__ cb,
                                                                const float *__restrict__ caux, const float4 vb,
-                                                               float y_one, float theta)
+                                                               float y_one, float theta, int r_lane, int c_base,
+                                                               int grp_begin = 0, int grp_end = kTile / kFusedGroup)
 {
     unsigned long long acc = 0;
-    constexpr int kGroup = 8;  // outranking boxes fetched together: 40 SGPRs
+    constexpr int kGroup = kFusedGroup;
 #pragma unroll 1
-    for (int grp = 0; grp < kTile / kGroup; ++grp) {
+    for (int grp = grp_begin; grp < grp_end; ++grp) {
         const nms_uniform_float_ptr cg = (nms_uniform_float_ptr)(uintptr_t)(cb + kGroup * grp);
         const nms_uniform_float_ptr ag = (nms_uniform_float_ptr)(uintptr_t)(caux + kGroup * grp);
 #pragma unroll
@@ -210,12 +220,71 @@ __device__ __forceinline__ unsigned long long fused_candidates(const float4 *__r
             else
                 hit = nms_eliminates_exact(vb.x, vb.y, vb.z, vb.w, c.x, c.y, c.z, c.w, a, theta);
             unsigned long long word = __ballot(hit);
-            if (DIAG) {  // same tile: only victims ranked behind this box count
-                const int ci = kGroup * grp + k;
-                word &= ci == kTile - 1 ? 0ull : (~0ull << (ci + 1));
-            }
+            const int ci = kGroup * grp + k;
+            if (MASK == kMaskDiagonal) word &= ci == kTile - 1 ? 0ull : (~0ull << (ci + 1));
+            if (MASK == kMaskByRank) word &= __ballot(r_lane > c_base + ci);
             acc |= word;
         }
+    }
+    return acc;
+}
+
+// The same with the next group's scalar loads in flight while a group is worked on, for launches
+// that leave a SIMD with one or two wavefronts and nobody else to cover a load's latency (the
+// two-launch route's second launch).  Groups of four (two buffers of 20 scalar registers).  Scalar
+// loads may complete out of order, so a wait for one buffer waits for all loads issued before it:
+// the next group is requested only after the current one has arrived.
+template <int PAIR, int MASK>
+__device__ __forceinline__ unsigned long long fused_candidates_ahead(const float4 *__restrict__ cb,
+                                                                     const float *__restrict__ caux, const float4 vb,
+                                                                     float y_one, float theta, int r_lane, int c_base)
+{
+    constexpr int kGroup = 4;
+    constexpr int kGroups = kTile / kGroup;
+    unsigned long long acc = 0;
+    float4 c[2][kGroup];
+    float a[2][kGroup];
+    auto fetch = [&](int buf, int grp) __attribute__((always_inline)) {
+        const nms_uniform_float_ptr cg = (nms_uniform_float_ptr)(uintptr_t)(cb + kGroup * grp);
+        const nms_uniform_float_ptr ag = (nms_uniform_float_ptr)(uintptr_t)(caux + kGroup * grp);
+#pragma unroll
+        for (int k = 0; k < kGroup; ++k) {
+            c[buf][k] = make_float4(cg[4 * k], cg[4 * k + 1], cg[4 * k + 2], cg[4 * k + 3]);
+            a[buf][k] = ag[k];
+        }
+    };
+    auto work = [&](int buf, int grp) __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < kGroup; ++k) {
+            const float4 cc = c[buf][k];
+            const float aa = a[buf][k];
+            bool hit;
+            if (PAIR == kPairFastYScaled)
+                hit = nms_eliminates_fast_yscaled(vb.x, vb.y, vb.z, vb.w, cc.x, cc.y, cc.z, cc.w, aa, y_one);
+            else if (PAIR == kPairFast)
+                hit = nms_eliminates_fast(vb.x, vb.y, vb.z, vb.w, cc.x, cc.y, cc.z, cc.w, aa * (1.0f / NMS_YSCALE));
+            else
+                hit = nms_eliminates_exact(vb.x, vb.y, vb.z, vb.w, cc.x, cc.y, cc.z, cc.w, aa, theta);
+            unsigned long long word = __ballot(hit);
+            const int ci = kGroup * grp + k;
+            if (MASK == kMaskDiagonal) word &= ci == kTile - 1 ? 0ull : (~0ull << (ci + 1));
+            if (MASK == kMaskByRank) word &= __ballot(r_lane > c_base + ci);
+            acc |= word;
+        }
+    };
+    fetch(0, 0);
+#pragma unroll 1
+    for (int grp = 0; grp < kGroups; grp += 2) {
+        asm volatile("" ::"s"(a[0][kGroup - 1]));  // buffer 0 has arrived ...
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(1, grp + 1);                           // ... request the next group, then work
+        __builtin_amdgcn_sched_barrier(0);
+        work(0, grp);
+        asm volatile("" ::"s"(a[1][kGroup - 1]));
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(0, grp + 2 < kGroups ? grp + 2 : 0);  // (the last request is not used)
+        __builtin_amdgcn_sched_barrier(0);
+        work(1, grp + 1);
     }
     return acc;
 }
@@ -272,16 +341,16 @@ map_fused_kernel(const float *__restrict__ sorted5, const int32_t *__restrict__ 
         const int tc = T - 1 - v;
         if (r_regular && ytile_f[tc] != 0) {
             if (tc == tr)
-                acc |= fused_candidates<kPairFastYScaled, true>(ysc4 + tc * kTile, tsc_f + tc * kTile, vbs, y_one, th.theta);
+                acc |= fused_candidates<kPairFastYScaled, kMaskDiagonal>(ysc4 + tc * kTile, tsc_f + tc * kTile, vbs, y_one, th.theta, 0, 0);
             else
-                acc |= fused_candidates<kPairFastYScaled, false>(ysc4 + tc * kTile, tsc_f + tc * kTile, vbs, y_one, th.theta);
+                acc |= fused_candidates<kPairFastYScaled, kMaskNone>(ysc4 + tc * kTile, tsc_f + tc * kTile, vbs, y_one, th.theta, 0, 0);
         } else {
             const float4 vb = box4[row];
             const float *caux = FAST ? tsc_f + tc * kTile : area + tc * kTile;
             if (tc == tr)
-                acc |= fused_candidates<FAST ? kPairFast : kPairExact, true>(box4 + tc * kTile, caux, vb, y_one, th.theta);
+                acc |= fused_candidates<FAST ? kPairFast : kPairExact, kMaskDiagonal>(box4 + tc * kTile, caux, vb, y_one, th.theta, 0, 0);
             else
-                acc |= fused_candidates<FAST ? kPairFast : kPairExact, false>(box4 + tc * kTile, caux, vb, y_one, th.theta);
+                acc |= fused_candidates<FAST ? kPairFast : kPairExact, kMaskNone>(box4 + tc * kTile, caux, vb, y_one, th.theta, 0, 0);
         }
     }
     if (((acc >> lane) & 1ull) && row < n_f) keep_out[(size_t)f * n_max + order[(size_t)f * n_max + row]] = 0;

@@ -18,6 +18,7 @@
 #include <hip/hip_runtime.h>
 
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <mutex>
@@ -53,6 +54,7 @@ __device__ __forceinline__ int frame_count(const int32_t *counts, int f, int n_m
 #include "kernels/greedy_walk.h"
 #include "kernels/variants.h"
 #include "kernels/early_exit.h"
+#include "kernels/staged.h"
 #include "kernels/matrix_form.h"
 
 // ----------------------------------------------------------------------------- host side
@@ -130,19 +132,6 @@ int rank_launch(const float *boxes, const float *scores, const int32_t *counts, 
     rank_merge_kernel<<<dim3((n_pad * kMergeLanes + 255) / 256, frames), dim3(256), 0, stream>>>(
         boxes, counts, n_max, n_pad, n_chunks, keys_ws, order, sorted5, ysc, ytile, tsc, m);
     return launch_status();
-}
-
-// Frames small enough that launch latency, not arithmetic, decides: one launch of the
-// direct form instead of rank + map.  (Twice the pairs and two more compares per pair:
-// about 2.5x the VALU work of the ranked triangle.)
-// The crossover in GPU time sits near 2^25 pair slots per batch and moves with the frame size,
-// because the rank step it saves does (15 us at 1024 boxes, 23 us at 4096): measured 24 to 32
-// frames of 1024 boxes, 8 to 12 of 2048, 3 to 4 of 4096.
-inline bool use_direct_form(int n_max, int frames)
-{
-    const long long slots = (long long)frames * n_max * n_max;
-    const long long limit = n_max > 2048 ? (3ll << 24) : (n_max > 512 && n_max <= 1024 ? (3ll << 23) : (1ll << 25));
-    return n_max <= 4096 && slots <= limit;
 }
 
 int direct_launch(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
@@ -249,6 +238,17 @@ size_t nms_workspace_bytes(int n_max, int frames)
     return nms_run_layout(n_max, nms_padded_n(n_max), frames, kChunk).end;
 }
 
+static_assert(kNmsRouteDirect == NMS_ROUTE_DIRECT && kNmsRouteAllPairs == NMS_ROUTE_ALL_PAIRS &&
+                  kNmsRouteTwoLaunch == NMS_ROUTE_TWO_LAUNCH && kNmsRouteEarlyExit == NMS_ROUTE_EARLY_EXIT,
+              "route numbers of the header and of the host logic");
+
+int nms_route(int n_max, int frames)
+{
+    int st;
+    if (!sizes_ok(n_max, frames, &st) || n_max == 0 || frames == 0) return -1;
+    return nms_route_for(n_max, frames, kChunk);
+}
+
 int nms_sort_batched(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
                      int32_t *order, float *sorted5, void *workspace, size_t ws_bytes, void *stream)
 {
@@ -314,6 +314,7 @@ struct RunWorkspace {
     unsigned *ytile;    // [frames][n_pad / 64]  1 = every box of the tile may use the y-scaled form
     float *tsc;         // [frames][n_pad]       NMS_YSCALE * T per box (fused map kernel)
     void *keys;         // rank scratch (n_max > NMS_SORT_CHUNK only)
+    unsigned long long *stage;  // [frames][n_pad / 64][32] lane masks of the victims that each unit of the two-launch route's first launch eliminates (n_max > NMS_SORT_CHUNK only)
     char *end;
 };
 
@@ -328,6 +329,7 @@ inline RunWorkspace carve_workspace(void *workspace, int n_max, int frames)
     w.ytile = reinterpret_cast<unsigned *>(base + l.ytile);
     w.tsc = reinterpret_cast<float *>(base + l.tsc);
     w.keys = base + l.keys;
+    w.stage = reinterpret_cast<unsigned long long *>(base + l.stage);
     w.end = base + l.end;
     return w;
 }
@@ -359,19 +361,36 @@ static int fused_launch(const RunWorkspace &w, const int32_t *counts, int n_max,
     return launch_status();
 }
 
+static int staged_launch(const RunWorkspace &w, const int32_t *counts, int n_max, int frames, const NmsThetaConst &th,
+                         uint8_t *keep_out, hipStream_t stream)
+{
+    const int n_pad = nms_padded_n(n_max);
+    const int T = n_pad / kTile;
+    const dim3 first_grid((unsigned)(T * kStageTiles / kMapWaves), frames);
+    int parts = 256 / frames;  // persistent workgroups of the second launch: one per compute unit (192 to 384 measure alike, 512: +3 %, 128: +18 %)
+    if (parts < 1) parts = 1;
+    begin_launch();
+    if (th.fast)
+        staged_first_kernel<true><<<first_grid, dim3(kMapWaves * 64), 0, stream>>>(w.sorted5, counts, n_max, n_pad, th, w.order,
+                                                                                   keep_out, w.ysc, w.ytile, w.tsc, w.stage);
+    else
+        staged_first_kernel<false><<<first_grid, dim3(kMapWaves * 64), 0, stream>>>(w.sorted5, counts, n_max, n_pad, th, w.order,
+                                                                                    keep_out, w.ysc, w.ytile, w.tsc, w.stage);
+    int st = launch_status();
+    if (st != NMS_OK) return st;
+    begin_launch();
+    if (th.fast)
+        staged_second_kernel<true><<<dim3(parts, frames), dim3(kStageWaves * 64), 0, stream>>>(
+            w.sorted5, counts, n_max, n_pad, th, w.order, keep_out, w.ysc, w.ytile, w.tsc, w.stage);
+    else
+        staged_second_kernel<false><<<dim3(parts, frames), dim3(kStageWaves * 64), 0, stream>>>(
+            w.sorted5, counts, n_max, n_pad, th, w.order, keep_out, w.ysc, w.ytile, w.tsc, w.stage);
+    return launch_status();
+}
+
 // forward: defined with the early-exit entry point below
 static int early_exit_launch(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
                              float threshold, uint8_t *keep_out, void *workspace, hipStream_t s);
-
-// Large batches of frames of a thousand boxes or more: the route that stops testing a victim
-// once it has an eliminator returns the same keep vector 1.3 to 3.3 times sooner on clustered
-// detections (what a detector emits) and 0.7 to 1.0 times as fast when almost nothing is
-// eliminated (measured on 32 to 1024 frames of 1024 to 4096 boxes).  Frames of 512 boxes or
-// fewer never gain: their stages are mostly barriers.
-inline bool use_early_exit(int n_max, int frames)
-{
-    return n_max >= 1024 && (long long)frames * n_max * n_max >= (1ll << 29);
-}
 
 // kRouteAuto: direct, ranked or early exit by size.  kRouteAllPairs: direct or ranked by size
 // (every pair of the ranked triangle is evaluated).
@@ -387,14 +406,14 @@ static int run_routed(Route route, const float *boxes, const float *scores, cons
     if (n_max == 0 || frames == 0) return NMS_OK;
     if (!boxes || !scores || !keep_out) return NMS_ERR_INVALID_ARG;
     const bool by_size = route == kRouteAuto || route == kRouteAllPairs;
-    const bool direct = route == kRouteDirect || (by_size && use_direct_form(n_max, frames));
+    const bool direct = route == kRouteDirect || (by_size && nms_use_direct_form(n_max, frames));
     if (route != kRouteDirect) {  // the automatic route validates the workspace whichever way it goes
         const size_t need = nms_workspace_bytes(n_max, frames);
         if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)) return NMS_ERR_WORKSPACE;
     }
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (route == kRouteAuto && !direct && use_early_exit(n_max, frames))
+    if (route == kRouteAuto && !direct && nms_use_early_exit(n_max, frames, kChunk))
         return early_exit_launch(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, s);
     auto mark = [&](int i) {
         if (!events || !events[i]) return true;
@@ -412,11 +431,15 @@ static int run_routed(Route route, const float *boxes, const float *scores, cons
 
     const RunWorkspace w = carve_workspace(workspace, n_max, frames);
     const NmsThetaConst th = nms_make_theta_const(threshold);
+    const bool staged = route == kRouteAuto && nms_use_two_launches(n_max, frames, kChunk);
     st = rank_launch(boxes, scores, counts, n_max, frames, w.order, w.sorted5, w.keys, keep_out, w.ysc, w.ytile, s,
                      th.fast ? w.tsc : nullptr, th.m);
     if (st != NMS_OK) return st;
     if (!mark(1)) return NMS_ERR_LAUNCH;
-    st = fused_launch(w, counts, n_max, frames, th, keep_out, s);
+    if (staged)
+        st = staged_launch(w, counts, n_max, frames, th, keep_out, s);
+    else
+        st = fused_launch(w, counts, n_max, frames, th, keep_out, s);
     if (st != NMS_OK) return st;
     return mark(2) ? NMS_OK : NMS_ERR_LAUNCH;
 }

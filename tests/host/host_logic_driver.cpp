@@ -64,7 +64,7 @@ int main(int argc, char **argv)
         while (scanf("%d %d %d", &n_max, &frames, &chunk) == 3) {
             const int n_pad = (n_max + 63) / 64 * 64;
             const NmsRunLayout l = nms_run_layout(n_max, n_pad, frames, chunk);
-            printf("%zu %zu %zu %zu %zu %zu %zu\n", l.order, l.sorted5, l.ysc, l.ytile, l.tsc, l.keys, l.end);
+            printf("%zu %zu %zu %zu %zu %zu %zu %zu\n", l.order, l.sorted5, l.ysc, l.ytile, l.tsc, l.keys, l.stage, l.end);
         }
         return 0;
     }

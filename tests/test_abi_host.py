@@ -55,12 +55,30 @@ def test_size_helpers(nms):
     assert nms.nms_sort_workspace_bytes(4097, 1) == 4160 * 8
     assert nms.nms_sort_workspace_bytes(16384, 2) == 2 * 16384 * 8
     # order (int32) + box table (5 floats) + y-scaled boxes (4 floats) + scaled threshold (1 float) per padded
-    # box + one flag word per tile, 256-byte aligned parts
+    # box + one flag word per tile, 256-byte aligned parts; beyond 4096 boxes the rank step's keys and the
+    # two-launch route's masks (32 words per tile of ranks)
     assert nms.nms_workspace_bytes(1024, 1) == 1024 * 4 + 1024 * 20 + 1024 * 16 + 256 + 1024 * 4
-    assert nms.nms_workspace_bytes(16384, 1) == 16384 * 4 + 16384 * 20 + 16384 * 16 + 1024 + 16384 * 4 + 16384 * 8
+    assert nms.nms_workspace_bytes(16384, 1) == 16384 * 4 + 16384 * 20 + 16384 * 16 + 1024 + 16384 * 4 + 16384 * 8 + 256 * 32 * 8
     assert nms.nms_workspace_bytes(100, 3) == 1280 + 7680 + 6144 + 256 + 1536  # 1200 -> 1280; 3*5*128*4; 3*128*16; 3*2*4 -> 256; 3*128*4
     assert nms.nms_greedy_workspace_bytes(1024, 2) == nms.nms_workspace_bytes(1024, 2) + 2 * 16 * 1024 * 8
     assert nms.nms_workspace_bytes(-1, 1) == 0 and nms.nms_workspace_bytes(1, 70000) == 0
+
+
+def test_route_by_size():
+    """nms_route: which kernels the automatic call launches, for the five benchmark shapes and at
+    each border of the size rules."""
+    import paper_2502_00535_amd.binding as nms
+
+    D, A, T, E = nms.NMS_ROUTE_DIRECT, nms.NMS_ROUTE_ALL_PAIRS, nms.NMS_ROUTE_TWO_LAUNCH, nms.NMS_ROUTE_EARLY_EXIT
+    shapes = {(256, 1): D, (4096, 1): D, (1024, 64): A, (16384, 1): T, (4096, 256): E,
+              (1024, 24): D, (1024, 25): A, (4096, 3): D, (4096, 4): A,
+              (1024, 511): A, (1024, 512): E, (1023, 4096): A, (512, 60000): A, (4096, 31): A, (4096, 32): E,
+              (4097, 1): A, (11585, 1): A, (11586, 1): T, (16384, 7): T, (16384, 8): E, (46340, 1): T, (46341, 1): E,
+              (65536, 1): E, (8192, 2): T, (8192, 1): A}
+    for (n, f), want in shapes.items():
+        assert nms.nms_route(n, f) == want, (n, f)
+    assert nms.nms_route(0, 1) == -1 and nms.nms_route(5, 0) == -1 and nms.nms_route(-1, 1) == -1
+    assert nms.nms_route(70000, 1) == -1
 
 
 def test_argument_errors_before_launch(nms):

@@ -54,15 +54,16 @@ def test_workspace_layout_matches_the_size_helper(driver):
              (16384, 40), (65536, 1), (65536, 9), (300, 65535)]
     text = "".join(f"{n} {f} 4096\n" for n, f in cases)
     rows = [list(map(int, line.split())) for line in run(driver, "layout", stdin=text).strip().split("\n")]
-    for (n, f), (order, sorted5, ysc, ytile, tsc, keys, end) in zip(cases, rows):
+    for (n, f), (order, sorted5, ysc, ytile, tsc, keys, stage, end) in zip(cases, rows):
         n_pad = nms.nms_padded_n(n)
         assert end == nms.nms_workspace_bytes(n, f), (n, f)
-        offsets = [order, sorted5, ysc, ytile, tsc, keys, end]
+        offsets = [order, sorted5, ysc, ytile, tsc, keys, stage, end]
         assert offsets == sorted(offsets) and all(o % 256 == 0 for o in offsets)
         # every part holds what is stored there
         assert sorted5 - order >= 4 * n * f and ysc - sorted5 >= 20 * n_pad * f
         assert ytile - ysc >= 16 * n_pad * f and tsc - ytile >= 4 * (n_pad // 64) * f and keys - tsc >= 4 * n_pad * f
-        assert end - keys == nms.nms_sort_workspace_bytes(n, f)
+        assert stage - keys == nms.nms_sort_workspace_bytes(n, f)
+        assert end - stage == (0 if n <= 4096 else -(-(f * (n_pad // 64) * 32 * 8) // 256) * 256)
 
 
 def real_key(score, index):
