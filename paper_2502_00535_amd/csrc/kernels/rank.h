@@ -137,6 +137,97 @@ __device__ __forceinline__ void radix_rank_chunk(unsigned (&key)[4], unsigned (&
     }
 }
 
+// The same sort for workgroups of at most four wavefronts (W = blockDim.x / 64), with fewer trips
+// through LDS and two barriers per pass instead of four:
+//   - a wavefront keeps one table of lane masks per register q, so the four ORs and the reads are
+//     issued together: element (q, lane) with digit d stands behind the elements of earlier q
+//     with that digit (population counts of their masks at d) and behind the lower lanes of its
+//     own mask; the first lane of each mask adds its population to the wavefront's histogram and
+//     clears the entry;
+//   - after the barrier every wavefront turns the W histograms into its own start offsets (lane l
+//     takes digits 4l .. 4l+3: totals over the wavefronts, prefix sum across the lanes, plus the
+//     counts of the wavefronts before its own) and keeps them in a row of its own, so the scatter
+//     follows without another barrier.
+// match: W x 4 x 256 lane masks; hist, wbase: W x 256 counters each.
+template <int W>
+__device__ __forceinline__ void radix_rank_small(unsigned (&key)[4], unsigned (&idx)[4], const int (&e)[4],
+                                                 unsigned long long *buf, unsigned *hist, unsigned *wbase,
+                                                 unsigned long long *match)
+{
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    unsigned *myhist = hist + wave * 256;
+    unsigned *mybase = wbase + wave * 256;
+    unsigned long long *mytab = match + wave * 1024;
+    for (int i = lane; i < 1024; i += 64) mytab[i] = 0ull;
+#pragma unroll 1
+    for (int shift = 0; shift < 32; shift += 8) {
+        reinterpret_cast<uint4 *>(myhist)[lane] = make_uint4(0u, 0u, 0u, 0u);
+        unsigned d[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            d[q] = (key[q] >> shift) & 255u;
+            __hip_atomic_fetch_or(&mytab[q * 256 + d[q]], 1ull << lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+        }
+        // a wavefront's LDS instructions execute in order: the fence only keeps the compiler from moving the reads up
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        unsigned long long own[4];
+        unsigned before[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            before[q] = 0;
+#pragma unroll
+            for (int p = 0; p < q; ++p)
+                before[q] += (unsigned)__popcll(__hip_atomic_load(&mytab[p * 256 + d[q]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT));
+            own[q] = __hip_atomic_load(&mytab[q * 256 + d[q]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        unsigned place[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const unsigned m_lo = (unsigned)own[q], m_hi = (unsigned)(own[q] >> 32);
+            const unsigned below = __builtin_amdgcn_mbcnt_hi(m_hi, __builtin_amdgcn_mbcnt_lo(m_lo, 0u));
+            place[q] = before[q] + below;
+            if (below == 0) {
+                __hip_atomic_fetch_add(&myhist[d[q]], __popc(m_lo) + __popc(m_hi), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                __hip_atomic_store(&mytab[q * 256 + d[q]], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+            }
+        }
+        __syncthreads();
+        {
+            uint4 h[W];
+#pragma unroll
+            for (int w = 0; w < W; ++w) h[w] = reinterpret_cast<const uint4 *>(hist + w * 256)[lane];
+            uint4 all = make_uint4(0u, 0u, 0u, 0u), pre = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int w = 0; w < W; ++w) {
+                if (w < wave) { pre.x += h[w].x; pre.y += h[w].y; pre.z += h[w].z; pre.w += h[w].w; }
+                all.x += h[w].x; all.y += h[w].y; all.z += h[w].z; all.w += h[w].w;
+            }
+            const unsigned sum = all.x + all.y + all.z + all.w;
+            const unsigned excl = wave_inclusive_sum(sum) - sum;
+            reinterpret_cast<uint4 *>(mybase)[lane] = make_uint4(excl + pre.x, excl + all.x + pre.y, excl + all.x + all.y + pre.z,
+                                                                 excl + all.x + all.y + all.z + pre.w);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const unsigned dest = __hip_atomic_load(&mybase[d[q]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT) + place[q];
+            buf[dest] = ((unsigned long long)key[q] << 32) | idx[q];
+        }
+        __syncthreads();
+        if (shift < 24) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const unsigned long long v = buf[e[q]];
+                key[q] = (unsigned)(v >> 32);
+                idx[q] = (unsigned)v;
+            }
+        }
+    }
+}
+
 // One workgroup ranks one chunk of up to kChunk boxes of one frame: P = 4 * blockDim.x
 // elements (P a multiple of 256, 256..4096), four per thread, sorted by radix_rank_chunk.
 // With a single chunk the kernel also writes order / sorted5 (and, for the fused path,
@@ -157,7 +248,9 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
     __shared__ unsigned hist[(P / 256) * 256];  // one row of 256 digit counts per wavefront
     __shared__ unsigned tot[256];
     __shared__ unsigned dbase[256];
-    __shared__ float4 stage[STAGE ? P : P / 2];  // during the sort: the wavefronts' digit-match tables (P / 256 x 256 x 8 bytes)
+    constexpr bool kSmall = P <= 1024;  // at most four wavefronts: radix_rank_small
+    __shared__ float4 stage[kSmall ? 2 * P : (STAGE ? P : P / 2)];  // during the sort: the wavefronts' digit-match tables (P x 8 bytes; P x 32 for radix_rank_small)
+    __shared__ unsigned wbase[kSmall ? P : 1];
     const int f = blockIdx.y;
     const int chunk = blockIdx.x;
     const int tid = threadIdx.x;
@@ -186,7 +279,11 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
         key32[q] = (unsigned)(K[q] >> 32);
         index[q] = (unsigned)K[q];
     }
-    radix_rank_chunk(key32, index, e, keys, hist, tot, dbase, reinterpret_cast<unsigned long long *>(stage));  // ends with a barrier; keys[] is sorted
+    if constexpr (kSmall)
+        radix_rank_small<P / 256>(key32, index, e, keys, hist, wbase, reinterpret_cast<unsigned long long *>(stage));
+    else
+        radix_rank_chunk(key32, index, e, keys, hist, tot, dbase, reinterpret_cast<unsigned long long *>(stage));
+    // both end with a barrier; keys[] is sorted
 
     int32_t *order_f = order + (size_t)f * n_max;
     float *sorted_f = sorted5 + (size_t)f * 5 * n_pad;
