@@ -297,7 +297,7 @@ def main():
     issue_bound_ms = pairs * VALU_PER_PAIR / calib["mix_lane_ops_per_s"] * 1e3
     issue_bound_classes_ms = pairs * sum(PAIR_TEST_MIX[c] / rates[c] for c in PAIR_TEST_MIX) * 1e3
     roofline = {
-        "kernel": "map_tile_kernel<fast, fused> (pair tests + row reduction)",
+        "kernel": "map_fused_kernel<fast, 4 victim tiles per unit> (pair tests + row reduction)",
         "bound": "alu",
         "achieved": round(achieved_tflops, 3),
         "peak": PEAK_FP32_VECTOR_TFLOPS,
@@ -324,7 +324,7 @@ def main():
     if os.path.exists(traffic_file):
         try:
             t = json.load(open(traffic_file))
-            roofline["traffic"] = t.get(w.name, {}).get("map_tile_kernel_fused_bytes")
+            roofline["traffic"] = t.get(w.name, {}).get("map_fused_kernel_bytes")
             if roofline["traffic"] is not None:
                 roofline["traffic_source"] = "profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not this run)"
         except Exception:
@@ -465,7 +465,16 @@ def main():
                 structure["differing_keep_bits_vs_oracle"] = differing
                 structure["oracle_1_core_us_per_frame"] = round((time.perf_counter() - t0) * 1e6 / wo.frames, 1)
             del ws_go, keep_go
+            route = {0: "direct (one launch)", 1: "all pairs (rank + fused pair-test kernel)",
+                     2: "two launches (best 2048 ranks, then the victims still alive)", 3: "early exit"}[nms.nms_route(wo.n, wo.frames)]
+            if nms.nms_route(wo.n, wo.frames) >= 2:
+                # the automatic route skips tests of decided victims here: time the all-pairs route beside it
+                ms_all = time_steps(lambda: nms.nms_run_ranked_batched(do["boxes"], do["scores"], None, wo.n, wo.frames, wo.theta,
+                                                                       do["keep"], do["ws"]), steps_o, 10)
+                structure["all_pairs_route_us_per_frame"] = round(ms_all * 1e3 / wo.frames, 3)
+                structure["all_pairs_route_equals_automatic"] = bool(np.array_equal(do["keep"].cpu().numpy(), keep_o))
             others[wo.name] = {
+                "route_of_nms_run_batched": route,
                 **structure,
                 "us_per_frame": round(ms_o * 1e3 / wo.frames, 3),
                 "frames_per_s": round(wo.frames / (ms_o * 1e-3), 1),
