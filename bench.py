@@ -220,6 +220,24 @@ def main():
             d["plan"] = nms.RunPlan(d["boxes"], d["scores"], None, d["n"], d["F"], d["w"].theta, d["keep"], d["ws"])
         d["plan"]()
 
+    def mask_set_bits(mask, frames, n):
+        """Pairs (victim, outranking box) that eliminate = bits set in the defined words of the mask
+        (word (w, r) at w * n_pad + r is written only for w <= r / 64)."""
+        n_pad_ = nms.nms_padded_n(n)
+        W_ = n_pad_ // 64
+        defined = (torch.arange(W_, device=dev)[:, None] <= (torch.arange(n_pad_, device=dev) // 64)[None, :])
+        total = 0
+        per = max(1, (64 << 20) // (W_ * n_pad_ * 8))  # frames per pass: 64 MiB of mask at a time
+        m3 = mask.view(frames, W_, n_pad_)
+        for f0 in range(0, frames, per):
+            x = torch.where(defined[None], m3[f0:f0 + per], torch.zeros((), dtype=torch.int64, device=dev)).contiguous().view(torch.int32)
+            x = x - ((x >> 1) & 0x55555555)
+            x = (x & 0x33333333) + ((x >> 2) & 0x33333333)
+            x = (x + (x >> 4)) & 0x0F0F0F0F
+            x = ((x * 0x01010101) >> 24) & 0xFF
+            total += int(x.sum(dtype=torch.int64).item())
+        return total
+
     def time_steps(fn, steps, warmup):
         """`steps` calls between two HIP events on the stream the kernels run on, bracketed by device
         synchronisation on both sides; ms per step (GPU time from the first kernel's start to the last one's end)"""
@@ -379,6 +397,7 @@ def main():
             "mask_read_GBs": round(tri_bytes / (split[2] * 1e-3) / 1e9, 1),
             "frac_hbm_peak_reduce": round(tri_bytes / (split[2] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
             "keep_equals_fused": bool(torch.equal(keep3, d["keep"])),
+            "eliminating_pairs_per_frame": round(mask_set_bits(mask, w.frames, w.n) / w.frames, 1),
         }
         # the selectable classic greedy rule on the same mask (sequential sweep, one workgroup per frame)
         keep_g = torch.empty((w.frames, w.n), dtype=torch.uint8, device=dev)
@@ -453,8 +472,18 @@ def main():
             keep_go = torch.empty((wo.frames, wo.n), dtype=torch.uint8, device=dev)
             nms.nms_run_greedy_batched(do["boxes"], do["scores"], None, wo.n, wo.frames, wo.theta, keep_go, ws_go)
             torch.cuda.synchronize()
+            # bits set in the mask of the three step calls: how many pairs eliminate
+            order_o = torch.empty((wo.frames, wo.n), dtype=torch.int32, device=dev)
+            sorted5_o = torch.empty((wo.frames, 5 * nms.nms_padded_n(wo.n)), dtype=torch.float32, device=dev)
+            sws_o = torch.empty(max(nms.nms_sort_workspace_bytes(wo.n, wo.frames), 256), dtype=torch.uint8, device=dev)
+            mask_o = torch.empty((wo.frames, nms.nms_mask_words(wo.n)), dtype=torch.int64, device=dev)
+            nms.nms_sort_batched(do["boxes"], do["scores"], None, wo.n, wo.frames, order_o, sorted5_o, sws_o)
+            nms.nms_overlap_mask_batched(sorted5_o, None, wo.n, wo.frames, wo.theta, mask_o)
+            torch.cuda.synchronize()
             structure = {"survivors_per_frame": round(float(keep_o.sum()) / wo.frames, 1),
-                         "survivors_per_frame_greedy_rule": round(float(keep_go.sum().item()) / wo.frames, 1)}
+                         "survivors_per_frame_greedy_rule": round(float(keep_go.sum().item()) / wo.frames, 1),
+                         "eliminating_pairs_per_frame": round(mask_set_bits(mask_o, wo.frames, wo.n) / wo.frames, 1)}
+            del order_o, sorted5_o, sws_o, mask_o
             if not args.no_cpu_baseline:
                 from oracle import Oracle
 

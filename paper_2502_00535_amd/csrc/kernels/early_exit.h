@@ -399,15 +399,15 @@ early_exit_wide_kernel(const float *__restrict__ sorted5, const int32_t *__restr
 
 // The same with the rank step inside (frames of more than 2048 boxes, where the rank kernel
 // would run with this kernel's 1024 threads anyway): scores and boxes are fetched in input
-// order, sorted in LDS (radix_rank_chunk of rank.h), and go from the registers straight into the
+// order, sorted in LDS (radix_rank_large of rank.h), and go from the registers straight into the
 // staged table -- no order / box table in memory, no second launch.  The LDS of the rank step is
 // the LDS of the list afterwards.
 struct EarlyRankShared {
     unsigned long long keys[NMS_SORT_CHUNK];
-    unsigned hist[NMS_SORT_CHUNK];  // one row of 256 digit counts per wavefront
+    unsigned hist[NMS_SORT_CHUNK];   // one row of 256 digit counts per wavefront
+    unsigned wbase[NMS_SORT_CHUNK];  // one row of 256 start offsets per wavefront
     unsigned tot[256];
-    unsigned dbase[256];
-    float4 stage[NMS_SORT_CHUNK];   // during the sort: the wavefronts' digit-match tables
+    float4 stage[NMS_SORT_CHUNK];    // during the sort: the wavefronts' lane-mask tables
 };
 
 template <int PAIR>
@@ -438,7 +438,7 @@ early_exit_ranked_kernel(const float *__restrict__ boxes, const float *__restric
         index[q] = (unsigned)key;
         mine[q] = e[q] < n_f ? boxes_f[e[q]] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    radix_rank_chunk(key32, index, e, rk.keys, rk.hist, rk.tot, rk.dbase, reinterpret_cast<unsigned long long *>(rk.stage));  // ends with a barrier
+    radix_rank_large<kEarlyWaves>(key32, index, e, rk.keys, rk.hist, rk.tot, rk.wbase, reinterpret_cast<unsigned long long *>(rk.stage));  // ends with a barrier
 #pragma unroll
     for (int q = 0; q < 4; ++q) rk.stage[e[q]] = mine[q];
     __syncthreads();

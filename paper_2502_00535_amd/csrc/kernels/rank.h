@@ -49,101 +49,22 @@ __device__ __forceinline__ unsigned wave_inclusive_sum(unsigned x)
 // thread.  Stability is what makes 32-bit keys enough: elements start in index order, so
 // equal scores keep the lower index first (the tie rule) without the index taking part in
 // any compare.  Per pass:
-//   - every wavefront ranks its 256 elements among themselves: for q = 0..3 in turn, the
-//     lanes that hold the same digit find each other (see below), take their place
-//     after the elements of earlier q with that digit (running per-wavefront histogram in
-//     LDS, touched by its own wavefront only) and the group's first lane bumps the histogram;
-//   - the histograms are turned into start offsets per (digit, wavefront): column sums,
-//     then one wavefront scans the 256 digit totals;
+//   - every wavefront ranks its 256 elements among themselves.  The lanes that hold the same
+//     digit find each other through tables of 256 lane masks: every lane ORs its bit into the
+//     entry of its digit (an LDS atomic; OR does not care in which order) and reads the entry
+//     back; the mask's first lane clears the entry again, so a table is all zero between uses.
+//     An element stands behind the elements of earlier registers q with its digit and behind
+//     the lower lanes of its own mask; the first lane of each mask adds the mask's population
+//     to a per-wavefront histogram in LDS, touched by its own wavefront only.  (A wavefront's
+//     LDS instructions execute in order, so no barrier is needed inside a wavefront.)
+//   - the histograms are turned into start offsets per (digit, wavefront);
 //   - every element goes to start + place in `buf`, and the threads read their elements back.
 // After the last pass `buf` holds ((key << 32) | index) in sorted order.
-__device__ __forceinline__ void radix_rank_chunk(unsigned (&key)[4], unsigned (&idx)[4], const int (&e)[4],
-                                                 unsigned long long *buf, unsigned *hist, unsigned *tot,
-                                                 unsigned *dbase, unsigned long long *match)
-{
-    const int tid = threadIdx.x;
-    const int nth = blockDim.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int W = nth >> 6;
-    unsigned *myhist = hist + wave * 256;
-    // The lanes that hold the same digit find each other through a table of 256 lane masks per
-    // wavefront: every lane ORs its bit into the entry of its digit (an LDS atomic; OR does not
-    // care in which order) and reads the entry back.  The group's first lane clears the entry
-    // again, so the table is all zero between uses.  (A wavefront's LDS instructions execute in
-    // order, so no barrier is needed inside a wavefront.)
-    unsigned long long *mymatch = match + wave * 256;
-    for (int i = lane; i < 256; i += 64) mymatch[i] = 0ull;
-#pragma unroll 1
-    for (int shift = 0; shift < 32; shift += 8) {
-        for (int i = lane; i < 256; i += 64) myhist[i] = 0;
-        unsigned place[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const unsigned d = (key[q] >> shift) & 255u;
-            __hip_atomic_fetch_or(&mymatch[d], 1ull << lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-            const unsigned long long m = __hip_atomic_load(&mymatch[d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);  // lanes whose digit equals mine
-            const unsigned m_lo = (unsigned)m, m_hi = (unsigned)(m >> 32);
-            const unsigned below = __builtin_amdgcn_mbcnt_hi(m_hi, __builtin_amdgcn_mbcnt_lo(m_lo, 0u));
-            const unsigned total = __popc(m_lo) + __popc(m_hi);
-            const unsigned base = myhist[d];
-            if (below == 0) {
-                myhist[d] = base + total;
-                __hip_atomic_store(&mymatch[d], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-            }
-            place[q] = base + below;
-        }
-        __syncthreads();
-        for (int d = tid; d < 256; d += nth) {
-            // the counts of digit d in every wavefront (all reads issued together), then their running sums
-            unsigned t[kChunk / 256];
-#pragma unroll
-            for (int w = 0; w < kChunk / 256; ++w) t[w] = w < W ? hist[w * 256 + d] : 0u;
-            unsigned run = 0;
-#pragma unroll
-            for (int w = 0; w < kChunk / 256; ++w) {
-                if (w < W) hist[w * 256 + d] = run;
-                run += t[w];
-            }
-            tot[d] = run;
-        }
-        __syncthreads();
-        if (wave == 0) {
-            const unsigned a0 = tot[4 * lane], a1 = tot[4 * lane + 1], a2 = tot[4 * lane + 2], a3 = tot[4 * lane + 3];
-            const unsigned sum = a0 + a1 + a2 + a3;
-            const unsigned incl = wave_inclusive_sum(sum);
-            const unsigned excl = incl - sum;
-            dbase[4 * lane] = excl;
-            dbase[4 * lane + 1] = excl + a0;
-            dbase[4 * lane + 2] = excl + a0 + a1;
-            dbase[4 * lane + 3] = excl + a0 + a1 + a2;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const unsigned d = (key[q] >> shift) & 255u;
-            const unsigned dest = dbase[d] + myhist[d] + place[q];
-            buf[dest] = ((unsigned long long)key[q] << 32) | idx[q];
-        }
-        __syncthreads();
-        if (shift < 24) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const unsigned long long v = buf[e[q]];
-                key[q] = (unsigned)(v >> 32);
-                idx[q] = (unsigned)v;
-            }
-        }
-    }
-}
-
-// The same sort for workgroups of at most four wavefronts (W = blockDim.x / 64), with fewer trips
-// through LDS and two barriers per pass instead of four:
+//
+// Workgroups of at most four wavefronts (W = blockDim.x / 64): two barriers per pass.
 //   - a wavefront keeps one table of lane masks per register q, so the four ORs and the reads are
-//     issued together: element (q, lane) with digit d stands behind the elements of earlier q
-//     with that digit (population counts of their masks at d) and behind the lower lanes of its
-//     own mask; the first lane of each mask adds its population to the wavefront's histogram and
-//     clears the entry;
+//     issued together: element (q, lane) with digit d stands behind the population counts of the
+//     masks of earlier q at d;
 //   - after the barrier every wavefront turns the W histograms into its own start offsets (lane l
 //     takes digits 4l .. 4l+3: totals over the wavefronts, prefix sum across the lanes, plus the
 //     counts of the wavefronts before its own) and keeps them in a row of its own, so the scatter
@@ -228,8 +149,125 @@ __device__ __forceinline__ void radix_rank_small(unsigned (&key)[4], unsigned (&
     }
 }
 
+// The same sort for workgroups of eight or sixteen wavefronts (2048 or 4096 elements), where four
+// lane-mask tables per wavefront do not fit LDS: two tables, the registers in two rounds (0 and 1,
+// then 2 and 3).  The second round finds the elements of the first round with its digit in the
+// wavefront's histogram (a wavefront's LDS operations execute in order, so the first round's counts
+// are there).  The digit totals are summed over the wavefronts by the first 256 threads (a thread
+// per digit, all its reads issued together); the prefix sum over the 256 totals is then done by every wavefront for itself
+// (one 16-byte read per lane, a DPP scan) and added to its own histogram row, so that the scatter
+// follows without a third barrier: three per pass instead of four.
+// match: W x 2 x 256 lane masks; hist, wbase: W x 256 counters each; tot: 256.
+template <int W>
+__device__ __forceinline__ void radix_rank_large(unsigned (&key)[4], unsigned (&idx)[4], const int (&e)[4],
+                                                 unsigned long long *buf, unsigned *hist, unsigned *tot, unsigned *wbase,
+                                                 unsigned long long *match)
+{
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    unsigned *myhist = hist + wave * 256;
+    unsigned *mybase = wbase + wave * 256;
+    unsigned long long *tab0 = match + wave * 512;
+    unsigned long long *tab1 = tab0 + 256;
+    for (int i = lane; i < 512; i += 64) tab0[i] = 0ull;
+    auto or_bit = [&](unsigned long long *t, unsigned d) __attribute__((always_inline)) {
+        __hip_atomic_fetch_or(&t[d], 1ull << lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    };
+    auto load_mask = [&](unsigned long long *t, unsigned d) __attribute__((always_inline)) {
+        return __hip_atomic_load(&t[d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    };
+    auto below_in = [&](unsigned long long m) __attribute__((always_inline)) {
+        return __builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+    };
+    // the first lane of a mask adds its population to the histogram and clears the entry
+    auto settle = [&](unsigned long long *t, unsigned d, unsigned long long m, unsigned below) __attribute__((always_inline)) {
+        if (below == 0) {
+            __hip_atomic_fetch_add(&myhist[d], (unsigned)__popcll(m), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+            __hip_atomic_store(&t[d], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+        }
+    };
+#pragma unroll 1
+    for (int shift = 0; shift < 32; shift += 8) {
+        reinterpret_cast<uint4 *>(myhist)[lane] = make_uint4(0u, 0u, 0u, 0u);
+        unsigned d[4], place[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) d[q] = (key[q] >> shift) & 255u;
+        // (the fences only keep the compiler from reordering: a wavefront's LDS instructions execute in order)
+        or_bit(tab0, d[0]);
+        or_bit(tab1, d[1]);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        {
+            const unsigned long long m0 = load_mask(tab0, d[0]);
+            const unsigned long long m01 = load_mask(tab0, d[1]);
+            const unsigned long long m1 = load_mask(tab1, d[1]);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            const unsigned b0 = below_in(m0), b1 = below_in(m1);
+            place[0] = b0;
+            place[1] = (unsigned)__popcll(m01) + b1;
+            settle(tab0, d[0], m0, b0);
+            settle(tab1, d[1], m1, b1);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        or_bit(tab0, d[2]);
+        or_bit(tab1, d[3]);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        {
+            const unsigned h2 = __hip_atomic_load(&myhist[d[2]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+            const unsigned h3 = __hip_atomic_load(&myhist[d[3]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+            const unsigned long long m2 = load_mask(tab0, d[2]);
+            const unsigned long long m23 = load_mask(tab0, d[3]);
+            const unsigned long long m3 = load_mask(tab1, d[3]);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            const unsigned b2 = below_in(m2), b3 = below_in(m3);
+            place[2] = h2 + b2;
+            place[3] = h3 + (unsigned)__popcll(m23) + b3;
+            settle(tab0, d[2], m2, b2);
+            settle(tab1, d[3], m3, b3);
+        }
+        __syncthreads();
+        if (tid < 256) {
+            // the counts of digit tid in every wavefront (all reads issued together), then their running sums
+            unsigned t[W];
+#pragma unroll
+            for (int w = 0; w < W; ++w) t[w] = hist[w * 256 + tid];
+            unsigned run = 0;
+#pragma unroll
+            for (int w = 0; w < W; ++w) {
+                hist[w * 256 + tid] = run;
+                run += t[w];
+            }
+            tot[tid] = run;
+        }
+        __syncthreads();
+        {
+            const uint4 all = reinterpret_cast<const uint4 *>(tot)[lane];
+            const uint4 pre = reinterpret_cast<const uint4 *>(myhist)[lane];
+            const unsigned sum = all.x + all.y + all.z + all.w;
+            const unsigned excl = wave_inclusive_sum(sum) - sum;
+            reinterpret_cast<uint4 *>(mybase)[lane] = make_uint4(excl + pre.x, excl + all.x + pre.y, excl + all.x + all.y + pre.z,
+                                                                 excl + all.x + all.y + all.z + pre.w);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const unsigned dest = __hip_atomic_load(&mybase[d[q]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT) + place[q];
+            buf[dest] = ((unsigned long long)key[q] << 32) | idx[q];
+        }
+        __syncthreads();
+        if (shift < 24) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const unsigned long long v = buf[e[q]];
+                key[q] = (unsigned)(v >> 32);
+                idx[q] = (unsigned)v;
+            }
+        }
+    }
+}
+
 // One workgroup ranks one chunk of up to kChunk boxes of one frame: P = 4 * blockDim.x
-// elements (P a multiple of 256, 256..4096), four per thread, sorted by radix_rank_chunk.
+// elements (P a multiple of 256, 256..4096), four per thread, sorted by radix_rank_small or radix_rank_large.
 // With a single chunk the kernel also writes order / sorted5 (and, for the fused path,
 // presets keep_out); with several chunks it leaves the chunk's sorted keys in `keys_ws`
 // for the merge kernel.
@@ -245,12 +283,11 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
                   float4 *__restrict__ ysc, unsigned *__restrict__ ytile, float *__restrict__ tsc, double m)
 {
     __shared__ unsigned long long keys[P];
-    __shared__ unsigned hist[(P / 256) * 256];  // one row of 256 digit counts per wavefront
-    __shared__ unsigned tot[256];
-    __shared__ unsigned dbase[256];
+    __shared__ __align__(16) unsigned hist[(P / 256) * 256];  // one row of 256 digit counts per wavefront
+    __shared__ __align__(16) unsigned tot[256];
     constexpr bool kSmall = P <= 1024;  // at most four wavefronts: radix_rank_small
-    __shared__ float4 stage[kSmall ? 2 * P : (STAGE ? P : P / 2)];  // during the sort: the wavefronts' digit-match tables (P x 8 bytes; P x 32 for radix_rank_small)
-    __shared__ unsigned wbase[kSmall ? P : 1];
+    __shared__ float4 stage[kSmall ? 2 * P : (STAGE ? P : P / 2)];  // during the sort: the wavefronts' lane-mask tables (P x 16 bytes; P x 32 for radix_rank_small)
+    __shared__ __align__(16) unsigned wbase[P];  // one row of 256 start offsets per wavefront
     const int f = blockIdx.y;
     const int chunk = blockIdx.x;
     const int tid = threadIdx.x;
@@ -282,7 +319,7 @@ rank_chunk_kernel(const float *__restrict__ boxes, const float *__restrict__ sco
     if constexpr (kSmall)
         radix_rank_small<P / 256>(key32, index, e, keys, hist, wbase, reinterpret_cast<unsigned long long *>(stage));
     else
-        radix_rank_chunk(key32, index, e, keys, hist, tot, dbase, reinterpret_cast<unsigned long long *>(stage));
+        radix_rank_large<P / 256>(key32, index, e, keys, hist, tot, wbase, reinterpret_cast<unsigned long long *>(stage));
     // both end with a barrier; keys[] is sorted
 
     int32_t *order_f = order + (size_t)f * n_max;
