@@ -495,7 +495,8 @@ def main():
                 structure["oracle_1_core_us_per_frame"] = round((time.perf_counter() - t0) * 1e6 / wo.frames, 1)
             del ws_go, keep_go
             route = {0: "direct (one launch)", 1: "all pairs (rank + fused pair-test kernel)",
-                     2: "two launches (best 2048 ranks, then the victims still alive)", 3: "early exit"}[nms.nms_route(wo.n, wo.frames)]
+                     2: "two launches (best 2048 ranks, then the victims still alive)", 3: "early exit",
+                     4: "small frames (rank + two stages of pair tests in one launch)"}[nms.nms_route(wo.n, wo.frames)]
             if nms.nms_route(wo.n, wo.frames) >= 2:
                 # the automatic route skips tests of decided victims here: time the all-pairs route beside it
                 ms_all = time_steps(lambda: nms.nms_run_ranked_batched(do["boxes"], do["scores"], None, wo.n, wo.frames, wo.theta,

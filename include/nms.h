@@ -95,6 +95,7 @@ size_t nms_workspace_bytes(int n_max, int frames);        /* scratch of nms_run_
 #define NMS_ROUTE_ALL_PAIRS 1
 #define NMS_ROUTE_TWO_LAUNCH 2
 #define NMS_ROUTE_EARLY_EXIT 3
+#define NMS_ROUTE_SMALL_FRAMES 4
 int nms_route(int n_max, int frames);
 
 /*
@@ -141,15 +142,19 @@ int nms_reduce_batched(const uint64_t *mask, const int32_t *order, const int32_t
  * into the pair tests, and the result is the same keep vector as steps 1-3 give.
  * The call picks its route by size (nms_route() names it); every route returns the same bits:
  *   NMS_ROUTE_DIRECT      small work (up to about 2^25 pair slots = frames * n_max^2): one launch.
+ *   NMS_ROUTE_SMALL_FRAMES  frames of 257 to 1024 boxes beyond that, up to 2^29 pair slots (2^27
+ *                         for frames of at most 512 boxes): one launch that ranks a frame in LDS,
+ *                         tests every victim against the best 128 ranks and the victims still
+ *                         alive against the rest.
  *   NMS_ROUTE_ALL_PAIRS   rank step, then every pair test of the ranked triangle.
  *   NMS_ROUTE_TWO_LAUNCH  frames beyond NMS_SORT_CHUNK boxes, 2^27 <= pair slots < 2^31: rank step,
  *                         every victim against the best 2048 ranks, then only the victims still
  *                         alive against the rest.
  *   NMS_ROUTE_EARLY_EXIT  large batches (frames of 1024 to NMS_SORT_CHUNK boxes from 2^29 pair
  *                         slots, larger frames from 2^31): nms_run_early_exit_batched below.
- * The last two skip pair tests of victims that already have an eliminator, so their running
- * time depends on the data.  Callers that want every pair evaluated whatever the size (a fixed
- * running time) call nms_run_ranked_batched.
+ * All but DIRECT and ALL_PAIRS skip pair tests of victims that already have an eliminator, so
+ * their running time depends on the data.  Callers that want every pair evaluated whatever the
+ * size (a fixed running time) call nms_run_ranked_batched.
  *   workspace >= nms_workspace_bytes(n or n_max, 1 or frames) bytes, 256-byte aligned
  *             (always required, whichever route is taken).
  * Two calls that share a workspace must be ordered on one stream.

@@ -17,7 +17,7 @@ NMS_ERR_INVALID_ARG = -1
 NMS_ERR_TOO_LARGE = -2
 NMS_ERR_WORKSPACE = -3
 NMS_ERR_LAUNCH = -4
-NMS_ROUTE_DIRECT, NMS_ROUTE_ALL_PAIRS, NMS_ROUTE_TWO_LAUNCH, NMS_ROUTE_EARLY_EXIT = 0, 1, 2, 3
+NMS_ROUTE_DIRECT, NMS_ROUTE_ALL_PAIRS, NMS_ROUTE_TWO_LAUNCH, NMS_ROUTE_EARLY_EXIT, NMS_ROUTE_SMALL_FRAMES = 0, 1, 2, 3, 4
 
 EXPORTS = (
     "nms_status_string", "nms_version", "nms_last_launch_error", "nms_padded_n", "nms_mask_words",

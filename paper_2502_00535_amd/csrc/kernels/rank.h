@@ -70,6 +70,7 @@ __device__ __forceinline__ unsigned wave_inclusive_sum(unsigned x)
 //     counts of the wavefronts before its own) and keeps them in a row of its own, so the scatter
 //     follows without another barrier.
 // match: W x 4 x 256 lane masks; hist, wbase: W x 256 counters each.
+constexpr int kRadixSmallBarriers = 8;  // workgroup barriers inside radix_rank_small (wavefronts that do not sort must pass as many)
 template <int W>
 __device__ __forceinline__ void radix_rank_small(unsigned (&key)[4], unsigned (&idx)[4], const int (&e)[4],
                                                  unsigned long long *buf, unsigned *hist, unsigned *wbase,

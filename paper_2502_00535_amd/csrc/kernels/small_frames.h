@@ -1,0 +1,321 @@
+// Part of nms_kernels.hip (included there, inside its anonymous namespace): frames of at most 1024 boxes, rank step and two stages of pair tests in one launch.
+#pragma once
+
+// ----------------------------------------------------------------------------- small frames, one launch
+
+// A batch of some tens to hundreds of frames of at most a thousand boxes is too much arithmetic
+// for the direct form and too little for separate launches: the rank kernel keeps one compute
+// unit per frame busy for 8 us and hands its tables over through memory to a map launch that
+// needs 2 us to get going.  Here one workgroup does everything for its frame and the ranked table
+// never leaves LDS; and since V_i is the AND over all j (section "Algorithm Correctness"), a victim
+// that has met one eliminator needs no further test, which on clustered detections is most victims
+// after the best-ranked boxes have been tried:
+//
+//   rank      Algorithm 1's order "D[i].s < D[j].s" (ties by index): the first P / 256 wavefronts
+//             sort the frame's keys (radix_rank_small) while every thread holds one input box; the
+//             boxes change hands through LDS and thread r builds row r of the table (box, y scaled
+//             when every box of the frame allows it; its decision threshold T, or its area for
+//             thresholds that take the literal division; its input index);
+//   stage 1   every victim of the workgroup against the best kSmallFirst ranks: lane = victim, two
+//             victims per lane (two tiles of 64), the outranking boxes read from the table as
+//             broadcasts, eight per work item -- a broadcast moves 64 x 16 bytes whatever it is
+//             used for, and with one victim per lane the LDS path, not the VALU, would set the
+//             pace; the compare's lane mask is the set of victims the box eliminates, ORed up in
+//             a scalar register and merged per victim tile in LDS;
+//   pack      victims with an eliminator, and victims ranked inside the first stage's boxes, are
+//             final and written out; the others are listed in rank order;
+//   stage 2   the listed victims against the remaining tiles: lane = outranking box, four tiles
+//             per wavefront in registers, the victims read as broadcasts (one read per four rows);
+//             a tile counts from the rank of its first box on, the tile that holds the victim's
+//             own rank up to that rank.
+//
+// With fewer frames than compute units a frame is given to `parts` workgroups: each sorts the
+// whole frame (the sort is bound by latency, not by work: the copies cost nothing while the other
+// compute units would idle) and takes the victims of ranks part, part + parts, ... -- interleaved
+// ranks give every share the same mix of early and late victims.  Each victim's keep byte is
+// written once, by its workgroup.  Same keep vector as the all-pairs routes, bit for bit: a victim
+// is dropped only once an eliminator has been found.
+constexpr int kSmallWaves = 16;
+constexpr int kSmallThreads = kSmallWaves * 64;
+constexpr int kSmallFirst = 128;  // outranking boxes of the first stage
+constexpr int kSmallGroup = 8;    // outranking boxes per work item of the first stage
+constexpr int kSmallTiles = 4;    // tiles a wavefront holds in registers in the second stage
+
+template <int PAIR>
+__device__ __forceinline__ bool small_hit(const float4 v, const float4 c, float aux, float theta, float y_one)
+{
+    if (PAIR == kPairFastYScaled) return nms_eliminates_fast_yscaled(v.x, v.y, v.z, v.w, c.x, c.y, c.z, c.w, aux, y_one);
+    if (PAIR == kPairFast) return nms_eliminates_fast(v.x, v.y, v.z, v.w, c.x, c.y, c.z, c.w, aux);
+    return nms_eliminates_exact(v.x, v.y, v.z, v.w, c.x, c.y, c.z, c.w, aux, theta);
+}
+
+// Stage 1, one work item: the outranking ranks [c0, c0 + kSmallGroup) against two victim tiles
+// (victims va, vb of ranks ra, rb in this lane).  GUARD: some of the victims may be ranked at or
+// before some of the boxes, so a box counts only for the lanes whose victim is ranked behind it.
+template <int PAIR, bool GUARD>
+__device__ __forceinline__ void small_first_item(const float4 *tbox, const float *taux, int c0, const float4 va, const float4 vb,
+                                                 int ra, int rb, float theta, float y_one, unsigned long long &dead_a,
+                                                 unsigned long long &dead_b)
+{
+    float4 cb[kSmallGroup];
+    float ca[kSmallGroup];
+#pragma unroll
+    for (int k = 0; k < kSmallGroup; ++k) cb[k] = tbox[c0 + k];
+#pragma unroll
+    for (int k = 0; k < kSmallGroup; k += 4) {
+        const float4 a4 = *reinterpret_cast<const float4 *>(taux + c0 + k);
+        ca[k] = a4.x;
+        ca[k + 1] = a4.y;
+        ca[k + 2] = a4.z;
+        ca[k + 3] = a4.w;
+    }
+#pragma unroll
+    for (int k = 0; k < kSmallGroup; ++k) {
+        unsigned long long ha = __ballot(small_hit<PAIR>(va, cb[k], ca[k], theta, y_one));
+        unsigned long long hb = __ballot(small_hit<PAIR>(vb, cb[k], ca[k], theta, y_one));
+        if (GUARD) {
+            ha &= __ballot(ra > c0 + k);
+            hb &= __ballot(rb > c0 + k);
+        }
+        dead_a |= ha;
+        dead_b |= hb;
+    }
+}
+
+// Stage 2, one victim (rank r, box v, read as broadcasts) against the tiles t0 .. t0 + 3 held in
+// cb[], aux[]: is there an eliminator among the boxes ranked before r?  Branch-free, so that the
+// tests of several victims can be interleaved: every tile is tested and its lane mask cut down to
+// the boxes ranked before r (all, the lower r - 64 t lanes of the tile that holds rank r, none).
+// A tile beyond the frame's last is a copy of tile t0 with an empty mask.
+template <int PAIR>
+__device__ __forceinline__ bool small_second_victim(const float4 v, int r, const float4 (&cb)[kSmallTiles],
+                                                    const float (&aux)[kSmallTiles], int t0, int useful, float theta, float y_one)
+{
+    unsigned long long any = 0ull;
+#pragma unroll
+    for (int j = 0; j < kSmallTiles; ++j) {
+        int before = r - (t0 + j) * kTile;  // boxes of tile t0 + j ranked before the victim
+        before = before < 0 ? 0 : (before > kTile ? kTile : before);
+        if (j >= useful) before = 0;
+        const unsigned long long outranks = before >= kTile ? ~0ull : (1ull << before) - 1ull;
+        any |= __ballot(small_hit<PAIR>(v, cb[j], aux[j], theta, y_one)) & outranks;
+    }
+    return any != 0ull;
+}
+
+// The stages of one workgroup.  The table (tbox, taux) holds the frame in rank order; the workgroup's
+// victims are the ranks part + parts * i, i < m0.  Writes keep_f through tord (rank -> input index).
+template <int PAIR>
+__device__ __forceinline__ void small_stages(const float4 *tbox, const float *taux, const int *tord, unsigned long long *dead1,
+                                             int *list, unsigned char *flag2, int *wcount, int n_f, int part, int parts,
+                                             float theta, float y_one, uint8_t *keep_f)
+{
+    const int tid = (int)threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tiles_f = (n_f + kTile - 1) / kTile;
+    const int m0 = n_f > part ? (n_f - part + parts - 1) / parts : 0;
+    const int first = tiles_f * kTile < kSmallFirst ? tiles_f * kTile : kSmallFirst;  // boxes of stage 1 (padding rows included)
+
+    // ---- stage 1
+    {
+        const int vtiles = (m0 + kTile - 1) / kTile;
+        const int vpairs = (vtiles + 1) / 2;
+        const int groups = first / kSmallGroup;
+        for (int item = wave; item < vpairs * groups; item += kSmallWaves) {
+            const int vp = item / groups;
+            const int c0 = (item % groups) * kSmallGroup;
+            const int ia = (2 * vp) * kTile + lane, ib = (2 * vp + 1) * kTile + lane;
+            // a lane beyond the share tests the padding row of rank P - 1 or any row: its bits are never read
+            const int ra = ia < m0 ? part + parts * ia : 0;
+            const int rb = ib < m0 ? part + parts * ib : 0;
+            const float4 va = tbox[ra], vb = tbox[rb];
+            unsigned long long da = 0ull, db = 0ull;
+            // the lowest rank of the pair's victims is that of its first lane
+            if (part + parts * (2 * vp) * kTile >= c0 + kSmallGroup)
+                small_first_item<PAIR, false>(tbox, taux, c0, va, vb, ra, rb, theta, y_one, da, db);
+            else
+                small_first_item<PAIR, true>(tbox, taux, c0, va, vb, ra, rb, theta, y_one, da, db);
+            if (lane == 0) {
+                if (da != 0ull) atomicOr(&dead1[2 * vp], da);
+                if (db != 0ull) atomicOr(&dead1[2 * vp + 1], db);
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- pack: final victims are written out, the others listed in rank order
+    int r_mine = 0;
+    bool alive = false;
+    if (tid < m0) {
+        r_mine = part + parts * tid;
+        const bool dead = ((dead1[tid / kTile] >> (tid % kTile)) & 1ull) != 0ull;
+        if (dead || r_mine <= first)
+            keep_f[tord[r_mine]] = dead ? 0 : 1;  // every box ranked before r_mine was among the first stage's
+        else
+            alive = true;
+    }
+    // (counted here as well: per tile group of stage 2, the listed victims ranked at or before the group's
+    // first box -- they have nothing to meet in it, and the list being in rank order they come first)
+    const unsigned long long alive_mask = __ballot(alive);
+    const int t_begin = first / kTile;
+    if (lane == 0) wcount[wave] = (int)__popcll(alive_mask);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int n = (int)__popcll(__ballot(alive && r_mine <= (t_begin + g * kSmallTiles) * kTile));
+        if (lane == 0) wcount[kSmallWaves * (g + 1) + wave] = n;
+    }
+    __syncthreads();
+    int before = 0, listed = 0;
+    int start[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int w = 0; w < kSmallWaves; ++w) {
+        const int c = wcount[w];
+        if (w < wave) before += c;
+        listed += c;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) start[g] += wcount[kSmallWaves * (g + 1) + w];
+    }
+    listed = __builtin_amdgcn_readfirstlane(listed);  // the same in every lane: say so
+    if (alive) {
+        const int pos = before + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(alive_mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)alive_mask, 0u));
+        list[pos] = r_mine;
+        flag2[pos] = 0;
+    }
+    __syncthreads();
+
+    // ---- stage 2: tiles first / 64 .. tiles_f - 1 in groups of kSmallTiles.  The list is in rank order,
+    // so a group only meets the victims from some list position on; a unit is (group, four consecutive
+    // listed victims from there), the units of all groups in one numbering dealt round-robin to the wavefronts.
+    const int groups2 = (tiles_f - t_begin + kSmallTiles - 1) / kSmallTiles;  // at most 4: P / 64 - 2 tiles
+    if (listed > 0 && groups2 > 0) {
+        int units_before[5];
+        units_before[0] = 0;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            start[g] = __builtin_amdgcn_readfirstlane(g < groups2 ? start[g] : listed);
+            units_before[g + 1] = units_before[g] + (listed - start[g] + 3) / 4;
+        }
+        for (int unit = wave; unit < units_before[4]; unit += kSmallWaves) {
+            int g = 0;
+#pragma unroll
+            for (int q = 1; q < 4; ++q) g += unit >= units_before[q] ? 1 : 0;
+            const int k_begin = (g == 0 ? start[0] : g == 1 ? start[1] : g == 2 ? start[2] : start[3]) +
+                                4 * (unit - (g == 0 ? units_before[0] : g == 1 ? units_before[1] : g == 2 ? units_before[2] : units_before[3]));
+            const int t0 = t_begin + g * kSmallTiles;
+            const int useful = tiles_f - t0 < kSmallTiles ? tiles_f - t0 : kSmallTiles;
+            float4 cb[kSmallTiles];
+            float aux[kSmallTiles];
+#pragma unroll
+            for (int j = 0; j < kSmallTiles; ++j) {
+                const int row = (t0 + (j < useful ? j : 0)) * kTile + lane;
+                cb[j] = tbox[row];
+                aux[j] = taux[row];
+            }
+            // four victims, their reads issued together (a short last unit repeats its last victim)
+            int at[4], r[4];
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                at[u] = k_begin + u < listed ? k_begin + u : listed - 1;
+                r[u] = list[at[u]];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                r[u] = __builtin_amdgcn_readfirstlane(r[u]);
+                v[u] = tbox[r[u]];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const bool dead = small_second_victim<PAIR>(v[u], r[u], cb, aux, t0, useful, theta, y_one);
+                if (lane == 0 && dead) flag2[at[u]] = 1;
+            }
+        }
+    }
+    __syncthreads();
+    for (int k = tid; k < listed; k += kSmallThreads) keep_f[tord[list[k]]] = flag2[k] ? 0 : 1;
+}
+
+// P: 256, 512 or 1024 >= n_max.  FAST: the threshold has a division-free form (NmsThetaConst).
+// Grid: frames * parts workgroups of kSmallThreads threads.
+template <int P, bool FAST>
+__global__ void __launch_bounds__(kSmallThreads)
+small_frames_kernel(const float *__restrict__ boxes, const float *__restrict__ scores, const int32_t *__restrict__ counts,
+                    int n_max, int parts, NmsThetaConst th, uint8_t *__restrict__ keep_out)
+{
+    constexpr int W = P / 256;  // wavefronts that sort
+    __shared__ unsigned long long keys[P];
+    __shared__ __align__(16) unsigned hist[P];
+    __shared__ __align__(16) unsigned wbase[P];
+    __shared__ float4 stage[2 * P];  // the sort's lane-mask tables, then the boxes in input order
+    __shared__ float4 tbox[P];
+    __shared__ __align__(16) float taux[P];
+    __shared__ int tord[P];
+    __shared__ unsigned long long dead1[P / kTile];
+    __shared__ int list[P];
+    __shared__ unsigned char flag2[P];
+    __shared__ int wcount[5 * kSmallWaves];  // per wavefront: listed victims, and those before each of stage 2's tile groups
+    const int f = blockIdx.x / parts;
+    const int part = blockIdx.x % parts;
+    const int tid = (int)threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n_f = frame_count(counts, f, n_max);
+    const float *scores_f = scores + (size_t)f * n_max;
+    const float4 *boxes_f = reinterpret_cast<const float4 *>(boxes + (size_t)f * n_max * 4);
+    uint8_t *keep_f = keep_out + (size_t)f * n_max;
+
+    float4 mine = make_float4(0.f, 0.f, 0.f, 0.f);  // box tid of the input
+    if (tid < n_f) mine = boxes_f[tid];
+    if (wave < W) {
+        int e[4];
+        unsigned key32[4], index[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            e[q] = wave * 256 + q * 64 + lane;
+            const unsigned long long key = e[q] < n_f ? nms_rank_key(scores_f[e[q]], (unsigned)e[q]) : kSentinel;
+            key32[q] = (unsigned)(key >> 32);
+            index[q] = (unsigned)key;
+        }
+        radix_rank_small<W>(key32, index, e, keys, hist, wbase, reinterpret_cast<unsigned long long *>(stage));
+    } else {
+        // the other wavefronts only keep the sort's barriers company
+        for (int i = 0; i < kRadixSmallBarriers; ++i) __syncthreads();
+    }
+    if (tid < P) stage[tid] = mine;
+    if (tid < P / kTile) dead1[tid] = 0ull;
+    __syncthreads();
+
+    int idx = 0;
+    float4 b = make_float4(0.f, 0.f, 0.f, 0.f);  // rank tid, or the padding row: the one-pixel box (0,0,0,0)
+    if (tid < n_f) {
+        idx = (int)(unsigned)keys[tid];
+        b = stage[idx];
+    }
+    const bool odd = !(nms_y_regular(b.y) && nms_y_regular(b.w));
+    const bool scaled = FAST && __syncthreads_or(odd ? 1 : 0) == 0;
+    if (tid < P) {
+        const float area = nms_box_area(b.x, b.y, b.z, b.w);
+        float a = FAST ? (tid < n_f ? nms_pair_threshold(area, th.m) : INFINITY) : area;  // no intersection reaches a padding row's
+        if (scaled) {
+            b.y *= NMS_YSCALE;
+            b.w *= NMS_YSCALE;
+            a *= NMS_YSCALE;
+        }
+        tbox[tid] = b;
+        taux[tid] = a;
+        tord[tid] = idx;
+    }
+    __syncthreads();
+
+    float y_one;  // NMS_YSCALE in a vector register (opaque to the compiler so it stays there)
+    asm volatile("v_mov_b32 %0, 0x38800000" : "=v"(y_one));
+    if (!FAST)
+        small_stages<kPairExact>(tbox, taux, tord, dead1, list, flag2, wcount, n_f, part, parts, th.theta, y_one, keep_f);
+    else if (scaled)
+        small_stages<kPairFastYScaled>(tbox, taux, tord, dead1, list, flag2, wcount, n_f, part, parts, th.theta, y_one, keep_f);
+    else
+        small_stages<kPairFast>(tbox, taux, tord, dead1, list, flag2, wcount, n_f, part, parts, th.theta, y_one, keep_f);
+    if (part == 0)
+        for (int i = n_f + tid; i < n_max; i += kSmallThreads) keep_f[i] = 0;
+}

@@ -93,6 +93,7 @@ constexpr int kNmsRouteDirect = 0;     // one launch, full n x n pair set with t
 constexpr int kNmsRouteAllPairs = 1;   // rank, then every pair of the ranked triangle
 constexpr int kNmsRouteTwoLaunch = 2;  // rank, every victim against the best 2048 ranks, then the live victims only
 constexpr int kNmsRouteEarlyExit = 3;  // rank, then stages that drop a victim once it has an eliminator
+constexpr int kNmsRouteSmallFrames = 4;  // frames of at most 1024 boxes: rank and two such stages in one launch
 
 // Frames small enough that launch latency, not arithmetic, decides: one launch of the
 // direct form instead of rank + map.  (Twice the pairs and two more compares per pair:
@@ -130,10 +131,34 @@ NMS_HD bool nms_use_early_exit(int n_max, int frames, int sort_chunk)
     return n_max > sort_chunk ? slots >= (1ll << 31) : (n_max >= 1024 && slots >= (1ll << 29));
 }
 
+// Frames of 257 to 1024 boxes beyond the direct form's sizes: one launch that ranks the frame in LDS,
+// tests every victim against the best 128 ranks and the victims still alive against the rest
+// (clustered detections, whole call against the all-pairs route: 64 x 1024 16.5 us against 20.3,
+// 256 x 1024 31.7 against 42.4, 256 x 512 16.4 against 19.6).  Its workgroups are 1024 threads whatever
+// the frame size, which stops paying on large batches: from 2^29 pair slots on for frames beyond 512
+// boxes (512 x 1024: 56.9 us, the early-exit kernels 56.6), from 2^27 on for smaller ones (1024 x 512:
+// 58.5 against 49.2 for all pairs), and frames of at most 256 boxes never take it (1024 x 256: 41.5
+// against 24.0).
+NMS_HD bool nms_use_small_frames(int n_max, int frames)
+{
+    const long long slots = (long long)frames * n_max * n_max;
+    return n_max > 256 && n_max <= 1024 && !nms_use_direct_form(n_max, frames) && slots < (n_max > 512 ? (1ll << 29) : (1ll << 27));
+}
+
+// Workgroups that share a frame there (each ranks the whole frame and takes every parts-th victim):
+// doubled while that leaves at most one workgroup per compute unit (256), up to 16.
+NMS_HD int nms_small_frames_parts(int frames)
+{
+    int parts = 1;
+    while (parts < 16 && (long long)frames * parts * 2 <= 256) parts *= 2;
+    return parts;
+}
+
 // The route of the automatic whole-path call for a batch shape (1 <= n_max, 1 <= frames).
 NMS_HD int nms_route_for(int n_max, int frames, int sort_chunk)
 {
     if (nms_use_direct_form(n_max, frames)) return kNmsRouteDirect;
+    if (nms_use_small_frames(n_max, frames)) return kNmsRouteSmallFrames;
     if (nms_use_early_exit(n_max, frames, sort_chunk)) return kNmsRouteEarlyExit;
     if (nms_use_two_launches(n_max, frames, sort_chunk)) return kNmsRouteTwoLaunch;
     return kNmsRouteAllPairs;

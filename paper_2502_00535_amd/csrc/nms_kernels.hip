@@ -55,6 +55,7 @@ __device__ __forceinline__ int frame_count(const int32_t *counts, int f, int n_m
 #include "kernels/variants.h"
 #include "kernels/early_exit.h"
 #include "kernels/staged.h"
+#include "kernels/small_frames.h"
 #include "kernels/matrix_form.h"
 
 // ----------------------------------------------------------------------------- host side
@@ -239,7 +240,8 @@ size_t nms_workspace_bytes(int n_max, int frames)
 }
 
 static_assert(kNmsRouteDirect == NMS_ROUTE_DIRECT && kNmsRouteAllPairs == NMS_ROUTE_ALL_PAIRS &&
-                  kNmsRouteTwoLaunch == NMS_ROUTE_TWO_LAUNCH && kNmsRouteEarlyExit == NMS_ROUTE_EARLY_EXIT,
+                  kNmsRouteTwoLaunch == NMS_ROUTE_TWO_LAUNCH && kNmsRouteEarlyExit == NMS_ROUTE_EARLY_EXIT &&
+                  kNmsRouteSmallFrames == NMS_ROUTE_SMALL_FRAMES,
               "route numbers of the header and of the host logic");
 
 int nms_route(int n_max, int frames)
@@ -361,6 +363,26 @@ static int fused_launch(const RunWorkspace &w, const int32_t *counts, int n_max,
     return launch_status();
 }
 
+// Frames of at most 1024 boxes: rank step and two stages of pair tests in one launch (kernels/small_frames.h).
+static int small_frames_launch(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
+                               const NmsThetaConst &th, uint8_t *keep_out, hipStream_t stream)
+{
+    const int P = n_max <= 256 ? 256 : (n_max <= 512 ? 512 : 1024);
+    const int parts = nms_small_frames_parts(frames);
+    const dim3 grid((unsigned)(frames * parts)), block(kSmallThreads);
+    begin_launch();
+#define NMS_LAUNCH_SMALL(P_)                                                                                             \
+    do {                                                                                                                 \
+        if (th.fast) small_frames_kernel<P_, true><<<grid, block, 0, stream>>>(boxes, scores, counts, n_max, parts, th, keep_out); \
+        else small_frames_kernel<P_, false><<<grid, block, 0, stream>>>(boxes, scores, counts, n_max, parts, th, keep_out);  \
+    } while (0)
+    if (P == 256) NMS_LAUNCH_SMALL(256);
+    else if (P == 512) NMS_LAUNCH_SMALL(512);
+    else NMS_LAUNCH_SMALL(1024);
+#undef NMS_LAUNCH_SMALL
+    return launch_status();
+}
+
 static int staged_launch(const RunWorkspace &w, const int32_t *counts, int n_max, int frames, const NmsThetaConst &th,
                          uint8_t *keep_out, hipStream_t stream)
 {
@@ -392,7 +414,7 @@ static int staged_launch(const RunWorkspace &w, const int32_t *counts, int n_max
 static int early_exit_launch(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
                              float threshold, uint8_t *keep_out, void *workspace, hipStream_t s);
 
-// kRouteAuto: direct, ranked or early exit by size.  kRouteAllPairs: direct or ranked by size
+// kRouteAuto: direct, one launch for small frames, all pairs, two launches or early exit by size (nms_route_for).  kRouteAllPairs: direct or ranked by size
 // (every pair of the ranked triangle is evaluated).
 enum Route { kRouteAuto = 0, kRouteRanked = 1, kRouteDirect = 2, kRouteAllPairs = 3 };
 
@@ -413,6 +435,8 @@ static int run_routed(Route route, const float *boxes, const float *scores, cons
     }
 
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (route == kRouteAuto && !direct && nms_use_small_frames(n_max, frames))
+        return small_frames_launch(boxes, scores, counts, n_max, frames, nms_make_theta_const(threshold), keep_out, s);
     if (route == kRouteAuto && !direct && nms_use_early_exit(n_max, frames, kChunk))
         return early_exit_launch(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, s);
     auto mark = [&](int i) {

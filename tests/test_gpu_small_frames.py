@@ -1,0 +1,189 @@
+"""The one-launch route that nms_run_batched takes for batches of frames of 257 to 1024 boxes (rank
+step in LDS, every victim against the best 128 ranks, the victims still alive against the rest;
+a frame shared out among 1 to 16 workgroups) against the oracle's plain double loop, 0 differing
+bits, on what the route itself can meet: every number of workgroups per frame, frame lengths
+around the tile and stage sizes, ragged batches incl. empty frames and frames shorter than the
+first stage, nothing / everything / all but a few victims alive after the first stage, eliminators
+that sit only behind rank 128 (at tile and tile-group borders), y coordinates outside the scaled
+form's range, thresholds that take the literal division, scores of every kind."""
+import numpy as np
+import pytest
+
+from gpu_util import DeviceFrames, oracle_keep_frames
+from pins import staircase
+from workloads import clustered_frame, random_frame, scores_of_every_kind
+
+pytestmark = pytest.mark.gpu
+
+FIRST = 128  # ranks that the first stage tests every victim against
+
+
+@pytest.fixture(scope="module")
+def nms():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2502_00535_amd.binding as binding
+
+    return binding
+
+
+def check(nms, oracle, boxes, scores, theta, counts=None):
+    """nms_run_batched (which routes these shapes to the one launch) and the explicit all-pairs route."""
+    F, n = scores.shape
+    assert nms.nms_route(n, F) == nms.NMS_ROUTE_SMALL_FRAMES, f"{F} x {n} is not a shape of the one-launch route"
+    want = oracle_keep_frames(oracle, boxes, scores, np.float32(theta), counts)
+    dev = DeviceFrames(nms, boxes, scores, counts)
+    got = dev.fused(float(theta))
+    assert np.array_equal(got, want), f"{(got != want).sum()} differing keep bits"
+    dev.keep.fill_(77)
+    nms.nms_run_ranked_batched(dev.boxes, dev.scores, dev.counts, n, F, float(theta), dev.keep, dev.run_ws)
+    dev.torch.cuda.synchronize()
+    assert np.array_equal(dev.keep.cpu().numpy(), want)
+    return want
+
+
+def lattice(n, rng=None, pitch=40.0, size=30.0):
+    """n pairwise disjoint boxes."""
+    side = int(np.ceil(np.sqrt(n)))
+    gx, gy = np.meshgrid(np.arange(side), np.arange(side))
+    cells = np.stack([gx.ravel() * pitch, gy.ravel() * pitch], 1)[:n]
+    if rng is not None:
+        cells = cells[rng.permutation(n)]
+    return np.concatenate([cells, cells + size], 1).astype(np.float32)
+
+
+def batch(seed, F, n, **kw):
+    boxes = np.zeros((F, n, 4), np.float32)
+    scores = np.zeros((F, n), np.float32)
+    for f in range(F):
+        boxes[f], scores[f] = random_frame(seed + f, n, **kw)
+    return boxes, scores
+
+
+@pytest.mark.parametrize("frames", [25, 32, 33, 64, 65, 128, 129, 200, 256, 300, 500])
+def test_workgroups_per_frame(nms, oracle, frames):
+    """1024-box frames: 8, 4, 2 and 1 workgroups per frame (frames * parts <= 256) and batches beyond the compute units."""
+    print(f"case frames={frames}", flush=True)
+    rng = np.random.default_rng(frames)
+    boxes, scores = batch(3000 + 7 * frames, frames, 1024, extent=900, max_side=120, integer=(frames % 2 == 0), score_levels=300)
+    counts = rng.integers(0, 1025, frames).astype(np.int32) if frames % 3 == 0 else None
+    want = check(nms, oracle, boxes, scores, 0.45, counts)
+    assert 0 < want.sum() < want.size
+
+
+@pytest.mark.parametrize("n", [257, 300, 319, 320, 321, 383, 384, 385, 511, 512, 513, 640, 767, 768, 769, 895, 896, 897, 960, 1000, 1023, 1024])
+def test_frame_lengths(nms, oracle, n):
+    print(f"case n={n}", flush=True)
+    limit = (1 << 25) if n <= 512 else (3 << 23)   # the direct form takes batches up to this many pair slots
+    F = max(40, limit // (n * n) + 2)
+    boxes, scores = batch(5000 + n, F, n, extent=700, max_side=100, integer=(n % 2 == 1), score_levels=max(3, n // 3))
+    want = check(nms, oracle, boxes, scores, [0.5, 0.3, 0.45][n % 3])
+    assert 0 < want.sum() < want.size
+
+
+def test_ragged_batches(nms, oracle):
+    """Frames that are empty, shorter than a tile, shorter than the first stage, just beyond it, and full, in one call."""
+    F, n_max = 80, 1024
+    boxes, scores = batch(77, F, n_max, extent=800, max_side=110, integer=True, score_levels=200)
+    counts = np.array(([0, 1, 2, 63, 64, 65, 127, 128, 129, 130, 191, 192, 193, 255, 256, 257, 1023, 1024, 700, 5] * 4)[:F], np.int32)
+    check(nms, oracle, boxes, scores, 0.45, counts)
+    check(nms, oracle, boxes[:, :600], scores[:, :600], 0.3, np.minimum(counts, 600).astype(np.int32)[:F])
+    # 300 frames (one workgroup per frame), random counts
+    F = 300
+    boxes, scores = batch(99, F, 512, extent=500, max_side=90, integer=False, score_levels=0)
+    check(nms, oracle, boxes, scores, 0.4, np.random.default_rng(5).integers(0, 513, F).astype(np.int32))
+
+
+def test_live_victim_counts(nms, oracle):
+    """Disjoint boxes in rank order, of which a chosen set repeats the box of rank 0 (eliminated in the
+    first stage): the rest, `alive` of them behind rank 128, reach the second stage and survive."""
+    n, F = 1024, 32
+    base = lattice(n)
+    scores = np.tile((1.0 - np.arange(n) / n).astype(np.float32), (F, 1))
+    behind = n - FIRST
+    boxes = np.zeros((F, n, 4), np.float32)
+    alive_per_frame = [0, 1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 31, 32, 33, 63, 64, 65, 100, 127, 128, 129, 255, 256, 257, 500, 800, behind - 2,
+                       behind - 1, behind, 6, 60]
+    for f, alive in enumerate(alive_per_frame):
+        rng = np.random.default_rng(alive + 1000 * f)
+        boxes[f] = base
+        dead = FIRST + rng.permutation(behind)[:behind - alive]
+        boxes[f, dead] = base[0]
+    want = check(nms, oracle, boxes, scores, 0.5)
+    assert want.sum(1).tolist() == [FIRST + a for a in alive_per_frame]
+    # the same frames with the input order shuffled (ranks no longer equal indices)
+    perm = np.random.default_rng(1).permutation(n)
+    check(nms, oracle, boxes[:, perm], scores[:, perm], 0.5)
+
+
+def test_eliminators_only_behind_the_first_stage(nms, oracle):
+    """Victim v repeats the box of rank e(v) >= 128, its one and only eliminator, so v is alive after the
+    first stage and must be caught by the second: eliminators directly before their victims, at tile
+    borders, at the borders of the second stage's groups of four tiles, and far apart."""
+    n, F = 1024, 40
+    boxes1 = lattice(n)
+    scores = np.tile((1.0 - np.arange(n) / n).astype(np.float32), (F, 1))
+    pairs = [(128, 129), (128, 1023), (191, 192), (192, 193), (255, 256), (383, 384), (384, 385), (384, 447), (384, 448), (385, 449),
+             (639, 640), (640, 641), (895, 896), (896, 897), (896, 1022), (1020, 1021), (130, 700), (700, 701), (701, 702), (500, 501)]
+    victims = set()
+    for e, v in pairs:
+        assert e < v and v not in victims
+        boxes1[v] = boxes1[e]
+        victims.add(v)
+    boxes = np.tile(boxes1, (F, 1, 1))
+    # every frame but the first: a different half of the other boxes eliminated in the first stage
+    for f in range(1, F):
+        gone = FIRST + np.random.default_rng(f).permutation(n - FIRST)[:(n - FIRST) // 2]
+        keep_as_is = np.array(sorted({x for p in pairs for x in p}))
+        gone = np.setdiff1d(gone, keep_as_is)
+        boxes[f, gone] = boxes1[1]
+    want = check(nms, oracle, boxes, scores, 0.5)
+    assert sorted(np.flatnonzero(want[0] == 0).tolist()) == sorted(victims)
+
+
+def test_extremes(nms, oracle):
+    n, F = 1000, 48
+    rng = np.random.default_rng(3)
+    scores = np.stack([rng.permutation(n).astype(np.float32) / n for _ in range(F)])
+    disjoint = np.stack([lattice(n, rng) for _ in range(F)])
+    assert check(nms, oracle, disjoint, scores, 0.5).sum() == F * n                            # everything alive in both stages
+    same = np.tile(np.array([[10, 10, 90, 70]], np.float32), (F, n, 1))
+    assert check(nms, oracle, same, scores, 0.5).sum() == F                                    # nothing alive after the first stage
+    b, s = staircase(n)
+    assert check(nms, oracle, np.tile(b, (F, 1, 1)), np.tile(s, (F, 1)), 0.5).sum() == F       # each box eliminated by its predecessor only
+    assert check(nms, oracle, np.tile(b[::-1].copy(), (F, 1, 1)), np.tile(s[::-1].copy(), (F, 1)), np.float32(0.4)).sum() == F
+
+
+def test_clustered_detections(nms, oracle):
+    """The workload the route is for: clusters of candidates around objects, 64 and 200 frames."""
+    for F, n in ((64, 1024), (200, 768), (260, 400)):
+        fr = [clustered_frame(900 + f, objects=n // 16, width=1920, height=1080, size_lo=32.0, size_hi=256.0) for f in range(F)]
+        boxes = np.stack([x[0][:n] for x in fr])
+        scores = np.stack([x[1][:n] for x in fr])
+        print(f"case {F} x {boxes.shape[1]}", flush=True)
+        want = check(nms, oracle, boxes, scores, 0.5)
+        assert 0 < want.sum() < want.size // 4
+
+
+def test_y_ranges_and_literal_division(nms, oracle):
+    """Frames with y coordinates that rule out the scaled pair test (every third frame has boxes shifted
+    far up), and thresholds that take the literal division, through both stages."""
+    F, n = 60, 900
+    boxes, scores = batch(770, F, n, extent=800, max_side=100, integer=False, score_levels=250)
+    shifted = boxes.copy()
+    for f in range(0, F, 3):
+        idx = np.random.default_rng(f).permutation(n)[:1 + f]
+        shifted[f, idx, 1] += 20000.0
+        shifted[f, idx, 3] += 20000.0
+    check(nms, oracle, shifted, scores, 0.4)
+    for theta in (0.0, 2.0 ** -41, 1.5):
+        check(nms, oracle, boxes, scores, theta)
+    check(nms, oracle, shifted, scores, 0.0)
+
+
+def test_scores_of_every_kind(nms, oracle):
+    F, n = 50, 1024
+    boxes, _ = batch(5, F, n, extent=700, max_side=100, integer=True)
+    scores = np.stack([scores_of_every_kind(8 + f, n) for f in range(F)])
+    check(nms, oracle, boxes, scores, 0.4)
