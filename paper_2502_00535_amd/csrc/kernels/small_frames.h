@@ -11,9 +11,9 @@
 // that has met one eliminator needs no further test, which on clustered detections is most victims
 // after the best-ranked boxes have been tried:
 //
-//   rank      Algorithm 1's order "D[i].s < D[j].s" (ties by index): the first P / 256 wavefronts
-//             sort the frame's keys (radix_rank_small) while every thread holds one input box; the
-//             boxes change hands through LDS and thread r builds row r of the table (box, y scaled
+//   rank      Algorithm 1's order "D[i].s < D[j].s" (ties by index): thread e holds box and key of
+//             input element e, the workgroup sorts the keys (radix_rank_one, slots beyond the frame's
+//             count last), the boxes change hands through LDS and thread r builds row r of the table (box, y scaled
 //             when every box of the frame allows it; its decision threshold T, or its area for
 //             thresholds that take the literal division; its input index);
 //   stage 1   every victim of the workgroup against the best kSmallFirst ranks: lane = victim, two
@@ -49,36 +49,68 @@ __device__ __forceinline__ bool small_hit(const float4 v, const float4 c, float 
     return nms_eliminates_exact(v.x, v.y, v.z, v.w, c.x, c.y, c.z, c.w, aux, theta);
 }
 
-// Stage 1, one work item: the outranking ranks [c0, c0 + kSmallGroup) against two victim tiles
-// (victims va, vb of ranks ra, rb in this lane).  GUARD: some of the victims may be ranked at or
-// before some of the boxes, so a box counts only for the lanes whose victim is ranked behind it.
-template <int PAIR, bool GUARD>
-__device__ __forceinline__ void small_first_item(const float4 *tbox, const float *taux, int c0, const float4 va, const float4 vb,
-                                                 int ra, int rb, float theta, float y_one, unsigned long long &dead_a,
-                                                 unsigned long long &dead_b)
+// Stage 1, one work item: the outranking ranks [c0, c0 + kSmallGroup) against R victim tiles (this
+// lane's victims v[] of ranks r[]).  GUARD: some of the victims may be ranked at or before some of
+// the boxes, so a box counts only for the lanes whose victim is ranked behind it.
+template <int PAIR, bool GUARD, int R>
+__device__ __forceinline__ void small_first_item(const float4 *tbox, const float *taux, int c0, const float4 (&v)[R],
+                                                 const int (&r)[R], float theta, float y_one, unsigned long long (&dead)[R])
 {
-    float4 cb[kSmallGroup];
-    float ca[kSmallGroup];
+    // four boxes at a time: with all eight in flight next to four victims' chains the kernel runs out of registers
 #pragma unroll
-    for (int k = 0; k < kSmallGroup; ++k) cb[k] = tbox[c0 + k];
+    for (int half = 0; half < kSmallGroup; half += 4) {
+        float4 cb[4];
 #pragma unroll
-    for (int k = 0; k < kSmallGroup; k += 4) {
-        const float4 a4 = *reinterpret_cast<const float4 *>(taux + c0 + k);
-        ca[k] = a4.x;
-        ca[k + 1] = a4.y;
-        ca[k + 2] = a4.z;
-        ca[k + 3] = a4.w;
-    }
+        for (int k = 0; k < 4; ++k) cb[k] = tbox[c0 + half + k];
+        const float4 a4 = *reinterpret_cast<const float4 *>(taux + c0 + half);
+        const float ca[4] = {a4.x, a4.y, a4.z, a4.w};
 #pragma unroll
-    for (int k = 0; k < kSmallGroup; ++k) {
-        unsigned long long ha = __ballot(small_hit<PAIR>(va, cb[k], ca[k], theta, y_one));
-        unsigned long long hb = __ballot(small_hit<PAIR>(vb, cb[k], ca[k], theta, y_one));
-        if (GUARD) {
-            ha &= __ballot(ra > c0 + k);
-            hb &= __ballot(rb > c0 + k);
+        for (int k = 0; k < 4; ++k) {
+#pragma unroll
+            for (int q = 0; q < R; ++q) {
+                unsigned long long h = __ballot(small_hit<PAIR>(v[q], cb[k], ca[k], theta, y_one));
+                if (GUARD) h &= __ballot(r[q] > c0 + half + k);
+                dead[q] |= h;
+            }
         }
-        dead_a |= ha;
-        dead_b |= hb;
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// Stage 1 for the workgroup's victim tiles in sets of R: items (set, group of kSmallGroup boxes) dealt
+// round-robin to the wavefronts; a set's eliminated victims are merged per tile in dead1[].
+template <int PAIR, int R>
+__device__ __forceinline__ void small_first_stage(const float4 *tbox, const float *taux, unsigned long long *dead1, int m0,
+                                                  int first, int part, int parts, float theta, float y_one)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int vtiles = (m0 + kTile - 1) / kTile;
+    const int sets = (vtiles + R - 1) / R;
+    const int groups = first / kSmallGroup;
+    for (int item = wave; item < sets * groups; item += kSmallWaves) {
+        const int set = item / groups;
+        const int c0 = (item % groups) * kSmallGroup;
+        float4 v[R];
+        int r[R];
+        unsigned long long dead[R];
+#pragma unroll
+        for (int q = 0; q < R; ++q) {
+            const int i = (R * set + q) * kTile + lane;
+            r[q] = i < m0 ? part + parts * i : 0;  // a lane beyond the share tests row 0: its bits are never read
+            v[q] = tbox[r[q]];
+            dead[q] = 0ull;
+        }
+        // the lowest rank of the set's victims is that of its first lane
+        if (part + parts * (R * set) * kTile >= c0 + kSmallGroup)
+            small_first_item<PAIR, false, R>(tbox, taux, c0, v, r, theta, y_one, dead);
+        else
+            small_first_item<PAIR, true, R>(tbox, taux, c0, v, r, theta, y_one, dead);
+        if (lane == 0) {
+#pragma unroll
+            for (int q = 0; q < R; ++q)
+                if (dead[q] != 0ull && R * set + q < vtiles) atomicOr(&dead1[R * set + q], dead[q]);
+        }
     }
 }
 
@@ -117,31 +149,12 @@ __device__ __forceinline__ void small_stages(const float4 *tbox, const float *ta
     const int m0 = n_f > part ? (n_f - part + parts - 1) / parts : 0;
     const int first = tiles_f * kTile < kSmallFirst ? tiles_f * kTile : kSmallFirst;  // boxes of stage 1 (padding rows included)
 
-    // ---- stage 1
-    {
-        const int vtiles = (m0 + kTile - 1) / kTile;
-        const int vpairs = (vtiles + 1) / 2;
-        const int groups = first / kSmallGroup;
-        for (int item = wave; item < vpairs * groups; item += kSmallWaves) {
-            const int vp = item / groups;
-            const int c0 = (item % groups) * kSmallGroup;
-            const int ia = (2 * vp) * kTile + lane, ib = (2 * vp + 1) * kTile + lane;
-            // a lane beyond the share tests the padding row of rank P - 1 or any row: its bits are never read
-            const int ra = ia < m0 ? part + parts * ia : 0;
-            const int rb = ib < m0 ? part + parts * ib : 0;
-            const float4 va = tbox[ra], vb = tbox[rb];
-            unsigned long long da = 0ull, db = 0ull;
-            // the lowest rank of the pair's victims is that of its first lane
-            if (part + parts * (2 * vp) * kTile >= c0 + kSmallGroup)
-                small_first_item<PAIR, false>(tbox, taux, c0, va, vb, ra, rb, theta, y_one, da, db);
-            else
-                small_first_item<PAIR, true>(tbox, taux, c0, va, vb, ra, rb, theta, y_one, da, db);
-            if (lane == 0) {
-                if (da != 0ull) atomicOr(&dead1[2 * vp], da);
-                if (db != 0ull) atomicOr(&dead1[2 * vp + 1], db);
-            }
-        }
-    }
+    // ---- stage 1: four victims per lane where the share has three tiles or more (a broadcast of an outranking
+    // box then serves four rows), two otherwise (fewer idle lanes)
+    if ((m0 + kTile - 1) / kTile > 2)
+        small_first_stage<PAIR, 4>(tbox, taux, dead1, m0, first, part, parts, theta, y_one);
+    else
+        small_first_stage<PAIR, 2>(tbox, taux, dead1, m0, first, part, parts, theta, y_one);
     __syncthreads();
 
     // ---- pack: final victims are written out, the others listed in rank order
@@ -166,17 +179,14 @@ __device__ __forceinline__ void small_stages(const float4 *tbox, const float *ta
         if (lane == 0) wcount[kSmallWaves * (g + 1) + wave] = n;
     }
     __syncthreads();
-    int before = 0, listed = 0;
-    int start[4] = {0, 0, 0, 0};
-#pragma unroll
-    for (int w = 0; w < kSmallWaves; ++w) {
-        const int c = wcount[w];
-        if (w < wave) before += c;
-        listed += c;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) start[g] += wcount[kSmallWaves * (g + 1) + w];
-    }
-    listed = __builtin_amdgcn_readfirstlane(listed);  // the same in every lane: say so
+    // the five rows of sixteen counts summed by every wavefront for itself: a lane per count, prefix sums inside
+    // the rows of sixteen lanes (DPP), totals read from each row's last lane
+    const int sums_a = (int)row16_inclusive_sum((unsigned)wcount[lane]);
+    const int sums_b = (int)row16_inclusive_sum((unsigned)wcount[kTile + (lane & 15)]);
+    const int listed = __builtin_amdgcn_readlane(sums_a, 15);
+    const int before = wave == 0 ? 0 : __builtin_amdgcn_readlane(sums_a, wave - 1);
+    int start[4] = {__builtin_amdgcn_readlane(sums_a, 31), __builtin_amdgcn_readlane(sums_a, 47), __builtin_amdgcn_readlane(sums_a, 63),
+                    __builtin_amdgcn_readlane(sums_b, 15)};
     if (alive) {
         const int pos = before + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(alive_mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)alive_mask, 0u));
         list[pos] = r_mine;
@@ -193,7 +203,7 @@ __device__ __forceinline__ void small_stages(const float4 *tbox, const float *ta
         units_before[0] = 0;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            start[g] = __builtin_amdgcn_readfirstlane(g < groups2 ? start[g] : listed);
+            if (g >= groups2) start[g] = listed;
             units_before[g + 1] = units_before[g] + (listed - start[g] + 3) / 4;
         }
         for (int unit = wave; unit < units_before[4]; unit += kSmallWaves) {
@@ -204,14 +214,6 @@ __device__ __forceinline__ void small_stages(const float4 *tbox, const float *ta
                                 4 * (unit - (g == 0 ? units_before[0] : g == 1 ? units_before[1] : g == 2 ? units_before[2] : units_before[3]));
             const int t0 = t_begin + g * kSmallTiles;
             const int useful = tiles_f - t0 < kSmallTiles ? tiles_f - t0 : kSmallTiles;
-            float4 cb[kSmallTiles];
-            float aux[kSmallTiles];
-#pragma unroll
-            for (int j = 0; j < kSmallTiles; ++j) {
-                const int row = (t0 + (j < useful ? j : 0)) * kTile + lane;
-                cb[j] = tbox[row];
-                aux[j] = taux[row];
-            }
             // four victims, their reads issued together (a short last unit repeats its last victim)
             int at[4], r[4];
             float4 v[4];
@@ -219,6 +221,14 @@ __device__ __forceinline__ void small_stages(const float4 *tbox, const float *ta
             for (int u = 0; u < 4; ++u) {
                 at[u] = k_begin + u < listed ? k_begin + u : listed - 1;
                 r[u] = list[at[u]];
+            }
+            float4 cb[kSmallTiles];
+            float aux[kSmallTiles];
+#pragma unroll
+            for (int j = 0; j < kSmallTiles; ++j) {
+                const int row = (t0 + (j < useful ? j : 0)) * kTile + lane;
+                cb[j] = tbox[row];
+                aux[j] = taux[row];
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -236,17 +246,18 @@ __device__ __forceinline__ void small_stages(const float4 *tbox, const float *ta
     for (int k = tid; k < listed; k += kSmallThreads) keep_f[tord[list[k]]] = flag2[k] ? 0 : 1;
 }
 
-// P: 256, 512 or 1024 >= n_max.  FAST: the threshold has a division-free form (NmsThetaConst).
+// n_max <= kSmallThreads.  FAST: the threshold has a division-free form (NmsThetaConst).
 // Grid: frames * parts workgroups of kSmallThreads threads.
-template <int P, bool FAST>
+template <bool FAST>
 __global__ void __launch_bounds__(kSmallThreads)
 small_frames_kernel(const float *__restrict__ boxes, const float *__restrict__ scores, const int32_t *__restrict__ counts,
                     int n_max, int parts, NmsThetaConst th, uint8_t *__restrict__ keep_out)
 {
-    constexpr int W = P / 256;  // wavefronts that sort
+    constexpr int P = kSmallThreads;  // rows of the table: one per thread
     __shared__ unsigned long long keys[P];
-    __shared__ __align__(16) unsigned hist[P];
-    __shared__ __align__(16) unsigned wbase[P];
+    __shared__ __align__(16) unsigned hist[kSmallWaves * 256];
+    __shared__ __align__(16) unsigned wbase[kSmallWaves * 256];
+    __shared__ __align__(16) unsigned tot[256];
     __shared__ float4 stage[2 * P];  // the sort's lane-mask tables, then the boxes in input order
     __shared__ float4 tbox[P];
     __shared__ __align__(16) float taux[P];
@@ -258,31 +269,20 @@ small_frames_kernel(const float *__restrict__ boxes, const float *__restrict__ s
     const int f = blockIdx.x / parts;
     const int part = blockIdx.x % parts;
     const int tid = (int)threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n_f = frame_count(counts, f, n_max);
     const float *scores_f = scores + (size_t)f * n_max;
     const float4 *boxes_f = reinterpret_cast<const float4 *>(boxes + (size_t)f * n_max * 4);
     uint8_t *keep_f = keep_out + (size_t)f * n_max;
 
-    float4 mine = make_float4(0.f, 0.f, 0.f, 0.f);  // box tid of the input
-    if (tid < n_f) mine = boxes_f[tid];
-    if (wave < W) {
-        int e[4];
-        unsigned key32[4], index[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            e[q] = wave * 256 + q * 64 + lane;
-            const unsigned long long key = e[q] < n_f ? nms_rank_key(scores_f[e[q]], (unsigned)e[q]) : kSentinel;
-            key32[q] = (unsigned)(key >> 32);
-            index[q] = (unsigned)key;
-        }
-        radix_rank_small<W>(key32, index, e, keys, hist, wbase, reinterpret_cast<unsigned long long *>(stage));
-    } else {
-        // the other wavefronts only keep the sort's barriers company
-        for (int i = 0; i < kRadixSmallBarriers; ++i) __syncthreads();
+    // rank: thread e holds element e of the input (slots beyond the frame's count sort to the end)
+    float4 mine = make_float4(0.f, 0.f, 0.f, 0.f);
+    unsigned long long key = kSentinel;
+    if (tid < n_f) {
+        mine = boxes_f[tid];
+        key = nms_rank_key(scores_f[tid], (unsigned)tid);
     }
-    if (tid < P) stage[tid] = mine;
+    radix_rank_one<kSmallWaves>((unsigned)(key >> 32), (unsigned)key, keys, hist, tot, wbase, reinterpret_cast<unsigned long long *>(stage));
+    stage[tid] = mine;
     if (tid < P / kTile) dead1[tid] = 0ull;
     __syncthreads();
 
@@ -294,7 +294,7 @@ small_frames_kernel(const float *__restrict__ boxes, const float *__restrict__ s
     }
     const bool odd = !(nms_y_regular(b.y) && nms_y_regular(b.w));
     const bool scaled = FAST && __syncthreads_or(odd ? 1 : 0) == 0;
-    if (tid < P) {
+    {
         const float area = nms_box_area(b.x, b.y, b.z, b.w);
         float a = FAST ? (tid < n_f ? nms_pair_threshold(area, th.m) : INFINITY) : area;  // no intersection reaches a padding row's
         if (scaled) {

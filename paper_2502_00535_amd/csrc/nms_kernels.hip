@@ -367,19 +367,13 @@ static int fused_launch(const RunWorkspace &w, const int32_t *counts, int n_max,
 static int small_frames_launch(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
                                const NmsThetaConst &th, uint8_t *keep_out, hipStream_t stream)
 {
-    const int P = n_max <= 256 ? 256 : (n_max <= 512 ? 512 : 1024);
     const int parts = nms_small_frames_parts(frames);
     const dim3 grid((unsigned)(frames * parts)), block(kSmallThreads);
     begin_launch();
-#define NMS_LAUNCH_SMALL(P_)                                                                                             \
-    do {                                                                                                                 \
-        if (th.fast) small_frames_kernel<P_, true><<<grid, block, 0, stream>>>(boxes, scores, counts, n_max, parts, th, keep_out); \
-        else small_frames_kernel<P_, false><<<grid, block, 0, stream>>>(boxes, scores, counts, n_max, parts, th, keep_out);  \
-    } while (0)
-    if (P == 256) NMS_LAUNCH_SMALL(256);
-    else if (P == 512) NMS_LAUNCH_SMALL(512);
-    else NMS_LAUNCH_SMALL(1024);
-#undef NMS_LAUNCH_SMALL
+    if (th.fast)
+        small_frames_kernel<true><<<grid, block, 0, stream>>>(boxes, scores, counts, n_max, parts, th, keep_out);
+    else
+        small_frames_kernel<false><<<grid, block, 0, stream>>>(boxes, scores, counts, n_max, parts, th, keep_out);
     return launch_status();
 }
 
