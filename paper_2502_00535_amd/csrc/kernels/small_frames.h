@@ -50,9 +50,9 @@ __device__ __forceinline__ bool small_hit(const float4 v, const float4 c, float 
 }
 
 // Stage 1, one work item: the outranking ranks [c0, c0 + kSmallGroup) against R victim tiles (this
-// lane's victims v[] of ranks r[]).  GUARD: some of the victims may be ranked at or before some of
-// the boxes, so a box counts only for the lanes whose victim is ranked behind it.
-template <int PAIR, bool GUARD, int R>
+// lane's victims v[] of ranks r[]).  GUARD: the first so many tiles of the set hold victims ranked at
+// or before some of the boxes, so there a box counts only for the lanes whose victim is ranked behind it.
+template <int PAIR, int GUARD, int R>
 __device__ __forceinline__ void small_first_item(const float4 *tbox, const float *taux, int c0, const float4 (&v)[R],
                                                  const int (&r)[R], float theta, float y_one, unsigned long long (&dead)[R])
 {
@@ -69,7 +69,7 @@ __device__ __forceinline__ void small_first_item(const float4 *tbox, const float
 #pragma unroll
             for (int q = 0; q < R; ++q) {
                 unsigned long long h = __ballot(small_hit<PAIR>(v[q], cb[k], ca[k], theta, y_one));
-                if (GUARD) h &= __ballot(r[q] > c0 + half + k);
+                if (q < GUARD) h &= __ballot(r[q] > c0 + half + k);
                 dead[q] |= h;
             }
         }
@@ -101,11 +101,15 @@ __device__ __forceinline__ void small_first_stage(const float4 *tbox, const floa
             v[q] = tbox[r[q]];
             dead[q] = 0ull;
         }
-        // the lowest rank of the set's victims is that of its first lane
-        if (part + parts * (R * set) * kTile >= c0 + kSmallGroup)
-            small_first_item<PAIR, false, R>(tbox, taux, c0, v, r, theta, y_one, dead);
+        // a tile's lowest rank is that of its first lane; the ranks rise from tile to tile
+        int guarded = 0;
+        while (guarded < R && part + parts * (R * set + guarded) * kTile < c0 + kSmallGroup) ++guarded;
+        if (guarded == 0)
+            small_first_item<PAIR, 0, R>(tbox, taux, c0, v, r, theta, y_one, dead);
+        else if (guarded == 1)
+            small_first_item<PAIR, 1, R>(tbox, taux, c0, v, r, theta, y_one, dead);
         else
-            small_first_item<PAIR, true, R>(tbox, taux, c0, v, r, theta, y_one, dead);
+            small_first_item<PAIR, 2, R>(tbox, taux, c0, v, r, theta, y_one, dead);  // ranks < 128: at most the first two tiles
         if (lane == 0) {
 #pragma unroll
             for (int q = 0; q < R; ++q)
@@ -259,6 +263,7 @@ small_frames_kernel(const float *__restrict__ boxes, const float *__restrict__ s
     __shared__ __align__(16) unsigned wbase[kSmallWaves * 256];
     __shared__ __align__(16) unsigned tot[256];
     __shared__ float4 stage[2 * P];  // the sort's lane-mask tables, then the boxes in input order
+    __shared__ float saux[P];        // and their decision values
     __shared__ float4 tbox[P];
     __shared__ __align__(16) float taux[P];
     __shared__ int tord[P];
@@ -281,29 +286,28 @@ small_frames_kernel(const float *__restrict__ boxes, const float *__restrict__ s
         mine = boxes_f[tid];
         key = nms_rank_key(scores_f[tid], (unsigned)tid);
     }
+    // what the table needs per box is worked out here, in input order, while the loads are the only thing in flight:
+    // does every y of the frame allow the scaled form (slots beyond the count hold the box (0,0,0,0), which does), and
+    // the box's decision value (no intersection reaches a padding row's)
+    const bool odd = !(nms_y_regular(mine.y) && nms_y_regular(mine.w));
+    const bool scaled = FAST && __syncthreads_or(odd ? 1 : 0) == 0;
+    const float area = nms_box_area(mine.x, mine.y, mine.z, mine.w);
+    float mine_aux = FAST ? (tid < n_f ? nms_pair_threshold(area, th.m) : INFINITY) : area;
+    if (scaled) {
+        mine.y *= NMS_YSCALE;
+        mine.w *= NMS_YSCALE;
+        mine_aux *= NMS_YSCALE;
+    }
     radix_rank_one<kSmallWaves>((unsigned)(key >> 32), (unsigned)key, keys, hist, tot, wbase, reinterpret_cast<unsigned long long *>(stage));
     stage[tid] = mine;
+    saux[tid] = mine_aux;
     if (tid < P / kTile) dead1[tid] = 0ull;
     __syncthreads();
-
-    int idx = 0;
-    float4 b = make_float4(0.f, 0.f, 0.f, 0.f);  // rank tid, or the padding row: the one-pixel box (0,0,0,0)
-    if (tid < n_f) {
-        idx = (int)(unsigned)keys[tid];
-        b = stage[idx];
-    }
-    const bool odd = !(nms_y_regular(b.y) && nms_y_regular(b.w));
-    const bool scaled = FAST && __syncthreads_or(odd ? 1 : 0) == 0;
     {
-        const float area = nms_box_area(b.x, b.y, b.z, b.w);
-        float a = FAST ? (tid < n_f ? nms_pair_threshold(area, th.m) : INFINITY) : area;  // no intersection reaches a padding row's
-        if (scaled) {
-            b.y *= NMS_YSCALE;
-            b.w *= NMS_YSCALE;
-            a *= NMS_YSCALE;
-        }
-        tbox[tid] = b;
-        taux[tid] = a;
+        // row tid of the table: the box of rank tid, or the padding row (the input's slot tid: it holds one too)
+        const int idx = tid < n_f ? (int)(unsigned)keys[tid] : tid;
+        tbox[tid] = stage[idx];
+        taux[tid] = saux[idx];
         tord[tid] = idx;
     }
     __syncthreads();
