@@ -120,23 +120,59 @@ __device__ __forceinline__ void small_first_stage(const float4 *tbox, const floa
 
 // Stage 2, one victim (rank r, box v, read as broadcasts) against the tiles t0 .. t0 + 3 held in
 // cb[], aux[]: is there an eliminator among the boxes ranked before r?  Branch-free, so that the
-// tests of several victims can be interleaved: every tile is tested and its lane mask cut down to
-// the boxes ranked before r (all, the lower r - 64 t lanes of the tile that holds rank r, none).
-// A tile beyond the frame's last is a copy of tile t0 with an empty mask.
-template <int PAIR>
+// tests of several victims can be interleaved.  MASKED: the victim's rank lies inside the group's
+// tiles (or the group has fewer than four), so every tile's lane mask is cut down to the boxes ranked
+// before r (all, the lower r - 64 t lanes of the tile that holds rank r, none; a tile beyond the
+// frame's last is a copy of tile t0 with an empty mask).  Otherwise all four tiles are ranked before
+// r: the scalar unit, which the four SIMDs share, then has one instruction per row to do, not twelve.
+template <int PAIR, bool MASKED>
 __device__ __forceinline__ bool small_second_victim(const float4 v, int r, const float4 (&cb)[kSmallTiles],
                                                     const float (&aux)[kSmallTiles], int t0, int useful, float theta, float y_one)
 {
     unsigned long long any = 0ull;
 #pragma unroll
     for (int j = 0; j < kSmallTiles; ++j) {
-        int before = r - (t0 + j) * kTile;  // boxes of tile t0 + j ranked before the victim
-        before = before < 0 ? 0 : (before > kTile ? kTile : before);
-        if (j >= useful) before = 0;
-        const unsigned long long outranks = before >= kTile ? ~0ull : (1ull << before) - 1ull;
-        any |= __ballot(small_hit<PAIR>(v, cb[j], aux[j], theta, y_one)) & outranks;
+        unsigned long long h = __ballot(small_hit<PAIR>(v, cb[j], aux[j], theta, y_one));
+        if (MASKED) {
+            int before = r - (t0 + j) * kTile;  // boxes of tile t0 + j ranked before the victim
+            before = before < 0 ? 0 : (before > kTile ? kTile : before);
+            if (j >= useful) before = 0;
+            h &= before >= kTile ? ~0ull : (1ull << before) - 1ull;
+        }
+        any |= h;
     }
     return any != 0ull;
+}
+
+// A unit of stage 2: the listed victims [k_begin, k_end) against the tiles in cb[], aux[], four at a
+// time, their reads issued together (a short last batch repeats its last victim).  (Requesting the
+// next four while these are tested measured slower.)
+template <int PAIR, bool MASKED>
+__device__ __forceinline__ void small_second_unit(const float4 *tbox, const int *list, unsigned char *flag2, int k_begin, int k_end,
+                                                  const float4 (&cb)[kSmallTiles], const float (&aux)[kSmallTiles], int t0,
+                                                  int useful, float theta, float y_one)
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll 1
+    for (int k = k_begin; k < k_end; k += 4) {
+        int at[4], r[4];
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            at[u] = k + u < k_end ? k + u : k_end - 1;
+            r[u] = list[at[u]];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            r[u] = __builtin_amdgcn_readfirstlane(r[u]);
+            v[u] = tbox[r[u]];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const bool dead = small_second_victim<PAIR, MASKED>(v[u], r[u], cb, aux, t0, useful, theta, y_one);
+            if (lane == 0 && dead) flag2[at[u]] = 1;
+        }
+    }
 }
 
 // The stages of one workgroup.  The table (tbox, taux) holds the frame in rank order; the workgroup's
@@ -198,11 +234,12 @@ __device__ __forceinline__ void small_stages(const float4 *tbox, const float *ta
     }
     __syncthreads();
 
-    // ---- stage 2: tiles first / 64 .. tiles_f - 1 in groups of kSmallTiles.  The list is in rank order,
-    // so a group only meets the victims from some list position on; a unit is (group, four consecutive
-    // listed victims from there), the units of all groups in one numbering dealt round-robin to the wavefronts.
+    // ---- stage 2: tiles first / 64 .. tiles_f - 1 in groups of kSmallTiles.  The list is in rank order, so a
+    // group meets only the victims from list position start[g] on.
     const int groups2 = (tiles_f - t_begin + kSmallTiles - 1) / kSmallTiles;  // at most 4: P / 64 - 2 tiles
-    if (listed > 0 && groups2 > 0) {
+    if (listed > 0 && listed <= kTile && groups2 > 0) {
+        // A short list (clustered detections): a unit is (group, four consecutive listed victims), the units of
+        // all groups in one numbering dealt round-robin to the wavefronts.
         int units_before[5];
         units_before[0] = 0;
 #pragma unroll
@@ -241,9 +278,63 @@ __device__ __forceinline__ void small_stages(const float4 *tbox, const float *ta
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const bool dead = small_second_victim<PAIR>(v[u], r[u], cb, aux, t0, useful, theta, y_one);
+                const bool dead = small_second_victim<PAIR, true>(v[u], r[u], cb, aux, t0, useful, theta, y_one);
                 if (lane == 0 && dead) flag2[at[u]] = 1;
             }
+        }
+    }
+    if (listed > kTile && groups2 > 0) {
+        // A long list (little was eliminated).  From list position start[g + 1] on the victims are ranked behind all
+        // tiles of group g: two ranges per group (ranks inside the group's tiles: lane masks needed; beyond: none),
+        // each cut into units of `span` consecutive victims -- about two units per wavefront, so that a group's
+        // tiles are fetched once for many victims.
+        int range_begin[8], range_end[8], units_before[9];
+        int slots = 0;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int from = g < groups2 ? start[g] : listed;
+            const int full_group = (t_begin + (g + 1) * kSmallTiles) <= tiles_f;  // a group cut short by the frame's end keeps its masks
+            const int beyond = g + 1 < groups2 && full_group ? start[g + 1] : listed;
+            range_begin[2 * g] = from;
+            range_end[2 * g] = beyond;
+            range_begin[2 * g + 1] = beyond;
+            range_end[2 * g + 1] = listed;
+            slots += listed - from;
+        }
+        int span = (slots + 2 * kSmallWaves - 1) / (2 * kSmallWaves);
+        span = span < 4 ? 4 : (span + 3) / 4 * 4;
+        units_before[0] = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) units_before[i + 1] = units_before[i] + (range_end[i] - range_begin[i] + span - 1) / span;
+        for (int unit = wave; unit < units_before[8]; unit += kSmallWaves) {
+            int i = 0;
+#pragma unroll
+            for (int q = 1; q < 8; ++q) i += unit >= units_before[q] ? 1 : 0;
+            int first_unit = 0, from = 0, to = 0;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                if (q == i) {
+                    first_unit = units_before[q];
+                    from = range_begin[q];
+                    to = range_end[q];
+                }
+            }
+            const int k_begin = from + span * (unit - first_unit);
+            const int k_end = k_begin + span < to ? k_begin + span : to;
+            const int t0 = t_begin + (i / 2) * kSmallTiles;
+            const int useful = tiles_f - t0 < kSmallTiles ? tiles_f - t0 : kSmallTiles;
+            float4 cb[kSmallTiles];
+            float aux[kSmallTiles];
+#pragma unroll
+            for (int j = 0; j < kSmallTiles; ++j) {
+                const int row = (t0 + (j < useful ? j : 0)) * kTile + lane;
+                cb[j] = tbox[row];
+                aux[j] = taux[row];
+            }
+            if ((i & 1) == 0)
+                small_second_unit<PAIR, true>(tbox, list, flag2, k_begin, k_end, cb, aux, t0, useful, theta, y_one);
+            else
+                small_second_unit<PAIR, false>(tbox, list, flag2, k_begin, k_end, cb, aux, t0, useful, theta, y_one);
         }
     }
     __syncthreads();
