@@ -54,6 +54,21 @@ __device__ __forceinline__ unsigned row16_inclusive_sum(unsigned x)
     return x;
 }
 
+// The minimum over each row of 16 lanes, in every lane of the row (rotations inside the row).
+__device__ __forceinline__ unsigned row16_min(unsigned x)
+{
+    unsigned y;
+    y = (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x121, 0xf, 0xf, false);  // row_ror:1
+    x = y < x ? y : x;
+    y = (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x122, 0xf, 0xf, false);  // row_ror:2
+    x = y < x ? y : x;
+    y = (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x124, 0xf, 0xf, false);  // row_ror:4
+    x = y < x ? y : x;
+    y = (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x128, 0xf, 0xf, false);  // row_ror:8
+    x = y < x ? y : x;
+    return x;
+}
+
 // Stable LSD radix sort of the P = 4 * blockDim.x (key, index) pairs of a workgroup, eight
 // bits per pass, four passes.  Element e = 256 * wave + 64 * q + lane is register q of its
 // thread.  Stability is what makes 32-bit keys enough: elements start in index order, so
