@@ -71,6 +71,8 @@ PROBE(p_mul_abs, "v_mul_f32_e64 %0, %1, |%0|")
 PROBE(p_sub_clamp, "v_sub_f32_e64 %0, %1, %0 clamp")
 PROBE(p_mul_clamp, "v_mul_f32_e64 %0, %1, %0 clamp")
 PROBE(p_rcp, "v_rcp_f32 %0, %0")
+PROBE(p_readlane, "v_readlane_b32 s20, %0, 5")
+PROBE(p_cmp_lt_u32, "v_cmp_lt_u32 vcc, %1, %0")
 
 // float64 instructions (the variants' exact threshold compare uses a convert, a multiply and a compare)
 #define PROBE_BODY_F64(INSTR)                                                                                   \
@@ -105,6 +107,7 @@ PROBE_F64(p_mul_f64, "v_mul_f64 %0, %1, %0")
 PROBE_F64(p_fma_f64, "v_fma_f64 %0, %1, %0, %0")
 PROBE_F64(p_cmp_f64, "v_cmp_ge_f64 vcc, %1, %0")
 PROBE_F64(p_cvt_f64_f32, "v_cvt_f64_f32 %0, %2")
+PROBE_F64(p_cmp_lt_u64, "v_cmp_lt_u64 vcc, %1, %0")
 
 // The pair test's ten instructions as the fused map kernel issues them (victim coordinates as
 // scalar operands), on eight chains per lane, nothing else in the loop: the ceiling of that mix.
@@ -179,6 +182,9 @@ const Probe kProbes[] = {
     {"v_fma_f64", p_fma_f64},
     {"v_cmp_ge_f64", p_cmp_f64},
     {"v_cvt_f64_f32", p_cvt_f64_f32},
+    {"v_cmp_lt_u64", p_cmp_lt_u64},
+    {"v_cmp_lt_u32", p_cmp_lt_u32},
+    {"v_readlane_b32", p_readlane},
 };
 constexpr int kProbeCount = (int)(sizeof(kProbes) / sizeof(kProbes[0]));
 

@@ -1,11 +1,13 @@
-"""The one-launch route that nms_run_batched takes for batches of frames of 257 to 1024 boxes (rank
-step in LDS, every victim against the best 128 ranks, the victims still alive against the rest;
-a frame shared out among 1 to 16 workgroups) against the oracle's plain double loop, 0 differing
-bits, on what the route itself can meet: every number of workgroups per frame, frame lengths
-around the tile and stage sizes, ragged batches incl. empty frames and frames shorter than the
-first stage, nothing / everything / all but a few victims alive after the first stage, eliminators
-that sit only behind rank 128 (at tile and tile-group borders), y coordinates outside the scaled
-form's range, thresholds that take the literal division, scores of every kind."""
+"""The one-launch route that nms_run_batched takes for batches of frames of 257 to 1024 boxes (no
+sort: every victim against the two best-ranked of every sixteen input elements, the victims still
+alive against the whole frame, rank order as a compare of the two boxes' keys; a frame shared out
+among 1 to 16 workgroups) against the oracle's plain double loop, 0 differing bits, on what the
+route itself can meet: every number of workgroups per frame, frame lengths around the tile and
+stage sizes, ragged batches incl. empty frames and frames shorter than a tile, nothing / everything /
+all but a few victims alive after the first stage (short and long lists for the second, at the
+length where its form changes), eliminators that the first stage does not hold, equal scores,
+y coordinates outside the scaled form's range, thresholds that take the literal division, scores
+of every kind."""
 import numpy as np
 import pytest
 
@@ -15,7 +17,7 @@ from workloads import clustered_frame, random_frame, scores_of_every_kind
 
 pytestmark = pytest.mark.gpu
 
-FIRST = 128  # ranks that the first stage tests every victim against
+FIRST = 128  # boxes of the first stage: the two best-ranked of every 16 input elements
 
 
 @pytest.fixture(scope="module")
@@ -187,3 +189,83 @@ def test_scores_of_every_kind(nms, oracle):
     boxes, _ = batch(5, F, n, extent=700, max_side=100, integer=True)
     scores = np.stack([scores_of_every_kind(8 + f, n) for f in range(F)])
     check(nms, oracle, boxes, scores, 0.4)
+
+
+def test_eliminators_that_the_first_stage_does_not_hold(nms, oracle):
+    """Scores fall with the input index, so the first stage holds elements 0 and 1 of every sixteen.  Victims
+    repeat the box of an element at position 2 .. 15 of a row (same row, same tile, an earlier tile, the tile
+    before a tile-group border): alive after the first stage, caught only by the second; and victims that repeat
+    a first-stage box of a later row do not fall (it is ranked behind them)."""
+    n, F = 1024, 40
+    base = lattice(n)
+    scores = np.tile((1.0 - np.arange(n) / n).astype(np.float32), (F, 1))
+    pairs = [(2, 3), (2, 15), (14, 31), (4, 16), (5, 63), (62, 79), (61, 64), (18, 200), (255, 256), (254, 257), (300, 1023), (1006, 1007),
+             (130, 131), (515, 770), (766, 769)]
+    assert all(e < v and e % 16 >= 2 for e, v in pairs)
+    spared = [(33, 20), (161, 100), (1009, 500)]  # (first-stage box, a better-ranked element that repeats it)
+    boxes1 = base.copy()
+    victims = set()
+    for e, v in pairs:
+        assert v not in victims and all(v != a for a, _ in pairs + spared)
+        boxes1[v] = base[e]
+        victims.add(v)
+    for e, v in spared:
+        assert e % 16 < 2 and v < e and v not in victims and all(v not in p for p in pairs)
+        boxes1[v] = base[e]
+    boxes = np.tile(boxes1, (F, 1, 1))
+    for f in range(1, F):  # every frame but the first: a different half of the other boxes falls in the first stage
+        free = np.setdiff1d(np.arange(16, n), np.array(sorted({x for p in pairs + spared for x in p})))
+        gone = np.random.default_rng(f).permutation(free)[:free.size // 2]
+        boxes[f, gone] = base[0]
+    want = check(nms, oracle, boxes, scores, 0.5)
+    dead = set(np.flatnonzero(want[0] == 0).tolist())
+    assert dead == victims | {e for e, _ in spared}
+    perm = np.random.default_rng(2).permutation(n)
+    check(nms, oracle, boxes[:, perm], scores[:, perm], 0.5)
+
+
+def test_equal_scores(nms, oracle):
+    """One score for the whole frame (and frames of two or three levels, +0.0 next to -0.0): rank order is input
+    order, the lower index of a repeated box survives."""
+    n, F = 1000, 44
+    rng = np.random.default_rng(12)
+    boxes = np.stack([lattice(n, rng) for _ in range(F)])
+    for f in range(F):
+        src = rng.integers(0, n, n // 2)
+        dst = rng.integers(0, n, n // 2)
+        boxes[f, dst] = boxes[f, src]
+    scores = np.full((F, n), 0.25, np.float32)
+    scores[1::4] = rng.integers(0, 2, (len(scores[1::4]), n)).astype(np.float32)
+    scores[2::4] = rng.integers(0, 3, (len(scores[2::4]), n)).astype(np.float32) * np.float32(0.5) - np.float32(0.5)
+    scores[3::4] = np.where(rng.integers(0, 2, (len(scores[3::4]), n)) == 1, np.float32(0.0), np.float32(-0.0))
+    want = check(nms, oracle, boxes, scores, 0.5)
+    assert 0 < want.sum() < want.size
+
+
+@pytest.mark.parametrize("frames", [70, 130])
+def test_long_lists(nms, oracle, frames):
+    """Two and one workgroups per frame: disjoint boxes of which a chosen number repeat the best-ranked one, so that
+    a workgroup lists 0 .. all of its 512 or 1024 victims for the second stage -- around 256, where the second stage
+    changes its form -- and some of the listed fall to boxes that the first stage does not hold."""
+    n = 1024
+    share = n // (2 if frames <= 128 else 1)
+    per_group = [0, 1, 100, 254, 255, 256, 257, 258, 300, 319, 320, 321, 400, 511, 512, 513, 640, 767, 768, 769, 1000, 1022, 1023, 1024]
+    scores = np.tile((1.0 - np.arange(n) / n).astype(np.float32), (frames, 1))
+    base = lattice(n)
+    boxes = np.zeros((frames, n, 4), np.float32)
+    for f in range(frames):
+        rng = np.random.default_rng(1000 * frames + f)
+        alive = min(per_group[f % len(per_group)], share) * (n // share)
+        boxes[f] = base
+        gone = 1 + rng.permutation(n - 1)[:n - max(alive, 1)]
+        boxes[f, gone] = base[0]
+        stay = np.setdiff1d(np.arange(2, n), gone)
+        late = stay[stay % 16 >= 3]
+        for v in rng.permutation(late)[:min(7, late.size)]:  # falls to its unpicked neighbour, in the second stage
+            if (v - 1) % 16 >= 2 and boxes[f, v - 1, 0] == base[v - 1, 0]:
+                boxes[f, v] = base[v - 1]
+    print(f"case frames={frames}", flush=True)
+    want = check(nms, oracle, boxes, scores, 0.5)
+    assert want.sum(1).min() <= 8 and want.sum(1).max() >= n - 8
+    perm = np.random.default_rng(3).permutation(n)
+    check(nms, oracle, boxes[:, perm], scores[:, perm], 0.5)
