@@ -101,15 +101,15 @@ __device__ __forceinline__ void small_victim_item(const float4 *cbox, const uint
     }
 }
 
-// Lane = victim: `count` victim slots (slot i = list[i]; without a list, lane i % 64 of the workgroup's
-// i / 64-th tile, see small_share_element; a slot at or beyond n_f holds no victim) in sets of R tiles
-// against the first ncand rows (a multiple of kSmallGroup) of a table.  The wavefronts are shared out among the
+// Lane = victim: `count` victim slots (slot i = entry i of the list lbox / lkey; without a list, lane
+// i % 64 of the workgroup's i / 64-th tile, see small_share_element; a slot at or beyond n_f holds no
+// victim) in sets of R tiles against the first ncand rows (a multiple of kSmallGroup) of a table.  The wavefronts are shared out among the
 // sets, a wavefront keeps its set's victims in registers and takes every so-many-th group of boxes;
 // eliminated victims are merged per victim tile in dead_words[].
 template <int PAIR, bool PICKED, int R>
 __device__ __forceinline__ void small_victim_lanes(const float4 *tbox, const uint2 *tinfo, const float4 *cbox, const uint4 *cinfo,
-                                                   int ncand, const int *list, int count, int n_f, int part, int parts,
-                                                   unsigned long long *dead_words, float theta, float y_one)
+                                                   int ncand, const float4 *lbox, const unsigned long long *lkey, int count, int n_f,
+                                                   int part, int parts, unsigned long long *dead_words, float theta, float y_one)
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -125,11 +125,15 @@ __device__ __forceinline__ void small_victim_lanes(const float4 *tbox, const uin
 #pragma unroll
     for (int q = 0; q < R; ++q) {
         const int i = (R * set + q) * kTile + lane;
-        int e = -1;
-        if (i < count) e = list != nullptr ? list[i] : small_share_element(i, part, parts);
-        if (e >= n_f) e = -1;
-        v[q] = tbox[e < 0 ? 0 : e];
-        vkey[q] = e < 0 ? 0ull : small_key(tinfo[e].y, e);
+        if (lbox != nullptr) {
+            v[q] = lbox[i < count ? i : 0];
+            vkey[q] = i < count ? lkey[i] : 0ull;
+        } else {
+            int e = i < count ? small_share_element(i, part, parts) : -1;
+            if (e >= n_f) e = -1;
+            v[q] = tbox[e < 0 ? 0 : e];
+            vkey[q] = e < 0 ? 0ull : small_key(tinfo[e].y, e);
+        }
         dead[q] = 0ull;
     }
     for (int g = wave / sets; g < groups; g += waves_of_set)
@@ -146,8 +150,9 @@ __device__ __forceinline__ void small_victim_lanes(const float4 *tbox, const uin
 // workgroup's victims are the slots i < m0 of its share (small_share_element).
 template <int PAIR>
 __device__ __forceinline__ void small_stages(const float4 *tbox, const uint2 *tinfo, const float4 *pbox, const uint4 *pinfo,
-                                             unsigned long long *dead1, unsigned long long *dead2, int *list, int *wcount,
-                                             int n_f, int part, int parts, float theta, float y_one, uint8_t *keep_f)
+                                             unsigned long long *dead1, unsigned long long *dead2, float4 *lbox,
+                                             unsigned long long *lkey, int n_f, int part, int parts, float theta, float y_one,
+                                             uint8_t *keep_f)
 {
     const int tid = (int)threadIdx.x;
     const int lane = tid & 63;
@@ -158,30 +163,36 @@ __device__ __forceinline__ void small_stages(const float4 *tbox, const uint2 *ti
     // ---- stage 1: four victims per lane where the share has three tiles or more (a broadcast of an outranking
     // box then serves four rows), two otherwise (fewer idle lanes)
     if ((m0 + kTile - 1) / kTile > 2)
-        small_victim_lanes<PAIR, true, 4>(tbox, tinfo, pbox, pinfo, kSmallFirst, nullptr, m0, n_f, part, parts, dead1, theta, y_one);
+        small_victim_lanes<PAIR, true, 4>(tbox, tinfo, pbox, pinfo, kSmallFirst, nullptr, nullptr, m0, n_f, part, parts, dead1, theta, y_one);
     else
-        small_victim_lanes<PAIR, true, 2>(tbox, tinfo, pbox, pinfo, kSmallFirst, nullptr, m0, n_f, part, parts, dead1, theta, y_one);
+        small_victim_lanes<PAIR, true, 2>(tbox, tinfo, pbox, pinfo, kSmallFirst, nullptr, nullptr, m0, n_f, part, parts, dead1, theta, y_one);
     __syncthreads();
 
-    // ---- pack: victims with an eliminator are written out, the others listed
-    int e_mine = 0;
+    // ---- pack: victims with an eliminator are written out, the others listed (box and key), in slot order.  How many
+    // each of the share's tiles lists follows from dead1[], which every wavefront sums up for itself (lane t: tile t; a
+    // DPP prefix sum inside rows of sixteen lanes) -- no exchange of counts, no barrier for it.
+    const int t_lane = lane & 15;
+    int in_tile = n_f - (t_lane * parts + part) * kTile;  // victims in tile t_lane of the share
+    in_tile = t_lane * kTile < m0 ? (in_tile < 0 ? 0 : (in_tile > kTile ? kTile : in_tile)) : 0;
+    const unsigned long long there = in_tile >= kTile ? ~0ull : (1ull << in_tile) - 1ull;
+    const int sums = (int)row16_inclusive_sum((unsigned)__popcll(there & ~dead1[t_lane]));
+    const int listed = __builtin_amdgcn_readlane(sums, 15);
+    const int before = wave == 0 ? 0 : __builtin_amdgcn_readlane(sums, wave - 1);
     bool alive = false;
+    int e_mine = 0;
     if (tid < m0 && small_share_element(tid, part, parts) < n_f) {
         e_mine = small_share_element(tid, part, parts);
-        if (((dead1[tid / kTile] >> (tid % kTile)) & 1ull) != 0ull)
+        if (((dead1[wave] >> lane) & 1ull) != 0ull)
             keep_f[e_mine] = 0;
         else
             alive = true;
     }
     const unsigned long long alive_mask = __ballot(alive);
-    if (lane == 0) wcount[wave] = (int)__popcll(alive_mask);
-    __syncthreads();
-    // the sixteen counts summed by every wavefront for itself (a DPP prefix sum inside rows of sixteen lanes)
-    const int sums = (int)row16_inclusive_sum((unsigned)wcount[lane & 15]);
-    const int listed = __builtin_amdgcn_readlane(sums, 15);
-    const int before = wave == 0 ? 0 : __builtin_amdgcn_readlane(sums, wave - 1);
-    if (alive)
-        list[before + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(alive_mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)alive_mask, 0u))] = e_mine;
+    if (alive) {
+        const int pos = before + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(alive_mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)alive_mask, 0u));
+        lbox[pos] = tbox[e_mine];
+        lkey[pos] = small_key(tinfo[e_mine].y, e_mine);
+    }
     __syncthreads();
 
     // ---- stage 2: the listed victims against the whole frame
@@ -209,19 +220,14 @@ __device__ __forceinline__ void small_stages(const float4 *tbox, const uint2 *ti
             }
 #pragma unroll 1
             for (int batch = wave / groups2; batch < batches; batch += waves_of_group) {
-                int at[4], e[4];
+                int at[4];
                 float4 v[4];
                 unsigned long long vkey[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     at[u] = 4 * batch + u < listed ? 4 * batch + u : listed - 1;
-                    e[u] = list[at[u]];
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    e[u] = __builtin_amdgcn_readfirstlane(e[u]);
-                    v[u] = tbox[e[u]];
-                    vkey[u] = small_key((unsigned)__builtin_amdgcn_readfirstlane((int)tinfo[e[u]].y), e[u]);
+                    v[u] = lbox[at[u]];
+                    vkey[u] = lkey[at[u]];
                 }
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
@@ -235,15 +241,15 @@ __device__ __forceinline__ void small_stages(const float4 *tbox, const uint2 *ti
         }
     }
     if (listed > kSmallShort)
-        small_victim_lanes<PAIR, false, 4>(tbox, tinfo, tbox, nullptr, tiles_f * kTile, list, listed, n_f, 0, 1, dead2, theta, y_one);
+        small_victim_lanes<PAIR, false, 4>(tbox, tinfo, tbox, nullptr, tiles_f * kTile, lbox, lkey, listed, n_f, 0, 1, dead2, theta, y_one);
     __syncthreads();
-    for (int k = tid; k < listed; k += kSmallThreads) keep_f[list[k]] = ((dead2[k / kTile] >> (k % kTile)) & 1ull) != 0ull ? 0 : 1;
+    for (int k = tid; k < listed; k += kSmallThreads) keep_f[(unsigned)lkey[k]] = ((dead2[k / kTile] >> (k % kTile)) & 1ull) != 0ull ? 0 : 1;
 }
 
 // n_max <= kSmallThreads.  FAST: the threshold has a division-free form (NmsThetaConst).
 // Grid: frames * parts workgroups of kSmallThreads threads.
 template <bool FAST>
-__global__ void __launch_bounds__(kSmallThreads)
+__global__ void __launch_bounds__(kSmallThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
 small_frames_kernel(const float *__restrict__ boxes, const float *__restrict__ scores, const int32_t *__restrict__ counts,
                     int n_max, int parts, NmsThetaConst th, uint8_t *__restrict__ keep_out)
 {
@@ -257,8 +263,10 @@ small_frames_kernel(const float *__restrict__ boxes, const float *__restrict__ s
     __shared__ uint4 pinfo[kForms][kSmallFirst];
     __shared__ unsigned long long dead1[P / kTile];
     __shared__ unsigned long long dead2[P / kTile];
-    __shared__ int list[P];
-    __shared__ int wcount[kSmallWaves];
+    // the victims listed for the second stage (box and key) take the place of the tables in the form that is not
+    // used; with a single form they have room of their own
+    __shared__ float4 lbox_own[FAST ? 1 : P];
+    __shared__ unsigned long long lkey_own[FAST ? 1 : P];
     __shared__ int wodd[kSmallWaves];
     const int f = blockIdx.x / parts;
     const int part = blockIdx.x % parts;
@@ -324,12 +332,15 @@ small_frames_kernel(const float *__restrict__ boxes, const float *__restrict__ s
     float y_one;  // NMS_YSCALE in a vector register (opaque to the compiler so it stays there)
     asm volatile("v_mov_b32 %0, 0x38800000" : "=v"(y_one));
     if (!FAST)
-        small_stages<kPairExact>(tbox[0], tinfo[0], pbox[0], pinfo[0], dead1, dead2, list, wcount, n_f, part, parts, th.theta, y_one, keep_f);
+        small_stages<kPairExact>(tbox[0], tinfo[0], pbox[0], pinfo[0], dead1, dead2, lbox_own, lkey_own, n_f, part, parts, th.theta, y_one,
+                                 keep_f);
     else if (scaled)
-        small_stages<kPairFastYScaled>(tbox[kForms - 1], tinfo[kForms - 1], pbox[kForms - 1], pinfo[kForms - 1], dead1, dead2, list, wcount,
+        small_stages<kPairFastYScaled>(tbox[kForms - 1], tinfo[kForms - 1], pbox[kForms - 1], pinfo[kForms - 1], dead1, dead2, tbox[0],
+                                       reinterpret_cast<unsigned long long *>(tinfo[0]),
                                        n_f, part, parts, th.theta, y_one, keep_f);
     else
-        small_stages<kPairFast>(tbox[0], tinfo[0], pbox[0], pinfo[0], dead1, dead2, list, wcount, n_f, part, parts, th.theta, y_one, keep_f);
+        small_stages<kPairFast>(tbox[0], tinfo[0], pbox[0], pinfo[0], dead1, dead2, tbox[kForms - 1],
+                                reinterpret_cast<unsigned long long *>(tinfo[kForms - 1]), n_f, part, parts, th.theta, y_one, keep_f);
     if (part == 0)
         for (int i = n_f + tid; i < n_max; i += kSmallThreads) keep_f[i] = 0;
 }

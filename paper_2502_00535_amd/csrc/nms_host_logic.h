@@ -93,7 +93,7 @@ constexpr int kNmsRouteDirect = 0;     // one launch, full n x n pair set with t
 constexpr int kNmsRouteAllPairs = 1;   // rank, then every pair of the ranked triangle
 constexpr int kNmsRouteTwoLaunch = 2;  // rank, every victim against the best 2048 ranks, then the live victims only
 constexpr int kNmsRouteEarlyExit = 3;  // rank, then stages that drop a victim once it has an eliminator
-constexpr int kNmsRouteSmallFrames = 4;  // frames of at most 1024 boxes: rank and two such stages in one launch
+constexpr int kNmsRouteSmallFrames = 4;  // frames of at most 1024 boxes: two such stages in one launch, no sort
 
 // Frames small enough that launch latency, not arithmetic, decides: one launch of the
 // direct form instead of rank + map.  (Twice the pairs and two more compares per pair:
@@ -131,26 +131,36 @@ NMS_HD bool nms_use_early_exit(int n_max, int frames, int sort_chunk)
     return n_max > sort_chunk ? slots >= (1ll << 31) : (n_max >= 1024 && slots >= (1ll << 29));
 }
 
-// Frames of 257 to 1024 boxes beyond the direct form's sizes: one launch that ranks the frame in LDS,
-// tests every victim against the best 128 ranks and the victims still alive against the rest
-// (clustered detections, whole call against the all-pairs route: 64 x 1024 16.5 us against 20.3,
-// 256 x 1024 31.7 against 42.4, 256 x 512 16.4 against 19.6).  Its workgroups are 1024 threads whatever
-// the frame size, which stops paying on large batches: from 2^29 pair slots on for frames beyond 512
-// boxes (512 x 1024: 56.9 us, the early-exit kernels 56.6), from 2^27 on for smaller ones (1024 x 512:
-// 58.5 against 49.2 for all pairs), and frames of at most 256 boxes never take it (1024 x 256: 41.5
-// against 24.0).
+// Frames of 513 to 1024 boxes beyond the direct form's sizes: one launch without a sort, in which a
+// workgroup of 1024 threads tests every victim of its frame against the two best-ranked of every
+// sixteen input elements and the victims still alive against the whole frame (clustered detections,
+// whole call: 64 x 1024 11.8 us, all pairs 20.8; 256 x 1024 28.4, early exit 34.5, all pairs 43.2;
+// 2048 x 1024 155, early exit 197; 128 x 640 17.6, all pairs 20.3).  Its workgroups are 1024 threads
+// and its tables 1024 rows whatever the frame size, so short frames gain nothing (256 x 512: 19.3
+// against 20.4; 192 x 576: 26.0 against 21.7), and between 256 and 512 frames the workgroups beyond
+// one per compute unit share a compute unit with another (300 x 768: 40.8 against 37.7; 300 x 1024:
+// 45.0 against 47.9).  In tiles of 64 boxes per frame:
 NMS_HD bool nms_use_small_frames(int n_max, int frames)
 {
-    const long long slots = (long long)frames * n_max * n_max;
-    return n_max > 256 && n_max <= 1024 && !nms_use_direct_form(n_max, frames) && slots < (n_max > 512 ? (1ll << 29) : (1ll << 27));
+    if (n_max > 1024 || nms_use_direct_form(n_max, frames)) return false;
+    const int tiles = (n_max + 63) / 64;
+    if (frames <= 128) return tiles >= 9;
+    if (frames <= 256) return tiles >= 11;
+    if (frames < 512) return tiles >= 15;
+    return tiles >= 11;
 }
 
-// Workgroups that share a frame there (each ranks the whole frame and takes every parts-th victim):
-// doubled while that leaves at most one workgroup per compute unit (256), up to 16.
-NMS_HD int nms_small_frames_parts(int frames)
+// Workgroups that share a frame there (each builds the tables of the whole frame and takes every
+// parts-th tile of victims): doubled while that leaves at most one workgroup per compute unit (256),
+// and once more -- two workgroups fit a compute unit -- as long as a share keeps four tiles of
+// victims (measured: 256 x 1024 31.6 -> 28.4 us, 256 x 768 36.3 -> 26.5; with two-tile shares,
+// 64 x 1024 12.4 -> 13.9); up to 16.
+NMS_HD int nms_small_frames_parts(int frames, int n_max)
 {
     int parts = 1;
     while (parts < 16 && (long long)frames * parts * 2 <= 256) parts *= 2;
+    const int tiles = (n_max + 63) / 64;
+    while (parts < 16 && (long long)frames * parts * 2 <= 512 && tiles / (parts * 2) >= 4) parts *= 2;
     return parts;
 }
 

@@ -367,7 +367,7 @@ static int fused_launch(const RunWorkspace &w, const int32_t *counts, int n_max,
 static int small_frames_launch(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
                                const NmsThetaConst &th, uint8_t *keep_out, hipStream_t stream)
 {
-    const int parts = nms_small_frames_parts(frames);
+    const int parts = nms_small_frames_parts(frames, n_max);
     const dim3 grid((unsigned)(frames * parts)), block(kSmallThreads);
     begin_launch();
     if (th.fast)

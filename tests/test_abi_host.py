@@ -73,9 +73,11 @@ def test_route_by_size():
     S = nms.NMS_ROUTE_SMALL_FRAMES
     shapes = {(256, 1): D, (4096, 1): D, (1024, 64): S, (16384, 1): T, (4096, 256): E,
               (1024, 24): D, (1024, 25): S, (4096, 3): D, (4096, 4): A,
-              (1024, 511): S, (1024, 512): E, (1025, 511): A, (1025, 512): E, (1023, 513): S, (1023, 514): A,
-              (512, 128): D, (512, 129): S, (512, 511): S, (512, 512): A, (513, 95): D, (513, 96): S, (513, 2040): S, (513, 2041): A,
-              (256, 512): D, (256, 513): A, (257, 508): D, (257, 509): S, (257, 2032): S, (257, 2033): A, (100, 60000): A,
+              (1024, 511): S, (1024, 512): S, (1024, 60000): S, (1025, 511): A, (1025, 512): E, (1023, 513): S,
+              (512, 128): D, (512, 129): A, (512, 512): A, (513, 95): D, (513, 96): S, (513, 128): S, (513, 129): A, (513, 2040): A,
+              (640, 128): S, (640, 256): A, (641, 129): S, (641, 256): S, (641, 257): A, (896, 256): S, (896, 257): A, (896, 511): A,
+              (897, 257): S, (897, 511): S, (640, 512): A, (641, 512): S, (704, 5000): S,
+              (256, 512): D, (256, 513): A, (257, 508): D, (257, 509): A, (100, 60000): A,
               (4096, 31): A, (4096, 32): E,
               (4097, 1): A, (11585, 1): A, (11586, 1): T, (16384, 7): T, (16384, 8): E, (46340, 1): T, (46341, 1): E,
               (65536, 1): E, (8192, 2): T, (8192, 1): A}

@@ -74,11 +74,10 @@ def test_workgroups_per_frame(nms, oracle, frames):
     assert 0 < want.sum() < want.size
 
 
-@pytest.mark.parametrize("n", [257, 300, 319, 320, 321, 383, 384, 385, 511, 512, 513, 640, 767, 768, 769, 895, 896, 897, 960, 1000, 1023, 1024])
+@pytest.mark.parametrize("n", [513, 514, 575, 576, 577, 600, 639, 640, 641, 703, 704, 705, 767, 768, 769, 831, 895, 896, 897, 959, 960, 961, 1000, 1023, 1024])
 def test_frame_lengths(nms, oracle, n):
     print(f"case n={n}", flush=True)
-    limit = (1 << 25) if n <= 512 else (3 << 23)   # the direct form takes batches up to this many pair slots
-    F = max(40, limit // (n * n) + 2)
+    F = max(40, (3 << 23) // (n * n) + 2)   # the direct form takes batches up to 3 * 2^23 pair slots
     boxes, scores = batch(5000 + n, F, n, extent=700, max_side=100, integer=(n % 2 == 1), score_levels=max(3, n // 3))
     want = check(nms, oracle, boxes, scores, [0.5, 0.3, 0.45][n % 3])
     assert 0 < want.sum() < want.size
@@ -93,8 +92,8 @@ def test_ragged_batches(nms, oracle):
     check(nms, oracle, boxes[:, :600], scores[:, :600], 0.3, np.minimum(counts, 600).astype(np.int32)[:F])
     # 300 frames (one workgroup per frame), random counts
     F = 300
-    boxes, scores = batch(99, F, 512, extent=500, max_side=90, integer=False, score_levels=0)
-    check(nms, oracle, boxes, scores, 0.4, np.random.default_rng(5).integers(0, 513, F).astype(np.int32))
+    boxes, scores = batch(99, F, 1000, extent=700, max_side=90, integer=False, score_levels=0)
+    check(nms, oracle, boxes, scores, 0.4, np.random.default_rng(5).integers(0, 1001, F).astype(np.int32))
 
 
 def test_live_victim_counts(nms, oracle):
@@ -159,7 +158,7 @@ def test_extremes(nms, oracle):
 
 def test_clustered_detections(nms, oracle):
     """The workload the route is for: clusters of candidates around objects, 64 and 200 frames."""
-    for F, n in ((64, 1024), (200, 768), (260, 400)):
+    for F, n in ((64, 1024), (200, 768), (260, 960), (600, 704)):
         fr = [clustered_frame(900 + f, objects=n // 16, width=1920, height=1080, size_lo=32.0, size_hi=256.0) for f in range(F)]
         boxes = np.stack([x[0][:n] for x in fr])
         scores = np.stack([x[1][:n] for x in fr])
@@ -242,13 +241,13 @@ def test_equal_scores(nms, oracle):
     assert 0 < want.sum() < want.size
 
 
-@pytest.mark.parametrize("frames", [70, 130])
+@pytest.mark.parametrize("frames", [130, 260])
 def test_long_lists(nms, oracle, frames):
-    """Two and one workgroups per frame: disjoint boxes of which a chosen number repeat the best-ranked one, so that
-    a workgroup lists 0 .. all of its 512 or 1024 victims for the second stage -- around 256, where the second stage
-    changes its form -- and some of the listed fall to boxes that the first stage does not hold."""
+    """Two workgroups per frame (130 frames) and one (260): disjoint boxes of which a chosen number repeat the
+    best-ranked one, so that a workgroup lists 0 .. all of its 512 or 1024 victims for the second stage -- around 256,
+    where the second stage changes its form -- and some of the listed fall to boxes that the first stage does not hold."""
     n = 1024
-    share = n // (2 if frames <= 128 else 1)
+    share = n // (2 if frames <= 256 else 1)
     per_group = [0, 1, 100, 254, 255, 256, 257, 258, 300, 319, 320, 321, 400, 511, 512, 513, 640, 767, 768, 769, 1000, 1022, 1023, 1024]
     scores = np.tile((1.0 - np.arange(n) / n).astype(np.float32), (frames, 1))
     base = lattice(n)
