@@ -142,10 +142,11 @@ int nms_reduce_batched(const uint64_t *mask, const int32_t *order, const int32_t
  * into the pair tests, and the result is the same keep vector as steps 1-3 give.
  * The call picks its route by size (nms_route() names it); every route returns the same bits:
  *   NMS_ROUTE_DIRECT      small work (up to about 2^25 pair slots = frames * n_max^2): one launch.
- *   NMS_ROUTE_SMALL_FRAMES  frames of 257 to 1024 boxes beyond that, up to 2^29 pair slots (2^27
- *                         for frames of at most 512 boxes): one launch that ranks a frame in LDS,
- *                         tests every victim against the best 128 ranks and the victims still
- *                         alive against the rest.
+ *   NMS_ROUTE_SMALL_FRAMES  batches of ten or more frames of 513 to 1024 boxes (which batch sizes
+ *                         depends on the frame length; nms_route() tells): one launch without a
+ *                         sort, every victim against the two best-ranked of every sixteen input
+ *                         boxes, then the victims still alive against the whole frame; rank order
+ *                         enters as a compare of the two boxes' (score, index) keys.
  *   NMS_ROUTE_ALL_PAIRS   rank step, then every pair test of the ranked triangle.
  *   NMS_ROUTE_TWO_LAUNCH  frames beyond NMS_SORT_CHUNK boxes, 2^27 <= pair slots < 2^31: rank step,
  *                         every victim against the best 2048 ranks, then only the victims still

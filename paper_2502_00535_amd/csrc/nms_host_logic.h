@@ -131,7 +131,7 @@ NMS_HD bool nms_use_early_exit(int n_max, int frames, int sort_chunk)
     return n_max > sort_chunk ? slots >= (1ll << 31) : (n_max >= 1024 && slots >= (1ll << 29));
 }
 
-// Frames of 513 to 1024 boxes beyond the direct form's sizes: one launch without a sort, in which a
+// Frames of 513 to 1024 boxes, ten or more of them: one launch without a sort, in which a
 // workgroup of 1024 threads tests every victim of its frame against the two best-ranked of every
 // sixteen input elements and the victims still alive against the whole frame (clustered detections,
 // whole call: 64 x 1024 11.8 us, all pairs 20.8; 256 x 1024 28.4, early exit 34.5, all pairs 43.2;
@@ -142,8 +142,11 @@ NMS_HD bool nms_use_early_exit(int n_max, int frames, int sort_chunk)
 // 45.0 against 47.9).  In tiles of 64 boxes per frame:
 NMS_HD bool nms_use_small_frames(int n_max, int frames)
 {
-    if (n_max > 1024 || nms_use_direct_form(n_max, frames)) return false;
+    if (n_max > 1024) return false;
     const int tiles = (n_max + 63) / 64;
+    // against the direct form, where that would be taken (10 to 32 frames: 12 x 1024 7.1 us against 8.5, 24 x 1024 8.2
+    // against 15.4, 32 x 768 8.5 against 9.4; 8 x 1024 7.0 against 6.3, 16 x 768 7.2 against 6.2, 32 x 576 8.8 against 8.0)
+    if (nms_use_direct_form(n_max, frames)) return tiles >= 10 && (long long)frames * n_max * n_max > (5ll << 21);
     if (frames <= 128) return tiles >= 9;
     if (frames <= 256) return tiles >= 11;
     if (frames < 512) return tiles >= 15;
@@ -167,8 +170,8 @@ NMS_HD int nms_small_frames_parts(int frames, int n_max)
 // The route of the automatic whole-path call for a batch shape (1 <= n_max, 1 <= frames).
 NMS_HD int nms_route_for(int n_max, int frames, int sort_chunk)
 {
-    if (nms_use_direct_form(n_max, frames)) return kNmsRouteDirect;
     if (nms_use_small_frames(n_max, frames)) return kNmsRouteSmallFrames;
+    if (nms_use_direct_form(n_max, frames)) return kNmsRouteDirect;
     if (nms_use_early_exit(n_max, frames, sort_chunk)) return kNmsRouteEarlyExit;
     if (nms_use_two_launches(n_max, frames, sort_chunk)) return kNmsRouteTwoLaunch;
     return kNmsRouteAllPairs;

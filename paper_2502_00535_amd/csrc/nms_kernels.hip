@@ -363,7 +363,7 @@ static int fused_launch(const RunWorkspace &w, const int32_t *counts, int n_max,
     return launch_status();
 }
 
-// Frames of at most 1024 boxes: rank step and two stages of pair tests in one launch (kernels/small_frames.h).
+// Frames of at most 1024 boxes: two stages of pair tests in one launch, no sort (kernels/small_frames.h).
 static int small_frames_launch(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
                                const NmsThetaConst &th, uint8_t *keep_out, hipStream_t stream)
 {
@@ -408,7 +408,7 @@ static int staged_launch(const RunWorkspace &w, const int32_t *counts, int n_max
 static int early_exit_launch(const float *boxes, const float *scores, const int32_t *counts, int n_max, int frames,
                              float threshold, uint8_t *keep_out, void *workspace, hipStream_t s);
 
-// kRouteAuto: direct, one launch for small frames, all pairs, two launches or early exit by size (nms_route_for).  kRouteAllPairs: direct or ranked by size
+// kRouteAuto: one launch for small frames, direct, all pairs, two launches or early exit by size (nms_route_for).  kRouteAllPairs: direct or ranked by size
 // (every pair of the ranked triangle is evaluated).
 enum Route { kRouteAuto = 0, kRouteRanked = 1, kRouteDirect = 2, kRouteAllPairs = 3 };
 
@@ -422,14 +422,15 @@ static int run_routed(Route route, const float *boxes, const float *scores, cons
     if (n_max == 0 || frames == 0) return NMS_OK;
     if (!boxes || !scores || !keep_out) return NMS_ERR_INVALID_ARG;
     const bool by_size = route == kRouteAuto || route == kRouteAllPairs;
-    const bool direct = route == kRouteDirect || (by_size && nms_use_direct_form(n_max, frames));
+    const bool small = route == kRouteAuto && nms_use_small_frames(n_max, frames);
+    const bool direct = route == kRouteDirect || (by_size && !small && nms_use_direct_form(n_max, frames));
     if (route != kRouteDirect) {  // the automatic route validates the workspace whichever way it goes
         const size_t need = nms_workspace_bytes(n_max, frames);
         if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)) return NMS_ERR_WORKSPACE;
     }
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (route == kRouteAuto && !direct && nms_use_small_frames(n_max, frames))
+    if (small)
         return small_frames_launch(boxes, scores, counts, n_max, frames, nms_make_theta_const(threshold), keep_out, s);
     if (route == kRouteAuto && !direct && nms_use_early_exit(n_max, frames, kChunk))
         return early_exit_launch(boxes, scores, counts, n_max, frames, threshold, keep_out, workspace, s);

@@ -63,9 +63,9 @@ def batch(seed, F, n, **kw):
     return boxes, scores
 
 
-@pytest.mark.parametrize("frames", [25, 32, 33, 64, 65, 128, 129, 200, 256, 300, 500])
+@pytest.mark.parametrize("frames", [11, 12, 16, 17, 24, 25, 32, 33, 64, 65, 128, 129, 200, 256, 300, 500])
 def test_workgroups_per_frame(nms, oracle, frames):
-    """1024-box frames: 8, 4, 2 and 1 workgroups per frame (frames * parts <= 256) and batches beyond the compute units."""
+    """1024-box frames: 16, 8, 4, 2 and 1 workgroups per frame and batches beyond the compute units."""
     print(f"case frames={frames}", flush=True)
     rng = np.random.default_rng(frames)
     boxes, scores = batch(3000 + 7 * frames, frames, 1024, extent=900, max_side=120, integer=(frames % 2 == 0), score_levels=300)
@@ -268,3 +268,17 @@ def test_long_lists(nms, oracle, frames):
     assert want.sum(1).min() <= 8 and want.sum(1).max() >= n - 8
     perm = np.random.default_rng(3).permutation(n)
     check(nms, oracle, boxes[:, perm], scores[:, perm], 0.5)
+
+
+@pytest.mark.parametrize("frames,n", [(22, 700), (12, 960), (16, 900), (28, 641), (40, 600), (11, 1000)])
+def test_few_short_frames(nms, oracle, frames, n):
+    """More workgroups per frame than the frame has tiles of victims (some workgroups have none), shares of one
+    and two tiles, a last tile that is not full."""
+    print(f"case {frames} x {n}", flush=True)
+    boxes, scores = batch(8000 + n, frames, n, extent=800, max_side=110, integer=(n % 2 == 0), score_levels=n // 2)
+    counts = None
+    if frames % 2 == 0:
+        counts = np.random.default_rng(n).integers(0, n + 1, frames).astype(np.int32)
+        counts[:4] = [n, 0, 1, 65]
+    want = check(nms, oracle, boxes, scores, 0.45, counts)
+    assert 0 < want.sum() < want.size
