@@ -496,7 +496,7 @@ def main():
             del ws_go, keep_go
             route = {0: "direct (one launch)", 1: "all pairs (rank + fused pair-test kernel)",
                      2: "two launches (best 2048 ranks, then the victims still alive)", 3: "early exit",
-                     4: "small frames (rank + two stages of pair tests in one launch)"}[nms.nms_route(wo.n, wo.frames)]
+                     4: "small frames (one launch, no sort: picked boxes, then the victims still alive against the frame)"}[nms.nms_route(wo.n, wo.frames)]
             skips = nms.nms_route(wo.n, wo.frames) >= 2
             ms_pairs = ms_o  # the time in which every pair of the ranked triangle is evaluated
             if skips:

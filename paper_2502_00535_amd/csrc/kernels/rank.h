@@ -291,70 +291,6 @@ __device__ __forceinline__ void radix_rank_large(unsigned (&key)[4], unsigned (&
     }
 }
 
-// The same sort with ONE element per thread (element e = thread e), for kernels whose workgroup is
-// wider than a quarter of the elements anyway: a single table of lane masks per wavefront and a
-// single round, the rest as in radix_rank_large (three barriers per pass).
-// match: W x 256 lane masks; hist, wbase: W x 256 counters each; tot: 256.  After the last pass
-// `buf` holds ((key << 32) | index) in sorted order; ends with a barrier.
-template <int W>
-__device__ __forceinline__ void radix_rank_one(unsigned key, unsigned idx, unsigned long long *buf, unsigned *hist,
-                                               unsigned *tot, unsigned *wbase, unsigned long long *match)
-{
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    unsigned *myhist = hist + wave * 256;
-    unsigned *mybase = wbase + wave * 256;
-    unsigned long long *tab = match + wave * 256;
-    for (int i = lane; i < 256; i += 64) tab[i] = 0ull;
-#pragma unroll 1
-    for (int shift = 0; shift < 32; shift += 8) {
-        reinterpret_cast<uint4 *>(myhist)[lane] = make_uint4(0u, 0u, 0u, 0u);
-        const unsigned d = (key >> shift) & 255u;
-        // (the fences only keep the compiler from reordering: a wavefront's LDS instructions execute in order)
-        __hip_atomic_fetch_or(&tab[d], 1ull << lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        const unsigned long long m = __hip_atomic_load(&tab[d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        const unsigned place = __builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
-        if (place == 0) {
-            __hip_atomic_store(&myhist[d], (unsigned)__popcll(m), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-            __hip_atomic_store(&tab[d], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-        }
-        __syncthreads();
-        if (tid < 256) {
-            unsigned t[W];
-#pragma unroll
-            for (int w = 0; w < W; ++w) t[w] = hist[w * 256 + tid];
-            unsigned run = 0;
-#pragma unroll
-            for (int w = 0; w < W; ++w) {
-                hist[w * 256 + tid] = run;
-                run += t[w];
-            }
-            tot[tid] = run;
-        }
-        __syncthreads();
-        {
-            const uint4 all = reinterpret_cast<const uint4 *>(tot)[lane];
-            const uint4 pre = reinterpret_cast<const uint4 *>(myhist)[lane];
-            const unsigned sum = all.x + all.y + all.z + all.w;
-            const unsigned excl = wave_inclusive_sum(sum) - sum;
-            reinterpret_cast<uint4 *>(mybase)[lane] = make_uint4(excl + pre.x, excl + all.x + pre.y, excl + all.x + all.y + pre.z,
-                                                                 excl + all.x + all.y + all.z + pre.w);
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        const unsigned dest = __hip_atomic_load(&mybase[d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT) + place;
-        buf[dest] = ((unsigned long long)key << 32) | idx;
-        __syncthreads();
-        if (shift < 24) {
-            const unsigned long long v = buf[tid];
-            key = (unsigned)(v >> 32);
-            idx = (unsigned)v;
-        }
-    }
-}
-
 // One workgroup ranks one chunk of up to kChunk boxes of one frame: P = 4 * blockDim.x
 // elements (P a multiple of 256, 256..4096), four per thread, sorted by radix_rank_small or radix_rank_large.
 // With a single chunk the kernel also writes order / sorted5 (and, for the fused path,

@@ -11,9 +11,11 @@
 // that has met one eliminator needs no further test, which on clustered detections is most victims
 // once some well-ranked boxes have been tried:
 //
-//   table     thread e holds box and key of input element e and writes row e (box, y scaled when
-//             every box of the frame allows it; its decision threshold T, or its area for thresholds
-//             that take the literal division; the upper half of its key);
+//   table     thread e holds box and key of input element e and writes row e (the box; its decision
+//             threshold T, or its area for thresholds that take the literal division; the upper
+//             half of its key) -- in both forms, as the box is and with y and T scaled: which one
+//             the frame may use is known once every wavefront has seen its boxes, and writing
+//             both lets one barrier do for the tables and that;
 //   pick      the two best-ranked elements of every row of sixteen lanes (a DPP minimum over the row,
 //             twice) are copied to a second table: kSmallFirst boxes, the best of every stretch of
 //             the input -- any set of boxes would do for the result, a well-ranked one eliminates most;
@@ -23,7 +25,8 @@
 //             the VALU, would set the pace; a box counts for the lanes whose victim is ranked
 //             behind it; the compare's lane mask is the set of victims the box eliminates, ORed up
 //             in a scalar register and merged per victim tile in LDS;
-//   pack      victims with an eliminator are final and written out, the others are listed;
+//   pack      victims with an eliminator are final and written out, the others are listed (box and
+//             key; in the tables of the form that is not used);
 //   stage 2   the listed victims against every box of the frame.  A list of up to kSmallShort
 //             (clustered detections): lane = outranking box, four tiles of the table per wavefront
 //             in registers, the victims read as broadcasts.  A longer list (little was
@@ -32,7 +35,8 @@
 // With fewer frames than compute units a frame is given to `parts` workgroups: each builds the
 // tables of the whole frame and takes the victims of the input's tiles part, part + parts, ...  Each
 // victim's keep byte is written once, by its workgroup.  Same keep vector as the all-pairs routes,
-// bit for bit: a victim is dropped only once an eliminator has been found.
+// bit for bit: a victim is dropped only once an eliminator has been found.  The kernel is held to 64
+// vector registers and half a compute unit's LDS, so that two workgroups fit a compute unit.
 constexpr int kSmallWaves = 16;
 constexpr int kSmallThreads = kSmallWaves * 64;
 constexpr int kSmallPick = 8;                          // boxes a wavefront contributes to the first stage
@@ -249,6 +253,7 @@ __device__ __forceinline__ void small_stages(const float4 *tbox, const uint2 *ti
 // n_max <= kSmallThreads.  FAST: the threshold has a division-free form (NmsThetaConst).
 // Grid: frames * parts workgroups of kSmallThreads threads.
 template <bool FAST>
+// (eight wavefronts per SIMD = two workgroups per compute unit)
 __global__ void __launch_bounds__(kSmallThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
 small_frames_kernel(const float *__restrict__ boxes, const float *__restrict__ scores, const int32_t *__restrict__ counts,
                     int n_max, int parts, NmsThetaConst th, uint8_t *__restrict__ keep_out)

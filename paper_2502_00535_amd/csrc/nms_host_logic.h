@@ -124,7 +124,8 @@ NMS_HD bool nms_use_two_launches(int n_max, int frames, int sort_chunk)
 // detections (what a detector emits) and 0.7 to 1.0 times as fast when almost nothing is
 // eliminated (measured on 32 to 1024 frames of 1024 to 4096 boxes).  Frames of 512 boxes or
 // fewer never gain: their stages are mostly barriers.  Frames beyond sort_chunk boxes take it
-// from 2^31 pair slots on (below that the two launches are quicker).
+// from 2^31 pair slots on (below that the two launches are quicker).  (nms_route_for asks
+// nms_use_small_frames first, which takes the batches of frames of up to 1024 boxes.)
 NMS_HD bool nms_use_early_exit(int n_max, int frames, int sort_chunk)
 {
     const long long slots = (long long)frames * n_max * n_max;
