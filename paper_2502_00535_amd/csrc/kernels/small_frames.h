@@ -149,12 +149,83 @@ __device__ __forceinline__ void small_victim_lanes(const float4 *tbox, const uin
     }
 }
 
+// Lane = outranking box: `count` victim slots (entry i of the list lbox / lkey; without a list, slot i of the
+// workgroup's share, see small_share_element) against the first ctiles tiles of a table.  A wavefront
+// keeps one group of TILES tiles in registers and takes every so-many-th batch of four victims, read as
+// broadcasts, their reads issued together (a slot beyond the count repeats the last one); a victim with
+// an eliminator gets its bit in dead_words[slot / 64].  PICKED: the table of picked boxes, whose rows
+// carry their input index; otherwise the frame's table, where the row number is the index.
+template <int PAIR, bool PICKED, int TILES>
+__device__ __forceinline__ void small_candidate_lanes(const float4 *tbox, const uint2 *tinfo, const float4 *cbox, const uint4 *cinfo,
+                                                      int ctiles, const float4 *lbox, const unsigned long long *lkey, int count,
+                                                      int n_f, int part, int parts, unsigned long long *dead_words, float theta,
+                                                      float y_one)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int groups = (ctiles + TILES - 1) / TILES;
+    const int batches = (count + 3) / 4;
+    if (groups == 0 || batches == 0) return;
+    const int g = wave % groups;
+    if (g >= kSmallWaves) return;
+    const int waves_of_group = (kSmallWaves - g + groups - 1) / groups;
+    const int first_batch = wave / groups;
+    if (first_batch >= batches) return;
+    float4 cb[TILES];
+    float aux[TILES];
+    unsigned long long ckey[TILES];
+#pragma unroll 1
+    for (int t0 = g * TILES; t0 < ctiles; t0 += kSmallWaves * TILES) {  // (more groups than wavefronts: the table of a long frame)
+#pragma unroll
+        for (int j = 0; j < TILES; ++j) {
+            const bool real = t0 + j < ctiles;  // a tile beyond the table's last: a copy of tile t0 that is ranked before nothing
+            const int row = (t0 + (real ? j : 0)) * kTile + lane;
+            cb[j] = cbox[row];
+            if (PICKED) {
+                const uint4 info = cinfo[row];
+                aux[j] = __uint_as_float(info.x);
+                ckey[j] = real ? small_key(info.y, (int)info.z) : ~0ull;
+            } else {
+                const uint2 info = tinfo[row];
+                aux[j] = __uint_as_float(info.x);
+                ckey[j] = real ? small_key(info.y, row) : ~0ull;
+            }
+        }
+#pragma unroll 1
+        for (int batch = first_batch; batch < batches; batch += waves_of_group) {
+            int at[4];
+            float4 v[4];
+            unsigned long long vkey[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                at[u] = 4 * batch + u < count ? 4 * batch + u : count - 1;
+                if (lbox != nullptr) {
+                    v[u] = lbox[at[u]];
+                    vkey[u] = lkey[at[u]];
+                } else {
+                    const int e = small_share_element(at[u], part, parts);
+                    v[u] = tbox[e < n_f ? e : 0];
+                    vkey[u] = e < n_f ? small_key(tinfo[e].y, e) : 0ull;  // no victim in this slot: nothing is ranked before key 0
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                unsigned long long any = 0ull;
+#pragma unroll
+                for (int j = 0; j < TILES; ++j)
+                    any |= __ballot(small_hit<PAIR>(v[u], cb[j], aux[j], theta, y_one)) & __ballot(ckey[j] < vkey[u]);
+                if (lane == 0 && any != 0ull) atomicOr(&dead_words[at[u] / kTile], 1ull << (at[u] % kTile));
+            }
+        }
+    }
+}
+
 // The stages of one workgroup.  tbox / tinfo: the frame in input order (info = decision value, upper
 // key half); pbox / pinfo: the picked boxes (info = decision value, upper key half, input index).  The
 // workgroup's victims are the slots i < m0 of its share (small_share_element).
-template <int PAIR>
+template <int PAIR, int PICK_TILES>
 __device__ __forceinline__ void small_stages(const float4 *tbox, const uint2 *tinfo, const float4 *pbox, const uint4 *pinfo,
-                                             unsigned long long *dead1, unsigned long long *dead2, float4 *lbox,
+                                             int picked_rows, unsigned long long *dead1, unsigned long long *dead2, float4 *lbox,
                                              unsigned long long *lkey, int n_f, int part, int parts, float theta, float y_one,
                                              uint8_t *keep_f)
 {
@@ -164,12 +235,15 @@ __device__ __forceinline__ void small_stages(const float4 *tbox, const uint2 *ti
     const int tiles_f = (n_f + kTile - 1) / kTile;
     const int m0 = tiles_f > part ? (tiles_f - part + parts - 1) / parts * kTile : 0;  // victim slots of the share
 
-    // ---- stage 1: four victims per lane where the share has three tiles or more (a broadcast of an outranking
-    // box then serves four rows), two otherwise (fewer idle lanes)
-    if ((m0 + kTile - 1) / kTile > 2)
-        small_victim_lanes<PAIR, true, 4>(tbox, tinfo, pbox, pinfo, kSmallFirst, nullptr, nullptr, m0, n_f, part, parts, dead1, theta, y_one);
+    // ---- stage 1: lane = victim, four victims per lane, where the share has three tiles or more (a broadcast of an
+    // outranking box then serves four rows), two per lane for two tiles; lane = outranking box for a single tile
+    if (m0 / kTile > 2)
+        small_victim_lanes<PAIR, true, 4>(tbox, tinfo, pbox, pinfo, picked_rows, nullptr, nullptr, m0, n_f, part, parts, dead1, theta, y_one);
+    else if (m0 / kTile == 2 && PICK_TILES == 2)
+        small_victim_lanes<PAIR, true, 2>(tbox, tinfo, pbox, pinfo, picked_rows, nullptr, nullptr, m0, n_f, part, parts, dead1, theta, y_one);
     else
-        small_victim_lanes<PAIR, true, 2>(tbox, tinfo, pbox, pinfo, kSmallFirst, nullptr, nullptr, m0, n_f, part, parts, dead1, theta, y_one);
+        small_candidate_lanes<PAIR, true, PICK_TILES>(tbox, tinfo, pbox, pinfo, picked_rows / kTile, nullptr, nullptr, m0, n_f, part, parts, dead1,
+                                             theta, y_one);
     __syncthreads();
 
     // ---- pack: victims with an eliminator are written out, the others listed (box and key), in slot order.  How many
@@ -200,78 +274,38 @@ __device__ __forceinline__ void small_stages(const float4 *tbox, const uint2 *ti
     __syncthreads();
 
     // ---- stage 2: the listed victims against the whole frame
-    if (listed > 0 && listed <= kSmallShort) {
-        // lane = outranking box: a wavefront keeps one group of four tiles in registers and takes every
-        // so-many-th batch of four listed victims, their reads issued together (a short last batch
-        // repeats its last victim)
-        const int groups2 = (tiles_f + kSmallTiles - 1) / kSmallTiles;  // 1 .. 4
-        const int g = wave % groups2;
-        const int waves_of_group = (kSmallWaves - g + groups2 - 1) / groups2;
-        const int batches = (listed + 3) / 4;
-        if (wave / groups2 < batches) {
-            const int t0 = g * kSmallTiles;
-            float4 cb[kSmallTiles];
-            float aux[kSmallTiles];
-            unsigned long long ckey[kSmallTiles];
-#pragma unroll
-            for (int j = 0; j < kSmallTiles; ++j) {
-                const bool real = t0 + j < tiles_f;  // a tile beyond the frame's last: a copy of tile t0 that is ranked before nothing
-                const int row = (t0 + (real ? j : 0)) * kTile + lane;
-                cb[j] = tbox[row];
-                const uint2 info = tinfo[row];
-                aux[j] = __uint_as_float(info.x);
-                ckey[j] = real ? small_key(info.y, row) : ~0ull;
-            }
-#pragma unroll 1
-            for (int batch = wave / groups2; batch < batches; batch += waves_of_group) {
-                int at[4];
-                float4 v[4];
-                unsigned long long vkey[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    at[u] = 4 * batch + u < listed ? 4 * batch + u : listed - 1;
-                    v[u] = lbox[at[u]];
-                    vkey[u] = lkey[at[u]];
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    unsigned long long any = 0ull;
-#pragma unroll
-                    for (int j = 0; j < kSmallTiles; ++j)
-                        any |= __ballot(small_hit<PAIR>(v[u], cb[j], aux[j], theta, y_one)) & __ballot(ckey[j] < vkey[u]);
-                    if (lane == 0 && any != 0ull) atomicOr(&dead2[at[u] / kTile], 1ull << (at[u] % kTile));
-                }
-            }
-        }
-    }
+    if (listed <= kSmallShort)
+        small_candidate_lanes<PAIR, false, kSmallTiles>(tbox, tinfo, tbox, nullptr, tiles_f, lbox, lkey, listed, n_f, 0, 1, dead2, theta, y_one);
     if (listed > kSmallShort)
         small_victim_lanes<PAIR, false, 4>(tbox, tinfo, tbox, nullptr, tiles_f * kTile, lbox, lkey, listed, n_f, 0, 1, dead2, theta, y_one);
     __syncthreads();
     for (int k = tid; k < listed; k += kSmallThreads) keep_f[(unsigned)lkey[k]] = ((dead2[k / kTile] >> (k % kTile)) & 1ull) != 0ull ? 0 : 1;
 }
 
-// n_max <= kSmallThreads.  FAST: the threshold has a division-free form (NmsThetaConst).
-// Grid: frames * parts workgroups of kSmallThreads threads.
-template <bool FAST>
-// (eight wavefronts per SIMD = two workgroups per compute unit)
-__global__ void __launch_bounds__(kSmallThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
-small_frames_kernel(const float *__restrict__ boxes, const float *__restrict__ scores, const int32_t *__restrict__ counts,
-                    int n_max, int parts, NmsThetaConst th, uint8_t *__restrict__ keep_out)
+// The kernel's body.  E: input elements per thread (frames of at most E * 1024 boxes); register q of
+// thread t holds element 1024 q + t, so a wavefront's register is a tile of 64 neighbours.  FAST: the
+// threshold has a division-free form (NmsThetaConst).
+template <bool FAST, int E>
+__device__ __forceinline__ void small_frames_body(const float *__restrict__ boxes, const float *__restrict__ scores,
+                                                  const int32_t *__restrict__ counts, int n_max, int parts, const NmsThetaConst &th,
+                                                  uint8_t *__restrict__ keep_out)
 {
-    constexpr int P = kSmallThreads;  // rows of the tables: one per thread
-    // every table twice: as the boxes are, and with y (and the decision value) multiplied by NMS_YSCALE -- which of the
-    // two the stages read is known only once every wavefront has seen its boxes, and writing both saves a barrier
-    constexpr int kForms = FAST ? 2 : 1;
+    constexpr int P = kSmallThreads * E;    // rows of the tables
+    constexpr int kPicked = kSmallFirst * E;  // rows of the table of picked boxes
+    // One element per thread: every table twice, as the boxes are and with y (and the decision value) multiplied by
+    // NMS_YSCALE -- which of the two the stages read is known only once every wavefront has seen its boxes, and
+    // writing both saves a barrier; the list of the second stage then takes the place of the form that is not used.
+    // Longer frames have no room for that: the wavefronts exchange their flags first and write one form.
+    constexpr int kForms = (FAST && E == 1) ? 2 : 1;
+    constexpr int kList = kForms == 2 ? 1 : kSmallThreads;  // a workgroup's share is at most 1024 victims
     __shared__ float4 tbox[kForms][P];
     __shared__ uint2 tinfo[kForms][P];
-    __shared__ float4 pbox[kForms][kSmallFirst];
-    __shared__ uint4 pinfo[kForms][kSmallFirst];
-    __shared__ unsigned long long dead1[P / kTile];
-    __shared__ unsigned long long dead2[P / kTile];
-    // the victims listed for the second stage (box and key) take the place of the tables in the form that is not
-    // used; with a single form they have room of their own
-    __shared__ float4 lbox_own[FAST ? 1 : P];
-    __shared__ unsigned long long lkey_own[FAST ? 1 : P];
+    __shared__ float4 pbox[kForms][kPicked];
+    __shared__ uint4 pinfo[kForms][kPicked];
+    __shared__ unsigned long long dead1[kSmallThreads / kTile];
+    __shared__ unsigned long long dead2[kSmallThreads / kTile];
+    __shared__ float4 lbox_own[kList];
+    __shared__ unsigned long long lkey_own[kList];
     __shared__ int wodd[kSmallWaves];
     const int f = blockIdx.x / parts;
     const int part = blockIdx.x % parts;
@@ -283,69 +317,121 @@ small_frames_kernel(const float *__restrict__ boxes, const float *__restrict__ s
     const float4 *boxes_f = reinterpret_cast<const float4 *>(boxes + (size_t)f * n_max * 4);
     uint8_t *keep_f = keep_out + (size_t)f * n_max;
 
-    // thread e holds element e of the input; a slot beyond the frame's count holds the box (0,0,0,0) with the
-    // last of all keys: it is ranked before no box of the frame
-    float4 mine = make_float4(0.f, 0.f, 0.f, 0.f);
-    unsigned upper = ~0u;
-    if (tid < n_f) {
-        mine = boxes_f[tid];
-        upper = (unsigned)(nms_rank_key(scores_f[tid], (unsigned)tid) >> 32);
+    // a slot beyond the frame's count holds the box (0,0,0,0) with the last of all keys: it is ranked before no
+    // box of the frame
+    float4 mine[E];
+    unsigned upper[E];
+#pragma unroll
+    for (int q = 0; q < E; ++q) {
+        const int e = q * kSmallThreads + tid;
+        mine[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        upper[q] = ~0u;
+        if (e < n_f) {
+            mine[q] = boxes_f[e];
+            upper[q] = (unsigned)(nms_rank_key(scores_f[e], (unsigned)e) >> 32);
+        }
     }
     // pick: the two best-ranked elements of every row of sixteen lanes (equal upper key halves: the lower lane first)
-    bool picked = false;
+    bool picked[E];
+    int slot[E];
+    bool odd = false;
 #pragma unroll
-    for (int round = 0; round < kSmallPick / 4; ++round) {
-        const unsigned u = picked ? ~0u : upper;
-        const unsigned best = row16_min(u);
-        const unsigned long long is_best = __ballot(u == best && !picked);
-        const unsigned in_row = (unsigned)(is_best >> (lane & 48)) & 0xffffu;
-        if (u == best && !picked && (in_row & ((1u << (lane & 15)) - 1u)) == 0u) picked = true;
+    for (int q = 0; q < E; ++q) {
+        picked[q] = false;
+#pragma unroll
+        for (int round = 0; round < kSmallPick / 4; ++round) {
+            const unsigned u = picked[q] ? ~0u : upper[q];
+            const unsigned best = row16_min(u);
+            const unsigned long long is_best = __ballot(u == best && !picked[q]);
+            const unsigned in_row = (unsigned)(is_best >> (lane & 48)) & 0xffffu;
+            if (u == best && !picked[q] && (in_row & ((1u << (lane & 15)) - 1u)) == 0u) picked[q] = true;
+        }
+        const unsigned long long picked_mask = __ballot(picked[q]);
+        slot[q] = (q * kSmallWaves + wave) * kSmallPick +
+                  (int)__builtin_amdgcn_mbcnt_hi((unsigned)(picked_mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)picked_mask, 0u));
+        // per frame: does every y allow the scaled form (the box (0,0,0,0) does)
+        odd = odd || !(nms_y_regular(mine[q].y) && nms_y_regular(mine[q].w));
     }
-    const unsigned long long picked_mask = __ballot(picked);
-    const int slot = wave * kSmallPick + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(picked_mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)picked_mask, 0u));
-
-    // what the tables need per box: its decision value (no intersection reaches a padding row's); and per frame: does
-    // every y allow the scaled form (the box (0,0,0,0) does)
-    const bool odd = !(nms_y_regular(mine.y) && nms_y_regular(mine.w));
     const unsigned long long odd_mask = __ballot(odd);
     if (lane == 0) wodd[wave] = odd_mask != 0ull ? 1 : 0;
-    if (tid < P / kTile) {
+    if (tid < kSmallThreads / kTile) {
         dead1[tid] = 0ull;
         dead2[tid] = 0ull;
     }
-    const float area = nms_box_area(mine.x, mine.y, mine.z, mine.w);
-    const float mine_aux = FAST ? (tid < n_f ? nms_pair_threshold(area, th.m) : INFINITY) : area;
-    tbox[0][tid] = mine;
-    tinfo[0][tid] = make_uint2(__float_as_uint(mine_aux), upper);
-    if (picked) {
-        pbox[0][slot] = mine;
-        pinfo[0][slot] = make_uint4(__float_as_uint(mine_aux), upper, (unsigned)tid, 0u);
+    bool scaled = false;
+    if (kForms == 1 && FAST) {
+        __syncthreads();
+        scaled = __ballot(wodd[lane & (kSmallWaves - 1)] != 0) == 0ull;
     }
-    if (FAST) {
-        const float4 mine_s = make_float4(mine.x, mine.y * NMS_YSCALE, mine.z, mine.w * NMS_YSCALE);
-        const float aux_s = mine_aux * NMS_YSCALE;
-        tbox[kForms - 1][tid] = mine_s;
-        tinfo[kForms - 1][tid] = make_uint2(__float_as_uint(aux_s), upper);
-        if (picked) {
-            pbox[kForms - 1][slot] = mine_s;
-            pinfo[kForms - 1][slot] = make_uint4(__float_as_uint(aux_s), upper, (unsigned)tid, 0u);
+    // what the tables need per box: its decision value (no intersection reaches a padding row's)
+#pragma unroll
+    for (int q = 0; q < E; ++q) {
+        const int e = q * kSmallThreads + tid;
+        const float area = nms_box_area(mine[q].x, mine[q].y, mine[q].z, mine[q].w);
+        const float aux = FAST ? (e < n_f ? nms_pair_threshold(area, th.m) : INFINITY) : area;
+        const float y1 = mine[q].y, y2 = mine[q].w;
+        const float4 mine_s = make_float4(mine[q].x, y1 * NMS_YSCALE, mine[q].z, y2 * NMS_YSCALE);
+        const float aux_s = aux * NMS_YSCALE;
+        const bool first_scaled = kForms == 1 && scaled;  // the only form is the scaled one
+        const float4 row = make_float4(mine[q].x, first_scaled ? mine_s.y : y1, mine[q].z, first_scaled ? mine_s.w : y2);
+        const float row_aux = first_scaled ? aux_s : aux;
+        tbox[0][e] = row;
+        tinfo[0][e] = make_uint2(__float_as_uint(row_aux), upper[q]);
+        if (picked[q]) {
+            pbox[0][slot[q]] = row;
+            pinfo[0][slot[q]] = make_uint4(__float_as_uint(row_aux), upper[q], (unsigned)e, 0u);
+        }
+        if (kForms == 2) {
+            tbox[kForms - 1][e] = mine_s;
+            tinfo[kForms - 1][e] = make_uint2(__float_as_uint(aux_s), upper[q]);
+            if (picked[q]) {
+                pbox[kForms - 1][slot[q]] = mine_s;
+                pinfo[kForms - 1][slot[q]] = make_uint4(__float_as_uint(aux_s), upper[q], (unsigned)e, 0u);
+            }
         }
     }
     __syncthreads();
-    const bool scaled = FAST && __ballot(wodd[lane & (kSmallWaves - 1)] != 0) == 0ull;
+    if (kForms == 2) scaled = __ballot(wodd[lane & (kSmallWaves - 1)] != 0) == 0ull;
 
     float y_one;  // NMS_YSCALE in a vector register (opaque to the compiler so it stays there)
     asm volatile("v_mov_b32 %0, 0x38800000" : "=v"(y_one));
+    constexpr int kPickTiles = E == 1 ? 2 : kSmallTiles;  // tiles of picked boxes a wavefront holds when the boxes are the lanes
     if (!FAST)
-        small_stages<kPairExact>(tbox[0], tinfo[0], pbox[0], pinfo[0], dead1, dead2, lbox_own, lkey_own, n_f, part, parts, th.theta, y_one,
-                                 keep_f);
+        small_stages<kPairExact, kPickTiles>(tbox[0], tinfo[0], pbox[0], pinfo[0], kPicked, dead1, dead2, lbox_own, lkey_own, n_f, part,
+                                             parts, th.theta, y_one, keep_f);
+    else if (kForms == 1 && scaled)
+        small_stages<kPairFastYScaled, kPickTiles>(tbox[0], tinfo[0], pbox[0], pinfo[0], kPicked, dead1, dead2, lbox_own, lkey_own, n_f,
+                                                   part, parts, th.theta, y_one, keep_f);
+    else if (kForms == 1)
+        small_stages<kPairFast, kPickTiles>(tbox[0], tinfo[0], pbox[0], pinfo[0], kPicked, dead1, dead2, lbox_own, lkey_own, n_f, part,
+                                            parts, th.theta, y_one, keep_f);
     else if (scaled)
-        small_stages<kPairFastYScaled>(tbox[kForms - 1], tinfo[kForms - 1], pbox[kForms - 1], pinfo[kForms - 1], dead1, dead2, tbox[0],
-                                       reinterpret_cast<unsigned long long *>(tinfo[0]),
-                                       n_f, part, parts, th.theta, y_one, keep_f);
+        small_stages<kPairFastYScaled, kPickTiles>(tbox[kForms - 1], tinfo[kForms - 1], pbox[kForms - 1], pinfo[kForms - 1], kPicked,
+                                                   dead1, dead2, tbox[0], reinterpret_cast<unsigned long long *>(tinfo[0]), n_f, part,
+                                                   parts, th.theta, y_one, keep_f);
     else
-        small_stages<kPairFast>(tbox[0], tinfo[0], pbox[0], pinfo[0], dead1, dead2, tbox[kForms - 1],
-                                reinterpret_cast<unsigned long long *>(tinfo[kForms - 1]), n_f, part, parts, th.theta, y_one, keep_f);
+        small_stages<kPairFast, kPickTiles>(tbox[0], tinfo[0], pbox[0], pinfo[0], kPicked, dead1, dead2, tbox[kForms - 1],
+                                            reinterpret_cast<unsigned long long *>(tinfo[kForms - 1]), n_f, part, parts, th.theta,
+                                            y_one, keep_f);
     if (part == 0)
         for (int i = n_f + tid; i < n_max; i += kSmallThreads) keep_f[i] = 0;
+}
+
+// Frames of at most 1024 boxes.  Grid: frames * parts workgroups of kSmallThreads threads.  Held to
+// eight wavefronts per SIMD: two workgroups per compute unit.
+template <bool FAST>
+__global__ void __launch_bounds__(kSmallThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
+small_frames_kernel(const float *__restrict__ boxes, const float *__restrict__ scores, const int32_t *__restrict__ counts,
+                    int n_max, int parts, NmsThetaConst th, uint8_t *__restrict__ keep_out)
+{
+    small_frames_body<FAST, 1>(boxes, scores, counts, n_max, parts, th, keep_out);
+}
+
+// Frames of at most 1024 E boxes, E = 2 or 4; a workgroup's share is at most 1024 victims (parts >= tiles / 16).
+template <bool FAST, int E>
+__global__ void __launch_bounds__(kSmallThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))
+mid_frames_kernel(const float *__restrict__ boxes, const float *__restrict__ scores, const int32_t *__restrict__ counts,
+                  int n_max, int parts, NmsThetaConst th, uint8_t *__restrict__ keep_out)
+{
+    small_frames_body<FAST, E>(boxes, scores, counts, n_max, parts, th, keep_out);
 }

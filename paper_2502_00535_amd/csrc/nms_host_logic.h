@@ -93,7 +93,7 @@ constexpr int kNmsRouteDirect = 0;     // one launch, full n x n pair set with t
 constexpr int kNmsRouteAllPairs = 1;   // rank, then every pair of the ranked triangle
 constexpr int kNmsRouteTwoLaunch = 2;  // rank, every victim against the best 2048 ranks, then the live victims only
 constexpr int kNmsRouteEarlyExit = 3;  // rank, then stages that drop a victim once it has an eliminator
-constexpr int kNmsRouteSmallFrames = 4;  // frames of at most 1024 boxes: two such stages in one launch, no sort
+constexpr int kNmsRouteSmallFrames = 4;  // frames of at most 1024 boxes, or a few of up to 4096: two such stages in one launch, no sort
 
 // Frames small enough that launch latency, not arithmetic, decides: one launch of the
 // direct form instead of rank + map.  (Twice the pairs and two more compares per pair:
@@ -123,16 +123,39 @@ NMS_HD bool nms_use_two_launches(int n_max, int frames, int sort_chunk)
 // once it has an eliminator returns the same keep vector 1.3 to 3.3 times sooner on clustered
 // detections (what a detector emits) and 0.7 to 1.0 times as fast when almost nothing is
 // eliminated (measured on 32 to 1024 frames of 1024 to 4096 boxes).  Frames of 512 boxes or
-// fewer never gain: their stages are mostly barriers.  Frames beyond sort_chunk boxes take it
-// from 2^31 pair slots on (below that the two launches are quicker).  (nms_route_for asks
-// nms_use_small_frames first, which takes the batches of frames of up to 1024 boxes.)
+// fewer never gain: their stages are mostly barriers.  From 2^28 pair slots on (64 x 2048: 40 us
+// against 43 for all pairs; 64 x 1536, below: 38 against 33).  Frames beyond sort_chunk boxes take
+// it from 2^31 pair slots on (below that the two launches are quicker).  (nms_route_for asks
+// nms_use_small_frames first, which takes the batches of frames of up to 1024 boxes and small
+// batches of longer ones.)
 NMS_HD bool nms_use_early_exit(int n_max, int frames, int sort_chunk)
 {
     const long long slots = (long long)frames * n_max * n_max;
-    return n_max > sort_chunk ? slots >= (1ll << 31) : (n_max >= 1024 && slots >= (1ll << 29));
+    return n_max > sort_chunk ? slots >= (1ll << 31) : (n_max > 1024 && slots >= (1ll << 28));
 }
 
-// Frames of 513 to 1024 boxes, ten or more of them: one launch without a sort, in which a
+// Workgroups that share a frame in the small-frames kernels (each builds the tables of the whole
+// frame and takes every parts-th tile of victims; a share is at most 16 tiles, and more workgroups
+// than tiles would only build tables).  Frames of up to 1024 boxes: doubled while that leaves at most
+// one workgroup per compute unit (256), and once more -- two workgroups fit a compute unit -- as
+// long as a share keeps four tiles of victims (measured: 256 x 1024 31.6 -> 28.4 us, 256 x 768
+// 36.3 -> 26.5; with two-tile shares, 64 x 1024 12.4 -> 13.9).  Longer frames: one workgroup per
+// compute unit (their tables fill its LDS), as many as that allows.
+NMS_HD int nms_small_frames_parts(int frames, int n_max)
+{
+    const int tiles = (n_max + 63) / 64;
+    const int most = tiles < 64 ? tiles : 64;  // a workgroup without a tile of victims would only build tables
+    int parts = (tiles + 15) / 16;
+    if (n_max > 1024) {
+        const int fit = 256 / (frames < 256 ? frames : 256);
+        return fit > most ? most : (fit < parts ? parts : fit);
+    }
+    while (parts * 2 <= most && (long long)frames * parts * 2 <= 256) parts *= 2;
+    while (parts * 2 <= most && (long long)frames * parts * 2 <= 512 && tiles / (parts * 2) >= 4) parts *= 2;
+    return parts;
+}
+
+// Frames of 513 to 1024 boxes, ten or more of them (longer frames: inside): one launch without a sort, in which a
 // workgroup of 1024 threads tests every victim of its frame against the two best-ranked of every
 // sixteen input elements and the victims still alive against the whole frame (clustered detections,
 // whole call: 64 x 1024 11.8 us, all pairs 20.8; 256 x 1024 28.4, early exit 34.5, all pairs 43.2;
@@ -143,8 +166,18 @@ NMS_HD bool nms_use_early_exit(int n_max, int frames, int sort_chunk)
 // 45.0 against 47.9).  In tiles of 64 boxes per frame:
 NMS_HD bool nms_use_small_frames(int n_max, int frames)
 {
-    if (n_max > 1024) return false;
     const int tiles = (n_max + 63) / 64;
+    if (n_max > 1024) {
+        // Frames of 1025 to 4096 boxes (two or four elements per thread), a few of them.  Below 2^25 pair slots the
+        // direct form is quicker (4 x 2048: 9.5 us against 10.6; the tables cost 4 us before the first pair test).
+        // Above that the kernel wins while a workgroup's share stays at four tiles of victims (five beyond 2048
+        // boxes) with one workgroup per compute unit: 8 x 2048 11 us against 17 (direct), 32 x 2048 25 against 30
+        // (all pairs), 4 x 4096 15 against 29, 16 x 4096 33 against 40 (early exit), 40 x 1536 24.5 against 26.4;
+        // 44 x 1536 31.5 against 28.5, 56 x 1100 30.8 against 25.0, 29 x 3000 47.8 against 48.1.
+        if (n_max > 4096 || frames > 256 || (long long)frames * n_max * n_max < (1ll << 25)) return false;
+        const int parts = nms_small_frames_parts(frames, n_max);
+        return (tiles + parts - 1) / parts <= (n_max > 2048 ? 5 : 4);
+    }
     // against the direct form, where that would be taken (10 to 32 frames: 12 x 1024 7.1 us against 8.5, 24 x 1024 8.2
     // against 15.4, 32 x 768 8.5 against 9.4; 8 x 1024 7.0 against 6.3, 16 x 768 7.2 against 6.2, 32 x 576 8.8 against 8.0)
     if (nms_use_direct_form(n_max, frames)) return tiles >= 10 && (long long)frames * n_max * n_max > (5ll << 21);
@@ -152,20 +185,6 @@ NMS_HD bool nms_use_small_frames(int n_max, int frames)
     if (frames <= 256) return tiles >= 11;
     if (frames < 512) return tiles >= 15;
     return tiles >= 11;
-}
-
-// Workgroups that share a frame there (each builds the tables of the whole frame and takes every
-// parts-th tile of victims): doubled while that leaves at most one workgroup per compute unit (256),
-// and once more -- two workgroups fit a compute unit -- as long as a share keeps four tiles of
-// victims (measured: 256 x 1024 31.6 -> 28.4 us, 256 x 768 36.3 -> 26.5; with two-tile shares,
-// 64 x 1024 12.4 -> 13.9); up to 16.
-NMS_HD int nms_small_frames_parts(int frames, int n_max)
-{
-    int parts = 1;
-    while (parts < 16 && (long long)frames * parts * 2 <= 256) parts *= 2;
-    const int tiles = (n_max + 63) / 64;
-    while (parts < 16 && (long long)frames * parts * 2 <= 512 && tiles / (parts * 2) >= 4) parts *= 2;
-    return parts;
 }
 
 // The route of the automatic whole-path call for a batch shape (1 <= n_max, 1 <= frames).

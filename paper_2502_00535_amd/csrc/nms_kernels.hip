@@ -370,10 +370,22 @@ static int small_frames_launch(const float *boxes, const float *scores, const in
     const int parts = nms_small_frames_parts(frames, n_max);
     const dim3 grid((unsigned)(frames * parts)), block(kSmallThreads);
     begin_launch();
-    if (th.fast)
-        small_frames_kernel<true><<<grid, block, 0, stream>>>(boxes, scores, counts, n_max, parts, th, keep_out);
-    else
-        small_frames_kernel<false><<<grid, block, 0, stream>>>(boxes, scores, counts, n_max, parts, th, keep_out);
+    if (n_max <= kSmallThreads) {
+        if (th.fast)
+            small_frames_kernel<true><<<grid, block, 0, stream>>>(boxes, scores, counts, n_max, parts, th, keep_out);
+        else
+            small_frames_kernel<false><<<grid, block, 0, stream>>>(boxes, scores, counts, n_max, parts, th, keep_out);
+    } else if (n_max <= 2 * kSmallThreads) {
+        if (th.fast)
+            mid_frames_kernel<true, 2><<<grid, block, 0, stream>>>(boxes, scores, counts, n_max, parts, th, keep_out);
+        else
+            mid_frames_kernel<false, 2><<<grid, block, 0, stream>>>(boxes, scores, counts, n_max, parts, th, keep_out);
+    } else {
+        if (th.fast)
+            mid_frames_kernel<true, 4><<<grid, block, 0, stream>>>(boxes, scores, counts, n_max, parts, th, keep_out);
+        else
+            mid_frames_kernel<false, 4><<<grid, block, 0, stream>>>(boxes, scores, counts, n_max, parts, th, keep_out);
+    }
     return launch_status();
 }
 

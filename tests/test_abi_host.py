@@ -72,13 +72,15 @@ def test_route_by_size():
     D, A, T, E = nms.NMS_ROUTE_DIRECT, nms.NMS_ROUTE_ALL_PAIRS, nms.NMS_ROUTE_TWO_LAUNCH, nms.NMS_ROUTE_EARLY_EXIT
     S = nms.NMS_ROUTE_SMALL_FRAMES
     shapes = {(256, 1): D, (4096, 1): D, (1024, 64): S, (16384, 1): T, (4096, 256): E,
-              (1024, 10): D, (1024, 11): S, (1024, 24): S, (1024, 25): S, (576, 75): D, (577, 31): D, (577, 32): S, (768, 17): D, (768, 18): S, (4096, 3): D, (4096, 4): A,
-              (1024, 511): S, (1024, 512): S, (1024, 60000): S, (1025, 511): A, (1025, 512): E, (1023, 513): S,
+              (4096, 2): S, (4096, 16): S, (4096, 19): S, (4096, 20): E, (2048, 7): D, (2048, 8): S, (2048, 32): S, (2048, 33): A,
+              (2048, 64): E, (1536, 14): D, (1536, 15): S, (1536, 42): S, (1536, 43): A, (3000, 3): D, (3000, 4): S, (3000, 25): S, (3000, 26): A,
+              (1025, 31): D, (1025, 32): S, (1100, 51): S, (1100, 52): A, (4097, 2): A,
+              (1024, 10): D, (1024, 11): S, (1024, 24): S, (1024, 25): S, (576, 75): D, (577, 31): D, (577, 32): S, (768, 17): D, (768, 18): S, 
+              (1024, 511): S, (1024, 512): S, (1024, 60000): S, (1025, 255): A, (1025, 256): E, (1023, 513): S,
               (512, 128): D, (512, 129): A, (512, 512): A, (513, 95): D, (513, 96): S, (640, 25): D, (640, 26): S, (513, 128): S, (513, 129): A, (513, 2040): A,
               (640, 128): S, (640, 256): A, (641, 129): S, (641, 256): S, (641, 257): A, (896, 256): S, (896, 257): A, (896, 511): A,
               (897, 257): S, (897, 511): S, (640, 512): A, (641, 512): S, (704, 5000): S,
               (256, 512): D, (256, 513): A, (257, 508): D, (257, 509): A, (100, 60000): A,
-              (4096, 31): A, (4096, 32): E,
               (4097, 1): A, (11585, 1): A, (11586, 1): T, (16384, 7): T, (16384, 8): E, (46340, 1): T, (46341, 1): E,
               (65536, 1): E, (8192, 2): T, (8192, 1): A}
     for (n, f), want in shapes.items():
