@@ -142,16 +142,17 @@ int nms_reduce_batched(const uint64_t *mask, const int32_t *order, const int32_t
  * into the pair tests, and the result is the same keep vector as steps 1-3 give.
  * The call picks its route by size (nms_route() names it); every route returns the same bits:
  *   NMS_ROUTE_DIRECT      small work (up to about 2^25 pair slots = frames * n_max^2): one launch.
- *   NMS_ROUTE_SMALL_FRAMES  batches of ten or more frames of 513 to 1024 boxes (which batch sizes
- *                         depends on the frame length; nms_route() tells): one launch without a
- *                         sort, every victim against the two best-ranked of every sixteen input
- *                         boxes, then the victims still alive against the whole frame; rank order
- *                         enters as a compare of the two boxes' (score, index) keys.
+ *   NMS_ROUTE_SMALL_FRAMES  batches of ten or more frames of 513 to 1024 boxes, and 2 to about 40
+ *                         frames of 1025 to 4096 boxes (which batch sizes depends on the frame
+ *                         length; nms_route() tells): one launch without a sort, every victim
+ *                         against the two best-ranked of every sixteen input boxes, then the
+ *                         victims still alive against the whole frame; rank order enters as a
+ *                         compare of the two boxes' (score, index) keys.
  *   NMS_ROUTE_ALL_PAIRS   rank step, then every pair test of the ranked triangle.
  *   NMS_ROUTE_TWO_LAUNCH  frames beyond NMS_SORT_CHUNK boxes, 2^27 <= pair slots < 2^31: rank step,
  *                         every victim against the best 2048 ranks, then only the victims still
  *                         alive against the rest.
- *   NMS_ROUTE_EARLY_EXIT  large batches (frames of 1024 to NMS_SORT_CHUNK boxes from 2^29 pair
+ *   NMS_ROUTE_EARLY_EXIT  large batches (frames of 1025 to NMS_SORT_CHUNK boxes from 2^28 pair
  *                         slots, larger frames from 2^31): nms_run_early_exit_batched below.
  * All but DIRECT and ALL_PAIRS skip pair tests of victims that already have an eliminator, so
  * their running time depends on the data.  Callers that want every pair evaluated whatever the
@@ -262,7 +263,7 @@ int nms_run_ex_batched(const float *boxes, const float *scores, const int32_t *c
  * LDS and takes the outranking boxes in stages of doubling width (with fewer frames than compute
  * units a frame's victims are shared out among several workgroups; frames beyond NMS_SORT_CHUNK
  * boxes always are, and their workgroups fetch the outranking boxes from the ranked table in
- * memory); it pays from about 2^29 pair slots per batch (frames * n_max^2) on.  Sizes as
+ * memory); it pays from about 2^28 pair slots per batch (frames * n_max^2) on.  Sizes as
  * nms_run_batched; workspace >= nms_workspace_bytes(n_max, frames), 256-byte aligned (used
  * for the rank step's tables unless the rank step runs inside the kernel; required in either case).
  * Arguments, layout, ownership and errors as nms_run_batched.
