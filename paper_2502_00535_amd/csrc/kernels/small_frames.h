@@ -1,4 +1,4 @@
-// Part of nms_kernels.hip (included there, inside its anonymous namespace): frames of at most 1024 boxes, two stages of pair tests in one launch, no sort.
+// Part of nms_kernels.hip (included there, inside its anonymous namespace): frames of at most 1024 boxes (a few of up to 4096), two stages of pair tests in one launch, no sort.
 #pragma once
 
 // ----------------------------------------------------------------------------- small frames, one launch
@@ -37,6 +37,12 @@
 // victim's keep byte is written once, by its workgroup.  Same keep vector as the all-pairs routes,
 // bit for bit: a victim is dropped only once an eliminator has been found.  The kernel is held to 64
 // vector registers and half a compute unit's LDS, so that two workgroups fit a compute unit.
+//
+// Frames of up to 2048 and 4096 boxes take the same body with two and four input elements per thread
+// (mid_frames_kernel): one form of the tables, chosen after the wavefronts have exchanged their flags,
+// one workgroup per compute unit, a frame shared out among up to 64 of them; for shares of one or two
+// tiles the first stage takes the second stage's form (lane = outranking box, the picked boxes being
+// the table).
 constexpr int kSmallWaves = 16;
 constexpr int kSmallThreads = kSmallWaves * 64;
 constexpr int kSmallPick = 8;                          // boxes a wavefront contributes to the first stage
