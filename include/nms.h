@@ -142,7 +142,8 @@ int nms_reduce_batched(const uint64_t *mask, const int32_t *order, const int32_t
  * into the pair tests, and the result is the same keep vector as steps 1-3 give.
  * The call picks its route by size (nms_route() names it); every route returns the same bits:
  *   NMS_ROUTE_DIRECT      small work (up to about 2^25 pair slots = frames * n_max^2): one launch.
- *   NMS_ROUTE_SMALL_FRAMES  batches of ten or more frames of 513 to 1024 boxes, and 2 to about 40
+ *   NMS_ROUTE_SMALL_FRAMES  batches of ten or more frames of 513 to 1024 boxes (of 128 or more
+ *                         frames from 449 boxes on), and 2 to about 40
  *                         frames of 1025 to 4096 boxes (which batch sizes depends on the frame
  *                         length; nms_route() tells): one launch without a sort, every victim
  *                         against the two best-ranked of every sixteen input boxes, then the

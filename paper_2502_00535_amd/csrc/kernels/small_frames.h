@@ -42,7 +42,7 @@
 // (mid_frames_kernel): one form of the tables, chosen after the wavefronts have exchanged their flags,
 // one workgroup per compute unit, a frame shared out among up to 64 of them; for shares of one or two
 // tiles the first stage takes the second stage's form (lane = outranking box, the picked boxes being
-// the table).
+// the table).  Frames of at most 512 boxes: the body in workgroups of eight wavefronts (tiny_frames_kernel).
 constexpr int kSmallWaves = 16;
 constexpr int kSmallThreads = kSmallWaves * 64;
 constexpr int kSmallPick = 8;                          // boxes a wavefront contributes to the first stage
@@ -116,7 +116,7 @@ __device__ __forceinline__ void small_victim_item(const float4 *cbox, const uint
 // victim) in sets of R tiles against the first ncand rows (a multiple of kSmallGroup) of a table.  The wavefronts are shared out among the
 // sets, a wavefront keeps its set's victims in registers and takes every so-many-th group of boxes;
 // eliminated victims are merged per victim tile in dead_words[].
-template <int PAIR, bool PICKED, int R>
+template <int PAIR, bool PICKED, int R, int W>
 __device__ __forceinline__ void small_victim_lanes(const float4 *tbox, const uint2 *tinfo, const float4 *cbox, const uint4 *cinfo,
                                                    int ncand, const float4 *lbox, const unsigned long long *lkey, int count, int n_f,
                                                    int part, int parts, unsigned long long *dead_words, float theta, float y_one)
@@ -127,7 +127,7 @@ __device__ __forceinline__ void small_victim_lanes(const float4 *tbox, const uin
     const int sets = (vtiles + R - 1) / R;  // at most 1024 / 64 / R <= 8 for R >= 2
     if (sets == 0) return;
     const int set = wave % sets;
-    const int waves_of_set = (kSmallWaves - set + sets - 1) / sets;
+    const int waves_of_set = (W - set + sets - 1) / sets;
     const int groups = ncand / kSmallGroup;
     float4 v[R];
     unsigned long long vkey[R];
@@ -161,7 +161,7 @@ __device__ __forceinline__ void small_victim_lanes(const float4 *tbox, const uin
 // broadcasts, their reads issued together (a slot beyond the count repeats the last one); a victim with
 // an eliminator gets its bit in dead_words[slot / 64].  PICKED: the table of picked boxes, whose rows
 // carry their input index; otherwise the frame's table, where the row number is the index.
-template <int PAIR, bool PICKED, int TILES>
+template <int PAIR, bool PICKED, int TILES, int W>
 __device__ __forceinline__ void small_candidate_lanes(const float4 *tbox, const uint2 *tinfo, const float4 *cbox, const uint4 *cinfo,
                                                       int ctiles, const float4 *lbox, const unsigned long long *lkey, int count,
                                                       int n_f, int part, int parts, unsigned long long *dead_words, float theta,
@@ -173,15 +173,14 @@ __device__ __forceinline__ void small_candidate_lanes(const float4 *tbox, const 
     const int batches = (count + 3) / 4;
     if (groups == 0 || batches == 0) return;
     const int g = wave % groups;
-    if (g >= kSmallWaves) return;
-    const int waves_of_group = (kSmallWaves - g + groups - 1) / groups;
+    const int waves_of_group = (W - g + groups - 1) / groups;
     const int first_batch = wave / groups;
     if (first_batch >= batches) return;
     float4 cb[TILES];
     float aux[TILES];
     unsigned long long ckey[TILES];
 #pragma unroll 1
-    for (int t0 = g * TILES; t0 < ctiles; t0 += kSmallWaves * TILES) {  // (more groups than wavefronts: the table of a long frame)
+    for (int t0 = g * TILES; t0 < ctiles; t0 += W * TILES) {  // (more groups than wavefronts: the table of a long frame)
 #pragma unroll
         for (int j = 0; j < TILES; ++j) {
             const bool real = t0 + j < ctiles;  // a tile beyond the table's last: a copy of tile t0 that is ranked before nothing
@@ -229,7 +228,7 @@ __device__ __forceinline__ void small_candidate_lanes(const float4 *tbox, const 
 // The stages of one workgroup.  tbox / tinfo: the frame in input order (info = decision value, upper
 // key half); pbox / pinfo: the picked boxes (info = decision value, upper key half, input index).  The
 // workgroup's victims are the slots i < m0 of its share (small_share_element).
-template <int PAIR, int PICK_TILES>
+template <int PAIR, int PICK_TILES, int W>
 __device__ __forceinline__ void small_stages(const float4 *tbox, const uint2 *tinfo, const float4 *pbox, const uint4 *pinfo,
                                              int picked_rows, unsigned long long *dead1, unsigned long long *dead2, float4 *lbox,
                                              unsigned long long *lkey, int n_f, int part, int parts, float theta, float y_one,
@@ -244,11 +243,11 @@ __device__ __forceinline__ void small_stages(const float4 *tbox, const uint2 *ti
     // ---- stage 1: lane = victim, four victims per lane, where the share has three tiles or more (a broadcast of an
     // outranking box then serves four rows), two per lane for two tiles; lane = outranking box for a single tile
     if (m0 / kTile > 2)
-        small_victim_lanes<PAIR, true, 4>(tbox, tinfo, pbox, pinfo, picked_rows, nullptr, nullptr, m0, n_f, part, parts, dead1, theta, y_one);
+        small_victim_lanes<PAIR, true, 4, W>(tbox, tinfo, pbox, pinfo, picked_rows, nullptr, nullptr, m0, n_f, part, parts, dead1, theta, y_one);
     else if (m0 / kTile == 2 && PICK_TILES == 2)
-        small_victim_lanes<PAIR, true, 2>(tbox, tinfo, pbox, pinfo, picked_rows, nullptr, nullptr, m0, n_f, part, parts, dead1, theta, y_one);
+        small_victim_lanes<PAIR, true, 2, W>(tbox, tinfo, pbox, pinfo, picked_rows, nullptr, nullptr, m0, n_f, part, parts, dead1, theta, y_one);
     else
-        small_candidate_lanes<PAIR, true, PICK_TILES>(tbox, tinfo, pbox, pinfo, picked_rows / kTile, nullptr, nullptr, m0, n_f, part, parts, dead1,
+        small_candidate_lanes<PAIR, true, PICK_TILES, W>(tbox, tinfo, pbox, pinfo, picked_rows / kTile, nullptr, nullptr, m0, n_f, part, parts, dead1,
                                              theta, y_one);
     __syncthreads();
 
@@ -281,38 +280,39 @@ __device__ __forceinline__ void small_stages(const float4 *tbox, const uint2 *ti
 
     // ---- stage 2: the listed victims against the whole frame
     if (listed <= kSmallShort)
-        small_candidate_lanes<PAIR, false, kSmallTiles>(tbox, tinfo, tbox, nullptr, tiles_f, lbox, lkey, listed, n_f, 0, 1, dead2, theta, y_one);
+        small_candidate_lanes<PAIR, false, kSmallTiles, W>(tbox, tinfo, tbox, nullptr, tiles_f, lbox, lkey, listed, n_f, 0, 1, dead2, theta, y_one);
     if (listed > kSmallShort)
-        small_victim_lanes<PAIR, false, 4>(tbox, tinfo, tbox, nullptr, tiles_f * kTile, lbox, lkey, listed, n_f, 0, 1, dead2, theta, y_one);
+        small_victim_lanes<PAIR, false, 4, W>(tbox, tinfo, tbox, nullptr, tiles_f * kTile, lbox, lkey, listed, n_f, 0, 1, dead2, theta, y_one);
     __syncthreads();
-    for (int k = tid; k < listed; k += kSmallThreads) keep_f[(unsigned)lkey[k]] = ((dead2[k / kTile] >> (k % kTile)) & 1ull) != 0ull ? 0 : 1;
+    for (int k = tid; k < listed; k += W * kTile) keep_f[(unsigned)lkey[k]] = ((dead2[k / kTile] >> (k % kTile)) & 1ull) != 0ull ? 0 : 1;
 }
 
 // The kernel's body.  E: input elements per thread (frames of at most E * 1024 boxes); register q of
 // thread t holds element 1024 q + t, so a wavefront's register is a tile of 64 neighbours.  FAST: the
 // threshold has a division-free form (NmsThetaConst).
-template <bool FAST, int E>
+template <bool FAST, int E, int W>
 __device__ __forceinline__ void small_frames_body(const float *__restrict__ boxes, const float *__restrict__ scores,
                                                   const int32_t *__restrict__ counts, int n_max, int parts, const NmsThetaConst &th,
                                                   uint8_t *__restrict__ keep_out)
 {
-    constexpr int P = kSmallThreads * E;    // rows of the tables
-    constexpr int kPicked = kSmallFirst * E;  // rows of the table of picked boxes
+    constexpr int T = W * kTile;               // threads of the workgroup
+    constexpr int P = T * E;                   // rows of the tables
+    constexpr int kPicked = W * kSmallPick * E;  // rows of the table of picked boxes
     // One element per thread: every table twice, as the boxes are and with y (and the decision value) multiplied by
     // NMS_YSCALE -- which of the two the stages read is known only once every wavefront has seen its boxes, and
     // writing both saves a barrier; the list of the second stage then takes the place of the form that is not used.
     // Longer frames have no room for that: the wavefronts exchange their flags first and write one form.
     constexpr int kForms = (FAST && E == 1) ? 2 : 1;
-    constexpr int kList = kForms == 2 ? 1 : kSmallThreads;  // a workgroup's share is at most 1024 victims
+    constexpr int kList = kForms == 2 ? 1 : T;  // a workgroup's share is at most one victim per thread
     __shared__ float4 tbox[kForms][P];
     __shared__ uint2 tinfo[kForms][P];
     __shared__ float4 pbox[kForms][kPicked];
     __shared__ uint4 pinfo[kForms][kPicked];
-    __shared__ unsigned long long dead1[kSmallThreads / kTile];
-    __shared__ unsigned long long dead2[kSmallThreads / kTile];
+    __shared__ unsigned long long dead1[16];
+    __shared__ unsigned long long dead2[16];
     __shared__ float4 lbox_own[kList];
     __shared__ unsigned long long lkey_own[kList];
-    __shared__ int wodd[kSmallWaves];
+    __shared__ int wodd[W];
     const int f = blockIdx.x / parts;
     const int part = blockIdx.x % parts;
     const int tid = (int)threadIdx.x;
@@ -329,7 +329,7 @@ __device__ __forceinline__ void small_frames_body(const float *__restrict__ boxe
     unsigned upper[E];
 #pragma unroll
     for (int q = 0; q < E; ++q) {
-        const int e = q * kSmallThreads + tid;
+        const int e = q * T + tid;
         mine[q] = make_float4(0.f, 0.f, 0.f, 0.f);
         upper[q] = ~0u;
         if (e < n_f) {
@@ -353,26 +353,26 @@ __device__ __forceinline__ void small_frames_body(const float *__restrict__ boxe
             if (u == best && !picked[q] && (in_row & ((1u << (lane & 15)) - 1u)) == 0u) picked[q] = true;
         }
         const unsigned long long picked_mask = __ballot(picked[q]);
-        slot[q] = (q * kSmallWaves + wave) * kSmallPick +
+        slot[q] = (q * W + wave) * kSmallPick +
                   (int)__builtin_amdgcn_mbcnt_hi((unsigned)(picked_mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)picked_mask, 0u));
         // per frame: does every y allow the scaled form (the box (0,0,0,0) does)
         odd = odd || !(nms_y_regular(mine[q].y) && nms_y_regular(mine[q].w));
     }
     const unsigned long long odd_mask = __ballot(odd);
     if (lane == 0) wodd[wave] = odd_mask != 0ull ? 1 : 0;
-    if (tid < kSmallThreads / kTile) {
+    if (tid < 16) {
         dead1[tid] = 0ull;
         dead2[tid] = 0ull;
     }
     bool scaled = false;
     if (kForms == 1 && FAST) {
         __syncthreads();
-        scaled = __ballot(wodd[lane & (kSmallWaves - 1)] != 0) == 0ull;
+        scaled = __ballot(wodd[lane & (W - 1)] != 0) == 0ull;
     }
     // what the tables need per box: its decision value (no intersection reaches a padding row's)
 #pragma unroll
     for (int q = 0; q < E; ++q) {
-        const int e = q * kSmallThreads + tid;
+        const int e = q * T + tid;
         const float area = nms_box_area(mine[q].x, mine[q].y, mine[q].z, mine[q].w);
         const float aux = FAST ? (e < n_f ? nms_pair_threshold(area, th.m) : INFINITY) : area;
         const float y1 = mine[q].y, y2 = mine[q].w;
@@ -397,30 +397,30 @@ __device__ __forceinline__ void small_frames_body(const float *__restrict__ boxe
         }
     }
     __syncthreads();
-    if (kForms == 2) scaled = __ballot(wodd[lane & (kSmallWaves - 1)] != 0) == 0ull;
+    if (kForms == 2) scaled = __ballot(wodd[lane & (W - 1)] != 0) == 0ull;
 
     float y_one;  // NMS_YSCALE in a vector register (opaque to the compiler so it stays there)
     asm volatile("v_mov_b32 %0, 0x38800000" : "=v"(y_one));
-    constexpr int kPickTiles = E == 1 ? 2 : kSmallTiles;  // tiles of picked boxes a wavefront holds when the boxes are the lanes
+    constexpr int kPickTiles = kPicked / kTile < kSmallTiles ? kPicked / kTile : kSmallTiles;  // tiles of picked boxes a wavefront holds when the boxes are the lanes
     if (!FAST)
-        small_stages<kPairExact, kPickTiles>(tbox[0], tinfo[0], pbox[0], pinfo[0], kPicked, dead1, dead2, lbox_own, lkey_own, n_f, part,
+        small_stages<kPairExact, kPickTiles, W>(tbox[0], tinfo[0], pbox[0], pinfo[0], kPicked, dead1, dead2, lbox_own, lkey_own, n_f, part,
                                              parts, th.theta, y_one, keep_f);
     else if (kForms == 1 && scaled)
-        small_stages<kPairFastYScaled, kPickTiles>(tbox[0], tinfo[0], pbox[0], pinfo[0], kPicked, dead1, dead2, lbox_own, lkey_own, n_f,
+        small_stages<kPairFastYScaled, kPickTiles, W>(tbox[0], tinfo[0], pbox[0], pinfo[0], kPicked, dead1, dead2, lbox_own, lkey_own, n_f,
                                                    part, parts, th.theta, y_one, keep_f);
     else if (kForms == 1)
-        small_stages<kPairFast, kPickTiles>(tbox[0], tinfo[0], pbox[0], pinfo[0], kPicked, dead1, dead2, lbox_own, lkey_own, n_f, part,
+        small_stages<kPairFast, kPickTiles, W>(tbox[0], tinfo[0], pbox[0], pinfo[0], kPicked, dead1, dead2, lbox_own, lkey_own, n_f, part,
                                             parts, th.theta, y_one, keep_f);
     else if (scaled)
-        small_stages<kPairFastYScaled, kPickTiles>(tbox[kForms - 1], tinfo[kForms - 1], pbox[kForms - 1], pinfo[kForms - 1], kPicked,
+        small_stages<kPairFastYScaled, kPickTiles, W>(tbox[kForms - 1], tinfo[kForms - 1], pbox[kForms - 1], pinfo[kForms - 1], kPicked,
                                                    dead1, dead2, tbox[0], reinterpret_cast<unsigned long long *>(tinfo[0]), n_f, part,
                                                    parts, th.theta, y_one, keep_f);
     else
-        small_stages<kPairFast, kPickTiles>(tbox[0], tinfo[0], pbox[0], pinfo[0], kPicked, dead1, dead2, tbox[kForms - 1],
+        small_stages<kPairFast, kPickTiles, W>(tbox[0], tinfo[0], pbox[0], pinfo[0], kPicked, dead1, dead2, tbox[kForms - 1],
                                             reinterpret_cast<unsigned long long *>(tinfo[kForms - 1]), n_f, part, parts, th.theta,
                                             y_one, keep_f);
     if (part == 0)
-        for (int i = n_f + tid; i < n_max; i += kSmallThreads) keep_f[i] = 0;
+        for (int i = n_f + tid; i < n_max; i += T) keep_f[i] = 0;
 }
 
 // Frames of at most 1024 boxes.  Grid: frames * parts workgroups of kSmallThreads threads.  Held to
@@ -430,7 +430,7 @@ __global__ void __launch_bounds__(kSmallThreads) __attribute__((amdgpu_waves_per
 small_frames_kernel(const float *__restrict__ boxes, const float *__restrict__ scores, const int32_t *__restrict__ counts,
                     int n_max, int parts, NmsThetaConst th, uint8_t *__restrict__ keep_out)
 {
-    small_frames_body<FAST, 1>(boxes, scores, counts, n_max, parts, th, keep_out);
+    small_frames_body<FAST, 1, kSmallWaves>(boxes, scores, counts, n_max, parts, th, keep_out);
 }
 
 // Frames of at most 1024 E boxes, E = 2 or 4; a workgroup's share is at most 1024 victims (parts >= tiles / 16).
@@ -439,5 +439,16 @@ __global__ void __launch_bounds__(kSmallThreads) __attribute__((amdgpu_waves_per
 mid_frames_kernel(const float *__restrict__ boxes, const float *__restrict__ scores, const int32_t *__restrict__ counts,
                   int n_max, int parts, NmsThetaConst th, uint8_t *__restrict__ keep_out)
 {
-    small_frames_body<FAST, E>(boxes, scores, counts, n_max, parts, th, keep_out);
+    small_frames_body<FAST, E, kSmallWaves>(boxes, scores, counts, n_max, parts, th, keep_out);
+}
+
+// Frames of at most 512 boxes: workgroups of eight wavefronts, up to four of them on a compute unit.
+constexpr int kTinyWaves = 8;
+constexpr int kTinyThreads = kTinyWaves * 64;
+template <bool FAST>
+__global__ void __launch_bounds__(kTinyThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
+tiny_frames_kernel(const float *__restrict__ boxes, const float *__restrict__ scores, const int32_t *__restrict__ counts,
+                   int n_max, int parts, NmsThetaConst th, uint8_t *__restrict__ keep_out)
+{
+    small_frames_body<FAST, 1, kTinyWaves>(boxes, scores, counts, n_max, parts, th, keep_out);
 }

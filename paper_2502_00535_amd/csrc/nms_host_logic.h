@@ -146,6 +146,11 @@ NMS_HD int nms_small_frames_parts(int frames, int n_max)
     const int tiles = (n_max + 63) / 64;
     const int most = tiles < 64 ? tiles : 64;  // a workgroup without a tile of victims would only build tables
     int parts = (tiles + 15) / 16;
+    if (n_max <= 512) {  // workgroups of 512 threads, up to four on a compute unit
+        parts = 1;
+        while (parts * 2 <= tiles && (long long)frames * parts * 2 <= 512) parts *= 2;
+        return parts;
+    }
     if (n_max > 1024) {
         const int fit = 256 / (frames < 256 ? frames : 256);
         return fit > most ? most : (fit < parts ? parts : fit);
@@ -155,7 +160,7 @@ NMS_HD int nms_small_frames_parts(int frames, int n_max)
     return parts;
 }
 
-// Frames of 513 to 1024 boxes, ten or more of them (longer frames: inside): one launch without a sort, in which a
+// Frames of 513 to 1024 boxes, ten or more of them (longer and shorter frames: inside): one launch without a sort, in which a
 // workgroup of 1024 threads tests every victim of its frame against the two best-ranked of every
 // sixteen input elements and the victims still alive against the whole frame (clustered detections,
 // whole call: 64 x 1024 11.8 us, all pairs 20.8; 256 x 1024 28.4, early exit 34.5, all pairs 43.2;
@@ -178,6 +183,10 @@ NMS_HD bool nms_use_small_frames(int n_max, int frames)
         const int parts = nms_small_frames_parts(frames, n_max);
         return (tiles + parts - 1) / parts <= (n_max > 2048 ? 5 : 4);
     }
+    // frames of 449 to 512 boxes (workgroups of 512 threads), many of them: 256 x 512 16.3 us against 20.1 for all pairs,
+    // 2048 x 512 72 against 97; 128 x 512 13.2 against 14.4 (direct); shorter frames or fewer gain nothing (512 x 384: 25.0
+    // against 23.9; 64 x 512: 8.9 against 8.6)
+    if (n_max <= 512) return tiles == 8 && frames >= 128;
     // against the direct form, where that would be taken (10 to 32 frames: 12 x 1024 7.1 us against 8.5, 24 x 1024 8.2
     // against 15.4, 32 x 768 8.5 against 9.4; 8 x 1024 7.0 against 6.3, 16 x 768 7.2 against 6.2, 32 x 576 8.8 against 8.0)
     if (nms_use_direct_form(n_max, frames)) return tiles >= 10 && (long long)frames * n_max * n_max > (5ll << 21);

@@ -370,7 +370,13 @@ static int small_frames_launch(const float *boxes, const float *scores, const in
     const int parts = nms_small_frames_parts(frames, n_max);
     const dim3 grid((unsigned)(frames * parts)), block(kSmallThreads);
     begin_launch();
-    if (n_max <= kSmallThreads) {
+    if (n_max <= kTinyThreads) {
+        const dim3 tiny_block(kTinyThreads);
+        if (th.fast)
+            tiny_frames_kernel<true><<<grid, tiny_block, 0, stream>>>(boxes, scores, counts, n_max, parts, th, keep_out);
+        else
+            tiny_frames_kernel<false><<<grid, tiny_block, 0, stream>>>(boxes, scores, counts, n_max, parts, th, keep_out);
+    } else if (n_max <= kSmallThreads) {
         if (th.fast)
             small_frames_kernel<true><<<grid, block, 0, stream>>>(boxes, scores, counts, n_max, parts, th, keep_out);
         else

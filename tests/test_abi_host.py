@@ -77,7 +77,7 @@ def test_route_by_size():
               (1025, 31): D, (1025, 32): S, (1100, 51): S, (1100, 52): A, (4097, 2): A,
               (1024, 10): D, (1024, 11): S, (1024, 24): S, (1024, 25): S, (576, 75): D, (577, 31): D, (577, 32): S, (768, 17): D, (768, 18): S, 
               (1024, 511): S, (1024, 512): S, (1024, 60000): S, (1025, 255): A, (1025, 256): E, (1023, 513): S,
-              (512, 128): D, (512, 129): A, (512, 512): A, (513, 95): D, (513, 96): S, (640, 25): D, (640, 26): S, (513, 128): S, (513, 129): A, (513, 2040): A,
+              (512, 127): D, (512, 128): S, (512, 4000): S, (449, 128): S, (448, 128): D, (448, 500): A, (513, 95): D, (513, 96): S, (640, 25): D, (640, 26): S, (513, 128): S, (513, 129): A, (513, 2040): A,
               (640, 128): S, (640, 256): A, (641, 129): S, (641, 256): S, (641, 257): A, (896, 256): S, (896, 257): A, (896, 511): A,
               (897, 257): S, (897, 511): S, (640, 512): A, (641, 512): S, (704, 5000): S,
               (256, 512): D, (256, 513): A, (257, 508): D, (257, 509): A, (100, 60000): A,

@@ -282,3 +282,21 @@ def test_few_short_frames(nms, oracle, frames, n):
         counts[:4] = [n, 0, 1, 65]
     want = check(nms, oracle, boxes, scores, 0.45, counts)
     assert 0 < want.sum() < want.size
+
+
+@pytest.mark.parametrize("frames,n", [(128, 512), (129, 449), (300, 500), (600, 480), (1030, 512)])
+def test_frames_of_at_most_512_boxes(nms, oracle, frames, n):
+    """The same kernel body in workgroups of eight wavefronts: one, two and four workgroups per frame, batches
+    beyond four workgroups per compute unit, ragged counts, sparse frames (long lists), equal scores."""
+    print(f"case {frames} x {n}", flush=True)
+    boxes, scores = batch(9000 + n, frames, n, extent=600, max_side=100, integer=(n % 2 == 0), score_levels=n // 2)
+    counts = None
+    if frames % 2 == 0:
+        counts = np.random.default_rng(n).integers(0, n + 1, frames).astype(np.int32)
+        counts[:4] = [n, 0, 1, 65]
+    want = check(nms, oracle, boxes, scores, 0.45, counts)
+    assert 0 < want.sum() < want.size
+    sparse, _ = batch(9500 + n, frames, n, extent=100000, max_side=60, integer=False)
+    assert check(nms, oracle, sparse, scores, 0.5, counts).sum() > 0.4 * frames * n
+    check(nms, oracle, boxes, np.full((frames, n), -1.5, np.float32), 0.3)
+    check(nms, oracle, boxes, scores, 0.0)
