@@ -17,8 +17,8 @@
 //             the frame may use is known once every wavefront has seen its boxes, and writing
 //             both lets one barrier do for the tables and that;
 //   pick      the two best-ranked elements of every row of sixteen lanes (a DPP minimum over the row,
-//             twice) are copied to a second table: kSmallFirst boxes, the best of every stretch of
-//             the input -- any set of boxes would do for the result, a well-ranked one eliminates most;
+//             twice) are copied to a second table: an eighth of the frame, the best of every stretch
+//             of the input -- any set of boxes would do for the result, a well-ranked one eliminates most;
 //   stage 1   every victim of the workgroup against the picked boxes: lane = victim, four victims
 //             per lane, the outranking boxes read from the table as broadcasts -- a broadcast moves
 //             64 x 16 bytes whatever it is used for, and with one victim per lane the LDS path, not
@@ -45,8 +45,7 @@
 // the table).  Frames of at most 512 boxes: the body in workgroups of eight wavefronts (tiny_frames_kernel).
 constexpr int kSmallWaves = 16;
 constexpr int kSmallThreads = kSmallWaves * 64;
-constexpr int kSmallPick = 8;                          // boxes a wavefront contributes to the first stage
-constexpr int kSmallFirst = kSmallWaves * kSmallPick;  // outranking boxes of the first stage
+constexpr int kSmallPick = 8;                          // boxes a wavefront picks for the first stage among 64 elements
 constexpr int kSmallGroup = 8;                         // outranking boxes per work item in the lane = victim form
 constexpr int kSmallTiles = 4;                         // tiles a wavefront holds in registers in the second stage
 constexpr int kSmallShort = 256;                       // longest list the second stage takes in its lane = outranking box form
@@ -113,8 +112,8 @@ __device__ __forceinline__ void small_victim_item(const float4 *cbox, const uint
 
 // Lane = victim: `count` victim slots (slot i = entry i of the list lbox / lkey; without a list, lane
 // i % 64 of the workgroup's i / 64-th tile, see small_share_element; a slot at or beyond n_f holds no
-// victim) in sets of R tiles against the first ncand rows (a multiple of kSmallGroup) of a table.  The wavefronts are shared out among the
-// sets, a wavefront keeps its set's victims in registers and takes every so-many-th group of boxes;
+// victim) in sets of R tiles against the first ncand rows (a multiple of kSmallGroup) of a table.
+// The wavefronts are shared out among the sets, a wavefront keeps its set's victims in registers and takes every so-many-th group of boxes;
 // eliminated victims are merged per victim tile in dead_words[].
 template <int PAIR, bool PICKED, int R, int W>
 __device__ __forceinline__ void small_victim_lanes(const float4 *tbox, const uint2 *tinfo, const float4 *cbox, const uint4 *cinfo,
@@ -247,8 +246,8 @@ __device__ __forceinline__ void small_stages(const float4 *tbox, const uint2 *ti
     else if (m0 / kTile == 2 && PICK_TILES == 2)
         small_victim_lanes<PAIR, true, 2, W>(tbox, tinfo, pbox, pinfo, picked_rows, nullptr, nullptr, m0, n_f, part, parts, dead1, theta, y_one);
     else
-        small_candidate_lanes<PAIR, true, PICK_TILES, W>(tbox, tinfo, pbox, pinfo, picked_rows / kTile, nullptr, nullptr, m0, n_f, part, parts, dead1,
-                                             theta, y_one);
+        small_candidate_lanes<PAIR, true, PICK_TILES, W>(tbox, tinfo, pbox, pinfo, picked_rows / kTile, nullptr, nullptr, m0, n_f, part, parts,
+                                                         dead1, theta, y_one);
     __syncthreads();
 
     // ---- pack: victims with an eliminator are written out, the others listed (box and key), in slot order.  How many
@@ -287,9 +286,10 @@ __device__ __forceinline__ void small_stages(const float4 *tbox, const uint2 *ti
     for (int k = tid; k < listed; k += W * kTile) keep_f[(unsigned)lkey[k]] = ((dead2[k / kTile] >> (k % kTile)) & 1ull) != 0ull ? 0 : 1;
 }
 
-// The kernel's body.  E: input elements per thread (frames of at most E * 1024 boxes); register q of
-// thread t holds element 1024 q + t, so a wavefront's register is a tile of 64 neighbours.  FAST: the
-// threshold has a division-free form (NmsThetaConst).
+// The kernel's body.  W: wavefronts of the workgroup (T = 64 W threads); E: input elements per thread
+// (frames of at most E * T boxes); register q of thread t holds element T q + t, so a wavefront's
+// register is a tile of 64 neighbours.  A workgroup's share is at most T victims.  FAST: the threshold
+// has a division-free form (NmsThetaConst).
 template <bool FAST, int E, int W>
 __device__ __forceinline__ void small_frames_body(const float *__restrict__ boxes, const float *__restrict__ scores,
                                                   const int32_t *__restrict__ counts, int n_max, int parts, const NmsThetaConst &th,
