@@ -59,6 +59,30 @@ int main(int argc, char **argv)
         printf("last_unit_mismatches %d\n", outside);
         return 0;
     }
+    if (!strcmp(argv[1], "shares")) {
+        // every batch shape that the small-frames kernels take: the share of a workgroup must fit the kernel's tables
+        // (one victim per thread: 512 threads up to 512 boxes per frame, 1024 beyond), no workgroup beyond the frame's tiles
+        long long taken = 0, bad = 0;
+        for (int n_max = 1; n_max <= 4200; ++n_max) {
+            for (int frames = 1; frames <= 70000; frames = frames < 600 ? frames + 1 : frames * 2 + 1) {
+                if (!nms_use_small_frames(n_max, frames)) continue;
+                ++taken;
+                const int tiles = (n_max + 63) / 64;
+                const int parts = nms_small_frames_parts(frames, n_max);
+                const int share_tiles = (tiles + parts - 1) / parts;
+                const int threads = n_max <= 512 ? 512 : 1024;
+                const bool ok = n_max > 448 && n_max <= 4096 && parts >= 1 && parts <= 64 && parts <= tiles &&
+                                share_tiles * 64 <= threads && (long long)frames * parts <= 2147483647ll &&
+                                nms_route_for(n_max, frames, 4096) == kNmsRouteSmallFrames;
+                if (!ok) {
+                    if (!bad) printf("first_bad %d %d parts %d\n", n_max, frames, parts);
+                    ++bad;
+                }
+            }
+        }
+        printf("taken %lld bad %lld\n", taken, bad);
+        return 0;
+    }
     if (!strcmp(argv[1], "layout")) {
         int n_max, frames, chunk;
         while (scanf("%d %d %d", &n_max, &frames, &chunk) == 3) {

@@ -47,6 +47,15 @@ def test_unit_numbering_for_every_unit_a_launch_can_hold(driver):
     assert out[2] == "last_unit_mismatches 0"
 
 
+def test_small_frames_shares_fit_the_kernels(driver):
+    """Every batch shape the one-launch sort-free kernels take (frames up to 4200 boxes, up to 70,000 frames): a
+    workgroup's share of victims fits its tables, no workgroup is without a tile, and nms_route_for names the route."""
+    out = run(driver, "shares").strip().split("\n")
+    taken, bad = int(out[-1].split()[1]), int(out[-1].split()[3])
+    assert bad == 0, out
+    assert taken > 100000
+
+
 def test_workspace_layout_matches_the_size_helper(driver):
     import paper_2502_00535_amd.binding as nms
 
