@@ -300,3 +300,37 @@ def test_frames_of_at_most_512_boxes(nms, oracle, frames, n):
     assert check(nms, oracle, sparse, scores, 0.5, counts).sum() > 0.4 * frames * n
     check(nms, oracle, boxes, np.full((frames, n), -1.5, np.float32), 0.3)
     check(nms, oracle, boxes, scores, 0.0)
+
+
+def test_route_can_be_captured_in_a_hip_graph(nms, oracle):
+    """The route enqueues one kernel and nothing else, so it may be captured; replays with new inputs in the same
+    buffers and eager work in between must give the oracle's keep vectors (frames of 1000, 500 and 3000 boxes: the three
+    kernels of the route)."""
+    import torch
+
+    dev = torch.device("cuda:0")
+    for F, n in ((24, 1000), (130, 500), (5, 3000)):
+        assert nms.nms_route(n, F) == nms.NMS_ROUTE_SMALL_FRAMES
+        boxes = torch.zeros((F, n, 4), dtype=torch.float32, device=dev)
+        scores = torch.zeros((F, n), dtype=torch.float32, device=dev)
+        keep = torch.zeros((F, n), dtype=torch.uint8, device=dev)
+        ws = torch.zeros(nms.nms_workspace_bytes(n, F), dtype=torch.uint8, device=dev)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            nms.nms_run_batched(boxes, scores, None, n, F, 0.45, keep, ws)
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                nms.nms_run_batched(boxes, scores, None, n, F, 0.45, keep, ws)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            b, s = batch(31000 + 1000 * rep + n, F, n, extent=900, max_side=120, integer=(rep % 2 == 0), score_levels=100)
+            boxes.copy_(torch.from_numpy(b))
+            scores.copy_(torch.from_numpy(s))
+            keep.fill_(9)
+            (boxes.sum() + scores.sum()).item()
+            graph.replay()
+            torch.cuda.synchronize()
+            want = oracle_keep_frames(oracle, b, s, np.float32(0.45))
+            assert np.array_equal(keep.cpu().numpy(), want), f"{F} x {n}, replay {rep}"
