@@ -83,3 +83,40 @@ def test_variants(nms, oracle, case):
         want = oracle_ex(oracle, boxes, scores, classes, theta, opts, counts)
         got = dev.run(theta, opts)
         assert np.array_equal(got, want), f"{opts}: {(got != want).sum()} differing keep bits"
+
+
+@pytest.mark.parametrize("case", range(36))
+def test_batches_of_the_one_launch_route(nms, oracle, case):
+    """Random batch shapes among those that nms_run_batched gives to its sort-free one-launch kernels (frames of 449
+    to 4096 boxes; see nms_route), with random counts, coordinate styles, score levels (down to a single one) and
+    thresholds (including 0 and beyond 1); the all-pairs and early-exit routes are run beside it."""
+    rng = np.random.default_rng(9900 + case)
+    while True:
+        if case % 3 == 0:
+            n_max, F = int(rng.integers(449, 1025)), int(rng.choice([11, 16, 24, 33, 64, 100, 128, 129, 200, 256, 300, 520, 900]))
+        elif case % 3 == 1:
+            n_max = int(rng.integers(1025, 4097))
+            F = (1 << 25) // (n_max * n_max) + int(rng.integers(1, 24))
+        else:
+            n_max, F = int(rng.choice([449, 512, 513, 577, 640, 1023, 1024, 1025, 2047, 2048, 2049, 4095, 4096])), int(rng.integers(2, 140))
+        if nms.nms_route(n_max, F) == nms.NMS_ROUTE_SMALL_FRAMES:
+            break
+    boxes = np.zeros((F, n_max, 4), np.float32)
+    scores = np.zeros((F, n_max), np.float32)
+    extent = float(rng.choice([200, 900, 4000, 100000]))
+    side = float(rng.choice([30, 120, 400]))
+    base = [random_frame(int(rng.integers(1 << 30)), n_max, extent=extent, max_side=side, integer=bool(rng.integers(2)),
+                         score_levels=int(rng.choice([0, 1, 2, 9, 300]))) for _ in range(min(F, 5))]
+    for f in range(F):
+        b, s = base[f % len(base)]
+        perm = rng.permutation(n_max) if f >= len(base) else np.arange(n_max)
+        boxes[f], scores[f] = b[perm], s[perm]
+    counts = rng.integers(0, n_max + 1, F).astype(np.int32)
+    counts[rng.integers(0, F)] = n_max
+    counts[rng.integers(0, F)] = int(rng.choice([0, 1, 63, 64, 65]))
+    use_counts = counts if case % 2 else None
+    theta = float(np.float32(rng.choice([0.0, 0.3, 0.45, 0.5, 0.7, 1.0, 1.25, rng.uniform(0.05, 0.95)])))
+    print(f"case {case}: frames={F} n_max={n_max} theta={theta}", flush=True)
+    want = oracle_keep_frames(oracle, boxes, scores, np.float32(theta), use_counts)
+    DeviceFrames(nms, boxes, scores, use_counts).fused(theta, want=want)
+
